@@ -1,0 +1,400 @@
+"""Pins for the CPU oracle: each check ties one of its functions to something
+other than itself — a library routine, a closed form, an invariant, exhaustive
+search on a tiny case, or a number the paper prints."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def golden_distortion():
+    out = {}
+    with open(os.path.join(GOLDEN, "paper_gaussian_distortion.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            name, bits, mean, std = line.split()
+            out[name] = (float(bits), float(mean), float(std))
+    return out
+
+
+# ------------------------------------------------------------------ fp16
+def test_half_conversion_exhaustive():
+    pat = np.arange(65536, dtype=np.uint16)
+    got = oracle.half_to_double(pat)
+    want = pat.view(np.float16).astype(np.float64)
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], want[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))
+
+
+# ------------------------------------------------------------ bit access
+def pack_lsb_first(codes, width):
+    """Independent packer: Python big integers, code q occupies bits [q*width, (q+1)*width)."""
+    big = 0
+    for q, c in enumerate(codes):
+        big |= int(c) << (q * width)
+    nbytes = (len(codes) * width + 7) // 8
+    return np.frombuffer(big.to_bytes(nbytes, "little"), dtype=np.uint8).copy()
+
+
+def test_bit_order_hand_example():
+    # byte0 = 0b10110100, byte1 = 0b00000011 -> stream bits (p=0..): 0,0,1,0,1,1,0,1, 1,1,0,0,0,0,0,0
+    s = np.array([0b10110100, 0b00000011], dtype=np.uint8)
+    L = oracle.lib()
+    assert [L.qpo_bit(s, p) for p in range(16)] == [0, 0, 1, 0, 1, 1, 0, 1, 1, 1, 0, 0, 0, 0, 0, 0]
+    # 3-bit codes: (0,0,1)->4, (0,1,1)->6, (0,1,1)->6, (1,0,0)->1 (value = sum bit_t 2^t)
+    assert [L.qpo_code(s, 3 * q, 3) for q in range(4)] == [4, 6, 6, 1]
+    # 4-bit: weight 2m in the low nibble of byte m
+    assert [L.qpo_code(s, 4 * q, 4) for q in range(4)] == [0x4, 0xB, 0x3, 0x0]
+    # circular window: 16 bits from bit 8 of a 16-bit stream wrap to the start
+    assert L.qpo_window(s, 8, 16, 16) == (0b00000011 | (0b10110100 << 8))
+
+
+@pytest.mark.parametrize("width", [2, 3, 4, 5, 7])
+def test_pack_unpack_identity(width):
+    g = np.random.default_rng(100 + width)
+    codes = g.integers(0, 1 << width, size=8 * 37)
+    stream = pack_lsb_first(codes, width)
+    L = oracle.lib()
+    got = [L.qpo_code(stream, q * width, width) for q in range(len(codes))]
+    assert got == list(codes)
+
+
+# -------------------------------------------------------- SQ / VQ decode
+def unpack_indices_numpy(codes_u8, width, count):
+    """Independent unpack with numpy.unpackbits (library routine)."""
+    bits = np.unpackbits(codes_u8, axis=-1, bitorder="little")
+    bits = bits[..., : count * width].reshape(*codes_u8.shape[:-1], count, width)
+    return (bits.astype(np.int64) << np.arange(width)).sum(-1)
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_sq_decode_is_table_take(bits):
+    M, N = 5, 256
+    lay = synth.make_layer(90, bits, synth.SQ, M, N, bits)
+    idx = unpack_indices_numpy(lay.codes, bits, N)
+    want = np.take(lay.lut.view(np.uint16), idx)
+    assert np.array_equal(oracle.decode(lay), want)
+
+
+@pytest.mark.parametrize("cbits", [3, 5, 7])
+def test_vq_decode_is_table_take(cbits):
+    M, N = 6, 512
+    lay = synth.make_layer(91, cbits, synth.VQ, M, N, cbits)
+    idx = unpack_indices_numpy(lay.codes, cbits, N // 2)
+    want = np.take(lay.lut.view(np.uint16).reshape(-1, 2), idx, axis=0).reshape(M, N)
+    got = oracle.decode(lay)
+    assert np.array_equal(got, want)
+    # component 0 lands on the even column
+    assert got[0, 0] == lay.lut.view(np.uint16).reshape(-1, 2)[idx[0, 0], 0]
+    assert got[0, 1] == lay.lut.view(np.uint16).reshape(-1, 2)[idx[0, 0], 1]
+
+
+# ------------------------------------------------------------ TCQ decode
+def tcq_layer(k, M=3, N=512, L=16, seed=0, lut=None):
+    return synth.make_layer(92, seed * 10 + k, synth.TCQ, M, N, k, window_bits=L, lut=lut)
+
+
+@pytest.mark.parametrize("k", [2, 3, 4])
+def test_tcq_constant_streams(k):
+    lay = tcq_layer(k)
+    lut = lay.lut.view(np.uint16)
+    lay.codes[:] = 0
+    assert np.all(oracle.decode(lay) == lut[0])
+    lay.codes[:] = 0xFF
+    assert np.all(oracle.decode(lay) == lut[0xFFFF])
+
+
+@pytest.mark.parametrize("k", [2, 3, 4])
+def test_tcq_single_bit_and_tail_biting(k):
+    T, L = 256, 16
+    nbits = k * T
+    lay = tcq_layer(k, M=1, N=T)
+    lut = lay.lut.view(np.uint16)
+    for p in [0, 5, 15, 16, 17, nbits // 2 + 1, nbits - 1]:
+        lay.codes[:] = 0
+        lay.codes[0, p >> 3] = 1 << (p & 7)
+        got = oracle.decode(lay)[0]
+        want = np.full(T, lut[0], dtype=np.uint16)
+        hits = 0
+        for i in range(T):
+            d = (p - i * k) % nbits          # position of the set bit inside window i
+            if d < L:
+                want[i] = lut[1 << d]
+                hits += 1
+        assert np.array_equal(got, want), (k, p)
+        assert hits in (L // k, -(-L // k))     # every bit is read by L/k windows (rounded either way)
+        if p < L - 1:
+            # the bit is also seen by windows at the END of the tile: that is the wrap
+            assert any(want[i] != lut[0] for i in range(T - L // k, T))
+
+
+@pytest.mark.parametrize("k", [2, 4])
+def test_tcq_with_window_equal_shift_is_scalar_decode(k):
+    """L = k: windows do not overlap, the trellis is a plain 2^k scalar quantizer."""
+    M, N = 4, 512
+    lut = synth.rng(93, k, 1).standard_normal(1 << k).astype(np.float16)
+    lay = synth.make_layer(93, k, synth.TCQ, M, N, k, window_bits=k, lut=lut)
+    sq = synth.make_layer(93, k, synth.SQ, M, N, k, lut=lut)
+    assert np.array_equal(sq.codes, lay.codes)
+    assert np.array_equal(oracle.decode(lay), oracle.decode(sq))
+
+
+@pytest.mark.parametrize("k,L,V", [(2, 16, 1), (3, 16, 1), (4, 16, 1), (2, 6, 1), (3, 16, 2), (5, 16, 2)])
+def test_tcq_window_form_equals_shift_register(k, L, V):
+    T, N = 256, 768
+    lut = synth.rng(94, k, 1).standard_normal((1 << L) * V).astype(np.float16)
+    lay = synth.make_layer(94, k * 100 + L, synth.TCQ, 2, N, k, vec=V, window_bits=L, lut=lut)
+    a = np.empty(N, dtype=np.uint16)
+    b = np.empty(N, dtype=np.uint16)
+    for j in range(2):
+        oracle.lib().qpo_decode_row_tcq(lay.codes[j], N, k, L, T, V, lay.lut.view(np.uint16), a)
+        oracle.lib().qpo_decode_row_tcq_recurrence(lay.codes[j], N, k, L, T, V, lay.lut.view(np.uint16), b)
+        assert np.array_equal(a, b)
+    # bitwidth invariant: a tile of T weights occupies s*T/V bits  (bits per weight = s/V)
+    assert lay.row_bytes * 8 == N // V * k
+
+
+def test_tcq_tiles_are_independent():
+    """Changing one tile's bytes changes only that tile's 256 weights."""
+    lay = tcq_layer(3, M=1, N=1024)
+    base = oracle.decode(lay).copy()
+    tb = 3 * 256 // 8
+    lay.codes[0, tb:2 * tb] ^= 0x5A
+    diff = np.nonzero(oracle.decode(lay)[0] != base[0])[0]
+    assert diff.min() >= 256 and diff.max() < 512
+
+
+# ----------------------------------------- decode checked as a quantizer
+def test_tcq_viterbi_equals_exhaustive_on_tiny_trellis():
+    """L=6, k=2, T=8: 2^16 streams.  Exhaustive argmin through the decode definition
+    must equal the exact tail-biting Viterbi optimum."""
+    L, k, T = 6, 2, 8
+    g = np.random.default_rng(7)
+    lut = g.standard_normal(1 << L).astype(np.float16)
+    for trial in range(4):
+        v = g.standard_normal(T)
+        sb, eb = oracle.tcq_encode(v, k, L, T, 1, lut, method="brute")
+        sv, ev = oracle.tcq_encode(v, k, L, T, 1, lut, method="exact")
+        assert abs(eb - ev) < 1e-12
+        # both streams decode (through the oracle's decode) to that error
+        for s in (sb, sv):
+            lay = synth.make_layer(95, 0, synth.TCQ, 1, T, k, window_bits=L, tile=T, lut=lut)
+            lay.codes = s.reshape(1, -1).copy()
+            w = oracle.half_to_double(oracle.decode(lay))[0]
+            assert abs(((w - v) ** 2).sum() - eb) < 1e-12
+        # the two-pass heuristic is valid (never better than the optimum)
+        _, eh = oracle.tcq_encode(v, k, L, T, 1, lut, method="viterbi")
+        assert eh >= eb - 1e-12
+
+
+def test_tcq_v2_viterbi_equals_exhaustive():
+    L, s, T, V = 6, 3, 8, 2      # 1.5 bits per weight, 12-bit streams
+    g = np.random.default_rng(8)
+    lut = g.standard_normal((1 << L) * V).astype(np.float16)
+    for trial in range(4):
+        v = g.standard_normal(T)
+        _, eb = oracle.tcq_encode(v, s, L, T, V, lut, method="brute")
+        _, ev = oracle.tcq_encode(v, s, L, T, V, lut, method="exact")
+        assert abs(eb - ev) < 1e-12
+
+
+def test_tcq2_distortion_between_rate_bound_and_scalar():
+    """k=2, L=16, T=256 on N(0,1): the distortion reached through the decode
+    definition must lie between the rate-distortion bound 2^(-2R) and the 2-bit
+    scalar quantizer's distortion the paper prints."""
+    gold = golden_distortion()
+    nuq2 = gold["NUQ-2"][1]
+    k, L, T = 2, 16, 256
+    lut = synth.tcq_lut(2, 0)
+    ntiles = 24
+    v = np.random.default_rng(11).standard_normal((ntiles, T))
+    streams, errs = oracle.tcq_encode_tiles(v, k, L, T, 1, lut)
+    lay = synth.make_layer(96, 0, synth.TCQ, ntiles, T, k, lut=lut)
+    lay.codes = streams
+    w = oracle.half_to_double(oracle.decode(lay))
+    mse = ((w - v) ** 2).mean() / (v ** 2).mean()
+    assert abs(((w - v) ** 2).sum(1) - errs).max() < 1e-9
+    assert 2.0 ** (-2 * 2) < mse < nuq2
+    # well inside: a trellis with 2^16 states is far better than scalar
+    assert mse < 0.085, mse
+
+
+def test_lloyd_max_reproduces_paper_nuq2_distortion():
+    gold = golden_distortion()
+    _, mean, std = gold["NUQ-2"]
+    c = synth.lloyd_max_gaussian(4)
+    # closed form: D = 1 - sum_i P_i c_i^2 at the fixed point
+    t = np.concatenate(([-np.inf], 0.5 * (c[:-1] + c[1:]), [np.inf]))
+    P = np.array([0.5 * (math.erf(t[i + 1] / math.sqrt(2)) - math.erf(t[i] / math.sqrt(2))) for i in range(4)])
+    D = 1.0 - float((P * c * c).sum())
+    assert abs(D - mean) < 5 * std + 5e-6, D
+    assert D > 2.0 ** (-4)
+    # and through the oracle: RTN encode + decode of Gaussian samples
+    lut16 = c.astype(np.float16)
+    n = 1 << 21
+    v = np.random.default_rng(12).standard_normal(n)
+    stream = oracle.rtn_sq(v, 2, lut16)
+    lay = synth.make_layer(97, 0, synth.SQ, 1, n, 2, lut=lut16)
+    lay.codes = stream.reshape(1, -1)
+    w = oracle.half_to_double(oracle.decode(lay))[0]
+    mse = ((w - v) ** 2).mean() / (v ** 2).mean()
+    assert abs(mse - mean) < 6e-4, mse
+
+
+def test_lloyd_max_16_levels():
+    c = synth.lloyd_max_gaussian(16)
+    assert np.all(np.diff(c) > 0) and np.allclose(c, -c[::-1], atol=1e-10)
+    t = np.concatenate(([-np.inf], 0.5 * (c[:-1] + c[1:]), [np.inf]))
+    P = np.array([0.5 * (math.erf(t[i + 1] / math.sqrt(2)) - math.erf(t[i] / math.sqrt(2))) for i in range(16)])
+    D = 1.0 - float((P * c * c).sum())
+    assert 2.0 ** (-8) < D < 0.0100 and abs(D - 0.009497) < 2e-5, D
+
+
+def test_vq_product_codebook_reproduces_scalar_distortion():
+    """A 2-D codebook that is the product of two 4-level scalar codebooks is the
+    2-bit scalar quantizer in disguise: RTN + decode through the VQ routines must
+    give the paper's NUQ-2 distortion, and must pair components (even, odd)."""
+    gold = golden_distortion()
+    c = synth.lloyd_max_gaussian(4)
+    # entry index = a + 4 b  ->  (c[a], c[b])
+    lut = np.array([[c[i % 4], c[i // 4]] for i in range(16)]).astype(np.float16)
+    n = 1 << 20
+    v = np.random.default_rng(13).standard_normal(n)
+    v[1::2] *= 1.0           # same law for both components
+    stream = oracle.rtn_vq(v, 4, 2, lut)
+    lay = synth.make_layer(98, 0, synth.VQ, 1, n, 4, lut=lut.reshape(-1))
+    lay.codes = stream.reshape(1, -1)
+    w = oracle.half_to_double(oracle.decode(lay))[0]
+    mse = ((w - v) ** 2).mean()
+    assert abs(mse - gold["NUQ-2"][1]) < 8e-4, mse
+    # the same bytes are two independent 2-bit scalar codes per 4-bit index
+    sq = synth.make_layer(98, 0, synth.SQ, 1, n, 2, lut=c.astype(np.float16))
+    sq.codes = stream.reshape(1, -1)
+    assert np.array_equal(oracle.decode(sq), oracle.decode(lay))
+
+
+# -------------------------------------------------------------- Hadamard
+@pytest.mark.parametrize("n", [2, 4, 8, 64, 1024])
+def test_hadamard_orthogonality_exact(n):
+    L = oracle.lib()
+    m = min(n, 64)   # full matrix up to 64; a 64-row slab for 1024 (rows chosen to span all bits)
+    rows = np.arange(n) if n <= 64 else np.r_[0:32, n - 32:n]
+    H = np.array([[L.qpo_hadamard_entry(int(a), b) for b in range(n)] for a in rows], dtype=np.int64)
+    G = H @ H.T
+    assert np.array_equal(G, n * np.eye(len(rows), dtype=np.int64))
+    if n <= 64:
+        assert np.array_equal(H, H.T)
+    if n == 2:
+        assert H.tolist() == [[1, 1], [1, -1]]
+    if n == 4:
+        assert H.tolist() == [[1, 1, 1, 1], [1, -1, 1, -1], [1, 1, -1, -1], [1, -1, -1, 1]]
+
+
+def test_hadamard_full_1024_orthogonality():
+    idx = np.arange(1024, dtype=np.uint32)
+    pop = np.zeros((1024, 1024), dtype=np.int64)
+    a = idx[:, None] & idx[None, :]
+    for b in range(10):
+        pop += (a >> b) & 1
+    Hn = 1 - 2 * (pop & 1)
+    L = oracle.lib()
+    # the oracle's entry function agrees with the popcount formula on a random sample
+    g = np.random.default_rng(3)
+    for a_, b_ in g.integers(0, 1024, size=(500, 2)):
+        assert L.qpo_hadamard_entry(int(a_), int(b_)) == Hn[a_, b_]
+    assert np.array_equal(Hn @ Hn.T, 1024 * np.eye(1024, dtype=np.int64))
+
+
+@pytest.mark.parametrize("n,block", [(8, 8), (256, 256), (1024, 1024), (3072, 1024), (512, 128)])
+def test_hadamard_dense_properties(n, block):
+    g = np.random.default_rng(n + block)
+    B = 2
+    x = g.standard_normal((B, n)).astype(np.float16)
+    sg = synth.make_signs(50, n, n)
+    ones = np.ones(n, dtype=np.int8)
+    xd = oracle.half_to_double(x)
+    dense = oracle.hadamard(x, sg, block)
+    fast = oracle.hadamard(x, sg, block, fast=True)
+    assert np.max(np.abs(dense - fast)) < 1e-12
+    # Parseval
+    assert np.allclose((dense ** 2).sum(1), (xd ** 2).sum(1), rtol=1e-12)
+    # unit vector -> a column of H (with its sign), scaled
+    e = np.zeros((1, n), dtype=np.float16)
+    i = int(g.integers(0, n))
+    e[0, i] = 1.0
+    col = oracle.hadamard(e, sg, block)[0]
+    q = i // block
+    want = np.zeros(n)
+    want[q * block:(q + 1) * block] = [sg[i] * oracle.lib().qpo_hadamard_entry(a, i % block) / math.sqrt(block)
+                                       for a in range(block)]
+    assert np.max(np.abs(col - want)) < 1e-15
+    # block-diagonal: support stays inside block q
+    assert np.all(col[: q * block] == 0) and np.all(col[(q + 1) * block:] == 0)
+    # involution with sigma = 1 (values chosen exactly representable so fp16 round trip is exact)
+    xi = g.integers(-8, 9, size=(1, n)).astype(np.float16)
+    once = oracle.hadamard(xi, ones, block) * math.sqrt(block)      # integers up to rounding
+    assert np.max(np.abs(once - np.round(once))) < 1e-9
+    once = np.round(once)
+    if np.max(np.abs(once)) < 2048:
+        twice = oracle.hadamard(once.astype(np.float16), ones, block) / math.sqrt(block)
+        assert np.max(np.abs(twice - oracle.half_to_double(xi))) < 1e-12
+
+
+def test_hadamard_hand_examples():
+    x = np.array([[1.0, 2.0]], dtype=np.float16)
+    s = np.array([1, -1], dtype=np.int8)
+    r = oracle.hadamard(x, s, 2)[0]
+    assert np.allclose(r, [(1 - 2) / math.sqrt(2), (1 + 2) / math.sqrt(2)], rtol=0, atol=1e-15)
+    x = np.array([[1.0, 2.0, 3.0, 4.0]], dtype=np.float16)
+    s = np.array([1, 1, -1, 1], dtype=np.int8)
+    r = oracle.hadamard(x, s, 4)[0]
+    u = np.array([1.0, 2.0, -3.0, 4.0])
+    want = np.array([u.sum(), u[0] - u[1] + u[2] - u[3], u[0] + u[1] - u[2] - u[3], u[0] - u[1] - u[2] + u[3]]) / 2
+    assert np.allclose(r, want, rtol=0, atol=1e-15)
+
+
+def test_rotation_leaves_products_unchanged():
+    """(x R^T)(R w) = x w for the rotation the oracle applies (Section 3.3)."""
+    g = np.random.default_rng(5)
+    n, block = 2048, 1024
+    x = g.standard_normal((3, n)).astype(np.float16)
+    w = g.standard_normal((4, n)).astype(np.float16)
+    sg = synth.make_signs(51, 0, n)
+    xr, wr = oracle.hadamard(x, sg, block), oracle.hadamard(w, sg, block)
+    assert np.allclose(xr @ wr.T, oracle.half_to_double(x) @ oracle.half_to_double(w).T, rtol=0, atol=1e-10)
+
+
+# ---------------------------------------------------------------- matmul
+@pytest.mark.parametrize("scheme,cb", [(synth.SQ, 4), (synth.VQ, 5), (synth.VQ, 7), (synth.TCQ, 2),
+                                       (synth.TCQ, 3), (synth.TCQ, 4)])
+def test_linear_equals_numpy_float64(scheme, cb):
+    M, N, B = 24, 1024, 3
+    lay = synth.make_layer(60, cb + 10 * scheme, scheme, M, N, cb)
+    x = synth.make_x(60, 0, B, N)
+    W = oracle.decode(lay)
+    Wd = W.view(np.float16).astype(np.float64)
+    want = (x.astype(np.float64) @ Wd.T) * lay.scales.astype(np.float64)[None, :]
+    got = oracle.linear(lay, x)
+    got_thr = oracle.linear(lay, x, threads=True)
+    got_mm = oracle.matmul_scaled(x.astype(np.float64), W, lay.scales)
+    scale = np.abs(want).max()
+    assert np.max(np.abs(got - want)) < 1e-12 * scale
+    assert np.array_equal(got, got_thr)
+    assert np.array_equal(got, got_mm)
+    # one-hot x picks out single decoded weights times the scale
+    e = np.zeros((1, N), dtype=np.float16)
+    e[0, 257] = 1.0
+    y = oracle.linear(lay, e)[0]
+    assert np.array_equal(y, Wd[:, 257] * lay.scales.astype(np.float64))
+    # rows= computes only that range
+    part = oracle.linear(lay, x, rows=(5, 9))
+    assert np.array_equal(part[:, 5:9], got[:, 5:9]) and np.all(part[:, :5] == 0) and np.all(part[:, 9:] == 0)
