@@ -1,0 +1,137 @@
+/*
+ * qp.h — C ABI of the MI355X (gfx950) quantized-linear library.
+ *
+ * The library computes the inference hot path of Q-Palette: a linear layer whose
+ * weight matrix W^ is never stored but decoded on the fly from packed
+ * fractional-bit codes, applied to activations that were rotated by a randomized
+ * Hadamard transform:
+ *
+ *        y[b, j] = s[j] * sum_i xr[b, i] * W^[j, i]          (Section 3.3)
+ *
+ * with W^ given by one of three quantizer families (Section 3.2, Appendix C):
+ *   QP_SQ   non-uniform scalar quantizer:  W^[j,i]           = LUT[code]          (App. C.1 "Dequantization")
+ *   QP_VQ   2-D vector quantizer:          (W^[j,2m],W^[j,2m+1]) = LUT[code]      (App. C.2 "Dequantization")
+ *   QP_TCQ  bitshift trellis, tail-biting: W^[j,tT+i]        = LUT[r_t[ik : ik+L]] (App. C.3.1 "Dequantization")
+ *
+ * Notation: M = out_features = rows of W^, N = in_features = columns, B = batch.
+ *
+ * CANONICAL LAYOUT (QP_LAYOUT_CANONICAL).  Row j of W^ is one bitstream of
+ * N/vec codes of code_bits bits, starting at codes + j*row_stride.  Stream bit p
+ * is bit (p mod 8) of byte floor(p/8); a code that starts at stream bit q has the
+ * value sum_t bit(q+t) 2^t.  For QP_TCQ a row is N/tile consecutive tiles of
+ * code_bits*tile bits; inside a tile weight i is LUT[window], the window being
+ * the window_bits stream bits from i*code_bits on, taken modulo the tile's length.
+ *
+ * NATIVE LAYOUT (QP_LAYOUT_NATIVE), produced by qp_repack; needs M % 16 == 0 and
+ * N % 1024 == 0.  The matrix is cut into blocks of 16 rows x 1024 columns, stored
+ * block-row-major (all column blocks of rows 0..15, then rows 16..31, ...).  Within
+ * a block, "lane" l = 16*g + i (g = 0..3, i = 0..15) owns row i, columns
+ * 256*g .. 256*g+255 of the block: the same 32*bpw bytes that the canonical stream
+ * holds for that span (bpw = code_bits/vec).  Those bytes are cut into P = 2*bpw
+ * pieces of 16 bytes; piece p of lane l sits at byte (p*64 + l)*16 of the block, so
+ * one 128-bit load per lane of a 64-wide wavefront reads 1 KiB contiguously.
+ * row_stride is ignored for this layout.
+ *
+ * All pointers named "device" are device (HBM) pointers owned by the caller; the
+ * library allocates no device memory and keeps no mutable state.  Every entry
+ * point validates its arguments on the host first and returns a QP_ERR_* code
+ * without touching the device when they are bad; it then only enqueues kernels on
+ * the given hipStream_t (passed as void*; NULL is the default stream) and returns
+ * without synchronising.  A failed launch returns QP_ERR_DEVICE.  Nothing throws.
+ */
+#ifndef QP_H
+#define QP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    QP_OK = 0,
+    QP_ERR_NULL = 1,        /* a required pointer is NULL                                  */
+    QP_ERR_SHAPE = 2,       /* M, N, B, n, block, ld* out of range or not divisible        */
+    QP_ERR_UNSUPPORTED = 3, /* (scheme, code_bits, vec, window_bits, tile) not in the set  */
+    QP_ERR_ALIGN = 4,       /* pointer or stride not aligned as documented                 */
+    QP_ERR_LAYOUT = 5,      /* layout value unknown, or shape not representable in it      */
+    QP_ERR_DEVICE = 6,      /* HIP reported a launch error                                 */
+    QP_ERR_WORKSPACE = 7    /* workspace smaller than qp_linear_workspace_bytes()          */
+} qp_status;
+
+typedef enum { QP_SQ = 0, QP_VQ = 1, QP_TCQ = 2 } qp_scheme;
+typedef enum { QP_LAYOUT_CANONICAL = 0, QP_LAYOUT_NATIVE = 1 } qp_layout;
+
+#define QP_MAX_BATCH 16
+
+/* One quantized layer.  Supported set:
+ *   QP_SQ : vec 1, code_bits 4                       (16-entry fp16 LUT)
+ *   QP_VQ : vec 2, code_bits 5 or 7                  (2.5 / 3.5 bits per weight; LUT fp16 [2^code_bits][2])
+ *   QP_TCQ: vec 1, window_bits 16, tile 256, code_bits 2, 3 or 4  (LUT fp16 [65536])
+ * Fused layers (QKV, gate+up; Section 4.2) are one qp_weight with M the sum of the
+ * members' out_features. */
+typedef struct {
+    int32_t scheme;      /* qp_scheme                                                          */
+    int32_t M, N;        /* rows (output channels), columns (input channels)                   */
+    int32_t code_bits;   /* SQ: bits per weight; VQ: bits per vec-vector; TCQ: bits shifted per step */
+    int32_t vec;         /* V                                                                  */
+    int32_t window_bits; /* TCQ: L; otherwise 0                                                */
+    int32_t tile;        /* TCQ: T, weights per tail-biting tile; otherwise 0                  */
+    int32_t layout;      /* qp_layout                                                          */
+    int64_t row_stride;  /* canonical: bytes between rows of codes, multiple of 16, >= row bytes */
+    const void *codes;   /* device, 16-byte aligned                                            */
+    const void *lut;     /* device, fp16, 4-byte aligned: SQ 2^code_bits; VQ 2^code_bits*vec; TCQ 2^L*vec */
+    const void *scales;  /* device, fp16 [M], 2-byte aligned: per-output-channel factor s      */
+} qp_weight;
+
+/* Fused dequantize-and-multiply (Section 3.3 "Kernel implementation"; the fused
+ * kernels of Appendix D).  x: device fp16 [B, ldx] (already rotated; this call does
+ * not rotate), 16-byte aligned with ldx % 8 == 0, ldx >= N.  y: device fp16
+ * [B, ldy], ldy >= M; written for all b < B, j < M, rounded to nearest even from
+ * the fp32 value s[j]*acc.  1 <= B <= QP_MAX_BATCH.  Accumulation is fp32; the
+ * summation order is unspecified.  workspace: device scratch of at least
+ * qp_linear_workspace_bytes(w, B) bytes (may be NULL when that is 0). */
+qp_status qp_linear(const qp_weight *w, const void *x, int32_t B, int64_t ldx, void *y, int64_t ldy,
+                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Dequantize only (the dequantization-only kernels of Appendix D): writes the
+ * unscaled W^ as fp16 [M, N] row-major, ld = N, to W_out (device, 16-byte aligned).
+ * Every element is a bit copy of a LUT entry. */
+qp_status qp_dequant(const qp_weight *w, void *W_out, void *hip_stream);
+
+/* Online rotation of activations, X -> X R (Section 3.3 "Reducing rotation
+ * overhead"): for each row b < B and each contiguous block of `block` entries,
+ *     xr_block = H_block (signs .* x)_block / sqrt(block)
+ * with H the Sylvester Hadamard matrix in natural order.  x: device fp16 [B, ldx];
+ * signs: device int8 in {-1,+1} [n]; xr: device fp16 [B, ldxr], may alias x
+ * exactly (same pointer and ld) but must not overlap it otherwise.  n % block == 0,
+ * block a power of two in 2..16384, 1 <= B, B*(n/block) <= 2^31-1.  fp32 butterflies, one rounding to
+ * fp16 at the end. */
+qp_status qp_hadamard(const void *x, const int8_t *signs, int32_t B, int32_t n, int32_t block,
+                      int64_t ldx, void *xr, int64_t ldxr, void *hip_stream);
+
+/* One-time conversion canonical -> native.  `canonical` describes device codes in
+ * canonical layout; native_codes is a device buffer of `bytes` >=
+ * qp_native_bytes(canonical) bytes, 16-byte aligned, not overlapping the source.
+ * On success *native_out is a copy of the descriptor with layout, codes and
+ * row_stride (0) updated; lut and scales are shared with the source. */
+qp_status qp_repack(const qp_weight *canonical, qp_weight *native_out, void *native_codes, size_t bytes,
+                    void *hip_stream);
+
+/* Bytes of the native code buffer for this layer, 0 if it has no native form. */
+size_t qp_native_bytes(const qp_weight *canonical);
+
+/* Scratch bytes qp_linear needs for (w, B); 0 when no cross-workgroup reduction is used. */
+size_t qp_linear_workspace_bytes(const qp_weight *w, int32_t B);
+
+/* Check a descriptor alone (what qp_linear / qp_dequant check first). */
+qp_status qp_validate(const qp_weight *w);
+
+const char *qp_status_string(qp_status s);
+int32_t qp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QP_H */

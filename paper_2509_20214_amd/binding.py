@@ -1,0 +1,183 @@
+"""ctypes binding of libqp.so.  Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libqp.so")
+
+QP_SQ, QP_VQ, QP_TCQ = 0, 1, 2
+QP_LAYOUT_CANONICAL, QP_LAYOUT_NATIVE = 0, 1
+QP_OK = 0
+
+EXPORTS = ["qp_linear", "qp_dequant", "qp_hadamard", "qp_repack", "qp_native_bytes",
+           "qp_linear_workspace_bytes", "qp_validate", "qp_status_string", "qp_version"]
+
+
+class qp_weight(C.Structure):
+    _fields_ = [("scheme", C.c_int32), ("M", C.c_int32), ("N", C.c_int32), ("code_bits", C.c_int32),
+                ("vec", C.c_int32), ("window_bits", C.c_int32), ("tile", C.c_int32), ("layout", C.c_int32),
+                ("row_stride", C.c_int64), ("codes", C.c_void_p), ("lut", C.c_void_p), ("scales", C.c_void_p)]
+
+
+class QpError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: qp_status {code} ({qp_status_string(code)})")
+        self.code = code
+
+
+_lib = None
+
+
+def load_library(build_if_missing: bool = True):
+    """Load libqp.so (building it with hipcc first if it is not there).  Raises if
+    neither works: there is no fallback implementation."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        if not build_if_missing:
+            raise FileNotFoundError(LIB_PATH)
+        from . import build as _b
+        _b.build()
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    wp = C.POINTER(qp_weight)
+    L.qp_linear.restype = C.c_int
+    L.qp_linear.argtypes = [wp, vp, i32, i64, vp, i64, vp, sz, vp]
+    L.qp_dequant.restype = C.c_int
+    L.qp_dequant.argtypes = [wp, vp, vp]
+    L.qp_hadamard.restype = C.c_int
+    L.qp_hadamard.argtypes = [vp, vp, i32, i32, i32, i64, vp, i64, vp]
+    L.qp_repack.restype = C.c_int
+    L.qp_repack.argtypes = [wp, wp, vp, sz, vp]
+    L.qp_native_bytes.restype = sz
+    L.qp_native_bytes.argtypes = [wp]
+    L.qp_linear_workspace_bytes.restype = sz
+    L.qp_linear_workspace_bytes.argtypes = [wp, i32]
+    L.qp_validate.restype = C.c_int
+    L.qp_validate.argtypes = [wp]
+    L.qp_status_string.restype = C.c_char_p
+    L.qp_status_string.argtypes = [C.c_int]
+    L.qp_version.restype = i32
+    L.qp_version.argtypes = []
+    _lib = L
+    return L
+
+
+def qp_status_string(code: int) -> str:
+    return load_library().qp_status_string(int(code)).decode()
+
+
+def qp_version() -> int:
+    return int(load_library().qp_version())
+
+
+def _stream_ptr(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _check(code: int, what: str):
+    if code != QP_OK:
+        raise QpError(code, what)
+
+
+class Weight:
+    """A quantized layer resident on the device: torch tensors (owned here) plus the
+    C descriptor that points at them."""
+
+    def __init__(self, scheme, M, N, code_bits, vec, window_bits, tile, codes, lut, scales,
+                 layout=QP_LAYOUT_CANONICAL, row_stride=None):
+        self.codes, self.lut, self.scales = codes, lut, scales
+        if row_stride is None:
+            row_stride = codes.shape[1] if (layout == QP_LAYOUT_CANONICAL and codes.dim() == 2) else 0
+        self.desc = qp_weight(scheme, M, N, code_bits, vec, window_bits, tile, layout, row_stride,
+                              codes.data_ptr(), lut.data_ptr(), scales.data_ptr())
+
+    @classmethod
+    def from_layer(cls, layer, device="cuda"):
+        """Upload a synth.Layer-like object (numpy arrays, canonical layout)."""
+        import numpy as np
+        import torch
+        codes = torch.from_numpy(np.ascontiguousarray(layer.codes)).to(device)
+        lut = torch.from_numpy(np.ascontiguousarray(layer.lut).view(np.int16)).to(device)
+        scales = torch.from_numpy(np.ascontiguousarray(layer.scales).view(np.int16)).to(device)
+        return cls(layer.scheme, layer.M, layer.N, layer.code_bits, layer.vec, layer.window_bits,
+                   layer.tile, codes, lut, scales)
+
+    @property
+    def M(self):
+        return self.desc.M
+
+    @property
+    def N(self):
+        return self.desc.N
+
+    @property
+    def code_bytes(self) -> int:
+        d = self.desc
+        return d.M * (d.N // d.vec * d.code_bits // 8)
+
+
+def qp_validate(w: Weight) -> int:
+    return int(load_library().qp_validate(C.byref(w.desc)))
+
+
+def qp_native_bytes(w: Weight) -> int:
+    return int(load_library().qp_native_bytes(C.byref(w.desc)))
+
+
+def qp_linear_workspace_bytes(w: Weight, B: int) -> int:
+    return int(load_library().qp_linear_workspace_bytes(C.byref(w.desc), B))
+
+
+def qp_repack(w: Weight, stream=None) -> Weight:
+    """Canonical -> native copy of the codes (LUT and scales are shared)."""
+    import torch
+    nbytes = qp_native_bytes(w)
+    if nbytes == 0:
+        raise QpError(5, "qp_repack")
+    out = torch.empty(nbytes, dtype=torch.uint8, device=w.codes.device)
+    d = w.desc
+    nw = Weight(d.scheme, d.M, d.N, d.code_bits, d.vec, d.window_bits, d.tile, out, w.lut, w.scales,
+                layout=QP_LAYOUT_NATIVE, row_stride=0)
+    tmp = qp_weight()
+    _check(load_library().qp_repack(C.byref(w.desc), C.byref(tmp), out.data_ptr(), nbytes,
+                                    _stream_ptr(stream)), "qp_repack")
+    nw.desc = tmp
+    return nw
+
+
+def qp_linear(w: Weight, x, y=None, workspace=None, stream=None):
+    """y[b, j] = s[j] * sum_i x[b, i] W^[j, i].  x: fp16 [B, N] (row stride = x.stride(0))."""
+    import torch
+    B = x.shape[0]
+    if y is None:
+        y = torch.empty((B, w.M), dtype=torch.float16, device=x.device)
+    ws_ptr, ws_bytes = (None, 0) if workspace is None else (workspace.data_ptr(), workspace.numel() * workspace.element_size())
+    _check(load_library().qp_linear(C.byref(w.desc), x.data_ptr(), B, x.stride(0), y.data_ptr(), y.stride(0),
+                                    ws_ptr, ws_bytes, _stream_ptr(stream)), "qp_linear")
+    return y
+
+
+def qp_dequant(w: Weight, out=None, stream=None):
+    import torch
+    if out is None:
+        out = torch.empty((w.M, w.N), dtype=torch.float16, device=w.codes.device)
+    _check(load_library().qp_dequant(C.byref(w.desc), out.data_ptr(), _stream_ptr(stream)), "qp_dequant")
+    return out
+
+
+def qp_hadamard(x, signs, block: int, out=None, stream=None):
+    """xr = H_block (signs .* x) / sqrt(block) per contiguous block of each row."""
+    import torch
+    B, n = x.shape
+    if out is None:
+        out = torch.empty_like(x)
+    _check(load_library().qp_hadamard(x.data_ptr(), signs.data_ptr(), B, n, block, x.stride(0),
+                                      out.data_ptr(), out.stride(0), _stream_ptr(stream)), "qp_hadamard")
+    return out

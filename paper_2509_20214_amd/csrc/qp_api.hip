@@ -1,0 +1,154 @@
+// C ABI: host-side validation and dispatch.  No device memory is allocated here and
+// no call synchronises with the device.
+#include <cstring>
+
+#include "qp_internal.h"
+
+#define QP_VERSION 100
+
+static inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+static qp_status scheme_supported(const qp_weight *w) {
+    switch (w->scheme) {
+        case QP_SQ:
+            return (w->vec == 1 && w->code_bits == 4) ? QP_OK : QP_ERR_UNSUPPORTED;
+        case QP_VQ:
+            return (w->vec == 2 && (w->code_bits == 5 || w->code_bits == 7)) ? QP_OK : QP_ERR_UNSUPPORTED;
+        case QP_TCQ:
+            return (w->vec == 1 && w->window_bits == 16 && w->tile == 256 && w->code_bits >= 2 &&
+                    w->code_bits <= 4)
+                       ? QP_OK
+                       : QP_ERR_UNSUPPORTED;
+        default:
+            return QP_ERR_UNSUPPORTED;
+    }
+}
+
+static inline int64_t row_bytes(const qp_weight *w) { return (int64_t)w->N / w->vec * w->code_bits / 8; }
+static inline int span_bytes(const qp_weight *w) { return 32 * w->code_bits / w->vec; }
+
+extern "C" qp_status qp_validate(const qp_weight *w) {
+    if (!w) return QP_ERR_NULL;
+    qp_status s = scheme_supported(w);
+    if (s != QP_OK) return s;
+    if (w->M <= 0 || w->N <= 0) return QP_ERR_SHAPE;
+    if (w->N % 8 != 0) return QP_ERR_SHAPE;
+    if (w->scheme == QP_TCQ && w->N % w->tile != 0) return QP_ERR_SHAPE;
+    if (!w->codes || !w->lut || !w->scales) return QP_ERR_NULL;
+    if (w->layout == QP_LAYOUT_CANONICAL) {
+        if (w->row_stride % 16 != 0) return QP_ERR_ALIGN;
+        if (w->row_stride < row_bytes(w)) return QP_ERR_SHAPE;
+        if ((int64_t)w->row_stride * w->M > ((int64_t)1 << 40)) return QP_ERR_SHAPE;
+    } else if (w->layout == QP_LAYOUT_NATIVE) {
+        if (w->M % 16 != 0 || w->N % 1024 != 0) return QP_ERR_LAYOUT;
+    } else {
+        return QP_ERR_LAYOUT;
+    }
+    if (!aligned(w->codes, 16) || !aligned(w->lut, 4) || !aligned(w->scales, 2)) return QP_ERR_ALIGN;
+    return QP_OK;
+}
+
+static QpW make_dev(const qp_weight *w) {
+    QpW d;
+    d.codes = static_cast<const uint8_t *>(w->codes);
+    d.lut = static_cast<const uint16_t *>(w->lut);
+    d.scales = static_cast<const uint16_t *>(w->scales);
+    d.M = w->M;
+    d.N = w->N;
+    d.row_stride = w->row_stride;
+    d.layout = w->layout;
+    d.nbc = w->N / 1024;
+    return d;
+}
+
+extern "C" size_t qp_linear_workspace_bytes(const qp_weight *w, int32_t B) {
+    (void)w;
+    (void)B;
+    return 0;
+}
+
+extern "C" qp_status qp_linear(const qp_weight *w, const void *x, int32_t B, int64_t ldx, void *y, int64_t ldy,
+                               void *workspace, size_t workspace_bytes, void *hip_stream) {
+    qp_status s = qp_validate(w);
+    if (s != QP_OK) return s;
+    if (!x || !y) return QP_ERR_NULL;
+    if (B < 1 || B > QP_MAX_BATCH) return QP_ERR_SHAPE;
+    if (ldx < w->N || ldy < w->M || ldx % 8 != 0) return QP_ERR_SHAPE;
+    if (!aligned(x, 16) || !aligned(y, 2)) return QP_ERR_ALIGN;
+    size_t need = qp_linear_workspace_bytes(w, B);
+    if (need && (!workspace || workspace_bytes < need)) return QP_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    QpW d = make_dev(w);
+    return qp_launch_linear_rowwave(d, w->scheme, w->code_bits, x, B, ldx, y, ldy, st);
+}
+
+extern "C" qp_status qp_dequant(const qp_weight *w, void *W_out, void *hip_stream) {
+    qp_status s = qp_validate(w);
+    if (s != QP_OK) return s;
+    if (!W_out) return QP_ERR_NULL;
+    if (!aligned(W_out, 16)) return QP_ERR_ALIGN;
+    return qp_launch_dequant(make_dev(w), w->scheme, w->code_bits, W_out, static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" qp_status qp_hadamard(const void *x, const int8_t *signs, int32_t B, int32_t n, int32_t block,
+                                 int64_t ldx, void *xr, int64_t ldxr, void *hip_stream) {
+    if (!x || !signs || !xr) return QP_ERR_NULL;
+    if (B < 1 || n < 1) return QP_ERR_SHAPE;
+    if (block < 2 || block > 16384 || (block & (block - 1)) != 0 || n % block != 0) return QP_ERR_SHAPE;
+    if (ldx < n || ldxr < n) return QP_ERR_SHAPE;
+    if ((int64_t)B * (n / block) > 0x7fffffffLL) return QP_ERR_SHAPE;
+    if (!aligned(x, 2) || !aligned(xr, 2)) return QP_ERR_ALIGN;
+    if (x != xr || ldx != ldxr) {
+        // partial overlap is not allowed
+        const char *a = static_cast<const char *>(x), *b = static_cast<const char *>(xr);
+        int64_t ea = ((int64_t)(B - 1) * ldx + n) * 2, eb = ((int64_t)(B - 1) * ldxr + n) * 2;
+        if (a < b + eb && b < a + ea) return QP_ERR_ALIGN;
+    }
+    return qp_launch_hadamard(x, signs, B, n, block, ldx, xr, ldxr, static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" size_t qp_native_bytes(const qp_weight *c) {
+    if (!c || scheme_supported(c) != QP_OK) return 0;
+    if (c->M <= 0 || c->N <= 0 || c->M % 16 != 0 || c->N % 1024 != 0) return 0;
+    return (size_t)c->M * (size_t)row_bytes(c);
+}
+
+extern "C" qp_status qp_repack(const qp_weight *c, qp_weight *native_out, void *native_codes, size_t bytes,
+                               void *hip_stream) {
+    if (!c || !native_out || !native_codes) return QP_ERR_NULL;
+    qp_status s = qp_validate(c);
+    if (s != QP_OK) return s;
+    if (c->layout != QP_LAYOUT_CANONICAL) return QP_ERR_LAYOUT;
+    size_t need = qp_native_bytes(c);
+    if (need == 0) return QP_ERR_LAYOUT;
+    if (bytes < need) return QP_ERR_SHAPE;
+    if (!aligned(native_codes, 16)) return QP_ERR_ALIGN;
+    {
+        const char *a = static_cast<const char *>(c->codes), *b = static_cast<const char *>(native_codes);
+        int64_t ea = (int64_t)c->row_stride * c->M;
+        if (a < b + (int64_t)need && b < a + ea) return QP_ERR_ALIGN;
+    }
+    s = qp_launch_repack(make_dev(c), span_bytes(c), native_codes, static_cast<hipStream_t>(hip_stream));
+    if (s != QP_OK) return s;
+    *native_out = *c;
+    native_out->layout = QP_LAYOUT_NATIVE;
+    native_out->codes = native_codes;
+    native_out->row_stride = 0;
+    return QP_OK;
+}
+
+extern "C" const char *qp_status_string(qp_status s) {
+    switch (s) {
+        case QP_OK: return "ok";
+        case QP_ERR_NULL: return "null pointer";
+        case QP_ERR_SHAPE: return "bad shape";
+        case QP_ERR_UNSUPPORTED: return "unsupported quantizer";
+        case QP_ERR_ALIGN: return "bad alignment or overlap";
+        case QP_ERR_LAYOUT: return "bad layout";
+        case QP_ERR_DEVICE: return "device launch error";
+        case QP_ERR_WORKSPACE: return "workspace too small";
+        default: return "unknown status";
+    }
+}
+
+extern "C" int32_t qp_version(void) { return QP_VERSION; }

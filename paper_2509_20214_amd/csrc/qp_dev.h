@@ -1,0 +1,125 @@
+// Device-side helpers shared by the gfx950 kernels: layout addressing, per-scheme
+// traits and the register-level decode of 8 consecutive weights.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "qp.h"
+
+typedef _Float16 half_t;
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+// What a kernel needs to know about a layer (passed by value).
+struct QpW {
+    const uint8_t *codes;
+    const uint16_t *lut;
+    const uint16_t *scales;
+    int32_t M, N;
+    int64_t row_stride;  // canonical layout only
+    int32_t layout;      // qp_layout
+    int32_t nbc;         // N / 1024, column blocks per block row (native layout)
+};
+
+// Compile-time facts about a (scheme, code_bits) pair.
+template <int S, int CB>
+struct QpTraits {
+    static constexpr int V = (S == QP_VQ) ? 2 : 1;
+    static constexpr int BITS8 = 8 * CB / V;           // stream bits that 8 weights advance
+    static constexpr int SPAN = 32 * CB / V;           // bytes of a 256-weight span
+    static constexpr int PIECES = SPAN / 16;           // 16-byte pieces per span
+    static constexpr int LUT_HALVES = (S == QP_TCQ) ? 65536 : (1 << CB) * V;
+    static constexpr int BLOCK_BYTES = 64 * SPAN;      // one 16 x 1024 native block
+};
+
+// Address of the aligned dword that holds canonical byte `byte_off` of row `row`.
+template <int SPAN>
+__device__ __forceinline__ const uint32_t *qp_dword_ptr(const QpW &w, int row, int byte_off) {
+    if (w.layout == QP_LAYOUT_CANONICAL)
+        return reinterpret_cast<const uint32_t *>(w.codes + (int64_t)row * w.row_stride + byte_off);
+    int span = byte_off / SPAN;
+    int beta = byte_off - span * SPAN;
+    int C = span >> 2, g = span & 3, i = row & 15, R = row >> 4;
+    int64_t blk = (int64_t)R * w.nbc + C;
+    return reinterpret_cast<const uint32_t *>(w.codes + blk * (64 * SPAN) +
+                                              ((((beta >> 4) * 64 + g * 16 + i) << 4) + (beta & 15)));
+}
+
+// The 64 stream bits that start at the first bit of weight group `grp` (8 weights)
+// of row `row`.  For the trellis the second dword wraps inside the 256-weight tile.
+template <int S, int CB>
+__device__ __forceinline__ uint64_t qp_group_bits(const QpW &w, int row, int grp) {
+    using T = QpTraits<S, CB>;
+    int d0, d1, r;
+    if (S == QP_TCQ) {
+        int tile = grp >> 5, u = grp & 31;
+        int off = u * T::BITS8;
+        r = off & 31;
+        int q0 = off >> 5;
+        int q1 = (q0 + 1 == T::SPAN / 4) ? 0 : q0 + 1;
+        d0 = tile * (T::SPAN / 4) + q0;
+        d1 = tile * (T::SPAN / 4) + q1;
+    } else {
+        int off = grp * T::BITS8;
+        r = off & 31;
+        d0 = off >> 5;
+        d1 = d0 + 1;
+        if (d1 * 4 >= (w.N / 8) * T::BITS8 / 8) d1 = d0;   // last dword of the row: nothing beyond is needed
+    }
+    uint32_t lo = *qp_dword_ptr<T::SPAN>(w, row, d0 * 4);
+    uint32_t hi = *qp_dword_ptr<T::SPAN>(w, row, d1 * 4);
+    return ((((uint64_t)hi) << 32) | lo) >> r;
+}
+
+// Decode the 8 weights whose codes start at bit 0 of `bits`.  `lut` is the LDS copy
+// of the table.  Every output is a bit copy of a table entry.
+template <int S, int CB>
+__device__ __forceinline__ void qp_decode8(uint64_t bits, const uint16_t *lut, uint16_t (&w)[8]) {
+    if (S == QP_SQ) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) w[e] = lut[(uint32_t)(bits >> (CB * e)) & ((1u << CB) - 1u)];
+    } else if (S == QP_VQ) {
+        const uint32_t *lut2 = reinterpret_cast<const uint32_t *>(lut);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            uint32_t p = lut2[(uint32_t)(bits >> (CB * c)) & ((1u << CB) - 1u)];
+            w[2 * c] = (uint16_t)p;
+            w[2 * c + 1] = (uint16_t)(p >> 16);
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) w[e] = lut[(uint32_t)(bits >> (CB * e)) & 0xffffu];
+    }
+}
+
+// Copy the table into LDS with all threads of the workgroup (caller synchronises).
+template <int HALVES>
+__device__ __forceinline__ void qp_stage_lut(const uint16_t *g, uint16_t *s) {
+    if (HALVES >= 8 * 64) {
+        const u32x4_t *g4 = reinterpret_cast<const u32x4_t *>(g);
+        u32x4_t *s4 = reinterpret_cast<u32x4_t *>(s);
+        for (int i = threadIdx.x; i < HALVES / 8; i += blockDim.x) s4[i] = g4[i];
+    } else {
+        const uint32_t *g2 = reinterpret_cast<const uint32_t *>(g);
+        uint32_t *s2 = reinterpret_cast<uint32_t *>(s);
+        for (int i = threadIdx.x; i < HALVES / 2; i += blockDim.x) s2[i] = g2[i];
+    }
+}
+
+__device__ __forceinline__ float qp_half_bits_to_float(uint16_t h) {
+    return (float)__builtin_bit_cast(half_t, h);
+}
+
+// Dispatch a (scheme, code_bits) pair known at run time to a template.
+#define QP_DISPATCH_SCHEME(scheme, cb, CALL)                                          \
+    do {                                                                              \
+        if ((scheme) == QP_SQ && (cb) == 4) { CALL(QP_SQ, 4); }                       \
+        else if ((scheme) == QP_VQ && (cb) == 5) { CALL(QP_VQ, 5); }                  \
+        else if ((scheme) == QP_VQ && (cb) == 7) { CALL(QP_VQ, 7); }                  \
+        else if ((scheme) == QP_TCQ && (cb) == 2) { CALL(QP_TCQ, 2); }                \
+        else if ((scheme) == QP_TCQ && (cb) == 3) { CALL(QP_TCQ, 3); }                \
+        else if ((scheme) == QP_TCQ && (cb) == 4) { CALL(QP_TCQ, 4); }                \
+        else return QP_ERR_UNSUPPORTED;                                               \
+    } while (0)

@@ -1,0 +1,17 @@
+// Host-side launcher prototypes (one per kernel family).  Each returns QP_OK or
+// QP_ERR_DEVICE / QP_ERR_UNSUPPORTED; arguments were validated by the caller.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "qp_dev.h"
+
+qp_status qp_launch_dequant(const QpW &w, int scheme, int cb, void *out, hipStream_t st);
+qp_status qp_launch_linear_rowwave(const QpW &w, int scheme, int cb, const void *x, int B, int64_t ldx,
+                                   void *y, int64_t ldy, hipStream_t st);
+qp_status qp_launch_hadamard(const void *x, const int8_t *signs, int B, int n, int block, int64_t ldx,
+                             void *xr, int64_t ldxr, hipStream_t st);
+qp_status qp_launch_repack(const QpW &src, int span_bytes, void *dst, hipStream_t st);
+
+static inline qp_status qp_check_launch() {
+    return hipGetLastError() == hipSuccess ? QP_OK : QP_ERR_DEVICE;
+}

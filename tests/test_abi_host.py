@@ -1,0 +1,119 @@
+"""Host-side checks of the C-ABI library: it loads, exports every symbol the header
+declares, and turns bad arguments into QP_ERR_* codes without touching a device
+(no compute call is made here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2509_20214_amd as qp
+from paper_2509_20214_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_symbols():
+    src = open(os.path.join(ROOT, "include", "qp.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(qp_[a-z_]+)\s*\(", src)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    L = qp.load_library()
+    syms = header_symbols()
+    assert set(syms) == set(binding.EXPORTS)
+    for s in syms:
+        assert hasattr(L, s), s
+    assert qp.qp_version() >= 100
+    assert qp.qp_status_string(0) == "ok"
+    for code in range(1, 8):
+        assert qp.qp_status_string(code) not in ("ok", "unknown status")
+
+
+def desc(**kw):
+    d = dict(scheme=qp.QP_SQ, M=16, N=1024, code_bits=4, vec=1, window_bits=0, tile=0,
+             layout=qp.QP_LAYOUT_CANONICAL, row_stride=512, codes=0x1000, lut=0x2000, scales=0x3000)
+    d.update(kw)
+    return binding.qp_weight(**d)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(), 0),
+    (dict(scheme=7), 3),
+    (dict(code_bits=3), 3),
+    (dict(scheme=qp.QP_VQ, vec=2, code_bits=6), 3),
+    (dict(scheme=qp.QP_VQ, vec=2, code_bits=5, row_stride=320), 0),
+    (dict(scheme=qp.QP_TCQ, code_bits=2, window_bits=16, tile=256, row_stride=256), 0),
+    (dict(scheme=qp.QP_TCQ, code_bits=2, window_bits=12, tile=256, row_stride=256), 3),
+    (dict(scheme=qp.QP_TCQ, code_bits=3, window_bits=16, tile=256, N=1000, row_stride=384), 2),
+    (dict(M=0), 2),
+    (dict(N=1020), 2),
+    (dict(codes=0), 1),
+    (dict(lut=0), 1),
+    (dict(scales=0), 1),
+    (dict(row_stride=500), 4),
+    (dict(row_stride=256), 2),
+    (dict(codes=0x1004), 4),
+    (dict(layout=5), 5),
+    (dict(layout=qp.QP_LAYOUT_NATIVE, M=24), 5),
+    (dict(layout=qp.QP_LAYOUT_NATIVE, N=1024 + 256, row_stride=640), 5),
+])
+def test_descriptor_validation(kw, code):
+    d = desc(**kw)
+    assert qp.load_library().qp_validate(C.byref(d)) == code
+
+
+def test_null_descriptor():
+    L = qp.load_library()
+    assert L.qp_validate(None) == 1
+    assert L.qp_native_bytes(None) == 0
+
+
+def test_linear_argument_errors_do_not_launch():
+    L = qp.load_library()
+    d = desc()
+    call = lambda x, B, ldx, y, ldy: L.qp_linear(C.byref(d), x, B, ldx, y, ldy, None, 0, None)
+    assert call(None, 1, 1024, 0x5000, 16) == 1
+    assert call(0x4000, 1, 1024, None, 16) == 1
+    assert call(0x4000, 0, 1024, 0x5000, 16) == 2
+    assert call(0x4000, 17, 1024, 0x5000, 16) == 2
+    assert call(0x4000, 1, 1000, 0x5000, 16) == 2
+    assert call(0x4000, 1, 1028, 0x5000, 16) == 2
+    assert call(0x4000, 1, 1024, 0x5000, 8) == 2
+    assert call(0x4008, 1, 1024, 0x5000, 16) == 4
+    assert L.qp_dequant(C.byref(d), None, None) == 1
+    assert L.qp_dequant(C.byref(d), 0x5004, None) == 4
+
+
+def test_hadamard_argument_errors_do_not_launch():
+    L = qp.load_library()
+    call = lambda x, s, B, n, blk, ldx, xr, ldxr: L.qp_hadamard(x, s, B, n, blk, ldx, xr, ldxr, None)
+    ok = (0x4000, 0x5000, 1, 1024, 1024, 1024, 0x8000, 1024)
+    assert call(None, *ok[1:]) == 1
+    assert call(0x4000, None, *ok[2:]) == 1
+    assert call(*ok[:6], None, 1024) == 1
+    assert call(0x4000, 0x5000, 0, 1024, 1024, 1024, 0x8000, 1024) == 2
+    assert call(0x4000, 0x5000, 1, 1024, 768, 1024, 0x8000, 1024) == 2      # not a power of two
+    assert call(0x4000, 0x5000, 1, 1024, 1, 1024, 0x8000, 1024) == 2
+    assert call(0x4000, 0x5000, 1, 1536, 1024, 1536, 0x8000, 1536) == 2     # block does not divide n
+    assert call(0x4000, 0x5000, 1, 1024, 1024, 512, 0x8000, 1024) == 2
+    assert call(0x4000, 0x5000, 1, 1024, 1024, 1024, 0x4400, 1024) == 4     # partial overlap
+
+
+def test_repack_argument_errors_do_not_launch():
+    L = qp.load_library()
+    out = binding.qp_weight()
+    d = desc()
+    assert L.qp_native_bytes(C.byref(d)) == 16 * 512
+    assert L.qp_native_bytes(C.byref(desc(M=24))) == 0
+    assert L.qp_repack(C.byref(d), C.byref(out), None, 16 * 512, None) == 1
+    assert L.qp_repack(C.byref(d), C.byref(out), 0x100000, 100, None) == 2
+    assert L.qp_repack(C.byref(desc(M=24)), C.byref(out), 0x100000, 1 << 20, None) == 5
+    assert L.qp_repack(C.byref(desc(layout=qp.QP_LAYOUT_NATIVE)), C.byref(out), 0x100000, 1 << 20, None) == 5
+    assert L.qp_repack(C.byref(d), C.byref(out), 0x1100, 1 << 20, None) == 4   # overlaps the source
+    sizes = {(qp.QP_VQ, 5, 2): 16 * 320, (qp.QP_VQ, 7, 2): 16 * 448, (qp.QP_TCQ, 3, 1): 16 * 384}
+    for (s, cb, v), want in sizes.items():
+        dd = desc(scheme=s, code_bits=cb, vec=v, window_bits=16 if s == qp.QP_TCQ else 0,
+                  tile=256 if s == qp.QP_TCQ else 0, row_stride=1024)
+        assert L.qp_native_bytes(C.byref(dd)) == want

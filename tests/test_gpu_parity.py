@@ -1,0 +1,163 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by
+element on the same seeded inputs.  Decode must be bit-exact; outputs must be within
+1e-2 of the fp64 reference, relative to its infinity norm (fp16 inputs, fp32
+accumulation, one fp16 rounding at the end)."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+SCHEMES = [(synth.SQ, 4), (synth.VQ, 5), (synth.VQ, 7), (synth.TCQ, 2), (synth.TCQ, 3), (synth.TCQ, 4)]
+IDS = ["sq4", "vq5", "vq7", "tcq2", "tcq3", "tcq4"]
+TOL = 1e-2
+
+
+@pytest.fixture(scope="module")
+def qp():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2509_20214_amd as m
+    m.load_library()
+    return m
+
+
+def dev(a):
+    if a.dtype == np.float16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.float16)
+    return torch.from_numpy(a).cuda()
+
+
+def host16(t):
+    return t.detach().cpu().view(torch.int16).numpy().view(np.uint16)
+
+
+def rel_err(y_gpu_u16, y_ref):
+    y = y_gpu_u16.view(np.float16).astype(np.float64)
+    return float(np.max(np.abs(y - y_ref)) / np.max(np.abs(y_ref)))
+
+
+# ----------------------------------------------------------------- decode
+@pytest.mark.parametrize("scheme,cb", SCHEMES, ids=IDS)
+@pytest.mark.parametrize("layout,M,N", [("canonical", 40, 1280), ("canonical", 33, 256), ("native", 48, 3072)])
+def test_dequant_bit_exact(qp, scheme, cb, layout, M, N):
+    lay = synth.make_layer(70, scheme * 10 + cb, scheme, M, N, cb)
+    want = oracle.decode(lay)
+    w = qp.Weight.from_layer(lay)
+    if layout == "native":
+        w = qp.qp_repack(w)
+    got = host16(qp.qp_dequant(w))
+    assert np.array_equal(got, want)
+
+
+def test_repack_layout_is_as_documented(qp):
+    """Piece p of lane l = 16 g + i of block (R, C) holds canonical bytes
+    [(4C+g)*span + 16p, +16) of row 16R+i."""
+    lay = synth.make_layer(71, 0, synth.VQ, 32, 2048, 5)
+    w = qp.Weight.from_layer(lay)
+    nat = qp.qp_repack(w).codes.cpu().numpy()
+    span, P, nbc = 80, 5, 2
+    want = np.empty_like(nat)
+    for R in range(2):
+        for C_ in range(nbc):
+            base = (R * nbc + C_) * 64 * span
+            for p in range(P):
+                for l in range(64):
+                    g, i = l >> 4, l & 15
+                    src = lay.codes[16 * R + i, (4 * C_ + g) * span + 16 * p:(4 * C_ + g) * span + 16 * p + 16]
+                    want[base + (p * 64 + l) * 16: base + (p * 64 + l) * 16 + 16] = src
+    assert np.array_equal(nat, want)
+
+
+# ----------------------------------------------------------------- linear
+@pytest.mark.parametrize("scheme,cb", SCHEMES, ids=IDS)
+@pytest.mark.parametrize("layout,M,N", [("canonical", 40, 1280), ("native", 48, 3072)])
+@pytest.mark.parametrize("B", [1, 2, 3, 4, 5, 8, 16])
+def test_linear_matches_oracle(qp, scheme, cb, layout, M, N, B):
+    lay = synth.make_layer(72, scheme * 10 + cb, scheme, M, N, cb)
+    x = synth.make_x(72, B, B, N)
+    want = oracle.linear(lay, x)
+    w = qp.Weight.from_layer(lay)
+    if layout == "native":
+        w = qp.qp_repack(w)
+    y = qp.qp_linear(w, dev(x))
+    torch.cuda.synchronize()
+    assert rel_err(host16(y), want) <= TOL
+
+
+def test_linear_with_leading_dimensions(qp):
+    lay = synth.make_layer(73, 0, synth.VQ, 32, 1024, 5)
+    B, ldx, ldy = 3, 1024 + 64, 32 + 5
+    x = synth.make_x(73, 0, B, 1024)
+    xd = torch.zeros((B, ldx), dtype=torch.float16, device="cuda")
+    xd[:, :1024] = dev(x)
+    yd = torch.full((B, ldy), 7.0, dtype=torch.float16, device="cuda")
+    w = qp.Weight.from_layer(lay)
+    qp.qp_linear(w, xd[:, :1024], y=yd[:, :32])
+    torch.cuda.synchronize()
+    want = oracle.linear(lay, x)
+    got = yd.cpu().numpy()
+    assert np.all(got[:, 32:] == 7.0)          # nothing written outside [B, M]
+    assert rel_err(np.ascontiguousarray(got[:, :32]).view(np.uint16), want) <= TOL
+
+
+def test_linear_one_hot_picks_single_weights(qp):
+    """x = e_i makes y[j] = s[j] W^[j, i]: exact up to one fp16 rounding."""
+    for scheme, cb in SCHEMES:
+        lay = synth.make_layer(74, scheme * 10 + cb, scheme, 16, 1024, cb)
+        e = np.zeros((1, 1024), dtype=np.float16)
+        e[0, 777] = 1.0
+        want = oracle.linear(lay, e)
+        y = host16(qp.qp_linear(qp.Weight.from_layer(lay), dev(e))).view(np.float16).astype(np.float64)
+        assert np.all(np.abs(y - want) <= np.abs(want) * 2.0 ** -11 + 1e-7)
+
+
+# --------------------------------------------------------------- Hadamard
+@pytest.mark.parametrize("B,n,block", [(1, 1024, 1024), (3, 4096, 4096), (2, 8192, 8192), (1, 14336, 1024),
+                                       (4, 14336, 1024), (16, 28672, 1024), (5, 64, 8), (1, 2, 2),
+                                       (2, 16384, 16384), (7, 1536, 512)])
+def test_hadamard_matches_oracle(qp, B, n, block):
+    x = synth.make_x(75, n % 97, B, n)
+    sg = synth.make_signs(75, n % 97, n)
+    want = oracle.hadamard(x, sg, block, fast=(block > 2048))
+    got = host16(qp.qp_hadamard(dev(x), dev(sg), block)).view(np.float16).astype(np.float64)
+    # fp32 butterflies then one fp16 rounding: half an fp16 ulp plus the fp32 error
+    # of log2(block) additions of O(sqrt(block))-sized numbers
+    tol = np.abs(want) * 2.0 ** -11 + np.max(np.abs(want)) * 2.0 ** -20 + 2.0 ** -24
+    assert np.all(np.abs(got - want) <= tol)
+
+
+def test_hadamard_in_place_and_strided(qp):
+    B, n, block, ld = 3, 2048, 1024, 2048 + 8
+    x = synth.make_x(76, 0, B, n)
+    sg = synth.make_signs(76, 0, n)
+    buf = torch.zeros((B, ld), dtype=torch.float16, device="cuda")
+    buf[:, :n] = dev(x)
+    view = buf[:, :n]
+    qp.qp_hadamard(view, dev(sg), block, out=view)
+    torch.cuda.synchronize()
+    want = oracle.hadamard(x, sg, block)
+    got = view.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - want) <= np.abs(want) * 2.0 ** -11 + 1e-5)
+    assert torch.all(buf[:, n:] == 0)
+
+
+# ---------------------------------------------------------------- chained
+@pytest.mark.parametrize("scheme,cb", SCHEMES, ids=IDS)
+def test_rotation_then_linear_matches_fp64_chain(qp, scheme, cb):
+    """Whole hot path: rotate x on the GPU, multiply on the GPU; the oracle stays in
+    fp64 from the fp16 x to the end."""
+    M, N, B = 64, 2048, 2
+    block = 1024
+    lay = synth.make_layer(77, scheme * 10 + cb, scheme, M, N, cb)
+    x = synth.make_x(77, 1, B, N)
+    sg = synth.make_signs(77, 1, N)
+    want = oracle.linear(lay, oracle.hadamard(x, sg, block))
+    w = qp.qp_repack(qp.Weight.from_layer(lay))
+    xr = qp.qp_hadamard(dev(x), dev(sg), block)
+    y = qp.qp_linear(w, xr)
+    assert rel_err(host16(y), want) <= TOL
