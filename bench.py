@@ -1,0 +1,225 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized-linear hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch: qp_hadamard (rotate x)
+followed by qp_linear (fused dequantize-and-multiply) on one layer.  The headline
+workload is the 4096x14336 down-projection with the 2.5-bit vector quantizer at
+batch 1 (seeded synthetic codes, LUT, scales and activations).  Weights are taken
+from a ring of distinct device buffers larger than twice the 256 MB Infinity Cache,
+so every step streams its codes from HBM ("cold"); inputs are resident in HBM before
+the timed region starts.  The K timed steps are captured once into a HIP graph and
+replayed, so that the host's per-call overhead does not hide the device time.
+
+Prints ONE JSON line (see the README of the benchmark contract in the design doc).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=2000)
+    p.add_argument("--warmup", type=int, default=200)
+    p.add_argument("--cfg", type=int, default=3, help="benchmark configuration 1..4 (headline: 3)")
+    p.add_argument("--layer", type=int, default=0)
+    p.add_argument("--batch", type=int, default=1)
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--no-cases", action="store_true", help="skip the table of other (layer, batch) cases")
+    p.add_argument("--profile-only", action="store_true",
+                   help="run a short sequence of the dominant kernel only (for rocprofv3)")
+    return p.parse_args()
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import synth
+    import paper_2509_20214_amd as qp
+    qp.load_library()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    def upload(arr):
+        if arr.dtype == np.float16:
+            return torch.from_numpy(arr.view(np.int16)).to(dev).view(torch.float16)
+        return torch.from_numpy(arr).to(dev)
+
+    class Case:
+        """One layer resident on the device: a ring of native-layout copies of its codes."""
+
+        def __init__(self, cfg, li, B, ring_bytes=640 << 20):
+            self.desc = synth.config_layers(cfg)[li]
+            self.lay = synth.build(self.desc)
+            lay = self.lay
+            self.B = B
+            self.code_bytes = lay.code_bytes
+            base = qp.Weight.from_layer(lay)
+            nat = qp.qp_repack(base)
+            n = max(2, -(-ring_bytes // lay.code_bytes))
+            self.ring = [nat]
+            for _ in range(n - 1):
+                c = nat.codes.clone()
+                d = nat.desc
+                self.ring.append(qp.Weight(d.scheme, d.M, d.N, d.code_bits, d.vec, d.window_bits, d.tile,
+                                           c, nat.lut, nat.scales, layout=qp.QP_LAYOUT_NATIVE, row_stride=0))
+            self.block = synth.hadamard_block(lay.N)
+            self.x = upload(synth.make_x(cfg, li, B, lay.N))
+            self.signs = upload(synth.make_signs(cfg, li, lay.N))
+            self.xr = torch.empty_like(self.x)
+            self.y = torch.empty((B, lay.M), dtype=torch.float16, device=dev)
+            self.i = 0
+            # algorithmic bytes of one qp_linear launch: codes + scales + x + y + one LUT
+            self.alg_bytes = lay.code_bytes + 2 * lay.M + 2 * B * lay.N + 2 * B * lay.M + 2 * lay.lut.size
+
+        def step(self):
+            qp.qp_hadamard(self.x, self.signs, self.block, out=self.xr)
+            qp.qp_linear(self.ring[self.i % len(self.ring)], self.xr, y=self.y)
+            self.i += 1
+
+        def linear_only(self):
+            qp.qp_linear(self.ring[self.i % len(self.ring)], self.xr, y=self.y)
+            self.i += 1
+
+        def hadamard_only(self):
+            qp.qp_hadamard(self.x, self.signs, self.block, out=self.xr)
+
+    def graph_of(fn, count):
+        """Capture `count` calls of fn into one HIP graph on a side stream."""
+        g = torch.cuda.CUDAGraph()
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            fn()
+            torch.cuda.synchronize()
+            with torch.cuda.graph(g, stream=s):
+                for _ in range(count):
+                    fn()
+        torch.cuda.current_stream().wait_stream(s)
+        torch.cuda.synchronize()
+        return g
+
+    def event_time_us(g, count, repeats=5):
+        """Median over `repeats` of (HIP-event time of one graph replay) / count, in us."""
+        out = []
+        for _ in range(repeats):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            g.replay()
+            e1.record()
+            e1.synchronize()
+            out.append(e0.elapsed_time(e1) * 1e3 / count)
+        return statistics.median(out)
+
+    head = Case(a.cfg, a.layer, a.batch)
+
+    if a.profile_only:
+        for _ in range(20):
+            head.step()
+        torch.cuda.synchronize()
+        for _ in range(200):
+            head.linear_only()
+        torch.cuda.synchronize()
+        return
+
+    # ---------------- whole-step throughput: W warm-up steps, then exactly K timed steps
+    chunk = min(a.steps, 500)
+    assert a.steps % chunk == 0, "--steps must be a multiple of 500 (or below 500)"
+    g_step = graph_of(head.step, chunk)
+    for _ in range(max(1, a.warmup // chunk)):
+        g_step.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps // chunk):
+        g_step.replay()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / a.steps
+    value = head.code_bytes / (ms_per_step * 1e-3) / 1e9
+
+    # ---------------- dominant kernel alone (qp_linear), HIP events on its own stream
+    R = 500
+    g_lin = graph_of(head.linear_only, R)
+    g_lin.replay()
+    lin_us = event_time_us(g_lin, R)
+    g_had = graph_of(head.hadamard_only, R)
+    g_had.replay()
+    had_us = event_time_us(g_had, R)
+    achieved = head.alg_bytes / (lin_us * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "kernel": "qp_linear", "us_per_launch": round(lin_us, 3),
+                "algorithmic_bytes": head.alg_bytes}
+
+    # ---------------- other (layer, batch) cases: us per qp_linear call, cold ring
+    cases = []
+    if not a.no_cases:
+        del g_lin, g_had
+        todo = [(3, 0, 4), (3, 0, 8), (2, 0, 1), (1, 0, 1),
+                (4, 0, 1), (4, 1, 1), (4, 2, 1), (4, 3, 1), (4, 3, 8), (4, 3, 16), (4, 2, 8)]
+        for cfg, li, B in todo:
+            if (cfg, li, B) == (a.cfg, a.layer, a.batch):
+                continue
+            c = Case(cfg, li, B)
+            c.hadamard_only()
+            g = graph_of(c.linear_only, 200)
+            g.replay()
+            us = event_time_us(g, 200, repeats=3)
+            cases.append({"workload": c.desc["name"], "batch": B, "us_per_call": round(us, 3),
+                          "weight_GBps": round(c.code_bytes / us / 1e3, 1),
+                          "frac_of_peak": round(c.code_bytes / us / 1e3 / HBM_PEAK_GBS, 4)})
+            del c, g
+            torch.cuda.empty_cache()
+
+    # ---------------- the oracle on this machine's host cores (a reported baseline, not a target)
+    cpu = None
+    if not a.no_cpu_baseline:
+        import oracle
+        xr_host = head.xr.cpu().view(torch.int16).numpy().view(np.uint16)
+        times = []
+        t_all = time.perf_counter()
+        while len(times) < 3 or (time.perf_counter() - t_all < 8.0 and len(times) < 25):
+            t = time.perf_counter()
+            oracle.linear(head.lay, xr_host, threads=True)
+            times.append(time.perf_counter() - t)
+        med = statistics.median(times)
+        cpu = {"value": round(head.code_bytes / med / 1e9, 4), "unit": "GB/s", "cores": oracle.num_threads(),
+               "kind": "oracle", "ms_per_call": round(med * 1e3, 2),
+               "sample": f"whole {head.desc['name']} layer, batch {a.batch}, qp_linear only, "
+                         f"median of {len(times)} calls, OpenMP over output rows"}
+
+    out = {
+        "metric": "effective weight HBM bandwidth of the quantized-linear step (rotation + fused dequant-matmul)",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(ms_per_step, 6), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16 inputs, f32 accumulate", "data": "synthetic",
+        "config": {"workload": f"cfg{a.cfg} {head.desc['name']} batch {a.batch}, native layout, cold ring of "
+                               f"{len(head.ring)} weight buffers ({len(head.ring) * head.code_bytes >> 20} MiB)",
+                   "steps_in_one_hip_graph": chunk},
+        "us_per_step": round(ms_per_step * 1e3, 3), "us_qp_linear": round(lin_us, 3),
+        "us_qp_hadamard": round(had_us, 3),
+        "linear_weight_GBps": round(head.code_bytes / lin_us / 1e3, 1),
+        "roofline": roofline, "cpu_baseline": cpu, "cases": cases,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

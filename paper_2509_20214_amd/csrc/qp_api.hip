@@ -1,5 +1,6 @@
 // C ABI: host-side validation and dispatch.  No device memory is allocated here and
 // no call synchronises with the device.
+#include <cstdlib>
 #include <cstring>
 
 #include "qp_internal.h"
@@ -79,7 +80,12 @@ extern "C" qp_status qp_linear(const qp_weight *w, const void *x, int32_t B, int
     if (need && (!workspace || workspace_bytes < need)) return QP_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     QpW d = make_dev(w);
-    return qp_launch_linear_rowwave(d, w->scheme, w->code_bits, x, B, ldx, y, ldy, st);
+    // QP_LINEAR_KERNEL=rowwave forces the layout-agnostic kernel (used by the tests to
+    // cover it on native-layout weights too); anything else lets the shape decide.
+    const char *force = getenv("QP_LINEAR_KERNEL");
+    bool rowwave = (w->layout != QP_LAYOUT_NATIVE) || d.nbc > 32 || (force && strcmp(force, "rowwave") == 0);
+    if (rowwave) return qp_launch_linear_rowwave(d, w->scheme, w->code_bits, x, B, ldx, y, ldy, st);
+    return qp_launch_linear_mfma(d, w->scheme, w->code_bits, x, B, ldx, y, ldy, st);
 }
 
 extern "C" qp_status qp_dequant(const qp_weight *w, void *W_out, void *hip_stream) {

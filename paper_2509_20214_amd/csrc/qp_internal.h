@@ -8,6 +8,8 @@
 qp_status qp_launch_dequant(const QpW &w, int scheme, int cb, void *out, hipStream_t st);
 qp_status qp_launch_linear_rowwave(const QpW &w, int scheme, int cb, const void *x, int B, int64_t ldx,
                                    void *y, int64_t ldy, hipStream_t st);
+qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x, int B, int64_t ldx, void *y,
+                                int64_t ldy, hipStream_t st);
 qp_status qp_launch_hadamard(const void *x, const int8_t *signs, int B, int n, int block, int64_t ldx,
                              void *xr, int64_t ldxr, hipStream_t st);
 qp_status qp_launch_repack(const QpW &src, int span_bytes, void *dst, hipStream_t st);

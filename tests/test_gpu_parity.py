@@ -75,15 +75,23 @@ def test_repack_layout_is_as_documented(qp):
 
 # ----------------------------------------------------------------- linear
 @pytest.mark.parametrize("scheme,cb", SCHEMES, ids=IDS)
-@pytest.mark.parametrize("layout,M,N", [("canonical", 40, 1280), ("native", 48, 3072)])
-@pytest.mark.parametrize("B", [1, 2, 3, 4, 5, 8, 16])
-def test_linear_matches_oracle(qp, scheme, cb, layout, M, N, B):
+@pytest.mark.parametrize("layout,M,N", [("canonical", 40, 1280), ("native", 48, 3072), ("native-rowwave", 48, 3072),
+                                        ("native", 1040, 2048), ("native", 16, 14336)])
+@pytest.mark.parametrize("B", [1, 2, 3, 4, 5, 8, 13, 16])
+def test_linear_matches_oracle(qp, scheme, cb, layout, M, N, B, monkeypatch):
+    """canonical -> one wavefront per row; native -> the matrix-core kernel (several row
+    blocks per workgroup at M=1040, 14 column blocks at N=14336); native-rowwave -> the
+    row kernel reading the native layout."""
     lay = synth.make_layer(72, scheme * 10 + cb, scheme, M, N, cb)
     x = synth.make_x(72, B, B, N)
-    want = oracle.linear(lay, x)
+    want = oracle.linear(lay, x, threads=True)
     w = qp.Weight.from_layer(lay)
-    if layout == "native":
+    if layout.startswith("native"):
         w = qp.qp_repack(w)
+    if layout == "native-rowwave":
+        monkeypatch.setenv("QP_LINEAR_KERNEL", "rowwave")
+    else:
+        monkeypatch.delenv("QP_LINEAR_KERNEL", raising=False)
     y = qp.qp_linear(w, dev(x))
     torch.cuda.synchronize()
     assert rel_err(host16(y), want) <= TOL
