@@ -12,16 +12,29 @@
 // *other steps*: column j holds batch row j / TT and the x chunk of step s0 + j % TT.
 // One coalesced 16-byte load per lane then serves TT consecutive steps; step s0 + t
 // accumulates into its own accumulator acc[t], of which only the columns with
-// j % TT == t are meaningful.  Summing those columns over t at the end gives the dot
-// products.  TT = min(16 / Bp, 8) with Bp = B rounded up to a power of two.
+// j % TT == t are meaningful.  Summing those columns over t at the end (a DPP fold
+// inside each row of 16 lanes) gives the dot products.  TT = 16 / Bp (capped at 8 for
+// the schemes whose pieces need the registers) with Bp
+// the batch rounded up to a power of two.
+//
+// Table lookups per scheme:
+//   SQ 4 bit : one LDS read per *byte* of codes returns two weights (merged table,
+//              256 entries of half2).  The table is replicated once per LDS bank
+//              (entry e of copy c at dword 32 e + c) and lane l only reads copy
+//              l % 32, so no two lanes of a pass ever collide in a bank.
+//   VQ 7 bit : same bank-replicated table, 128 entries of half2.
+//   VQ 5 bit : 32 entries of half2 = one dword per LDS bank, conflict-free as it is.
+//              (Keeping the table in a VGPR and fetching it with ds_bpermute saves the
+//              AND per code but ran 2x slower: the permute path has a lower rate.)
+//   TCQ      : the 2^16-entry fp16 table, 128 KiB of LDS, read with ds_read_u16.
 //
 // A workgroup owns a contiguous range of 16-row blocks and walks it in passes of G
 // row blocks; the G * (N / 1024) units of a pass are dealt round-robin to the
-// wavefronts, each unit's column-selected partial sums go to LDS, and after a barrier
-// the workgroup adds them up, applies the per-row scale and stores fp16.
+// wavefronts, each unit's partial sums go to LDS, and after a barrier the workgroup
+// adds them up in a fixed order, applies the per-row scale and stores fp16.
 #include "qp_internal.h"
 
-#define QP_UMAX 32  // units per pass (LDS: 1 KiB each)
+#define QP_UMAX 32  // units per pass
 
 #ifdef QP_TRACE  // development builds only: per-wavefront timestamps of the kernel's phases
 __device__ uint64_t *qp_trace_buf;
@@ -31,140 +44,384 @@ extern "C" void qp_debug_set_trace(void *p) { (void)hipMemcpyToSymbol(HIP_SYMBOL
         if ((threadIdx.x & 63) == 0)                                                                 \
             qp_trace_buf[((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 8 + (slot)] = __builtin_amdgcn_s_memtime(); \
     } while (0)
-#define QP_TID()                                                                                     \
-    do {                                                                                             \
-        if ((threadIdx.x & 63) == 0)                                                                 \
-            qp_trace_buf[((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 8 + 7] =                   \
-                ((uint64_t)__builtin_amdgcn_s_getreg(63492) << 32) | __builtin_amdgcn_s_getreg(63508); \
-    } while (0)
 #else
 #define QP_T(slot)
-#define QP_TID()
 #endif
 
-// Compile-time bit-field extraction from the lane's P 16-byte pieces, seen as one
-// little-endian stream of 128 P bits.  Every index is a constant once the step loop is
-// unrolled, so the pieces stay in registers.  WRAP: the stream is circular (tail-biting
-// trellis tile); otherwise the caller guarantees that the field lies inside it.
+// ------------------------------------------------------------------ bit fields
+// The lane's P pieces seen as one little-endian stream of 128 P bits.  Every index is
+// a constant once the step loop is unrolled, so the pieces stay in registers.
 template <int P>
 __device__ __forceinline__ uint32_t qp_dw(const u32x4_t (&q)[P], int idx) {
     return q[idx >> 2][idx & 3];
 }
 
+// 32 stream bits starting at `bitpos` (circular when WRAP; otherwise bits past the end
+// of the stream are unspecified).
 template <int P, bool WRAP>
-__device__ __forceinline__ uint32_t qp_field(const u32x4_t (&q)[P], int bitpos, int nbits) {
+__device__ __forceinline__ uint32_t qp_bits32(const u32x4_t (&q)[P], int bitpos) {
     const int i0 = bitpos >> 5, r = bitpos & 31;
-    const uint32_t mask = (nbits == 32) ? 0xffffffffu : ((1u << nbits) - 1u);
-    if (r + nbits <= 32) return (qp_dw<P>(q, i0) >> r) & mask;
-    const int i1 = WRAP ? ((i0 + 1) % (4 * P)) : (i0 + 1);
-    return __builtin_amdgcn_alignbit(qp_dw<P>(q, i1), qp_dw<P>(q, i0), r) & mask;
+    if (r == 0) return qp_dw<P>(q, i0);
+    const int i1 = WRAP ? ((i0 + 1) % (4 * P)) : ((i0 + 1 < 4 * P) ? i0 + 1 : i0);
+    return __builtin_amdgcn_alignbit(qp_dw<P>(q, i1), qp_dw<P>(q, i0), r);
 }
 
-// Decode the 8 weights of step s (columns 8 s .. 8 s + 7 of the lane's 256) into an
-// MFMA operand.
-template <int S, int CB, int P>
-__device__ __forceinline__ half8_t qp_decode_step(const u32x4_t (&q)[P], int s, const uint16_t *lut) {
-    half8_t a;
-    if (S == QP_SQ) {
+// (field << LSH) & (mask << LSH) for the nbits-wide field at `bitpos`: one shift and one
+// AND when the field sits inside a dword, one funnel shift and one AND when it straddles
+// two (a straddling field starts above bit 16 >= LSH, so the funnel can start LSH bits low).
+template <int P, bool WRAP, int LSH>
+__device__ __forceinline__ uint32_t qp_field_shl(const u32x4_t (&q)[P], int bitpos, int nbits) {
+    const int i0 = bitpos >> 5, r = bitpos & 31;
+    const uint32_t mask = ((1u << nbits) - 1u) << LSH;
+    if (r + nbits <= 32) {
+        const uint32_t w = qp_dw<P>(q, i0);
+        return ((r >= LSH) ? (w >> (r - LSH)) : (w << (LSH - r))) & mask;
+    }
+    return qp_bits32<P, WRAP>(q, bitpos - LSH) & mask;
+}
+
+// ------------------------------------------------------------------ per-scheme decode
+template <int S, int CB>
+struct QpDec;
+
+// Bank-replicated table of half2 entries: dword 32 e + c holds entry e for c = 0..31.
+template <int ENTRIES>
+struct QpBankTable {
+    static constexpr int TAB_BYTES = ENTRIES * 128;
+    static __device__ __forceinline__ uint32_t lane_const() { return (threadIdx.x & 31u) << 2; }
+};
+
+// Uniform (wave-wide) reads of the table's source go through the scalar cache: they do
+// not queue behind the vector loads of the weight stream.
+typedef const uint32_t __attribute__((address_space(4))) qp_cu32;
+__device__ __forceinline__ qp_cu32 *qp_scalar_ptr(const void *p) {
+    return (qp_cu32 *)(uintptr_t)p;
+}
+
+// Copy `NQ` 16-byte pieces of the table's source into LDS through scalar registers
+// (lane 0 of the calling wavefront writes them).
+template <int NQ>
+__device__ __forceinline__ void qp_scalar_to_lds(qp_cu32 *src, u32x4_t *dst) {
+    u32x4_t v[NQ];
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
-            a[e] = __builtin_bit_cast(half_t, lut[qp_field<P, false>(q, (8 * s + e) * CB, CB)]);
-    } else if (S == QP_VQ) {
-        const uint32_t *lut2 = reinterpret_cast<const uint32_t *>(lut);
+    for (int k = 0; k < NQ; ++k) v[k] = u32x4_t{src[4 * k], src[4 * k + 1], src[4 * k + 2], src[4 * k + 3]};
+    if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+        for (int k = 0; k < NQ; ++k) dst[k] = v[k];
+    }
+}
+
+template <>
+struct QpDec<QP_SQ, 4> : QpBankTable<256> {
+    struct Pre {};
+    static __device__ __forceinline__ Pre pre(const uint16_t *) { return Pre{}; }
+    // tab[e] = (LUT[e & 15], LUT[e >> 4]): the two weights of one code byte.  Built at
+    // kernel start, before any vector load is queued: the 32-byte source comes through
+    // scalar registers into `small`, then every thread writes its share of the copies.
+    static __device__ __forceinline__ void early(uint8_t *tab, uint16_t *small, const uint16_t *g) {
+        if (threadIdx.x < 64) qp_scalar_to_lds<2>(qp_scalar_ptr(g), reinterpret_cast<u32x4_t *>(small));
+        __syncthreads();
+        uint32_t *t32 = reinterpret_cast<uint32_t *>(tab);
+        for (int idx = threadIdx.x; idx < 256 * 32; idx += blockDim.x) {
+            int e = idx >> 5;
+            t32[idx] = (uint32_t)small[e & 15] | ((uint32_t)small[e >> 4] << 16);
+        }
+        __syncthreads();
+    }
+    static __device__ __forceinline__ void build(uint8_t *, uint16_t *, const Pre &) {}
+    template <int P>
+    static __device__ __forceinline__ half8_t step(const u32x4_t (&q)[P], int s, const uint8_t *tab, uint32_t lc,
+                                                   const Pre &) {
+        uint32_t r[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            uint32_t p = lut2[qp_field<P, false>(q, (4 * s + c) * CB, CB)];
-            half2_t h = __builtin_bit_cast(half2_t, p);
-            a[2 * c] = h[0];
-            a[2 * c + 1] = h[1];
+            uint32_t a = qp_field_shl<P, false, 7>(q, 32 * s + 8 * c, 8) | lc;
+            r[c] = *reinterpret_cast<const uint32_t *>(tab + a);
         }
-    } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-            a[e] = __builtin_bit_cast(half_t, lut[qp_field<P, true>(q, (8 * s + e) * CB, 16)]);
+        return __builtin_bit_cast(half8_t, u32x4_t{r[0], r[1], r[2], r[3]});
     }
-    return a;
+};
+
+template <>
+struct QpDec<QP_VQ, 7> : QpBankTable<128> {
+    struct Pre {};
+    static __device__ __forceinline__ Pre pre(const uint16_t *) { return Pre{}; }
+    // 512-byte source: the first four wavefronts bring 128 bytes each.
+    static __device__ __forceinline__ void early(uint8_t *tab, uint16_t *small, const uint16_t *g) {
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        if (wave < 4)
+            qp_scalar_to_lds<8>(qp_scalar_ptr(g) + 32 * wave, reinterpret_cast<u32x4_t *>(small) + 8 * wave);
+        __syncthreads();
+        const uint32_t *s32 = reinterpret_cast<const uint32_t *>(small);
+        uint32_t *t32 = reinterpret_cast<uint32_t *>(tab);
+        for (int idx = threadIdx.x; idx < 128 * 32; idx += blockDim.x) t32[idx] = s32[idx >> 5];
+        __syncthreads();
+    }
+    static __device__ __forceinline__ void build(uint8_t *, uint16_t *, const Pre &) {}
+    template <int P>
+    static __device__ __forceinline__ half8_t step(const u32x4_t (&q)[P], int s, const uint8_t *tab, uint32_t lc,
+                                                   const Pre &) {
+        uint32_t r[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            uint32_t a = qp_field_shl<P, false, 7>(q, 28 * s + 7 * c, 7) | lc;
+            r[c] = *reinterpret_cast<const uint32_t *>(tab + a);
+        }
+        return __builtin_bit_cast(half8_t, u32x4_t{r[0], r[1], r[2], r[3]});
+    }
+};
+
+template <>
+struct QpDec<QP_VQ, 5> {
+    // 32 entries of half2 = 32 dwords = one per LDS bank: two lanes either read the same
+    // entry (broadcast) or different banks, so the plain table is already conflict-free.
+    // Every wavefront keeps a private copy (16 x 128 bytes), filled from 32 scalar
+    // registers while its weight loads are in flight: no wavefront ever waits for another
+    // one before it can start decoding.
+    static constexpr int TAB_BYTES = 16 * 128;
+    struct Pre { u32x4_t raw[8]; };  // wave-uniform: lives in 32 scalar registers
+    static __device__ __forceinline__ void early(uint8_t *, uint16_t *, const uint16_t *) {}
+    static __device__ __forceinline__ Pre pre(const uint16_t *g) {
+        qp_cu32 *l32 = qp_scalar_ptr(g);
+        Pre p;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) p.raw[k] = u32x4_t{l32[4 * k], l32[4 * k + 1], l32[4 * k + 2], l32[4 * k + 3]};
+        return p;
+    }
+    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *, const Pre &p) {
+        if ((threadIdx.x & 63) == 0) {
+            u32x4_t *t4 = reinterpret_cast<u32x4_t *>(tab) + (threadIdx.x >> 6) * 8;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) t4[k] = p.raw[k];
+        }
+    }
+    static __device__ __forceinline__ uint32_t lane_const() { return (threadIdx.x >> 6) << 7; }
+    template <int P>
+    static __device__ __forceinline__ half8_t step(const u32x4_t (&q)[P], int s, const uint8_t *tab, uint32_t lc,
+                                                   const Pre &) {
+        uint32_t r[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            uint32_t a = qp_field_shl<P, false, 2>(q, 20 * s + 5 * c, 5) | lc;
+            r[c] = *reinterpret_cast<const uint32_t *>(tab + a);
+        }
+        return __builtin_bit_cast(half8_t, u32x4_t{r[0], r[1], r[2], r[3]});
+    }
+};
+
+template <int K>
+struct QpDecTcq {
+    static constexpr int TAB_BYTES = 131072;
+    static constexpr int PRE = 8;  // 128 KiB / (1024 threads * 16 bytes)
+    struct Pre { u32x4_t raw[PRE]; };
+    static __device__ __forceinline__ void early(uint8_t *, uint16_t *, const uint16_t *) {}
+    static __device__ __forceinline__ Pre pre(const uint16_t *g) {  // needs blockDim.x == 1024
+        Pre p;
+        const u32x4_t *g4 = reinterpret_cast<const u32x4_t *>(g);
+#pragma unroll
+        for (int k = 0; k < PRE; ++k) p.raw[k] = g4[k * 1024 + threadIdx.x];
+        return p;
+    }
+    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *, const Pre &p) {
+        u32x4_t *t4 = reinterpret_cast<u32x4_t *>(tab);
+#pragma unroll
+        for (int k = 0; k < PRE; ++k) t4[k * 1024 + threadIdx.x] = p.raw[k];
+        __syncthreads();
+    }
+    static __device__ __forceinline__ uint32_t lane_const() { return 0; }
+    template <int P>
+    static __device__ __forceinline__ half8_t step(const u32x4_t (&q)[P], int s, const uint8_t *tab, uint32_t,
+                                                   const Pre &) {
+        half8_t a;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            uint32_t ad = qp_field_shl<P, true, 1>(q, (8 * s + e) * K, 16);
+            a[e] = __builtin_bit_cast(half_t, *reinterpret_cast<const uint16_t *>(tab + ad));
+        }
+        return a;
+    }
+};
+template <> struct QpDec<QP_TCQ, 2> : QpDecTcq<2> {};
+template <> struct QpDec<QP_TCQ, 3> : QpDecTcq<3> {};
+template <> struct QpDec<QP_TCQ, 4> : QpDecTcq<4> {};
+
+// ------------------------------------------------------------------ DPP fold
+// v + (src shifted towards lane 0 by N lanes inside each row of 16 lanes).
+template <int N>
+__device__ __forceinline__ float qp_add_row_shl(float v, float src) {
+    int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, src), 0x100 + N, 0xf, 0xf, true);
+    return v + __builtin_bit_cast(float, moved);
+}
+
+template <int TT, int T = 1>
+struct QpFold {  // acc[0] + shl1(acc[1]) + ... : lane b*TT of every row ends up with the sum over t
+    static __device__ __forceinline__ void run(float4_t &v, const float4_t (&acc)[TT]) {
+        if constexpr (T < TT) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = qp_add_row_shl<T>(v[e], acc[T][e]);
+            QpFold<TT, T + 1>::run(v, acc);
+        }
+    }
+};
+
+// ------------------------------------------------------------------ the kernel
+// One unit's loads: P coalesced 128-bit pieces of codes, then the first PF activation
+// fragments.  Straight-line code (no branches) so that the waits the compiler inserts
+// later can name exactly the loads they need.
+template <int P, int PF, int TT>
+__device__ __forceinline__ void qp_unit_load(const u32x4_t *blk, const half_t *xu, int lane, u32x4_t (&q)[P],
+                                             half8_t (&xf)[PF]) {
+#pragma unroll
+    for (int p = 0; p < P; ++p) q[p] = __builtin_nontemporal_load(blk + p * 64 + lane);
+#pragma unroll
+    for (int n = 0; n < PF; ++n) xf[n] = *reinterpret_cast<const half8_t *>(xu + 8 * TT * n);
+}
+
+// Decode and multiply one unit; the lane that owns (rows 4g..4g+3, batch row b) returns
+// their partial dot products in v.
+template <int S, int CB, int P, int PF, int TT>
+__device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8_t (&xf)[PF], const half_t *xu,
+                                                    const uint8_t *tab, uint32_t lc,
+                                                    const typename QpDec<S, CB>::Pre &pre) {
+    using D = QpDec<S, CB>;
+    constexpr int NXF = 32 / TT;
+    float4_t acc[TT];
+#pragma unroll
+    for (int t = 0; t < TT; ++t) acc[t] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < 32; ++s) {
+        const int n = s / TT;
+        half8_t a = D::template step<P>(q, s, tab, lc, pre);
+        acc[s % TT] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, xf[n % PF], acc[s % TT], 0, 0, 0);
+        if (s % TT == TT - 1 && n + PF < NXF)  // this fragment is spent: refill its slot
+            xf[n % PF] = *reinterpret_cast<const half8_t *>(xu + 8 * TT * (n + PF));
+    }
+    float4_t v = acc[0];
+    QpFold<TT>::run(v, acc);
+    return v;
+}
+
+// After a pass: wait for every wavefront's partial sums, add them per output in a fixed
+// order (column blocks ascending), scale, round once to fp16 and store.
+template <int BP>
+__device__ __forceinline__ void qp_pass_store(const QpW &w, const float *red, half_t *y, int64_t ldy, int B,
+                                              int rb0, int gcount, int nbc, uint16_t scale_first) {
+    constexpr int LB = (BP == 1) ? 0 : (BP == 2) ? 1 : (BP == 4) ? 2 : (BP == 8) ? 3 : 4;
+    __syncthreads();
+    QP_T(5);
+    for (int o = threadIdx.x; o < (gcount << (4 + LB)); o += blockDim.x) {
+        const int i = o & 15, b = (o >> 4) & (BP - 1), slot = o >> (4 + LB);
+        if (b < B) {
+            const int row = (rb0 + slot) * 16 + i;
+            const uint16_t sc = (o == (int)threadIdx.x) ? scale_first : w.scales[row];
+            float sum = 0.f;
+            const float *r = &red[((slot * nbc) * BP + b) * 16 + i];
+            for (int C = 0; C < nbc; ++C) sum += r[C * BP * 16];
+            y[(int64_t)b * ldy + row] = (half_t)(qp_half_bits_to_float(sc) * sum);
+        }
+    }
+    __syncthreads();
 }
 
 template <int S, int CB, int BP>
 __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, int B, int64_t ldx, half_t *y,
-                                                      int64_t ldy, int G) {
+                                                      int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic) {
     using T = QpTraits<S, CB>;
+    using D = QpDec<S, CB>;
     constexpr int P = T::PIECES;
-    constexpr int TT = (16 / BP < 8) ? 16 / BP : 8;  // steps per activation fragment
-    __shared__ __attribute__((aligned(16))) uint16_t lut[T::LUT_HALVES];
-    __shared__ __attribute__((aligned(16))) float red[QP_UMAX][64][4];
+    constexpr int LB = (BP == 1) ? 0 : (BP == 2) ? 1 : (BP == 4) ? 2 : (BP == 8) ? 3 : 4;
+    // steps per activation fragment; 16 accumulators only where the registers allow it
+    constexpr int TTMAX = (S == QP_VQ) ? 16 : 8;
+    constexpr int TT = (16 / BP < TTMAX) ? 16 / BP : TTMAX;
+    constexpr int NXF = 32 / TT;                     // activation fragments per unit
+    constexpr int PF = (NXF < 8) ? NXF : 8;          // fragments kept in flight
+    constexpr int BLK16 = T::BLOCK_BYTES / 16;
+    __shared__ __attribute__((aligned(16))) uint8_t tab[D::TAB_BYTES];
+    __shared__ __attribute__((aligned(16))) float red[QP_UMAX * 16 * BP];  // [unit][b][row]
     QP_T(0);
-    QP_TID();
-    qp_stage_lut<T::LUT_HALVES>(w.lut, lut);
-    __syncthreads();
-    QP_T(1);
+
+    // ---- first pass, straight-line up to the first loads ------------------------------
+    // Tables shared by the whole workgroup are built right away from scalar loads (one
+    // early barrier, before any vector load is queued); a per-wavefront table only fetches
+    // its source here and is written once the weight loads are in flight; the trellis
+    // table's source is requested first so that it can be waited for alone.
+    D::early(tab, reinterpret_cast<uint16_t *>(red), w.lut);
+    const typename D::Pre pre = D::pre(w.lut);
 
     const int nw = blockDim.x >> 6;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int g = lane >> 4, j = lane & 15;
-    const int tj = j % TT;
-    int bj = j / TT;
-    if (bj >= B) bj = B - 1;  // spare columns re-read a valid row; their results are never used
     const int nbc = w.nbc;
-    const int rbk = w.M >> 4;
-    // balanced contiguous partition of the row blocks over the workgroups
-    const int rb_begin = (int)((int64_t)rbk * blockIdx.x / gridDim.x);
-    const int rb_end = (int)((int64_t)rbk * (blockIdx.x + 1) / gridDim.x);
-    const half_t *xlane = x + (int64_t)bj * ldx + 256 * g + 8 * tj;
+    // balanced contiguous partition of the row blocks over the workgroups: the first rb_r
+    // workgroups take rb_q + 1 blocks, the others rb_q
+    const int bx = blockIdx.x;
+    const int rb_begin = bx * rb_q + (bx < rb_r ? bx : rb_r);
+    const int rb_end = rb_begin + rb_q + (bx < rb_r ? 1 : 0);
+    const u32x4_t *codes16 = reinterpret_cast<const u32x4_t *>(w.codes);
 
-    for (int rb0 = rb_begin; rb0 < rb_end; rb0 += G) {
-        const int gcount = (rb_end - rb0 < G) ? (rb_end - rb0) : G;
-        const int units = gcount * nbc;
-        for (int u = wave; u < units; u += nw) {
-            const int slot = u / nbc, C = u - slot * nbc;
-            const u32x4_t *blk = reinterpret_cast<const u32x4_t *>(
-                w.codes + ((int64_t)(rb0 + slot) * nbc + C) * T::BLOCK_BYTES);
-            u32x4_t q[P];
+    int gcount = (rb_end - rb_begin < G) ? (rb_end - rb_begin) : G;
+    int units = gcount * nbc;
+    int u = wave;
+    // A wavefront without a unit loads unit 0 as well, to keep this code free of branches;
+    // it only skips the arithmetic.
+    const int uu = (u < units) ? u : 0;
+    u32x4_t q[P];
+    {
+        const u32x4_t *blk = codes16 + ((int64_t)rb_begin * nbc + uu) * BLK16;
 #pragma unroll
-            for (int p = 0; p < P; ++p) q[p] = __builtin_nontemporal_load(blk + p * 64 + lane);
-            const half_t *xu = xlane + (int64_t)C * 1024;
-            half8_t xf = *reinterpret_cast<const half8_t *>(xu);
-            float4_t acc[TT];
+        for (int p = 0; p < P; ++p) q[p] = __builtin_nontemporal_load(blk + p * 64 + lane);
+    }
+    const int g = lane >> 4, j = lane & 15;
+    const int tj = j & (TT - 1);
+    const int bj = j / TT;
+    const bool xlive = bj < B;  // columns beyond the batch re-read row 0; their results are dropped
+    const half_t *xlane = x + (int64_t)(xlive ? bj : 0) * ldx + 256 * g + 8 * tj;
+    const bool owner = (tj == 0) && xlive;  // lane (g, b*TT) ends up with rows 4g..4g+3 of batch row b
+    half8_t xf[PF];
+    const half_t *xu = xlane + (uu - ((uu * nbc_magic) >> 16) * nbc) * 1024;   // column block = uu % nbc
 #pragma unroll
-            for (int t = 0; t < TT; ++t) acc[t] = float4_t{0.f, 0.f, 0.f, 0.f};
-#ifdef QP_TRACE
-            if (u == wave && rb0 == rb_begin) {
-                if (q[0][0] == 0x12345 && q[P - 1][3] == 0x777) acc[0][0] = 1.f;  // forces the loads to have landed
-                QP_T(2);
-            }
-#endif
-#pragma unroll
-            for (int s = 0; s < 32; ++s) {
-                if (s > 0 && s % TT == 0) xf = *reinterpret_cast<const half8_t *>(xu + 8 * s);
-                half8_t a = qp_decode_step<S, CB, P>(q, s, lut);
-                acc[s % TT] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, xf, acc[s % TT], 0, 0, 0);
-            }
-            float4_t v = acc[0];
-#pragma unroll
-            for (int t = 1; t < TT; ++t)
-                if (tj == t) v = acc[t];
-            *reinterpret_cast<float4_t *>(&red[u][lane][0]) = v;
-            QP_T(3);
+    for (int n = 0; n < PF; ++n) xf[n] = *reinterpret_cast<const half8_t *>(xu + 8 * TT * n);
+    // the first output this thread stores after the pass: its per-row scale is fetched now
+    uint16_t scale_first;
+    {
+        const int o = threadIdx.x;
+        const int i = o & 15, slot = o >> (4 + LB);
+        scale_first = w.scales[(slot < gcount) ? (rb_begin + slot) * 16 + i : 0];
+    }
+    const uint32_t lc = D::lane_const();
+    QP_T(7);
+    D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
+    QP_T(1);
+    if (u < units) {
+        float4_t v = qp_unit_compute<S, CB, P, PF, TT>(q, xf, xu, tab, lc, pre);
+        if (owner) *reinterpret_cast<float4_t *>(&red[(u * BP + bj) * 16 + 4 * g]) = v;
+    }
+    QP_T(2);
+    int rb0 = rb_begin;
+    u += nw;
+    while (true) {
+        // ---- remaining units of this pass ----------------------------------------------
+        for (; u < units; u += nw) {
+            const int C = u - ((u * nbc_magic) >> 16) * nbc;
+            const half_t *xu2 = xlane + C * 1024;
+            u32x4_t q2[P];
+            half8_t xf2[PF];
+            qp_unit_load<P, PF, TT>(codes16 + ((int64_t)rb0 * nbc + u) * BLK16, xu2, lane, q2, xf2);
+            float4_t v = qp_unit_compute<S, CB, P, PF, TT>(q2, xf2, xu2, tab, lc, pre);
+            if (owner) *reinterpret_cast<float4_t *>(&red[(u * BP + bj) * 16 + 4 * g]) = v;
         }
         QP_T(4);
-        __syncthreads();
-        QP_T(5);
-        // outputs of this pass: (slot, b, i); consecutive threads take consecutive rows
-        for (int o = threadIdx.x; o < gcount * 16 * B; o += blockDim.x) {
-            const int i = o & 15;
-            const int b = (o >> 4) % B;
-            const int slot = (o >> 4) / B;
-            float sum = 0.f;
-            for (int C = 0; C < nbc; ++C) {
-                const float *r = &red[slot * nbc + C][16 * (i >> 2) + b * TT][i & 3];
-#pragma unroll
-                for (int t = 0; t < TT; ++t) sum += r[4 * t];
-            }
-            const int row = (rb0 + slot) * 16 + i;
-            y[(int64_t)b * ldy + row] = (half_t)(qp_half_bits_to_float(w.scales[row]) * sum);
+        qp_pass_store<BP>(w, red, y, ldy, B, rb0, gcount, nbc, scale_first);
+        // ---- next pass ------------------------------------------------------------------
+        rb0 += G;
+        if (rb0 >= rb_end) break;
+        gcount = (rb_end - rb0 < G) ? (rb_end - rb0) : G;
+        units = gcount * nbc;
+        u = wave;
+        {
+            const int o = threadIdx.x;
+            const int i = o & 15, slot = o >> (4 + LB);
+            scale_first = w.scales[(slot < gcount) ? (rb0 + slot) * 16 + i : 0];
         }
-        __syncthreads();
     }
     QP_T(6);
 }
@@ -178,12 +435,14 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
     int G = QP_UMAX / nbc;
     if (G > rb_per_wg) G = rb_per_wg;
     int units = G * nbc;
+    int rb_q = rbk / grid, rb_r = rbk % grid;
+    int nbc_magic = (65536 + nbc - 1) / nbc;  // u / nbc == (u * magic) >> 16 for u < 1024
     int nw = units < 16 ? units : 16;
-    if (scheme == QP_TCQ && nw < 16) nw = 16;  // all 1024 threads help staging the 128 KiB table
+    if (scheme == QP_TCQ) nw = 16;  // the table staging is written for 1024 threads
     if (nw < 4) nw = 4;
 #define CALL_BP(S, C, BP)                                                                              \
     hipLaunchKernelGGL((k_linear_mfma<S, C, BP>), dim3(grid), dim3(64 * nw), 0, st, w, (const half_t *)x, B, \
-                       ldx, (half_t *)y, ldy, G)
+                       ldx, (half_t *)y, ldy, G, rb_q, rb_r, nbc_magic)
 #define CALL(S, C)                                   \
     do {                                             \
         if (B <= 1) CALL_BP(S, C, 1);                \
