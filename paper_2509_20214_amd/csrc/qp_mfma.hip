@@ -80,6 +80,26 @@ __device__ __forceinline__ uint32_t qp_field_shl(const u32x4_t (&q)[P], int bitp
     return qp_bits32<P, WRAP>(q, bitpos - LSH) & mask;
 }
 
+// (field << LSH) | orv in two vector operations, v_bfe_u32 + v_lshl_or_b32, with the
+// per-lane constant folded into the second (the compiler, left alone, turns the OR into
+// a third, separate add).  A field that straddles two dwords costs one funnel shift more.
+template <int P, bool WRAP, int LSH>
+__device__ __forceinline__ uint32_t qp_field_addr(const u32x4_t (&q)[P], int bitpos, int nbits, uint32_t orv) {
+    const int i0 = bitpos >> 5, r = bitpos & 31;
+    uint32_t w, idx, a;
+    int off;
+    if (r + nbits <= 32) {
+        w = qp_dw<P>(q, i0);
+        off = r;
+    } else {
+        w = qp_bits32<P, WRAP>(q, bitpos);
+        off = 0;
+    }
+    asm("v_bfe_u32 %0, %1, %2, %3" : "=v"(idx) : "v"(w), "n"(off), "n"(nbits));
+    asm("v_lshl_or_b32 %0, %1, %2, %3" : "=v"(a) : "v"(idx), "n"(LSH), "v"(orv));
+    return a;
+}
+
 // ------------------------------------------------------------------ per-scheme decode
 template <int S, int CB>
 struct QpDec;
@@ -135,7 +155,7 @@ struct QpDec<QP_SQ, 4> : QpBankTable<256> {
         uint32_t r[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            uint32_t a = qp_field_shl<P, false, 7>(q, 32 * s + 8 * c, 8) | lc;
+            uint32_t a = qp_field_addr<P, false, 7>(q, 32 * s + 8 * c, 8, lc);
             r[c] = *reinterpret_cast<const uint32_t *>(tab + a);
         }
         return __builtin_bit_cast(half8_t, u32x4_t{r[0], r[1], r[2], r[3]});
@@ -164,7 +184,7 @@ struct QpDec<QP_VQ, 7> : QpBankTable<128> {
         uint32_t r[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            uint32_t a = qp_field_shl<P, false, 7>(q, 28 * s + 7 * c, 7) | lc;
+            uint32_t a = qp_field_addr<P, false, 7>(q, 28 * s + 7 * c, 7, lc);
             r[c] = *reinterpret_cast<const uint32_t *>(tab + a);
         }
         return __builtin_bit_cast(half8_t, u32x4_t{r[0], r[1], r[2], r[3]});
@@ -202,7 +222,7 @@ struct QpDec<QP_VQ, 5> {
         uint32_t r[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            uint32_t a = qp_field_shl<P, false, 2>(q, 20 * s + 5 * c, 5) | lc;
+            uint32_t a = qp_field_addr<P, false, 2>(q, 20 * s + 5 * c, 5, lc);
             r[c] = *reinterpret_cast<const uint32_t *>(tab + a);
         }
         return __builtin_bit_cast(half8_t, u32x4_t{r[0], r[1], r[2], r[3]});
@@ -265,16 +285,16 @@ struct QpFold {  // acc[0] + shl1(acc[1]) + ... : lane b*TT of every row ends up
 };
 
 // ------------------------------------------------------------------ the kernel
-// One unit's loads: P coalesced 128-bit pieces of codes, then the first PF activation
-// fragments.  Straight-line code (no branches) so that the waits the compiler inserts
+// One unit's loads: the first PF activation fragments, then P coalesced 128-bit pieces
+// of codes.  Straight-line code (no branches) so that the waits the compiler inserts
 // later can name exactly the loads they need.
 template <int P, int PF, int TT>
 __device__ __forceinline__ void qp_unit_load(const u32x4_t *blk, const half_t *xu, int lane, u32x4_t (&q)[P],
                                              half8_t (&xf)[PF]) {
 #pragma unroll
-    for (int p = 0; p < P; ++p) q[p] = __builtin_nontemporal_load(blk + p * 64 + lane);
-#pragma unroll
     for (int n = 0; n < PF; ++n) xf[n] = *reinterpret_cast<const half8_t *>(xu + 8 * TT * n);
+#pragma unroll
+    for (int p = 0; p < P; ++p) q[p] = __builtin_nontemporal_load(blk + p * 64 + lane);
 }
 
 // Decode and multiply one unit; the lane that owns (rows 4g..4g+3, batch row b) returns
@@ -285,6 +305,16 @@ __device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8
                                                     const typename QpDec<S, CB>::Pre &pre) {
     using D = QpDec<S, CB>;
     constexpr int NXF = 32 / TT;
+#ifdef QP_NODECODE  // development builds only: loads without decode, to time the memory side alone
+    {
+        uint32_t z = 0;
+#pragma unroll
+        for (int p = 0; p < P; ++p) z ^= q[p][0] ^ q[p][1] ^ q[p][2] ^ q[p][3];
+#pragma unroll
+        for (int n = 0; n < PF; ++n) z ^= __builtin_bit_cast(u32x4_t, xf[n])[0];
+        return float4_t{(float)z, 0.f, 0.f, 0.f};
+    }
+#endif
     float4_t acc[TT];
 #pragma unroll
     for (int t = 0; t < TT; ++t) acc[t] = float4_t{0.f, 0.f, 0.f, 0.f};
@@ -293,6 +323,10 @@ __device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8
         const int n = s / TT;
         half8_t a = D::template step<P>(q, s, tab, lc, pre);
         acc[s % TT] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, xf[n % PF], acc[s % TT], 0, 0, 0);
+#ifdef QP_TRACE
+        if (s == 0) QP_T(3);
+        if (s == 27) QP_T(4);
+#endif
         if (s % TT == TT - 1 && n + PF < NXF)  // this fragment is spent: refill its slot
             xf[n % PF] = *reinterpret_cast<const half8_t *>(xu + 8 * TT * (n + PF));
     }
@@ -316,7 +350,16 @@ __device__ __forceinline__ void qp_pass_store(const QpW &w, const float *red, ha
             const uint16_t sc = (o == (int)threadIdx.x) ? scale_first : w.scales[row];
             float sum = 0.f;
             const float *r = &red[((slot * nbc) * BP + b) * 16 + i];
-            for (int C = 0; C < nbc; ++C) sum += r[C * BP * 16];
+            for (int C0 = 0; C0 < nbc; C0 += 8) {  // eight independent LDS reads in flight, fixed order
+                float part[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const int C = C0 + k;
+                    part[k] = r[(C < nbc ? C : nbc - 1) * BP * 16];
+                }
+#pragma unroll
+                for (int k = 0; k < 8; ++k) sum += (C0 + k < nbc) ? part[k] : 0.f;
+            }
             y[(int64_t)b * ldy + row] = (half_t)(qp_half_bits_to_float(sc) * sum);
         }
     }
@@ -364,12 +407,8 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
     // A wavefront without a unit loads unit 0 as well, to keep this code free of branches;
     // it only skips the arithmetic.
     const int uu = (u < units) ? u : 0;
-    u32x4_t q[P];
-    {
-        const u32x4_t *blk = codes16 + ((int64_t)rb_begin * nbc + uu) * BLK16;
-#pragma unroll
-        for (int p = 0; p < P; ++p) q[p] = __builtin_nontemporal_load(blk + p * 64 + lane);
-    }
+    // Activation fragments first: they hit in L2, come back early, and - loads returning in
+    // issue order - let step 0 start as soon as the first piece of codes has landed.
     const int g = lane >> 4, j = lane & 15;
     const int tj = j & (TT - 1);
     const int bj = j / TT;
@@ -379,7 +418,19 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
     half8_t xf[PF];
     const half_t *xu = xlane + (uu - ((uu * nbc_magic) >> 16) * nbc) * 1024;   // column block = uu % nbc
 #pragma unroll
-    for (int n = 0; n < PF; ++n) xf[n] = *reinterpret_cast<const half8_t *>(xu + 8 * TT * n);
+    for (int n = 0; n < PF; ++n) {
+#ifdef QP_NOX
+        xf[n] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
+#else
+        xf[n] = *reinterpret_cast<const half8_t *>(xu + 8 * TT * n);
+#endif
+    }
+    u32x4_t q[P];
+    {
+        const u32x4_t *blk = codes16 + ((int64_t)rb_begin * nbc + uu) * BLK16;
+#pragma unroll
+        for (int p = 0; p < P; ++p) q[p] = __builtin_nontemporal_load(blk + p * 64 + lane);
+    }
     // the first output this thread stores after the pass: its per-row scale is fetched now
     uint16_t scale_first;
     {
@@ -409,7 +460,6 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
             float4_t v = qp_unit_compute<S, CB, P, PF, TT>(q2, xf2, xu2, tab, lc, pre);
             if (owner) *reinterpret_cast<float4_t *>(&red[(u * BP + bj) * 16 + 4 * g]) = v;
         }
-        QP_T(4);
         qp_pass_store<BP>(w, red, y, ldy, B, rb0, gcount, nbc, scale_first);
         // ---- next pass ------------------------------------------------------------------
         rb0 += G;
