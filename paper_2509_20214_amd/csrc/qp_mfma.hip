@@ -315,23 +315,51 @@ __device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8
         return float4_t{(float)z, 0.f, 0.f, 0.f};
     }
 #endif
-    float4_t acc[TT];
+    // NACC accumulators serve the TT steps of a fragment: step t adds into acc[t % NACC]
+    // and multiplies with a copy of the fragment in which only the columns of its own
+    // group (t / NACC) are kept, the others zeroed.  Column j of acc[a] then holds exactly
+    // the steps with t % TT == j % TT (if that is congruent to a; garbage-free zeros
+    // otherwise), and far fewer accumulators have to be folded than with one per step.
+    constexpr int NACC = (TT < 4) ? TT : 4;
+    constexpr int NM = TT / NACC;
+    const int lane_t = (int)(threadIdx.x & 15) % TT;
+    float4_t acc[NACC];
 #pragma unroll
-    for (int t = 0; t < TT; ++t) acc[t] = float4_t{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < NACC; ++t) acc[t] = float4_t{0.f, 0.f, 0.f, 0.f};
+    u32x4_t masked[NM];
 #pragma unroll
     for (int s = 0; s < 32; ++s) {
-        const int n = s / TT;
+        const int n = s / TT, t = s % TT;
+        if (t == 0) {
+            const u32x4_t raw = __builtin_bit_cast(u32x4_t, xf[n % PF]);
+            if constexpr (NM == 1) {
+                masked[0] = raw;
+            } else {
+#pragma unroll
+                for (int m = 0; m < NM; ++m) {
+                    const bool keep = (lane_t / NACC) == m;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) masked[m][r] = keep ? raw[r] : 0u;
+                }
+            }
+            if (n + PF < NXF)  // the raw fragment is spent: refill its slot
+                xf[n % PF] = *reinterpret_cast<const half8_t *>(xu + 8 * TT * (n + PF));
+        }
         half8_t a = D::template step<P>(q, s, tab, lc, pre);
-        acc[s % TT] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, xf[n % PF], acc[s % TT], 0, 0, 0);
+        acc[t % NACC] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, __builtin_bit_cast(half8_t, masked[t / NACC]),
+                                                               acc[t % NACC], 0, 0, 0);
 #ifdef QP_TRACE
         if (s == 0) QP_T(3);
         if (s == 27) QP_T(4);
 #endif
-        if (s % TT == TT - 1 && n + PF < NXF)  // this fragment is spent: refill its slot
-            xf[n % PF] = *reinterpret_cast<const half8_t *>(xu + 8 * TT * (n + PF));
     }
     float4_t v = acc[0];
-    QpFold<TT>::run(v, acc);
+    QpFold<NACC>::run(v, acc);   // lanes with t % NACC == 0 now hold their group's sum
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if constexpr (NM >= 2) v[e] = qp_add_row_shl<NACC>(v[e], v[e]);
+        if constexpr (NM >= 4) v[e] = qp_add_row_shl<2 * NACC>(v[e], v[e]);
+    }
     return v;
 }
 
@@ -374,7 +402,7 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
     constexpr int P = T::PIECES;
     constexpr int LB = (BP == 1) ? 0 : (BP == 2) ? 1 : (BP == 4) ? 2 : (BP == 8) ? 3 : 4;
     // steps per activation fragment; 16 accumulators only where the registers allow it
-    constexpr int TTMAX = (S == QP_VQ) ? 16 : 8;
+    constexpr int TTMAX = 16;
     constexpr int TT = (16 / BP < TTMAX) ? 16 / BP : TTMAX;
     constexpr int NXF = 32 / TT;                     // activation fragments per unit
     constexpr int PF = (NXF < 8) ? NXF : 8;          // fragments kept in flight
