@@ -141,8 +141,9 @@ def main():
         for _ in range(20):
             head.step()
         torch.cuda.synchronize()
-        for _ in range(200):
-            head.linear_only()
+        # the same back-to-back launch pattern as the timed region: one HIP graph of 200 launches
+        g = graph_of(head.linear_only, 200)
+        g.replay()
         torch.cuda.synchronize()
         return
 
@@ -170,8 +171,11 @@ def main():
     g_had.replay()
     had_us = event_time_us(g_had, R)
     achieved = head.alg_bytes / (lin_us * 1e-6) / 1e9
+    # HBM bytes per launch from the committed rocprofv3 --pmc runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0,
+    # factors from a plain copy of known size; profiles/qp_linear_pmc_*.md): only for the workload profiled
+    traffic = (18306 + 8) * 1024 if (a.cfg, a.layer, a.batch) == (3, 0, 1) else None
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "kernel": "qp_linear", "us_per_launch": round(lin_us, 3),
                 "algorithmic_bytes": head.alg_bytes}
 
@@ -179,8 +183,9 @@ def main():
     cases = []
     if not a.no_cases:
         del g_lin, g_had
-        todo = [(3, 0, 4), (3, 0, 8), (2, 0, 1), (1, 0, 1),
-                (4, 0, 1), (4, 1, 1), (4, 2, 1), (4, 3, 1), (4, 3, 8), (4, 3, 16), (4, 2, 8)]
+        todo = [(3, 0, 1), (3, 0, 4), (3, 0, 8), (2, 0, 1), (1, 0, 1),
+                (4, 0, 1), (4, 1, 1), (4, 2, 1), (4, 3, 1), (4, 3, 8), (4, 3, 16), (4, 2, 8),
+                (5, 0, 1), (5, 1, 1), (5, 2, 1), (5, 3, 1), (5, 2, 8), (5, 3, 8)]
         for cfg, li, B in todo:
             if (cfg, li, B) == (a.cfg, a.layer, a.batch):
                 continue
