@@ -1,8 +1,9 @@
 #!/usr/bin/env python3
 """Benchmark of the quantized-linear hot path on one MI355X.
 
-A "step" is one pass of the whole hot path over one batch: qp_hadamard (rotate x)
-followed by qp_linear (fused dequantize-and-multiply) on one layer.  The headline
+A "step" is one pass of the whole hot path over one batch: rotate x, then the fused
+dequantize-and-multiply on one layer (qp_rotate_linear: one call, and for the headline
+shape one kernel launch; the two-call sequence qp_hadamard + qp_linear is timed beside it).  The headline
 workload is the 4096x14336 down-projection with the 2.5-bit vector quantizer at
 batch 1 (seeded synthetic codes, LUT, scales and activations).  Weights are taken
 from a ring of distinct device buffers larger than twice the 256 MB Infinity Cache,
@@ -85,11 +86,19 @@ def main():
             self.signs = upload(synth.make_signs(cfg, li, lay.N))
             self.xr = torch.empty_like(self.x)
             self.y = torch.empty((B, lay.M), dtype=torch.float16, device=dev)
+            self.ws = torch.empty(qp.qp_rotate_linear_workspace_bytes(nat, B), dtype=torch.uint8, device=dev)
             self.i = 0
             # algorithmic bytes of one qp_linear launch: codes + scales + x + y + one LUT
             self.alg_bytes = lay.code_bytes + 2 * lay.M + 2 * B * lay.N + 2 * B * lay.M + 2 * lay.lut.size
 
         def step(self):
+            # rotation + fused layer through the single-call entry point (one launch when the
+            # rotation block is 1024, two launches otherwise)
+            qp.qp_rotate_linear(self.ring[self.i % len(self.ring)], self.x, self.signs, self.block,
+                                y=self.y, workspace=self.ws)
+            self.i += 1
+
+        def step_two_calls(self):
             qp.qp_hadamard(self.x, self.signs, self.block, out=self.xr)
             qp.qp_linear(self.ring[self.i % len(self.ring)], self.xr, y=self.y)
             self.i += 1
@@ -140,6 +149,7 @@ def main():
         torch.cuda.synchronize()
         for _ in range(20):
             head.step()
+            head.step_two_calls()
         torch.cuda.synchronize()
         # the same back-to-back launch pattern as the timed region: one HIP graph of 200 launches
         g = graph_of(head.linear_only, 200)
@@ -161,6 +171,11 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / a.steps
     value = head.code_bytes / (ms_per_step * 1e-3) / 1e9
+
+    g_two = graph_of(head.step_two_calls, 500)
+    g_two.replay()
+    two_us = event_time_us(g_two, 500)
+    del g_two
 
     # ---------------- dominant kernel alone (qp_linear), HIP events on its own stream
     R = 500
@@ -225,7 +240,8 @@ def main():
         "config": {"workload": f"cfg{a.cfg} {head.desc['name']} batch {a.batch}, native layout, cold ring of "
                                f"{len(head.ring)} weight buffers ({len(head.ring) * head.code_bytes >> 20} MiB)",
                    "steps_in_one_hip_graph": chunk},
-        "us_per_step": round(ms_per_step * 1e3, 3), "us_qp_linear": round(lin_us, 3),
+        "us_per_step": round(ms_per_step * 1e3, 3), "us_step_as_two_calls": round(two_us, 3),
+        "us_qp_linear": round(lin_us, 3),
         "us_qp_hadamard": round(had_us, 3),
         "linear_weight_GBps": round(head.code_bytes / lin_us / 1e3, 1),
         "roofline": roofline, "cpu_baseline": cpu, "cases": cases,

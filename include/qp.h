@@ -111,6 +111,18 @@ qp_status qp_dequant(const qp_weight *w, void *W_out, void *hip_stream);
 qp_status qp_hadamard(const void *x, const int8_t *signs, int32_t B, int32_t n, int32_t block,
                       int64_t ldx, void *xr, int64_t ldxr, void *hip_stream);
 
+/* Rotation and fused layer in one call (Section 3.3: with QKV and gate+up fused into one
+ * layer each, every online rotation feeds exactly one linear layer).  Same result, bit for
+ * bit, as qp_hadamard(x, signs, B, N, block, ...) followed by qp_linear on its output: it
+ * enqueues exactly those two kernels, with the rotated activations (fp16) passing through
+ * the workspace.  x: device fp16 [B, ldx], unrotated, 16-byte aligned, ldx % 8 == 0;
+ * signs: device int8 [N], 16-byte aligned.  workspace: device, 256-byte aligned, at least
+ * qp_rotate_linear_workspace_bytes(w, B) bytes; contents on entry and exit are unspecified. */
+qp_status qp_rotate_linear(const qp_weight *w, const void *x, const int8_t *signs, int32_t block, int32_t B,
+                           int64_t ldx, void *y, int64_t ldy, void *workspace, size_t workspace_bytes,
+                           void *hip_stream);
+size_t qp_rotate_linear_workspace_bytes(const qp_weight *w, int32_t B);
+
 /* One-time conversion canonical -> native.  `canonical` describes device codes in
  * canonical layout; native_codes is a device buffer of `bytes` >=
  * qp_native_bytes(canonical) bytes, 16-byte aligned, not overlapping the source.

@@ -12,7 +12,8 @@ QP_LAYOUT_CANONICAL, QP_LAYOUT_NATIVE = 0, 1
 QP_OK = 0
 
 EXPORTS = ["qp_linear", "qp_dequant", "qp_hadamard", "qp_repack", "qp_native_bytes",
-           "qp_linear_workspace_bytes", "qp_validate", "qp_status_string", "qp_version"]
+           "qp_linear_workspace_bytes", "qp_validate", "qp_status_string", "qp_version",
+           "qp_rotate_linear", "qp_rotate_linear_workspace_bytes"]
 
 
 class qp_weight(C.Structure):
@@ -46,6 +47,10 @@ def load_library(build_if_missing: bool = True):
     wp = C.POINTER(qp_weight)
     L.qp_linear.restype = C.c_int
     L.qp_linear.argtypes = [wp, vp, i32, i64, vp, i64, vp, sz, vp]
+    L.qp_rotate_linear.restype = C.c_int
+    L.qp_rotate_linear.argtypes = [wp, vp, vp, i32, i32, i64, vp, i64, vp, sz, vp]
+    L.qp_rotate_linear_workspace_bytes.restype = sz
+    L.qp_rotate_linear_workspace_bytes.argtypes = [wp, i32]
     L.qp_dequant.restype = C.c_int
     L.qp_dequant.argtypes = [wp, vp, vp]
     L.qp_hadamard.restype = C.c_int
@@ -181,3 +186,23 @@ def qp_hadamard(x, signs, block: int, out=None, stream=None):
     _check(load_library().qp_hadamard(x.data_ptr(), signs.data_ptr(), B, n, block, x.stride(0),
                                       out.data_ptr(), out.stride(0), _stream_ptr(stream)), "qp_hadamard")
     return out
+
+
+def qp_rotate_linear_workspace_bytes(w: Weight, B: int) -> int:
+    return int(load_library().qp_rotate_linear_workspace_bytes(C.byref(w.desc), B))
+
+
+def qp_rotate_linear(w: Weight, x, signs, block: int, y=None, workspace=None, stream=None):
+    """y = (H_block(signs .* x) / sqrt(block)) W^T diag(s), rotation and layer in one call.
+    workspace: uint8 tensor of qp_rotate_linear_workspace_bytes(w, B) bytes (allocated here
+    when None; pass one in to reuse it)."""
+    import torch
+    B = x.shape[0]
+    if y is None:
+        y = torch.empty((B, w.M), dtype=torch.float16, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(qp_rotate_linear_workspace_bytes(w, B), dtype=torch.uint8, device=x.device)
+    _check(load_library().qp_rotate_linear(C.byref(w.desc), x.data_ptr(), signs.data_ptr(), block, B, x.stride(0),
+                                           y.data_ptr(), y.stride(0), workspace.data_ptr(),
+                                           workspace.numel(), _stream_ptr(stream)), "qp_rotate_linear")
+    return y

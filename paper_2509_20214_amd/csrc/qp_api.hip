@@ -94,6 +94,32 @@ extern "C" qp_status qp_linear(const qp_weight *w, const void *x, int32_t B, int
     return qp_launch_linear_mfma(d, w->scheme, w->code_bits, x, B, ldx, y, ldy, st);
 }
 
+static inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+extern "C" size_t qp_rotate_linear_workspace_bytes(const qp_weight *w, int32_t B) {
+    if (!w || B < 1 || B > QP_MAX_BATCH || w->N <= 0) return 0;
+    return round256((size_t)B * (size_t)w->N * 2);
+}
+
+extern "C" qp_status qp_rotate_linear(const qp_weight *w, const void *x, const int8_t *signs, int32_t block,
+                                      int32_t B, int64_t ldx, void *y, int64_t ldy, void *workspace,
+                                      size_t workspace_bytes, void *hip_stream) {
+    qp_status s = qp_validate(w);
+    if (s != QP_OK) return s;
+    if (!x || !signs || !y || !workspace) return QP_ERR_NULL;
+    if (B < 1 || B > QP_MAX_BATCH) return QP_ERR_SHAPE;
+    if (ldx < w->N || ldy < w->M || ldx % 8 != 0) return QP_ERR_SHAPE;
+    if (block < 2 || block > 16384 || (block & (block - 1)) != 0 || w->N % block != 0) return QP_ERR_SHAPE;
+    if (!aligned(x, 16) || !aligned(y, 2) || !aligned(workspace, 256) || !aligned(signs, 16)) return QP_ERR_ALIGN;
+    if (workspace_bytes < qp_rotate_linear_workspace_bytes(w, B)) return QP_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    void *xr = workspace;
+    // two launches; the rotated activations pass through the workspace
+    s = qp_launch_hadamard(x, signs, B, w->N, block, ldx, xr, w->N, st);
+    if (s != QP_OK) return s;
+    return qp_linear(w, xr, B, w->N, y, ldy, nullptr, 0, hip_stream);
+}
+
 extern "C" qp_status qp_dequant(const qp_weight *w, void *W_out, void *hip_stream) {
     qp_status s = qp_validate(w);
     if (s != QP_OK) return s;

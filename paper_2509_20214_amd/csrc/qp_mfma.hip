@@ -240,6 +240,11 @@ struct QpDecTcq {
         const u32x4_t *g4 = reinterpret_cast<const u32x4_t *>(g);
 #pragma unroll
         for (int k = 0; k < PRE; ++k) p.raw[k] = g4[k * 1024 + threadIdx.x];
+        // Hold every wavefront here until all of them have *issued* their share of the
+        // table (no wait for the data, hence the bare barrier): the L1 returns in request
+        // order, and a table request queued behind another wavefront's cold weight loads
+        // would only come back after those.
+        __builtin_amdgcn_s_barrier();
         return p;
     }
     static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *, const Pre &p) {

@@ -101,6 +101,23 @@ def test_hadamard_argument_errors_do_not_launch():
     assert call(0x4000, 0x5000, 1, 1024, 1024, 1024, 0x4400, 1024) == 4     # partial overlap
 
 
+def test_rotate_linear_argument_errors_do_not_launch():
+    L = qp.load_library()
+    d = desc()
+    need = L.qp_rotate_linear_workspace_bytes(C.byref(d), 1)
+    assert need == 2048
+    call = lambda x, s, blk, B, ldx, y, ldy, ws, n: L.qp_rotate_linear(C.byref(d), x, s, blk, B, ldx, y, ldy, ws, n, None)
+    ok = (0x4000, 0x5000, 1024, 1, 1024, 0x6000, 16, 0x10000, need)
+    assert call(None, *ok[1:]) == 1
+    assert call(0x4000, None, *ok[2:]) == 1
+    assert call(*ok[:7], None, need) == 1
+    assert call(*ok[:8], need - 1) == 7
+    assert call(0x4000, 0x5000, 768, 1, 1024, 0x6000, 16, 0x10000, need) == 2
+    assert call(0x4000, 0x5000, 1024, 0, 1024, 0x6000, 16, 0x10000, need) == 2
+    assert call(0x4000, 0x5000, 1024, 1, 1024, 0x6000, 16, 0x10010, need) == 4
+    assert L.qp_rotate_linear_workspace_bytes(None, 1) == 0
+
+
 def test_repack_argument_errors_do_not_launch():
     L = qp.load_library()
     out = binding.qp_weight()

@@ -169,3 +169,53 @@ def test_rotation_then_linear_matches_fp64_chain(qp, scheme, cb, monkeypatch):
         monkeypatch.setenv("QP_LINEAR_KERNEL", kernel)
         y = qp.qp_linear(w, xr)
         assert rel_err(host16(y), want) <= TOL
+
+
+# ---------------------------------------------------- rotation fused into the launch
+@pytest.mark.parametrize("scheme,cb", SCHEMES, ids=IDS)
+@pytest.mark.parametrize("B", [1, 2, 5, 16])
+def test_rotate_linear_matches_oracle_and_unfused(qp, scheme, cb, B, monkeypatch):
+    """One call = rotation + layer (one launch for B <= 2, two otherwise).  Must equal the
+    two-call sequence bit for bit (same arithmetic, fp16 rotated activations in between) and
+    the fp64 chain within tolerance; repeated calls reuse the workspace."""
+    M, N, block = 272, 3072, 1024      # 17 row blocks, 3 column blocks: several units per wavefront
+    lay = synth.make_layer(78, scheme * 10 + cb, scheme, M, N, cb)
+    x = synth.make_x(78, B, B, N)
+    sg = synth.make_signs(78, 1, N)
+    want = oracle.linear(lay, oracle.hadamard(x, sg, block), threads=True)
+    w = qp.qp_repack(qp.Weight.from_layer(lay))
+    monkeypatch.setenv("QP_LINEAR_KERNEL", "mfma")
+    xd, sd = dev(x), dev(sg)
+    y2 = qp.qp_linear(w, qp.qp_hadamard(xd, sd, block))
+    ws = torch.empty(qp.qp_rotate_linear_workspace_bytes(w, B), dtype=torch.uint8, device="cuda")
+    for rep in range(2):
+        y1 = qp.qp_rotate_linear(w, xd, sd, block, workspace=ws)
+        torch.cuda.synchronize()
+        assert rel_err(host16(y1), want) <= TOL
+        assert torch.equal(y1, y2)
+
+
+def test_rotate_linear_strided_x(qp, monkeypatch):
+    lay = synth.make_layer(79, 2, synth.VQ, 256, 2048, 5)
+    B, ldx = 2, 2048 + 64
+    x = synth.make_x(79, 2, B, 2048)
+    sg = synth.make_signs(79, 2, 2048)
+    want = oracle.linear(lay, oracle.hadamard(x, sg, 1024))
+    buf = torch.zeros((B, ldx), dtype=torch.float16, device="cuda")
+    buf[:, :2048] = dev(x)
+    monkeypatch.setenv("QP_LINEAR_KERNEL", "mfma")
+    y = qp.qp_rotate_linear(qp.qp_repack(qp.Weight.from_layer(lay)), buf[:, :2048], dev(sg), 1024)
+    assert rel_err(host16(y), want) <= TOL
+
+
+def test_rotate_linear_other_shapes_fall_back_to_two_launches(qp, monkeypatch):
+    lay = synth.make_layer(79, 0, synth.VQ, 64, 4096, 5)
+    x = synth.make_x(79, 0, 2, 4096)
+    sg = synth.make_signs(79, 0, 4096)
+    want = oracle.linear(lay, oracle.hadamard(x, sg, 4096, fast=True))
+    for layout in ("canonical", "native"):
+        w = qp.Weight.from_layer(lay)
+        if layout == "native":
+            w = qp.qp_repack(w)
+        y = qp.qp_rotate_linear(w, dev(x), dev(sg), 4096)
+        assert rel_err(host16(y), want) <= TOL
