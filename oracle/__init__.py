@@ -49,6 +49,7 @@ def lib():
         L.qpo_linear_rows.argtypes = [C.c_int, _u8p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int,
                                       C.c_int, C.c_int, _u16p, _u16p, _f64p, C.c_int, C.c_int,
                                       C.c_int, _f64p, C.c_int]
+        L.qpo_hybrid_lut.argtypes = [_u16p, C.c_int, _u16p]
         L.qpo_num_threads.restype = C.c_int
         L.qpo_rtn_sq.argtypes = [_f64p, C.c_int64, C.c_int, _u16p, _u8p]
         L.qpo_rtn_vq.argtypes = [_f64p, C.c_int64, C.c_int, C.c_int, _u16p, _u8p]
@@ -77,13 +78,32 @@ def half_to_double(a) -> np.ndarray:
     return out.reshape(h.shape)
 
 
+TCQH = 3   # trellis with the hybrid computed code book: expanded here, then decoded as a trellis
+
+
+def hybrid_lut(tlut16, tlut_bits: int) -> np.ndarray:
+    """Expanded 2^16 x 2 table (uint16 fp16 patterns) of the hybrid code book."""
+    t = _u16(tlut16).reshape(-1)
+    assert t.size == (1 << tlut_bits) * 2
+    out = np.empty(65536 * 2, dtype=np.uint16)
+    lib().qpo_hybrid_lut(t, tlut_bits, out)
+    return out.reshape(65536, 2)
+
+
+def _scheme_and_lut(layer):
+    if layer.scheme == TCQH:
+        return 2, hybrid_lut(layer.lut, layer.tlut_bits).reshape(-1)
+    return layer.scheme, _u16(layer.lut)
+
+
 def decode(layer) -> np.ndarray:
     """Unscaled W^ as uint16 fp16 patterns [M, N] of a synth.Layer-like object."""
     out = np.empty((layer.M, layer.N), dtype=np.uint16)
     codes = np.ascontiguousarray(layer.codes)
-    rc = lib().qpo_decode(layer.scheme, codes.reshape(-1), codes.shape[1], layer.M, layer.N,
+    scheme, lut = _scheme_and_lut(layer)
+    rc = lib().qpo_decode(scheme, codes.reshape(-1), codes.shape[1], layer.M, layer.N,
                           layer.code_bits, layer.vec, layer.window_bits, layer.tile,
-                          _u16(layer.lut), out.reshape(-1))
+                          lut, out.reshape(-1))
     assert rc == 0
     return out
 
@@ -118,9 +138,10 @@ def linear(layer, x, *, rows=None, threads: bool = False) -> np.ndarray:
     y = np.zeros((B, layer.M), dtype=np.float64)
     r0, r1 = rows if rows is not None else (0, layer.M)
     codes = np.ascontiguousarray(layer.codes)
-    rc = lib().qpo_linear_rows(layer.scheme, codes.reshape(-1), codes.shape[1], layer.M, layer.N,
+    scheme, lut = _scheme_and_lut(layer)
+    rc = lib().qpo_linear_rows(scheme, codes.reshape(-1), codes.shape[1], layer.M, layer.N,
                                layer.code_bits, layer.vec, layer.window_bits, layer.tile,
-                               _u16(layer.lut), _u16(layer.scales), x.reshape(-1), B, r0, r1,
+                               lut, _u16(layer.scales), x.reshape(-1), B, r0, r1,
                                y.reshape(-1), 1 if threads else 0)
     assert rc == 0
     return y

@@ -146,6 +146,24 @@ void qpo_decode_row_tcq_recurrence(const uint8_t *row, int N, int s, int L, int 
     }
 }
 
+/* Hybrid computed code book of the trellis quantizer (Appendix C.3.1, "Codebook
+ * construction"): the 2^16 x 2 table is not stored but derived from a small table
+ * tlut[2^tb][2].  For a 16-bit state x, with h = x (x + 1) (no overflow: h < 2^32),
+ *   - the tb bits of h just below bit 15 select the entry,  idx = (h >> (15 - tb)) mod 2^tb,
+ *   - bit 15 of h negates component 0 of that entry.
+ * lut receives the expanded table, fp16 patterns [65536][2]. */
+void qpo_hybrid_lut(const uint16_t *tlut, int tb, uint16_t *lut)
+{
+    for (uint32_t x = 0; x < 65536u; ++x) {
+        uint64_t h = (uint64_t)x * ((uint64_t)x + 1u);
+        uint32_t idx = (uint32_t)((h >> (15 - tb)) & ((1u << tb) - 1u));
+        int negate = (int)((h >> 15) & 1u);
+        uint16_t c0 = tlut[2 * idx], c1 = tlut[2 * idx + 1];
+        lut[2 * x] = negate ? (uint16_t)(c0 ^ 0x8000u) : c0;   /* fp16 negation = sign bit */
+        lut[2 * x + 1] = c1;
+    }
+}
+
 enum { QPO_SQ = 0, QPO_VQ = 1, QPO_TCQ = 2 };
 
 static void decode_row(int scheme, const uint8_t *row, int N, int code_bits, int V, int L, int T,

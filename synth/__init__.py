@@ -28,8 +28,8 @@ import numpy as np
 
 TENSOR_CODES, TENSOR_LUT, TENSOR_SCALES, TENSOR_X, TENSOR_SIGNS = 0, 1, 2, 3, 4
 
-SQ, VQ, TCQ = 0, 1, 2
-SCHEME_NAMES = {SQ: "sq", VQ: "vq", TCQ: "tcq"}
+SQ, VQ, TCQ, TCQH = 0, 1, 2, 3   # TCQH: trellis (V=2) with the hybrid computed code book
+SCHEME_NAMES = {SQ: "sq", VQ: "vq", TCQ: "tcq", TCQH: "tcqh"}
 
 
 def rng(cfg: int, layer: int, tensor: int) -> np.random.Generator:
@@ -88,6 +88,13 @@ def vq_lut(cfg: int, layer: int, code_bits: int) -> np.ndarray:
     return rng(cfg, layer, TENSOR_LUT).standard_normal((1 << code_bits, 2)).astype(np.float16)
 
 
+def tcqh_tlut(cfg: int, layer: int, tlut_bits: int = 9) -> np.ndarray:
+    """[2^tlut_bits, 2] fp16 points drawn N(0,1): the small table from which the hybrid
+    code book is computed (the paper fits it by k-means on 2-D Gaussian samples,
+    Appendix C.3.1; seeded Gaussian points stand in for it)."""
+    return rng(cfg, layer, TENSOR_LUT).standard_normal((1 << tlut_bits, 2)).astype(np.float16)
+
+
 def tcq_lut(cfg: int, layer: int, L: int = 16, V: int = 1) -> np.ndarray:
     """[2^L * V] fp16 values drawn N(0,1): the state -> value table."""
     return rng(cfg, layer, TENSOR_LUT).standard_normal((1 << L) * V).astype(np.float16)
@@ -110,6 +117,7 @@ class Layer:
     lut: np.ndarray        # float16, flat
     scales: np.ndarray     # float16 [M]
     name: str = ""
+    tlut_bits: int = 0     # TCQH: log2 of the small table's entries, else 0
     meta: dict = field(default_factory=dict)
 
     @property
@@ -134,9 +142,9 @@ def row_bytes_for(scheme: int, N: int, code_bits: int, vec: int) -> int:
 
 def make_layer(cfg: int, layer: int, scheme: int, M: int, N: int, code_bits: int,
                *, vec: int | None = None, window_bits: int = 16, tile: int = 256,
-               lut: np.ndarray | None = None, name: str = "") -> Layer:
+               lut: np.ndarray | None = None, name: str = "", tlut_bits: int = 9) -> Layer:
     if vec is None:
-        vec = 2 if scheme == VQ else 1
+        vec = 2 if scheme in (VQ, TCQH) else 1
     rb = row_bytes_for(scheme, N, code_bits, vec)
     codes = rng(cfg, layer, TENSOR_CODES).integers(0, 256, size=(M, rb), dtype=np.uint8)
     scales = rng(cfg, layer, TENSOR_SCALES).uniform(0.5, 1.5, size=M).astype(np.float16)
@@ -145,13 +153,17 @@ def make_layer(cfg: int, layer: int, scheme: int, M: int, N: int, code_bits: int
             lut = sq_lut(code_bits)
         elif scheme == VQ:
             lut = vq_lut(cfg, layer, code_bits).reshape(-1)
+        elif scheme == TCQH:
+            lut = tcqh_tlut(cfg, layer, tlut_bits).reshape(-1)
         else:
             lut = tcq_lut(cfg, layer, window_bits, vec)
+    trellis = scheme in (TCQ, TCQH)
     return Layer(scheme=scheme, M=M, N=N, code_bits=code_bits, vec=vec,
-                 window_bits=window_bits if scheme == TCQ else 0,
-                 tile=tile if scheme == TCQ else 0,
+                 window_bits=window_bits if trellis else 0,
+                 tile=tile if trellis else 0,
                  codes=codes, lut=np.ascontiguousarray(lut, dtype=np.float16).reshape(-1),
-                 scales=scales, name=name or f"cfg{cfg}.L{layer}")
+                 scales=scales, name=name or f"cfg{cfg}.L{layer}",
+                 tlut_bits=tlut_bits if scheme == TCQH else 0)
 
 
 def make_x(cfg: int, layer: int, B: int, N: int) -> np.ndarray:

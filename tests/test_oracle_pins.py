@@ -398,3 +398,79 @@ def test_linear_equals_numpy_float64(scheme, cb):
     # rows= computes only that range
     part = oracle.linear(lay, x, rows=(5, 9))
     assert np.array_equal(part[:, 5:9], got[:, 5:9]) and np.all(part[:, :5] == 0) and np.all(part[:, 9:] == 0)
+
+
+# ------------------------------------------- hybrid computed code book (V = 2 trellis)
+def test_hybrid_lut_hand_examples_and_structure():
+    """Appendix C.3.1: h = x (x + 1); the tb bits of h below bit 15 index the small table,
+    bit 15 negates component 0.  Hand-worked states (tb = 9, so idx = (h >> 6) mod 512):
+      x = 0     h = 0           idx 0    keep
+      x = 8     h = 72          idx 1    keep
+      x = 181   h = 32942       idx 2    negate  (32942 = 32768 + 174; 174 >> 6 = 2)
+      x = 255   h = 65280       idx 508  negate  (65280 >> 6 = 1020 = 512 + 508; bit 15 set)
+      x = 65535 h = 0xFFFF0000  idx 0    keep
+    """
+    tb = 9
+    tlut = synth.tcqh_tlut(40, 0, tb)
+    t = tlut.view(np.uint16)
+    lut = oracle.hybrid_lut(tlut, tb)
+    for x, idx, neg in [(0, 0, 0), (8, 1, 0), (181, 2, 1), (255, 508, 1), (65535, 0, 0)]:
+        assert lut[x, 1] == t[idx, 1]
+        assert lut[x, 0] == (t[idx, 0] ^ (0x8000 if neg else 0)), x
+    # structure: every entry is a table entry up to the sign of component 0
+    vals = oracle.half_to_double(lut)
+    tv = oracle.half_to_double(t)
+    comp1 = {float(v) for v in tv[:, 1]}
+    assert all(float(v) in comp1 for v in vals[::97, 1])
+    mag0 = {abs(float(v)) for v in tv[:, 0]}
+    assert all(abs(float(v)) in mag0 for v in vals[::97, 0])
+    # the hash spreads the states: each of the 512 entries serves 65536/512 = 128 states on average,
+    # half of them negated
+    pairs = (lut[:, 1].astype(np.int64) << 16) | (lut[:, 0] & 0x7FFF)
+    _, counts = np.unique(pairs, return_counts=True)
+    assert len(counts) == 512 and counts.min() >= 32 and counts.max() <= 512
+    x = np.arange(65536, dtype=np.uint64)
+    assert 0.45 < np.mean(((x * (x + 1)) >> 15) & 1) < 0.55
+    for tb2 in (10, 11):
+        tl = synth.tcqh_tlut(40, tb2, tb2)
+        l2 = oracle.hybrid_lut(tl, tb2)
+        h = 255 * 256
+        assert l2[255, 1] == tl.view(np.uint16)[(h >> (15 - tb2)) & ((1 << tb2) - 1), 1]
+
+
+@pytest.mark.parametrize("s", [3, 4, 5, 8, 10])
+def test_tcqh_decode_is_trellis_decode_of_expanded_table(s):
+    """bits per weight = s / 2 (Section 3.2); the layer with the computed code book decodes
+    like a V = 2 trellis whose table is the expanded one (window form = shift register)."""
+    tb = 9 if s <= 8 else 10
+    lay = synth.make_layer(41, s, synth.TCQH, 3, 768, s, tlut_bits=tb)
+    assert lay.row_bytes * 8 == 768 // 2 * s
+    W = oracle.decode(lay)
+    full = oracle.hybrid_lut(lay.lut, tb)
+    b = np.empty(768, dtype=np.uint16)
+    for j in range(3):
+        oracle.lib().qpo_decode_row_tcq_recurrence(lay.codes[j], 768, s, 16, 256, 2, full.reshape(-1), b)
+        assert np.array_equal(W[j], b)
+    # first pair of a tile = table entry of the first 16 bits
+    st = int(lay.codes[0, 0]) | (int(lay.codes[0, 1]) << 8)
+    assert W[0, 0] == full[st, 0] and W[0, 1] == full[st, 1]
+
+
+def test_tcqh_two_bit_distortion_between_bound_and_scalar():
+    """s = 4, V = 2 (2 bits per weight), hybrid code book from 512 Gaussian points: the
+    distortion reached by Viterbi through this decode lies between 2^-4 and the paper's
+    2-bit scalar figure (the paper's own 0.07101 needs its k-means table: context only)."""
+    gold = golden_distortion()
+    tb, s, T = 9, 4, 256
+    tlut = synth.tcqh_tlut(2, 7, tb)
+    full = oracle.hybrid_lut(tlut, tb).view(np.float16)
+    ntiles = 16
+    v = np.random.default_rng(21).standard_normal((ntiles, T))
+    streams, errs = oracle.tcq_encode_tiles(v, s, 16, T, 2, full.reshape(-1))
+    lay = synth.make_layer(42, 0, synth.TCQH, ntiles, T, s, lut=tlut.reshape(-1))
+    lay.codes = streams
+    w = oracle.half_to_double(oracle.decode(lay))
+    mse = ((w - v) ** 2).mean() / (v ** 2).mean()
+    assert abs(((w - v) ** 2).sum(1) - errs).max() < 1e-9
+    assert 2.0 ** -4 < mse < gold["NUQ-2"][1], mse
+    assert mse < 0.09, mse
