@@ -12,6 +12,10 @@
  *   QP_SQ   non-uniform scalar quantizer:  W^[j,i]           = LUT[code]          (App. C.1 "Dequantization")
  *   QP_VQ   2-D vector quantizer:          (W^[j,2m],W^[j,2m+1]) = LUT[code]      (App. C.2 "Dequantization")
  *   QP_TCQ  bitshift trellis, tail-biting: W^[j,tT+i]        = LUT[r_t[ik : ik+L]] (App. C.3.1 "Dequantization")
+ *   QP_TCQH the paper's own trellis: V = 2 weights per step of s bits (s/2 bits per weight),
+ *           (W^[j,tT+2i], W^[j,tT+2i+1]) = LUT[r_t[is : is+16]], with the 2^16 x 2 LUT *computed* from a
+ *           small table tlut[2^tb][2]: h = x(x+1), entry (h >> (15-tb)) mod 2^tb, component 0 negated
+ *           when bit 15 of h is set (App. C.3.1 "Codebook construction")
  *
  * Notation: M = out_features = rows of W^, N = in_features = columns, B = batch.
  *
@@ -60,7 +64,7 @@ typedef enum {
     QP_ERR_WORKSPACE = 7    /* workspace smaller than qp_linear_workspace_bytes()          */
 } qp_status;
 
-typedef enum { QP_SQ = 0, QP_VQ = 1, QP_TCQ = 2 } qp_scheme;
+typedef enum { QP_SQ = 0, QP_VQ = 1, QP_TCQ = 2, QP_TCQH = 3 } qp_scheme;
 typedef enum { QP_LAYOUT_CANONICAL = 0, QP_LAYOUT_NATIVE = 1 } qp_layout;
 
 #define QP_MAX_BATCH 16
@@ -69,6 +73,8 @@ typedef enum { QP_LAYOUT_CANONICAL = 0, QP_LAYOUT_NATIVE = 1 } qp_layout;
  *   QP_SQ : vec 1, code_bits 4                       (16-entry fp16 LUT)
  *   QP_VQ : vec 2, code_bits 5 or 7                  (2.5 / 3.5 bits per weight; LUT fp16 [2^code_bits][2])
  *   QP_TCQ: vec 1, window_bits 16, tile 256, code_bits 2, 3 or 4  (LUT fp16 [65536])
+ *   QP_TCQH: vec 2, window_bits 16, tile 256, code_bits s = 3..8 (1.5 .. 4 bits per weight),
+ *            tlut_bits 9  (lut = the small table, fp16 [512][2])
  * Fused layers (QKV, gate+up; Section 4.2) are one qp_weight with M the sum of the
  * members' out_features. */
 typedef struct {
@@ -81,8 +87,10 @@ typedef struct {
     int32_t layout;      /* qp_layout                                                          */
     int64_t row_stride;  /* canonical: bytes between rows of codes, multiple of 16, >= row bytes */
     const void *codes;   /* device, 16-byte aligned                                            */
-    const void *lut;     /* device, fp16, 4-byte aligned: SQ 2^code_bits; VQ 2^code_bits*vec; TCQ 2^L*vec */
+    const void *lut;     /* device, fp16, 4-byte aligned: SQ 2^code_bits; VQ 2^code_bits*vec; TCQ 2^L*vec; TCQH 2^tlut_bits*vec */
     const void *scales;  /* device, fp16 [M], 2-byte aligned: per-output-channel factor s      */
+    int32_t tlut_bits;   /* QP_TCQH: log2 of the small table's entries; otherwise 0            */
+    int32_t reserved;    /* 0                                                                  */
 } qp_weight;
 
 /* Fused dequantize-and-multiply (Section 3.3 "Kernel implementation"; the fused

@@ -7,7 +7,7 @@ import os
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libqp.so")
 
-QP_SQ, QP_VQ, QP_TCQ = 0, 1, 2
+QP_SQ, QP_VQ, QP_TCQ, QP_TCQH = 0, 1, 2, 3
 QP_LAYOUT_CANONICAL, QP_LAYOUT_NATIVE = 0, 1
 QP_OK = 0
 
@@ -19,7 +19,8 @@ EXPORTS = ["qp_linear", "qp_dequant", "qp_hadamard", "qp_repack", "qp_native_byt
 class qp_weight(C.Structure):
     _fields_ = [("scheme", C.c_int32), ("M", C.c_int32), ("N", C.c_int32), ("code_bits", C.c_int32),
                 ("vec", C.c_int32), ("window_bits", C.c_int32), ("tile", C.c_int32), ("layout", C.c_int32),
-                ("row_stride", C.c_int64), ("codes", C.c_void_p), ("lut", C.c_void_p), ("scales", C.c_void_p)]
+                ("row_stride", C.c_int64), ("codes", C.c_void_p), ("lut", C.c_void_p), ("scales", C.c_void_p),
+                ("tlut_bits", C.c_int32), ("reserved", C.c_int32)]
 
 
 class QpError(RuntimeError):
@@ -96,12 +97,12 @@ class Weight:
     C descriptor that points at them."""
 
     def __init__(self, scheme, M, N, code_bits, vec, window_bits, tile, codes, lut, scales,
-                 layout=QP_LAYOUT_CANONICAL, row_stride=None):
+                 layout=QP_LAYOUT_CANONICAL, row_stride=None, tlut_bits=0):
         self.codes, self.lut, self.scales = codes, lut, scales
         if row_stride is None:
             row_stride = codes.shape[1] if (layout == QP_LAYOUT_CANONICAL and codes.dim() == 2) else 0
         self.desc = qp_weight(scheme, M, N, code_bits, vec, window_bits, tile, layout, row_stride,
-                              codes.data_ptr(), lut.data_ptr(), scales.data_ptr())
+                              codes.data_ptr(), lut.data_ptr(), scales.data_ptr(), tlut_bits, 0)
 
     @classmethod
     def from_layer(cls, layer, device="cuda"):
@@ -112,7 +113,7 @@ class Weight:
         lut = torch.from_numpy(np.ascontiguousarray(layer.lut).view(np.int16)).to(device)
         scales = torch.from_numpy(np.ascontiguousarray(layer.scales).view(np.int16)).to(device)
         return cls(layer.scheme, layer.M, layer.N, layer.code_bits, layer.vec, layer.window_bits,
-                   layer.tile, codes, lut, scales)
+                   layer.tile, codes, lut, scales, tlut_bits=getattr(layer, "tlut_bits", 0))
 
     @property
     def M(self):
@@ -149,7 +150,7 @@ def qp_repack(w: Weight, stream=None) -> Weight:
     out = torch.empty(nbytes, dtype=torch.uint8, device=w.codes.device)
     d = w.desc
     nw = Weight(d.scheme, d.M, d.N, d.code_bits, d.vec, d.window_bits, d.tile, out, w.lut, w.scales,
-                layout=QP_LAYOUT_NATIVE, row_stride=0)
+                layout=QP_LAYOUT_NATIVE, row_stride=0, tlut_bits=d.tlut_bits)
     tmp = qp_weight()
     _check(load_library().qp_repack(C.byref(w.desc), C.byref(tmp), out.data_ptr(), nbytes,
                                     _stream_ptr(stream)), "qp_repack")

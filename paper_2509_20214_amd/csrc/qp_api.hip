@@ -20,6 +20,11 @@ static qp_status scheme_supported(const qp_weight *w) {
                     w->code_bits <= 4)
                        ? QP_OK
                        : QP_ERR_UNSUPPORTED;
+        case QP_TCQH:
+            return (w->vec == 2 && w->window_bits == 16 && w->tile == 256 && w->code_bits >= 3 &&
+                    w->code_bits <= 8 && w->tlut_bits == 9)
+                       ? QP_OK
+                       : QP_ERR_UNSUPPORTED;
         default:
             return QP_ERR_UNSUPPORTED;
     }
@@ -34,7 +39,7 @@ extern "C" qp_status qp_validate(const qp_weight *w) {
     if (s != QP_OK) return s;
     if (w->M <= 0 || w->N <= 0) return QP_ERR_SHAPE;
     if (w->N % 8 != 0) return QP_ERR_SHAPE;
-    if (w->scheme == QP_TCQ && w->N % w->tile != 0) return QP_ERR_SHAPE;
+    if ((w->scheme == QP_TCQ || w->scheme == QP_TCQH) && w->N % w->tile != 0) return QP_ERR_SHAPE;
     if (!w->codes || !w->lut || !w->scales) return QP_ERR_NULL;
     if (w->layout == QP_LAYOUT_CANONICAL) {
         if (w->row_stride % 16 != 0) return QP_ERR_ALIGN;
@@ -59,6 +64,7 @@ static QpW make_dev(const qp_weight *w) {
     d.row_stride = w->row_stride;
     d.layout = w->layout;
     d.nbc = w->N / 1024;
+    d.tlut_bits = w->tlut_bits;
     return d;
 }
 

@@ -21,16 +21,17 @@ struct QpW {
     int64_t row_stride;  // canonical layout only
     int32_t layout;      // qp_layout
     int32_t nbc;         // N / 1024, column blocks per block row (native layout)
+    int32_t tlut_bits;   // QP_TCQH: log2 entries of the small table
 };
 
 // Compile-time facts about a (scheme, code_bits) pair.
 template <int S, int CB>
 struct QpTraits {
-    static constexpr int V = (S == QP_VQ) ? 2 : 1;
+    static constexpr int V = (S == QP_VQ || S == QP_TCQH) ? 2 : 1;
     static constexpr int BITS8 = 8 * CB / V;           // stream bits that 8 weights advance
     static constexpr int SPAN = 32 * CB / V;           // bytes of a 256-weight span
     static constexpr int PIECES = SPAN / 16;           // 16-byte pieces per span
-    static constexpr int LUT_HALVES = (S == QP_TCQ) ? 65536 : (1 << CB) * V;
+    static constexpr int LUT_HALVES = (S == QP_TCQ) ? 65536 : (S == QP_TCQH) ? 1024 : (1 << CB) * V;
     static constexpr int BLOCK_BYTES = 64 * SPAN;      // one 16 x 1024 native block
 };
 
@@ -94,6 +95,41 @@ __device__ __forceinline__ void qp_decode8(uint64_t bits, const uint16_t *lut, u
     }
 }
 
+// Entry of the hybrid computed code book for a 16-bit trellis state (Appendix C.3.1,
+// "Codebook construction"): h = x (x + 1); the tb bits of h below bit 15 index the small
+// table (half2 entries), bit 15 of h negates component 0 - the low half, whose sign bit is
+// bit 15 of the dword as well.
+__device__ __forceinline__ uint32_t qp_hybrid_entry(uint32_t state, const uint32_t *tlut2, int tb) {
+    const uint32_t h = state * (state + 1u);
+    const uint32_t idx = (h >> (15 - tb)) & ((1u << tb) - 1u);
+    return tlut2[idx] ^ (h & 0x8000u);
+}
+
+// 8 consecutive weights (group `grp`) of row `row`, any layout, any scheme.
+template <int S, int CB>
+__device__ __forceinline__ void qp_group_decode(const QpW &w, int row, int grp, const uint16_t *lut,
+                                                uint16_t (&v)[8]) {
+    if constexpr (S == QP_TCQH) {
+        using T = QpTraits<S, CB>;
+        const int tile = grp >> 5, u = grp & 31;
+        const uint32_t *lut2 = reinterpret_cast<const uint32_t *>(lut);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int bit = (4 * u + c) * CB;            // step 4u+c of the tile, CB bits per step
+            const int d0 = bit >> 5, r = bit & 31;
+            const int d1 = (d0 + 1 == T::SPAN / 4) ? 0 : d0 + 1;   // tail-biting wrap
+            const uint32_t lo = *qp_dword_ptr<T::SPAN>(w, row, tile * T::SPAN + d0 * 4);
+            const uint32_t hi = *qp_dword_ptr<T::SPAN>(w, row, tile * T::SPAN + d1 * 4);
+            const uint32_t state = (uint32_t)(((((uint64_t)hi) << 32) | lo) >> r) & 0xffffu;
+            const uint32_t e = qp_hybrid_entry(state, lut2, w.tlut_bits);
+            v[2 * c] = (uint16_t)e;
+            v[2 * c + 1] = (uint16_t)(e >> 16);
+        }
+    } else {
+        qp_decode8<S, CB>(qp_group_bits<S, CB>(w, row, grp), lut, v);
+    }
+}
+
 // Copy the table into LDS with all threads of the workgroup (caller synchronises).
 template <int HALVES>
 __device__ __forceinline__ void qp_stage_lut(const uint16_t *g, uint16_t *s) {
@@ -121,5 +157,11 @@ __device__ __forceinline__ float qp_half_bits_to_float(uint16_t h) {
         else if ((scheme) == QP_TCQ && (cb) == 2) { CALL(QP_TCQ, 2); }                \
         else if ((scheme) == QP_TCQ && (cb) == 3) { CALL(QP_TCQ, 3); }                \
         else if ((scheme) == QP_TCQ && (cb) == 4) { CALL(QP_TCQ, 4); }                \
+        else if ((scheme) == QP_TCQH && (cb) == 3) { CALL(QP_TCQH, 3); }              \
+        else if ((scheme) == QP_TCQH && (cb) == 4) { CALL(QP_TCQH, 4); }              \
+        else if ((scheme) == QP_TCQH && (cb) == 5) { CALL(QP_TCQH, 5); }              \
+        else if ((scheme) == QP_TCQH && (cb) == 6) { CALL(QP_TCQH, 6); }              \
+        else if ((scheme) == QP_TCQH && (cb) == 7) { CALL(QP_TCQH, 7); }              \
+        else if ((scheme) == QP_TCQH && (cb) == 8) { CALL(QP_TCQH, 8); }              \
         else return QP_ERR_UNSUPPORTED;                                               \
     } while (0)

@@ -27,6 +27,7 @@
 //              (Keeping the table in a VGPR and fetching it with ds_bpermute saves the
 //              AND per code but ran 2x slower: the permute path has a lower rate.)
 //   TCQ      : the 2^16-entry fp16 table, 128 KiB of LDS, read with ds_read_u16.
+//   TCQH     : computed code book, 1024-entry bank-replicated table (see QpDecTcqh).
 //
 // A workgroup owns a contiguous range of 16-row blocks and walks it in passes of G
 // row blocks; the G * (N / 1024) units of a pass are dealt round-robin to the
@@ -266,6 +267,57 @@ struct QpDecTcq {
         return a;
     }
 };
+// The paper's own trellis (V = 2, computed hybrid code book).  The small table has 2^9
+// half2 entries; the sign flag is bit 15 of h and the index bits sit right below it, so
+// bits [15:6] of h = x (x + 1) are one 10-bit index into a table of 1024 entries in which
+// the upper half is the lower half with component 0 negated.  That table is replicated
+// once per LDS bank like the scalar / 7-bit vector tables (128 KiB), so the lookups - one
+// per *two* weights - never collide; the per-state work is a 24-bit multiply-add, a
+// bit-field extract and a shift-or.
+template <int K>
+struct QpDecTcqh : QpBankTable<1024> {
+    struct Pre { uint32_t raw; };
+    static __device__ __forceinline__ void early(uint8_t *, uint16_t *, const uint16_t *) {}
+    static __device__ __forceinline__ Pre pre(const uint16_t *g) {  // needs blockDim.x >= 512
+        Pre p;
+        p.raw = (threadIdx.x < 512) ? reinterpret_cast<const uint32_t *>(g)[threadIdx.x] : 0u;
+        __builtin_amdgcn_s_barrier();   // every wavefront's table request is queued before any weight load
+        return p;
+    }
+    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *small, const Pre &p) {
+        uint32_t *s32 = reinterpret_cast<uint32_t *>(small);
+        if (threadIdx.x < 512) s32[threadIdx.x] = p.raw;
+        __syncthreads();
+        uint32_t *t32 = reinterpret_cast<uint32_t *>(tab);
+        for (int idx = threadIdx.x; idx < 1024 * 32; idx += blockDim.x) {
+            const int e = idx >> 5;
+            t32[idx] = s32[e & 511] ^ ((uint32_t)(e >> 9) << 15);
+        }
+        __syncthreads();
+    }
+    template <int P>
+    static __device__ __forceinline__ half8_t step(const u32x4_t (&q)[P], int s, const uint8_t *tab, uint32_t lc,
+                                                   const Pre &) {
+        uint32_t r[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t st = qp_field_shl<P, true, 0>(q, (4 * s + c) * K, 16);
+            uint32_t h, idx, a;
+            asm("v_mad_u32_u24 %0, %1, %1, %1" : "=v"(h) : "v"(st));   // x (x + 1), exact: x < 2^16
+            asm("v_bfe_u32 %0, %1, 6, 10" : "=v"(idx) : "v"(h));
+            asm("v_lshl_or_b32 %0, %1, 7, %2" : "=v"(a) : "v"(idx), "v"(lc));
+            r[c] = *reinterpret_cast<const uint32_t *>(tab + a);
+        }
+        return __builtin_bit_cast(half8_t, u32x4_t{r[0], r[1], r[2], r[3]});
+    }
+};
+template <> struct QpDec<QP_TCQH, 3> : QpDecTcqh<3> {};
+template <> struct QpDec<QP_TCQH, 4> : QpDecTcqh<4> {};
+template <> struct QpDec<QP_TCQH, 5> : QpDecTcqh<5> {};
+template <> struct QpDec<QP_TCQH, 6> : QpDecTcqh<6> {};
+template <> struct QpDec<QP_TCQH, 7> : QpDecTcqh<7> {};
+template <> struct QpDec<QP_TCQH, 8> : QpDecTcqh<8> {};
+
 template <> struct QpDec<QP_TCQ, 2> : QpDecTcq<2> {};
 template <> struct QpDec<QP_TCQ, 3> : QpDecTcq<3> {};
 template <> struct QpDec<QP_TCQ, 4> : QpDecTcq<4> {};
@@ -521,7 +573,7 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
     int rb_q = rbk / grid, rb_r = rbk % grid;
     int nbc_magic = (65536 + nbc - 1) / nbc;  // u / nbc == (u * magic) >> 16 for u < 1024
     int nw = units < 16 ? units : 16;
-    if (scheme == QP_TCQ) nw = 16;  // the table staging is written for 1024 threads
+    if (scheme == QP_TCQ || scheme == QP_TCQH) nw = 16;  // the table staging is written for 1024 threads
     if (nw < 4) nw = 4;
 #define CALL_BP(S, C, BP)                                                                              \
     hipLaunchKernelGGL((k_linear_mfma<S, C, BP>), dim3(grid), dim3(64 * nw), 0, st, w, (const half_t *)x, B, \

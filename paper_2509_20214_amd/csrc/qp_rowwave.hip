@@ -19,9 +19,8 @@ __global__ __launch_bounds__(1024) void k_dequant(QpW w, uint16_t *out) {
          t += (int64_t)gridDim.x * blockDim.x) {
         int row = (int)(t / groups_per_row);
         int grp = (int)(t - (int64_t)row * groups_per_row);
-        uint64_t bits = qp_group_bits<S, CB>(w, row, grp);
         uint16_t v[8];
-        qp_decode8<S, CB>(bits, lut, v);
+        qp_group_decode<S, CB>(w, row, grp, lut, v);
         u32x4_t o;
         o.x = v[0] | ((uint32_t)v[1] << 16);
         o.y = v[2] | ((uint32_t)v[3] << 16);
@@ -60,9 +59,8 @@ __global__ __launch_bounds__(1024) void k_linear_rowwave(QpW w, const half_t *x,
 #pragma unroll
         for (int b = 0; b < BT; ++b) acc[b] = 0.f;
         for (int grp = lane; grp < groups_per_row; grp += 64) {
-            uint64_t bits = qp_group_bits<S, CB>(w, row, grp);
             uint16_t v[8];
-            qp_decode8<S, CB>(bits, lut, v);
+            qp_group_decode<S, CB>(w, row, grp, lut, v);
             float wf[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) wf[e] = qp_half_bits_to_float(v[e]);
