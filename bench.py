@@ -77,10 +77,7 @@ def main():
             n = max(2, -(-ring_bytes // lay.code_bytes))
             self.ring = [nat]
             for _ in range(n - 1):
-                c = nat.codes.clone()
-                d = nat.desc
-                self.ring.append(qp.Weight(d.scheme, d.M, d.N, d.code_bits, d.vec, d.window_bits, d.tile,
-                                           c, nat.lut, nat.scales, layout=qp.QP_LAYOUT_NATIVE, row_stride=0))
+                self.ring.append(nat.with_codes(nat.codes.clone()))
             self.block = synth.hadamard_block(lay.N)
             self.x = upload(synth.make_x(cfg, li, B, lay.N))
             self.signs = upload(synth.make_signs(cfg, li, lay.N))
@@ -200,7 +197,8 @@ def main():
         del g_lin, g_had
         todo = [(3, 0, 1), (3, 0, 4), (3, 0, 8), (2, 0, 1), (1, 0, 1),
                 (4, 0, 1), (4, 1, 1), (4, 2, 1), (4, 3, 1), (4, 3, 8), (4, 3, 16), (4, 2, 8),
-                (5, 0, 1), (5, 1, 1), (5, 2, 1), (5, 3, 1), (5, 2, 8), (5, 3, 8)]
+                (5, 0, 1), (5, 1, 1), (5, 2, 1), (5, 3, 1), (5, 2, 8), (5, 3, 8),
+                (6, 0, 1), (6, 1, 1), (6, 2, 1), (6, 3, 1), (6, 1, 8)]
         for cfg, li, B in todo:
             if (cfg, li, B) == (a.cfg, a.layer, a.batch):
                 continue

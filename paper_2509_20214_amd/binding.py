@@ -115,6 +115,12 @@ class Weight:
         return cls(layer.scheme, layer.M, layer.N, layer.code_bits, layer.vec, layer.window_bits,
                    layer.tile, codes, lut, scales, tlut_bits=getattr(layer, "tlut_bits", 0))
 
+    def with_codes(self, codes):
+        """Same layer (table and scales shared) over another buffer of codes in the same layout."""
+        d = self.desc
+        return Weight(d.scheme, d.M, d.N, d.code_bits, d.vec, d.window_bits, d.tile, codes, self.lut, self.scales,
+                      layout=d.layout, row_stride=d.row_stride, tlut_bits=d.tlut_bits)
+
     @property
     def M(self):
         return self.desc.M

@@ -213,6 +213,13 @@ def config_layers(cfg: int, *, small: bool = False):
             s, cb = pal[int(g.integers(0, len(pal)))]
             out.append(d(i, f"{SCHEME_NAMES[s]}{cb}_{nm}_{M}x{N}", s, M, N, cb))
         return out
+    if cfg == 6:
+        # beyond the five benchmark configurations: the paper's own trellis quantizer (V = 2, hybrid
+        # computed code book) on the Llama-3-8B down projection at 2, 2.5 and 3 bits per weight
+        return [d(0, "tcqh2_down_4096x14336", TCQH, 4096, 14336, 4),
+                d(1, "tcqh2.5_down_4096x14336", TCQH, 4096, 14336, 5),
+                d(2, "tcqh3_down_4096x14336", TCQH, 4096, 14336, 6),
+                d(3, "tcqh2_q_proj_4096x4096", TCQH, 4096, 4096, 4)]
     raise ValueError(cfg)
 
 
