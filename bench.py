@@ -37,9 +37,96 @@ def parse():
     p.add_argument("--batch", type=int, default=1)
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--no-cases", action="store_true", help="skip the table of other (layer, batch) cases")
+    p.add_argument("--sweep70b", action="store_true",
+                   help="configuration 5: all 80 layers of the 70B-shaped mixed-scheme model resident, "
+                        "one decode step through every projection; prints its own JSON line")
     p.add_argument("--profile-only", action="store_true",
                    help="run a short sequence of the dominant kernel only (for rocprofv3)")
     return p.parse_args()
+
+
+def sweep70b(a, torch, synth, qp, dev, upload, graph_of, event_time_us):
+    """Configuration 5.  Codes are drawn on the device (seeded torch generator: 26 GB through
+    the host would take minutes); tables, scales, activations and signs come from synth."""
+    import oracle
+    model = synth.config5_model(80)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(5)
+    luts = {}
+    sampled = {}
+    layers = []
+    total_bytes = 0
+    t0 = time.perf_counter()
+    for row in model:
+        ws = []
+        for d in row:
+            vec = 2 if d["scheme"] == synth.VQ else 1
+            rb = synth.row_bytes_for(d["scheme"], d["N"], d["code_bits"], vec)
+            key = (d["scheme"], d["code_bits"])
+            if key not in luts:
+                tiny = synth.make_layer(5, 500 + len(luts), d["scheme"], 16, 1024, d["code_bits"])
+                luts[key] = upload(tiny.lut)
+            codes = torch.randint(0, 256, (d["M"], rb), dtype=torch.uint8, device=dev, generator=gen)
+            scales = upload(synth.rng(5, d["layer"], synth.TENSOR_SCALES).uniform(0.5, 1.5, d["M"]).astype(np.float16))
+            trellis = d["scheme"] == synth.TCQ
+            can = qp.Weight(d["scheme"], d["M"], d["N"], d["code_bits"], vec, 16 if trellis else 0,
+                            256 if trellis else 0, codes, luts[key].view(torch.int16), scales.view(torch.int16))
+            nat = qp.qp_repack(can)
+            ws.append((d, nat))
+            total_bytes += d["M"] * rb
+            if d["scheme"] not in sampled and len(sampled) < 3:
+                # keep a few rows of codes on the host: the oracle decodes those itself
+                rows = sorted(set(int(r) for r in np.random.default_rng(d["layer"]).integers(0, d["M"], 12)))
+                sampled[d["scheme"]] = (d, nat, rows, codes[torch.tensor(rows, device=dev)].cpu().numpy(),
+                                        scales.cpu().view(torch.int16).numpy().view(np.float16)[rows], luts[key])
+            del codes, can
+        layers.append(ws)
+    torch.cuda.synchronize()
+    setup_s = time.perf_counter() - t0
+    # parity on sampled rows of three projections of different schemes: the oracle decodes the
+    # rows' codes (copied back from the device generator's output) and multiplies in fp64
+    checked = []
+    for d, nat, rows, code_rows, scale_rows, lut_dev in sampled.values():
+        vec = 2 if d["scheme"] == synth.VQ else 1
+        trellis = d["scheme"] == synth.TCQ
+        sub = synth.Layer(scheme=d["scheme"], M=len(rows), N=d["N"], code_bits=d["code_bits"], vec=vec,
+                          window_bits=16 if trellis else 0, tile=256 if trellis else 0,
+                          codes=np.ascontiguousarray(code_rows),
+                          lut=lut_dev.cpu().view(torch.int16).numpy().view(np.float16).reshape(-1),
+                          scales=np.ascontiguousarray(scale_rows))
+        xh = synth.make_x(5, d["layer"], 2, d["N"])
+        y = qp.qp_linear(nat, upload(xh))
+        want = oracle.linear(sub, xh)
+        got = y[:, torch.tensor(rows, device=dev)].cpu().numpy().astype(np.float64)
+        err = float(np.max(np.abs(got - want)) / np.max(np.abs(want)))
+        assert err <= 1e-2, (d["name"], err)
+        checked.append({"layer": d["name"], "rows": len(rows), "rel_err_vs_oracle": round(err, 6)})
+    out_cases = []
+    for B in (1, 8):
+        xs = {N: upload(synth.make_x(5, N, B, N)) for N in (8192, 28672)}
+        sg = {N: upload(synth.make_signs(5, N, N)) for N in (8192, 28672)}
+        xr = {N: torch.empty_like(xs[N]) for N in xs}
+        ys = {M: torch.empty((B, M), dtype=torch.float16, device=dev) for M in (10240, 8192, 57344)}
+
+        def step():
+            for ws in layers:
+                for d, nat in ws:
+                    N = d["N"]
+                    qp.qp_hadamard(xs[N], sg[N], synth.hadamard_block(N), out=xr[N])
+                    qp.qp_linear(nat, xr[N], y=ys[d["M"]])
+
+        g = graph_of(step, 1)
+        g.replay()
+        us = event_time_us(g, 1, repeats=5)
+        out_cases.append({"batch": B, "ms_per_model_step": round(us / 1e3, 4),
+                          "weight_GBps": round(total_bytes / us / 1e3, 1),
+                          "frac_of_peak": round(total_bytes / us / 1e3 / HBM_PEAK_GBS, 4),
+                          "steps_per_s": round(1e6 / us, 1)})
+    print(json.dumps({"metric": "configuration 5: one decode step through all 320 quantized projections of the "
+                                "70B-shaped mixed-scheme model (80 layers resident)",
+                      "resident_weight_GiB": round(total_bytes / 2**30, 2), "setup_s": round(setup_s, 1),
+                      "launches_per_step": 640, "cases": out_cases, "parity": checked,
+                      "data": "synthetic (codes drawn on the device from a seeded generator)"}))
 
 
 def main():
@@ -133,6 +220,10 @@ def main():
             e1.synchronize()
             out.append(e0.elapsed_time(e1) * 1e3 / count)
         return statistics.median(out)
+
+    if a.sweep70b:
+        sweep70b(a, torch, synth, qp, dev, upload, graph_of, event_time_us)
+        return
 
     head = Case(a.cfg, a.layer, a.batch)
 

@@ -223,6 +223,24 @@ def config_layers(cfg: int, *, small: bool = False):
     raise ValueError(cfg)
 
 
+def config5_model(n_layers: int = 80):
+    """Llama-3-70B-shaped model of configuration 5: for every decoder layer the four
+    (fused) projections, each with a quantizer drawn from the seed among SQ 4, VQ 2.5 / 3.5
+    and TCQ 2 / 3 / 4 bits.  Returns descriptions only (list of lists)."""
+    pal = [(SQ, 4), (VQ, 5), (VQ, 7), (TCQ, 2), (TCQ, 3), (TCQ, 4)]
+    shapes = [("qkv", 10240, 8192), ("o", 8192, 8192), ("gateup", 57344, 8192), ("down", 8192, 28672)]
+    g = rng(5, 1, 99)
+    model = []
+    for L in range(n_layers):
+        row = []
+        for i, (nm, M, N) in enumerate(shapes):
+            s, cb = pal[int(g.integers(0, len(pal)))]
+            row.append(dict(cfg=5, layer=1000 + 4 * L + i, name=f"L{L}.{SCHEME_NAMES[s]}{cb}_{nm}", scheme=s,
+                            M=M, N=N, code_bits=cb))
+        model.append(row)
+    return model
+
+
 def build(desc: dict) -> Layer:
     return make_layer(desc["cfg"], desc["layer"], desc["scheme"], desc["M"], desc["N"],
                       desc["code_bits"], name=desc["name"])
