@@ -105,15 +105,14 @@ def sweep70b(a, torch, synth, qp, dev, upload, graph_of, event_time_us):
     for B in (1, 8):
         xs = {N: upload(synth.make_x(5, N, B, N)) for N in (8192, 28672)}
         sg = {N: upload(synth.make_signs(5, N, N)) for N in (8192, 28672)}
-        xr = {N: torch.empty_like(xs[N]) for N in xs}
+        wsp = {N: torch.empty(2 * 16 * N, dtype=torch.uint8, device=dev) for N in xs}
         ys = {M: torch.empty((B, M), dtype=torch.float16, device=dev) for M in (10240, 8192, 57344)}
 
         def step():
             for ws in layers:
                 for d, nat in ws:
                     N = d["N"]
-                    qp.qp_hadamard(xs[N], sg[N], synth.hadamard_block(N), out=xr[N])
-                    qp.qp_linear(nat, xr[N], y=ys[d["M"]])
+                    qp.qp_rotate_linear(nat, xs[N], sg[N], synth.hadamard_block(N), y=ys[d["M"]], workspace=wsp[N])
 
         g = graph_of(step, 1)
         g.replay()
@@ -176,8 +175,7 @@ def main():
             self.alg_bytes = lay.code_bytes + 2 * lay.M + 2 * B * lay.N + 2 * B * lay.M + 2 * lay.lut.size
 
         def step(self):
-            # rotation + fused layer through the single-call entry point (one launch when the
-            # rotation block is 1024, two launches otherwise)
+            # rotation + fused layer through the single-call entry point
             qp.qp_rotate_linear(self.ring[self.i % len(self.ring)], self.x, self.signs, self.block,
                                 y=self.y, workspace=self.ws)
             self.i += 1
@@ -298,7 +296,12 @@ def main():
             g = graph_of(c.linear_only, 200)
             g.replay()
             us = event_time_us(g, 200, repeats=3)
+            del g
+            g = graph_of(c.step, 200)
+            g.replay()
+            us_step = event_time_us(g, 200, repeats=3)
             cases.append({"workload": c.desc["name"], "batch": B, "us_per_call": round(us, 3),
+                          "us_rotate_linear": round(us_step, 3),
                           "weight_GBps": round(c.code_bytes / us / 1e3, 1),
                           "frac_of_peak": round(c.code_bytes / us / 1e3 / HBM_PEAK_GBS, 4)})
             del c, g

@@ -74,6 +74,23 @@ extern "C" size_t qp_linear_workspace_bytes(const qp_weight *w, int32_t B) {
     return 0;
 }
 
+// Which kernel runs a layer.  QP_LINEAR_KERNEL=rowwave / mfma forces one (used by the tests
+// to cover both on native-layout weights of any size); anything else lets the shape decide.
+// The matrix-core kernel pays a fixed table-build and reduction cost per workgroup; below
+// one 16x1024 block per CU (measured: 1024x1024 runs 3.2 us on the row kernel, 6.4 us on
+// the block kernel) the row kernel is the faster one.
+static bool use_rowwave(const qp_weight *w) {
+    const int nbc = w->N / 1024;
+    const char *force = getenv("QP_LINEAR_KERNEL");
+    const int64_t blocks = (int64_t)(w->M / 16) * nbc;
+    bool rowwave = (w->layout != QP_LAYOUT_NATIVE) || nbc > 32 || blocks < 256 ||
+                   (force && strcmp(force, "rowwave") == 0);
+    if (force && strcmp(force, "mfma") == 0 && w->layout == QP_LAYOUT_NATIVE && nbc <= 32) rowwave = false;
+    return rowwave;
+}
+
+static inline int pow2_at_least(int B) { return B <= 1 ? 1 : B <= 2 ? 2 : B <= 4 ? 4 : B <= 8 ? 8 : 16; }
+
 extern "C" qp_status qp_linear(const qp_weight *w, const void *x, int32_t B, int64_t ldx, void *y, int64_t ldy,
                                void *workspace, size_t workspace_bytes, void *hip_stream) {
     qp_status s = qp_validate(w);
@@ -86,25 +103,15 @@ extern "C" qp_status qp_linear(const qp_weight *w, const void *x, int32_t B, int
     if (need && (!workspace || workspace_bytes < need)) return QP_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     QpW d = make_dev(w);
-    // QP_LINEAR_KERNEL=rowwave / mfma forces a kernel (used by the tests to cover both on
-    // native-layout weights of any size); anything else lets the shape decide.
-    // The matrix-core kernel pays a fixed table-build and reduction cost per workgroup; below
-    // one 16x1024 block per CU (measured: 1024x1024 runs 3.2 us on the row kernel, 6.4 us on
-    // the block kernel) the row kernel is the faster one.
-    const char *force = getenv("QP_LINEAR_KERNEL");
-    const int64_t blocks = (int64_t)(w->M / 16) * d.nbc;
-    bool rowwave = (w->layout != QP_LAYOUT_NATIVE) || d.nbc > 32 || blocks < 256 ||
-                   (force && strcmp(force, "rowwave") == 0);
-    if (force && strcmp(force, "mfma") == 0 && w->layout == QP_LAYOUT_NATIVE && d.nbc <= 32) rowwave = false;
-    if (rowwave) return qp_launch_linear_rowwave(d, w->scheme, w->code_bits, x, B, ldx, y, ldy, st);
-    return qp_launch_linear_mfma(d, w->scheme, w->code_bits, x, B, ldx, y, ldy, st);
+    if (use_rowwave(w)) return qp_launch_linear_rowwave(d, w->scheme, w->code_bits, x, B, ldx, y, ldy, st);
+    return qp_launch_linear_mfma(d, w->scheme, w->code_bits, x, B, ldx, y, ldy, 0, st);
 }
 
 static inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 extern "C" size_t qp_rotate_linear_workspace_bytes(const qp_weight *w, int32_t B) {
     if (!w || B < 1 || B > QP_MAX_BATCH || w->N <= 0) return 0;
-    return round256((size_t)B * (size_t)w->N * 2);
+    return round256((size_t)pow2_at_least(B) * (size_t)w->N * 2);
 }
 
 extern "C" qp_status qp_rotate_linear(const qp_weight *w, const void *x, const int8_t *signs, int32_t block,
@@ -119,11 +126,19 @@ extern "C" qp_status qp_rotate_linear(const qp_weight *w, const void *x, const i
     if (!aligned(x, 16) || !aligned(y, 2) || !aligned(workspace, 256) || !aligned(signs, 16)) return QP_ERR_ALIGN;
     if (workspace_bytes < qp_rotate_linear_workspace_bytes(w, B)) return QP_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    void *xr = workspace;
-    // two launches; the rotated activations pass through the workspace
-    s = qp_launch_hadamard(x, signs, B, w->N, block, ldx, xr, w->N, st);
+    QpW d = make_dev(w);
+    // Two launches; the rotated activations pass through the workspace.  For the block kernel
+    // the rotation writes them in the order that kernel loads its B-operand fragments, so that
+    // every one of its activation loads is a contiguous KiB whatever the batch; the results
+    // are the same bit for bit (same values, same order of operations, other addresses).
+    if (use_rowwave(w)) {
+        s = qp_launch_hadamard(x, signs, B, w->N, block, ldx, workspace, w->N, 0, st);
+        if (s != QP_OK) return s;
+        return qp_launch_linear_rowwave(d, w->scheme, w->code_bits, workspace, B, w->N, y, ldy, st);
+    }
+    s = qp_launch_hadamard(x, signs, B, w->N, block, ldx, workspace, w->N, pow2_at_least(B), st);
     if (s != QP_OK) return s;
-    return qp_linear(w, xr, B, w->N, y, ldy, nullptr, 0, hip_stream);
+    return qp_launch_linear_mfma(d, w->scheme, w->code_bits, workspace, B, w->N, y, ldy, 1, st);
 }
 
 extern "C" qp_status qp_dequant(const qp_weight *w, void *W_out, void *hip_stream) {
@@ -148,7 +163,7 @@ extern "C" qp_status qp_hadamard(const void *x, const int8_t *signs, int32_t B, 
         int64_t ea = ((int64_t)(B - 1) * ldx + n) * 2, eb = ((int64_t)(B - 1) * ldxr + n) * 2;
         if (a < b + eb && b < a + ea) return QP_ERR_ALIGN;
     }
-    return qp_launch_hadamard(x, signs, B, n, block, ldx, xr, ldxr, static_cast<hipStream_t>(hip_stream));
+    return qp_launch_hadamard(x, signs, B, n, block, ldx, xr, ldxr, 0, static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" size_t qp_native_bytes(const qp_weight *c) {

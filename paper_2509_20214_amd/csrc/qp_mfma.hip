@@ -345,11 +345,11 @@ struct QpFold {  // acc[0] + shl1(acc[1]) + ... : lane b*TT of every row ends up
 // One unit's loads: the first PF activation fragments, then P coalesced 128-bit pieces
 // of codes.  Straight-line code (no branches) so that the waits the compiler inserts
 // later can name exactly the loads they need.
-template <int P, int PF, int TT>
-__device__ __forceinline__ void qp_unit_load(const u32x4_t *blk, const half_t *xu, int lane, u32x4_t (&q)[P],
-                                             half8_t (&xf)[PF]) {
+template <int P, int PF>
+__device__ __forceinline__ void qp_unit_load(const u32x4_t *blk, const half_t *xu, int xfs, int lane,
+                                             u32x4_t (&q)[P], half8_t (&xf)[PF]) {
 #pragma unroll
-    for (int n = 0; n < PF; ++n) xf[n] = *reinterpret_cast<const half8_t *>(xu + 8 * TT * n);
+    for (int n = 0; n < PF; ++n) xf[n] = *reinterpret_cast<const half8_t *>(xu + xfs * n);
 #pragma unroll
     for (int p = 0; p < P; ++p) q[p] = __builtin_nontemporal_load(blk + p * 64 + lane);
 }
@@ -358,7 +358,7 @@ __device__ __forceinline__ void qp_unit_load(const u32x4_t *blk, const half_t *x
 // their partial dot products in v.
 template <int S, int CB, int P, int PF, int TT>
 __device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8_t (&xf)[PF], const half_t *xu,
-                                                    const uint8_t *tab, uint32_t lc,
+                                                    int xfs, const uint8_t *tab, uint32_t lc,
                                                     const typename QpDec<S, CB>::Pre &pre) {
     using D = QpDec<S, CB>;
     constexpr int NXF = 32 / TT;
@@ -400,7 +400,7 @@ __device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8
                 }
             }
             if (n + PF < NXF)  // the raw fragment is spent: refill its slot
-                xf[n % PF] = *reinterpret_cast<const half8_t *>(xu + 8 * TT * (n + PF));
+                xf[n % PF] = *reinterpret_cast<const half8_t *>(xu + xfs * (n + PF));
         }
         half8_t a = D::template step<P>(q, s, tab, lc, pre);
         acc[t % NACC] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, __builtin_bit_cast(half8_t, masked[t / NACC]),
@@ -453,7 +453,8 @@ __device__ __forceinline__ void qp_pass_store(const QpW &w, const float *red, ha
 
 template <int S, int CB, int BP>
 __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, int B, int64_t ldx, half_t *y,
-                                                      int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic) {
+                                                      int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic,
+                                                      int x_packed) {
     using T = QpTraits<S, CB>;
     using D = QpDec<S, CB>;
     constexpr int P = T::PIECES;
@@ -498,16 +499,21 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
     const int tj = j & (TT - 1);
     const int bj = j / TT;
     const bool xlive = bj < B;  // columns beyond the batch re-read row 0; their results are dropped
-    const half_t *xlane = x + (int64_t)(xlive ? bj : 0) * ldx + 256 * g + 8 * tj;
+    // Activations either row-major [B, ldx] (fragment n of column block C: 16 bytes per lane
+    // at row bj, column 1024 C + 256 g + 8 (TT n + tj)) or already in fragment order
+    // (x_packed: fragment n of column block C is the 1 KiB at ((C NXF + n) 64 + lane) 16).
+    const half_t *xlane = x_packed ? x + 8 * lane : x + (int64_t)(xlive ? bj : 0) * ldx + 256 * g + 8 * tj;
+    const int xcs = x_packed ? 1024 * BP : 1024;   // halves between column blocks
+    const int xfs = x_packed ? 512 : 8 * TT;       // halves between fragments
     const bool owner = (tj == 0) && xlive;  // lane (g, b*TT) ends up with rows 4g..4g+3 of batch row b
     half8_t xf[PF];
-    const half_t *xu = xlane + (uu - ((uu * nbc_magic) >> 16) * nbc) * 1024;   // column block = uu % nbc
+    const half_t *xu = xlane + (uu - ((uu * nbc_magic) >> 16) * nbc) * xcs;   // column block = uu % nbc
 #pragma unroll
     for (int n = 0; n < PF; ++n) {
 #ifdef QP_NOX
         xf[n] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
 #else
-        xf[n] = *reinterpret_cast<const half8_t *>(xu + 8 * TT * n);
+        xf[n] = *reinterpret_cast<const half8_t *>(xu + xfs * n);
 #endif
     }
     u32x4_t q[P];
@@ -528,7 +534,7 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
     D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
     QP_T(1);
     if (u < units) {
-        float4_t v = qp_unit_compute<S, CB, P, PF, TT>(q, xf, xu, tab, lc, pre);
+        float4_t v = qp_unit_compute<S, CB, P, PF, TT>(q, xf, xu, xfs, tab, lc, pre);
         if (owner) *reinterpret_cast<float4_t *>(&red[(u * BP + bj) * 16 + 4 * g]) = v;
     }
     QP_T(2);
@@ -538,11 +544,11 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
         // ---- remaining units of this pass ----------------------------------------------
         for (; u < units; u += nw) {
             const int C = u - ((u * nbc_magic) >> 16) * nbc;
-            const half_t *xu2 = xlane + C * 1024;
+            const half_t *xu2 = xlane + C * xcs;
             u32x4_t q2[P];
             half8_t xf2[PF];
-            qp_unit_load<P, PF, TT>(codes16 + ((int64_t)rb0 * nbc + u) * BLK16, xu2, lane, q2, xf2);
-            float4_t v = qp_unit_compute<S, CB, P, PF, TT>(q2, xf2, xu2, tab, lc, pre);
+            qp_unit_load<P, PF>(codes16 + ((int64_t)rb0 * nbc + u) * BLK16, xu2, xfs, lane, q2, xf2);
+            float4_t v = qp_unit_compute<S, CB, P, PF, TT>(q2, xf2, xu2, xfs, tab, lc, pre);
             if (owner) *reinterpret_cast<float4_t *>(&red[(u * BP + bj) * 16 + 4 * g]) = v;
         }
         qp_pass_store<BP>(w, red, y, ldy, B, rb0, gcount, nbc, scale_first);
@@ -562,7 +568,7 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
 }
 
 qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x, int B, int64_t ldx, void *y,
-                                int64_t ldy, hipStream_t st) {
+                                int64_t ldy, int x_packed, hipStream_t st) {
     const int nbc = w.nbc, rbk = w.M / 16;
     if (nbc < 1 || nbc > QP_UMAX) return QP_ERR_UNSUPPORTED;
     int grid = rbk < 256 ? rbk : 256;
@@ -577,7 +583,7 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
     if (nw < 4) nw = 4;
 #define CALL_BP(S, C, BP)                                                                              \
     hipLaunchKernelGGL((k_linear_mfma<S, C, BP>), dim3(grid), dim3(64 * nw), 0, st, w, (const half_t *)x, B, \
-                       ldx, (half_t *)y, ldy, G, rb_q, rb_r, nbc_magic)
+                       ldx, (half_t *)y, ldy, G, rb_q, rb_r, nbc_magic, x_packed)
 #define CALL(S, C)                                   \
     do {                                             \
         if (B <= 1) CALL_BP(S, C, 1);                \

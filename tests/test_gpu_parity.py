@@ -174,10 +174,11 @@ def test_rotation_then_linear_matches_fp64_chain(qp, scheme, cb, monkeypatch):
 
 # ---------------------------------------------------- rotation fused into the launch
 @pytest.mark.parametrize("scheme,cb", SCHEMES, ids=IDS)
-@pytest.mark.parametrize("B", [1, 2, 5, 16])
+@pytest.mark.parametrize("B", [1, 2, 3, 4, 8, 13, 16])
 def test_rotate_linear_matches_oracle_and_unfused(qp, scheme, cb, B, monkeypatch):
-    """One call = rotation + layer (one launch for B <= 2, two otherwise).  Must equal the
-    two-call sequence bit for bit (same arithmetic, fp16 rotated activations in between) and
+    """One call = rotation + layer; the rotated activations pass through the workspace in the
+    block kernel's own fragment order.  Must equal the two-call sequence (row-major
+    activations) bit for bit - same arithmetic, fp16 rotated activations in between - and
     the fp64 chain within tolerance; repeated calls reuse the workspace."""
     M, N, block = 272, 3072, 1024      # 17 row blocks, 3 column blocks: several units per wavefront
     lay = synth.make_layer(78, scheme * 10 + cb, scheme, M, N, cb)
