@@ -73,8 +73,9 @@ typedef enum { QP_LAYOUT_CANONICAL = 0, QP_LAYOUT_NATIVE = 1 } qp_layout;
  *   QP_SQ : vec 1, code_bits 4                       (16-entry fp16 LUT)
  *   QP_VQ : vec 2, code_bits 5 or 7                  (2.5 / 3.5 bits per weight; LUT fp16 [2^code_bits][2])
  *   QP_TCQ: vec 1, window_bits 16, tile 256, code_bits 2, 3 or 4  (LUT fp16 [65536])
- *   QP_TCQH: vec 2, window_bits 16, tile 256, code_bits s = 3..8 (1.5 .. 4 bits per weight),
- *            tlut_bits 9  (lut = the small table, fp16 [512][2])
+ *   QP_TCQH: vec 2, window_bits 16, tile 256, code_bits s = 3..10 (1.5 .. 5 bits per weight),
+ *            tlut_bits 9 for s <= 8, 10 for s = 9, 11 for s = 10, the table sizes of App. C.3.1
+ *            (lut = the small table, fp16 [2^tlut_bits][2])
  * Fused layers (QKV, gate+up; Section 4.2) are one qp_weight with M the sum of the
  * members' out_features. */
 typedef struct {

@@ -21,8 +21,10 @@ static qp_status scheme_supported(const qp_weight *w) {
                        ? QP_OK
                        : QP_ERR_UNSUPPORTED;
         case QP_TCQH:
+            // table size follows the bitwidth as in the paper: 2^9 pairs up to 4 bits, 2^10 at 4.5, 2^11 at 5
             return (w->vec == 2 && w->window_bits == 16 && w->tile == 256 && w->code_bits >= 3 &&
-                    w->code_bits <= 8 && w->tlut_bits == 9)
+                    w->code_bits <= 10 &&
+                    w->tlut_bits == (w->code_bits <= 8 ? 9 : w->code_bits == 9 ? 10 : 11))
                        ? QP_OK
                        : QP_ERR_UNSUPPORTED;
         default:

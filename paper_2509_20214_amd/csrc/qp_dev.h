@@ -31,7 +31,9 @@ struct QpTraits {
     static constexpr int BITS8 = 8 * CB / V;           // stream bits that 8 weights advance
     static constexpr int SPAN = 32 * CB / V;           // bytes of a 256-weight span
     static constexpr int PIECES = SPAN / 16;           // 16-byte pieces per span
-    static constexpr int LUT_HALVES = (S == QP_TCQ) ? 65536 : (S == QP_TCQH) ? 1024 : (1 << CB) * V;
+    // QP_TCQH: the small table has 2^9 pairs up to 4 bits per weight, 2^10 at 4.5, 2^11 at 5
+    static constexpr int TLUT_BITS = (S != QP_TCQH) ? 0 : (CB <= 8) ? 9 : (CB == 9) ? 10 : 11;
+    static constexpr int LUT_HALVES = (S == QP_TCQ) ? 65536 : (S == QP_TCQH) ? (2 << TLUT_BITS) : (1 << CB) * V;
     static constexpr int BLOCK_BYTES = 64 * SPAN;      // one 16 x 1024 native block
 };
 
@@ -163,5 +165,7 @@ __device__ __forceinline__ float qp_half_bits_to_float(uint16_t h) {
         else if ((scheme) == QP_TCQH && (cb) == 6) { CALL(QP_TCQH, 6); }              \
         else if ((scheme) == QP_TCQH && (cb) == 7) { CALL(QP_TCQH, 7); }              \
         else if ((scheme) == QP_TCQH && (cb) == 8) { CALL(QP_TCQH, 8); }              \
+        else if ((scheme) == QP_TCQH && (cb) == 9) { CALL(QP_TCQH, 9); }              \
+        else if ((scheme) == QP_TCQH && (cb) == 10) { CALL(QP_TCQH, 10); }            \
         else return QP_ERR_UNSUPPORTED;                                               \
     } while (0)

@@ -267,31 +267,49 @@ struct QpDecTcq {
         return a;
     }
 };
-// The paper's own trellis (V = 2, computed hybrid code book).  The small table has 2^9
+// The paper's own trellis (V = 2, computed hybrid code book).  The small table has 2^TB
 // half2 entries; the sign flag is bit 15 of h and the index bits sit right below it, so
-// bits [15:6] of h = x (x + 1) are one 10-bit index into a table of 1024 entries in which
-// the upper half is the lower half with component 0 negated.  That table is replicated
-// once per LDS bank like the scalar / 7-bit vector tables (128 KiB), so the lookups - one
-// per *two* weights - never collide; the per-state work is a 24-bit multiply-add, a
-// bit-field extract and a shift-or.
+// bits [15 : 15-TB] of h = x (x + 1) are one (TB+1)-bit index into a table of 2^(TB+1)
+// entries in which the upper half is the lower half with component 0 negated.  That table
+// fills 128 KiB of LDS with as many copies as fit (entry e, copy c at dword COPIES e + c;
+// a lane reads copy l % COPIES): 32 copies for TB = 9, one per bank, so the lookups - one
+// per *two* weights - never collide; 16 and 8 copies for TB = 10 and 11, where only lanes
+// with equal l % COPIES can still meet in a bank.  The per-state work is a 24-bit
+// multiply-add, a bit-field extract and a shift-or.
 template <int K>
-struct QpDecTcqh : QpBankTable<1024> {
-    struct Pre { uint32_t raw; };
+struct QpDecTcqh {
+    static constexpr int TB = QpTraits<QP_TCQH, K>::TLUT_BITS;
+    static constexpr int ENTRIES = 2 << TB;
+    static constexpr int COPIES = 32768 / ENTRIES;          // 32, 16, 8
+    static constexpr int LSH = (COPIES == 32) ? 7 : (COPIES == 16) ? 6 : 5;
+    static constexpr int TAB_BYTES = 131072;
+    static constexpr int SMALL_BYTES = 4 << TB;             // staging room for the source
+    static constexpr int NSRC = (1 << TB) / 1024 ? (1 << TB) / 1024 : 1;   // source dwords per thread
+    struct Pre { uint32_t raw[NSRC]; };
+    static __device__ __forceinline__ uint32_t lane_const() { return (threadIdx.x & (COPIES - 1)) << 2; }
     static __device__ __forceinline__ void early(uint8_t *, uint16_t *, const uint16_t *) {}
-    static __device__ __forceinline__ Pre pre(const uint16_t *g) {  // needs blockDim.x >= 512
+    static __device__ __forceinline__ Pre pre(const uint16_t *g) {  // needs blockDim.x == 1024
         Pre p;
-        p.raw = (threadIdx.x < 512) ? reinterpret_cast<const uint32_t *>(g)[threadIdx.x] : 0u;
+#pragma unroll
+        for (int k = 0; k < NSRC; ++k) {
+            const int i = k * 1024 + threadIdx.x;
+            p.raw[k] = (i < (1 << TB)) ? reinterpret_cast<const uint32_t *>(g)[i] : 0u;
+        }
         __builtin_amdgcn_s_barrier();   // every wavefront's table request is queued before any weight load
         return p;
     }
     static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *small, const Pre &p) {
         uint32_t *s32 = reinterpret_cast<uint32_t *>(small);
-        if (threadIdx.x < 512) s32[threadIdx.x] = p.raw;
+#pragma unroll
+        for (int k = 0; k < NSRC; ++k) {
+            const int i = k * 1024 + threadIdx.x;
+            if (i < (1 << TB)) s32[i] = p.raw[k];
+        }
         __syncthreads();
         uint32_t *t32 = reinterpret_cast<uint32_t *>(tab);
-        for (int idx = threadIdx.x; idx < 1024 * 32; idx += blockDim.x) {
-            const int e = idx >> 5;
-            t32[idx] = s32[e & 511] ^ ((uint32_t)(e >> 9) << 15);
+        for (int idx = threadIdx.x; idx < 32768; idx += blockDim.x) {
+            const int e = idx / COPIES;
+            t32[idx] = s32[e & ((1 << TB) - 1)] ^ ((uint32_t)(e >> TB) << 15);
         }
         __syncthreads();
     }
@@ -304,8 +322,8 @@ struct QpDecTcqh : QpBankTable<1024> {
             const uint32_t st = qp_field_shl<P, true, 0>(q, (4 * s + c) * K, 16);
             uint32_t h, idx, a;
             asm("v_mad_u32_u24 %0, %1, %1, %1" : "=v"(h) : "v"(st));   // x (x + 1), exact: x < 2^16
-            asm("v_bfe_u32 %0, %1, 6, 10" : "=v"(idx) : "v"(h));
-            asm("v_lshl_or_b32 %0, %1, 7, %2" : "=v"(a) : "v"(idx), "v"(lc));
+            asm("v_bfe_u32 %0, %1, %2, %3" : "=v"(idx) : "v"(h), "n"(15 - TB), "n"(TB + 1));
+            asm("v_lshl_or_b32 %0, %1, %2, %3" : "=v"(a) : "v"(idx), "n"(LSH), "v"(lc));
             r[c] = *reinterpret_cast<const uint32_t *>(tab + a);
         }
         return __builtin_bit_cast(half8_t, u32x4_t{r[0], r[1], r[2], r[3]});
@@ -317,6 +335,8 @@ template <> struct QpDec<QP_TCQH, 5> : QpDecTcqh<5> {};
 template <> struct QpDec<QP_TCQH, 6> : QpDecTcqh<6> {};
 template <> struct QpDec<QP_TCQH, 7> : QpDecTcqh<7> {};
 template <> struct QpDec<QP_TCQH, 8> : QpDecTcqh<8> {};
+template <> struct QpDec<QP_TCQH, 9> : QpDecTcqh<9> {};
+template <> struct QpDec<QP_TCQH, 10> : QpDecTcqh<10> {};
 
 template <> struct QpDec<QP_TCQ, 2> : QpDecTcq<2> {};
 template <> struct QpDec<QP_TCQ, 3> : QpDecTcq<3> {};
@@ -466,7 +486,10 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
     constexpr int PF = (NXF < 8) ? NXF : 8;          // fragments kept in flight
     constexpr int BLK16 = T::BLOCK_BYTES / 16;
     __shared__ __attribute__((aligned(16))) uint8_t tab[D::TAB_BYTES];
-    __shared__ __attribute__((aligned(16))) float red[QP_UMAX * 16 * BP];  // [unit][b][row]
+    // [unit][b][row]; before the first pass the same room stages a table's source
+    constexpr int RED_FLOATS = QP_UMAX * 16 * BP;
+    constexpr int SMALL_FLOATS = (S == QP_TCQH) ? (1 << T::TLUT_BITS) : 0;
+    __shared__ __attribute__((aligned(16))) float red[RED_FLOATS > SMALL_FLOATS ? RED_FLOATS : SMALL_FLOATS];
     QP_T(0);
 
     // ---- first pass, straight-line up to the first loads ------------------------------

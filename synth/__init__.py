@@ -142,9 +142,11 @@ def row_bytes_for(scheme: int, N: int, code_bits: int, vec: int) -> int:
 
 def make_layer(cfg: int, layer: int, scheme: int, M: int, N: int, code_bits: int,
                *, vec: int | None = None, window_bits: int = 16, tile: int = 256,
-               lut: np.ndarray | None = None, name: str = "", tlut_bits: int = 9) -> Layer:
+               lut: np.ndarray | None = None, name: str = "", tlut_bits: int | None = None) -> Layer:
     if vec is None:
         vec = 2 if scheme in (VQ, TCQH) else 1
+    if tlut_bits is None:   # table size by bitwidth, as in the paper (App. C.3.1)
+        tlut_bits = 9 if code_bits <= 8 else 10 if code_bits == 9 else 11
     rb = row_bytes_for(scheme, N, code_bits, vec)
     codes = rng(cfg, layer, TENSOR_CODES).integers(0, 256, size=(M, rb), dtype=np.uint8)
     scales = rng(cfg, layer, TENSOR_SCALES).uniform(0.5, 1.5, size=M).astype(np.float16)
@@ -215,11 +217,14 @@ def config_layers(cfg: int, *, small: bool = False):
         return out
     if cfg == 6:
         # beyond the five benchmark configurations: the paper's own trellis quantizer (V = 2, hybrid
-        # computed code book) on the Llama-3-8B down projection at 2, 2.5 and 3 bits per weight
+        # computed code book) on the Llama-3-8B down projection at 2 .. 5 bits per weight
         return [d(0, "tcqh2_down_4096x14336", TCQH, 4096, 14336, 4),
                 d(1, "tcqh2.5_down_4096x14336", TCQH, 4096, 14336, 5),
                 d(2, "tcqh3_down_4096x14336", TCQH, 4096, 14336, 6),
-                d(3, "tcqh2_q_proj_4096x4096", TCQH, 4096, 4096, 4)]
+                d(3, "tcqh2_q_proj_4096x4096", TCQH, 4096, 4096, 4),
+                d(4, "tcqh4_down_4096x14336", TCQH, 4096, 14336, 8),
+                d(5, "tcqh4.5_down_4096x14336", TCQH, 4096, 14336, 9),
+                d(6, "tcqh5_down_4096x14336", TCQH, 4096, 14336, 10)]
     raise ValueError(cfg)
 
 

@@ -50,6 +50,10 @@ def desc(**kw):
     (dict(scheme=qp.QP_TCQH, vec=2, code_bits=5, window_bits=16, tile=256, tlut_bits=9, row_stride=320), 0),
     (dict(scheme=qp.QP_TCQH, vec=2, code_bits=5, window_bits=16, tile=256, tlut_bits=10, row_stride=320), 3),
     (dict(scheme=qp.QP_TCQH, vec=2, code_bits=9, window_bits=16, tile=256, tlut_bits=9, row_stride=576), 3),
+    (dict(scheme=qp.QP_TCQH, vec=2, code_bits=9, window_bits=16, tile=256, tlut_bits=10, row_stride=576), 0),
+    (dict(scheme=qp.QP_TCQH, vec=2, code_bits=10, window_bits=16, tile=256, tlut_bits=11, row_stride=640), 0),
+    (dict(scheme=qp.QP_TCQH, vec=2, code_bits=10, window_bits=16, tile=256, tlut_bits=10, row_stride=640), 3),
+    (dict(scheme=qp.QP_TCQH, vec=2, code_bits=11, window_bits=16, tile=256, tlut_bits=11, row_stride=704), 3),
     (dict(scheme=qp.QP_TCQH, vec=1, code_bits=4, window_bits=16, tile=256, tlut_bits=9, row_stride=512), 3),
     (dict(M=0), 2),
     (dict(N=1020), 2),

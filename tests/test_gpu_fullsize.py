@@ -16,6 +16,10 @@ CASES = [  # (cfg, layer index, batches)
     (3, 0, [1, 4, 8]),
     (4, 0, [1, 16]),
     (4, 3, [1, 2, 8]),
+    (5, 1, [1]),
+    (5, 3, [1, 8]),
+    (6, 1, [1, 8]),
+    (6, 6, [1]),
 ]
 
 
@@ -57,9 +61,13 @@ def test_full_size_layer_on_sampled_rows(qp, cfg, li, batches):
     for B in batches:
         x = synth.make_x(cfg, li, B, lay.N)
         xd = torch.from_numpy(x.view(np.int16)).cuda().view(torch.float16)
-        xr = qp.qp_hadamard(xd, torch.from_numpy(sg).cuda(), block)
+        sgd = torch.from_numpy(sg).cuda()
+        xr = qp.qp_hadamard(xd, sgd, block)
         y = qp.qp_linear(w, xr)
+        # the single-call step that bench.py times: same numbers, bit for bit
+        y_step = qp.qp_rotate_linear(w, xd, sgd, block)
         torch.cuda.synchronize()
+        assert torch.equal(y_step, y)
         xr_host = xr.cpu().view(torch.int16).numpy().view(np.uint16)
         # isolated check: the oracle multiplies the very fp16 xr the kernel received
         want = oracle.linear(sub, xr_host)

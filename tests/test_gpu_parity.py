@@ -13,8 +13,10 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 SCHEMES = [(synth.SQ, 4), (synth.VQ, 5), (synth.VQ, 7), (synth.TCQ, 2), (synth.TCQ, 3), (synth.TCQ, 4),
-           (synth.TCQH, 3), (synth.TCQH, 4), (synth.TCQH, 5), (synth.TCQH, 6), (synth.TCQH, 7), (synth.TCQH, 8)]
-IDS = ["sq4", "vq5", "vq7", "tcq2", "tcq3", "tcq4", "tcqh1.5", "tcqh2", "tcqh2.5", "tcqh3", "tcqh3.5", "tcqh4"]
+           (synth.TCQH, 3), (synth.TCQH, 4), (synth.TCQH, 5), (synth.TCQH, 6), (synth.TCQH, 7), (synth.TCQH, 8),
+           (synth.TCQH, 9), (synth.TCQH, 10)]
+IDS = ["sq4", "vq5", "vq7", "tcq2", "tcq3", "tcq4", "tcqh1.5", "tcqh2", "tcqh2.5", "tcqh3", "tcqh3.5", "tcqh4",
+       "tcqh4.5", "tcqh5"]
 TOL = 1e-2
 
 
