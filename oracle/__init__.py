@@ -79,6 +79,7 @@ def half_to_double(a) -> np.ndarray:
 
 
 TCQH = 3   # trellis with the hybrid computed code book: expanded here, then decoded as a trellis
+TCQHH = 4  # half-TCQ: first half of the input channels at code_bits per step, second half at code_bits + 1
 
 
 def hybrid_lut(tlut16, tlut_bits: int) -> np.ndarray:
@@ -93,6 +94,8 @@ def hybrid_lut(tlut16, tlut_bits: int) -> np.ndarray:
 def _scheme_and_lut(layer):
     if layer.scheme == TCQH:
         return 2, hybrid_lut(layer.lut, layer.tlut_bits).reshape(-1)
+    if layer.scheme == TCQHH:
+        return 3, hybrid_lut(layer.lut, layer.tlut_bits).reshape(-1)
     return layer.scheme, _u16(layer.lut)
 
 

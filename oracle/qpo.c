@@ -164,13 +164,28 @@ void qpo_hybrid_lut(const uint16_t *tlut, int tb, uint16_t *lut)
     }
 }
 
-enum { QPO_SQ = 0, QPO_VQ = 1, QPO_TCQ = 2 };
+/* Half-TCQ (Section 3.2; Appendix C.3.2 "Dequantization"): the input channels are cut in
+ * two halves; the first N/2 weights of a row are a trellis stream with s bits per step,
+ * the second N/2 a trellis stream with s + 1 bits per step (bitwidths b and b + 1/2 at
+ * V = 2), both decoded with the same table, and the two decoded halves are concatenated.
+ * The second stream starts at the byte after the first one's last tile. */
+void qpo_decode_row_half_tcq(const uint8_t *row, int N, int s, int L, int T, int V,
+                             const uint16_t *lut, uint16_t *out)
+{
+    int half = N / 2;
+    int64_t first_bytes = (int64_t)(half / T) * ((int64_t)s * T / V / 8);
+    qpo_decode_row_tcq(row, half, s, L, T, V, lut, out);
+    qpo_decode_row_tcq(row + first_bytes, half, s + 1, L, T, V, lut, out + half);
+}
+
+enum { QPO_SQ = 0, QPO_VQ = 1, QPO_TCQ = 2, QPO_HALF_TCQ = 3 };
 
 static void decode_row(int scheme, const uint8_t *row, int N, int code_bits, int V, int L, int T,
                        const uint16_t *lut, uint16_t *out)
 {
     if (scheme == QPO_SQ) qpo_decode_row_sq(row, N, code_bits, lut, out);
     else if (scheme == QPO_VQ) qpo_decode_row_vq(row, N, code_bits, V, lut, out);
+    else if (scheme == QPO_HALF_TCQ) qpo_decode_row_half_tcq(row, N, code_bits, L, T, V, lut, out);
     else qpo_decode_row_tcq(row, N, code_bits, L, T, V, lut, out);
 }
 
@@ -178,7 +193,7 @@ static void decode_row(int scheme, const uint8_t *row, int N, int code_bits, int
 int qpo_decode(int scheme, const uint8_t *codes, int64_t row_stride, int M, int N,
                int code_bits, int V, int L, int T, const uint16_t *lut, uint16_t *out)
 {
-    if (scheme < 0 || scheme > 2) return 1;
+    if (scheme < 0 || scheme > 3) return 1;
     for (int j = 0; j < M; ++j)
         decode_row(scheme, codes + (int64_t)j * row_stride, N, code_bits, V, L, T, lut,
                    out + (int64_t)j * N);
@@ -266,7 +281,7 @@ int qpo_linear_rows(int scheme, const uint8_t *codes, int64_t row_stride, int M,
                     int code_bits, int V, int L, int T, const uint16_t *lut, const uint16_t *scales,
                     const double *x, int B, int row_begin, int row_end, double *y, int use_threads)
 {
-    if (scheme < 0 || scheme > 2) return 1;
+    if (scheme < 0 || scheme > 3) return 1;
     (void)use_threads;
 #if defined(_OPENMP)
 #pragma omp parallel if (use_threads)

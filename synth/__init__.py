@@ -29,7 +29,9 @@ import numpy as np
 TENSOR_CODES, TENSOR_LUT, TENSOR_SCALES, TENSOR_X, TENSOR_SIGNS = 0, 1, 2, 3, 4
 
 SQ, VQ, TCQ, TCQH = 0, 1, 2, 3   # TCQH: trellis (V=2) with the hybrid computed code book
-SCHEME_NAMES = {SQ: "sq", VQ: "vq", TCQ: "tcq", TCQH: "tcqh"}
+TCQHH = 4                        # half-TCQ: TCQH with code_bits per step on the first N/2 input channels,
+                                 # code_bits + 1 on the rest, one small table (that of code_bits + 1)
+SCHEME_NAMES = {SQ: "sq", VQ: "vq", TCQ: "tcq", TCQH: "tcqh", TCQHH: "tcqhh"}
 
 
 def rng(cfg: int, layer: int, tensor: int) -> np.random.Generator:
@@ -126,7 +128,7 @@ class Layer:
 
     @property
     def bits_per_weight(self) -> float:
-        return self.code_bits / self.vec
+        return self.row_bytes * 8 / self.N
 
     @property
     def code_bytes(self) -> int:
@@ -134,6 +136,10 @@ class Layer:
 
 
 def row_bytes_for(scheme: int, N: int, code_bits: int, vec: int) -> int:
+    if scheme == TCQHH:
+        if N % 512:
+            raise ValueError("each half must be whole 256-weight tiles")
+        return row_bytes_for(TCQH, N // 2, code_bits, vec) + row_bytes_for(TCQH, N // 2, code_bits + 1, vec)
     bits = N // vec * code_bits
     if bits % 8:
         raise ValueError("row is not a whole number of bytes")
@@ -144,9 +150,11 @@ def make_layer(cfg: int, layer: int, scheme: int, M: int, N: int, code_bits: int
                *, vec: int | None = None, window_bits: int = 16, tile: int = 256,
                lut: np.ndarray | None = None, name: str = "", tlut_bits: int | None = None) -> Layer:
     if vec is None:
-        vec = 2 if scheme in (VQ, TCQH) else 1
-    if tlut_bits is None:   # table size by bitwidth, as in the paper (App. C.3.1)
-        tlut_bits = 9 if code_bits <= 8 else 10 if code_bits == 9 else 11
+        vec = 2 if scheme in (VQ, TCQH, TCQHH) else 1
+    if tlut_bits is None:   # table size by bitwidth, as in the paper (App. C.3.1; half-TCQ takes
+        # the table of its higher bitwidth, App. C.3.2)
+        top = code_bits + (1 if scheme == TCQHH else 0)
+        tlut_bits = 9 if top <= 8 else 10 if top == 9 else 11
     rb = row_bytes_for(scheme, N, code_bits, vec)
     codes = rng(cfg, layer, TENSOR_CODES).integers(0, 256, size=(M, rb), dtype=np.uint8)
     scales = rng(cfg, layer, TENSOR_SCALES).uniform(0.5, 1.5, size=M).astype(np.float16)
@@ -155,17 +163,17 @@ def make_layer(cfg: int, layer: int, scheme: int, M: int, N: int, code_bits: int
             lut = sq_lut(code_bits)
         elif scheme == VQ:
             lut = vq_lut(cfg, layer, code_bits).reshape(-1)
-        elif scheme == TCQH:
+        elif scheme in (TCQH, TCQHH):
             lut = tcqh_tlut(cfg, layer, tlut_bits).reshape(-1)
         else:
             lut = tcq_lut(cfg, layer, window_bits, vec)
-    trellis = scheme in (TCQ, TCQH)
+    trellis = scheme in (TCQ, TCQH, TCQHH)
     return Layer(scheme=scheme, M=M, N=N, code_bits=code_bits, vec=vec,
                  window_bits=window_bits if trellis else 0,
                  tile=tile if trellis else 0,
                  codes=codes, lut=np.ascontiguousarray(lut, dtype=np.float16).reshape(-1),
                  scales=scales, name=name or f"cfg{cfg}.L{layer}",
-                 tlut_bits=tlut_bits if scheme == TCQH else 0)
+                 tlut_bits=tlut_bits if scheme in (TCQH, TCQHH) else 0)
 
 
 def make_x(cfg: int, layer: int, B: int, N: int) -> np.ndarray:

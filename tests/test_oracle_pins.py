@@ -474,3 +474,108 @@ def test_tcqh_two_bit_distortion_between_bound_and_scalar():
     assert abs(((w - v) ** 2).sum(1) - errs).max() < 1e-9
     assert 2.0 ** -4 < mse < gold["NUQ-2"][1], mse
     assert mse < 0.09, mse
+
+
+# ------------------------------------------------------------------ half-TCQ
+def _half_layers(lay):
+    """The two halves of a half-TCQ layer as stand-alone TCQH layers (same table)."""
+    s, N = lay.code_bits, lay.N
+    nb0 = synth.row_bytes_for(synth.TCQH, N // 2, s, 2)
+    mk = lambda codes, cb: synth.Layer(scheme=synth.TCQH, M=lay.M, N=N // 2, code_bits=cb, vec=2, window_bits=16,
+                                       tile=256, codes=np.ascontiguousarray(codes), lut=lay.lut, scales=lay.scales,
+                                       tlut_bits=lay.tlut_bits)
+    return mk(lay.codes[:, :nb0], s), mk(lay.codes[:, nb0:], s + 1)
+
+
+@pytest.mark.parametrize("s", [3, 4, 8, 9])
+def test_half_tcq_bitwidth_and_concatenation(s):
+    """Section 3.2 / Appendix C.3.2: half of the input channels at b = s/2 bits, the other half
+    at b + 1/2, i.e. b + 1/4 bits per weight on average (1.75 for s = 3 ... 4.75 for s = 9); the
+    decoded row is the two decoded halves one after the other; the table is the one of the
+    higher bitwidth (2^9 pairs up to 4 bits, 2^10 at 4.5, 2^11 at 5)."""
+    N = 1024
+    lay = synth.make_layer(50, s, synth.TCQHH, 4, N, s)
+    assert lay.bits_per_weight == s / 2 + 0.25
+    assert lay.tlut_bits == (9 if s + 1 <= 8 else 10 if s + 1 == 9 else 11)
+    W = oracle.decode(lay)
+    lo, hi = _half_layers(lay)
+    assert np.array_equal(W[:, : N // 2], oracle.decode(lo))
+    assert np.array_equal(W[:, N // 2:], oracle.decode(hi))
+
+
+def test_half_tcq_split_point_and_order():
+    """All-zero bytes in the first half's stream and all-one bytes in the second: the first
+    N/2 weights read state 0, the last N/2 read state 0xffff - and the other way round.  Pins
+    which half comes first, where the second stream starts and which half has the extra bit."""
+    s, N = 4, 1024
+    lay = synth.make_layer(51, 0, synth.TCQHH, 1, N, s)
+    full = oracle.hybrid_lut(lay.lut, lay.tlut_bits)
+    nb0 = N // 4 * s // 8            # bytes of the first half: N/4 steps of s bits
+    assert lay.codes.shape[1] == nb0 + N // 4 * (s + 1) // 8
+    for first, second in ((0x00, 0xFF), (0xFF, 0x00)):
+        lay.codes[:] = second
+        lay.codes[:, :nb0] = first
+        W = oracle.decode(lay)[0]
+        e1 = full[0 if first == 0 else 0xFFFF]
+        e2 = full[0 if second == 0 else 0xFFFF]
+        assert np.array_equal(W[: N // 2].reshape(-1, 2), np.tile(e1, (N // 4, 1)))
+        assert np.array_equal(W[N // 2:].reshape(-1, 2), np.tile(e2, (N // 4, 1)))
+
+
+def test_half_tcq_tiles_do_not_cross_the_boundary():
+    """A single set bit in the last byte of the first half changes only weights of the first
+    half's last tile (tail-biting wraps inside that tile); one in the first byte of the second
+    half only weights of the second half's first tile."""
+    s, N, T = 5, 1024, 256
+    lay = synth.make_layer(52, 0, synth.TCQHH, 1, N, s)
+    nb0 = N // 4 * s // 8
+    lay.codes[:] = 0
+    base = oracle.decode(lay)[0].copy()
+    lay.codes[0, nb0 - 1] = 0x80      # last bit of the first stream
+    d = np.nonzero(oracle.decode(lay)[0] != base)[0]
+    assert d.size and d.min() >= N // 2 - T and d.max() < N // 2
+    # that bit is bit 15 of the last window and, wrapping, not part of the tile's first window
+    # (which starts at bit 0 and ends at bit 15 of the tile): the last pair must have changed
+    assert N // 2 - 1 in d or N // 2 - 2 in d
+    lay.codes[:] = 0
+    lay.codes[0, nb0] = 0x80          # bit 7 of the second stream: state 128 in its first window
+    d = np.nonzero(oracle.decode(lay)[0] != base)[0]
+    assert d.size and d.min() >= N // 2 and d.max() < N // 2 + T
+    assert d.min() == N // 2          # (h = 128 * 129 selects entry 258: the first pair changes)
+    # ... and by tail-biting the last window of that same tile (bits 762..767, 0..9) sees it as
+    # bit 13 of its state
+    assert d.max() >= N // 2 + T - 2
+
+
+def test_half_tcq_linear_is_sum_of_the_halves():
+    """y = x W^T diag(s) over the concatenated row = contribution of the first N/2 inputs
+    through the first half + the rest through the second."""
+    s, N, M, B = 6, 1024, 8, 3
+    lay = synth.make_layer(53, 0, synth.TCQHH, M, N, s)
+    x = synth.make_x(53, 0, B, N)
+    lo, hi = _half_layers(lay)
+    want = oracle.linear(lo, x[:, : N // 2]) + oracle.linear(hi, x[:, N // 2:])
+    got = oracle.linear(lay, x)
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-12)
+    Wd = oracle.half_to_double(oracle.decode(lay))
+    assert np.allclose(got, oracle.matmul_scaled(oracle.half_to_double(x), oracle.decode(lay), lay.scales), rtol=1e-12)
+    assert np.allclose(got, (oracle.half_to_double(x) @ Wd.T) * oracle.half_to_double(lay.scales), rtol=1e-10, atol=1e-10)
+
+
+def test_half_tcq_distortion_between_its_two_bitwidths():
+    """Encoding Gaussian tiles of the first half at 2 bits and of the second at 2.5 bits with the
+    Viterbi encoder and decoding the whole layer: the distortion of the mix lies strictly
+    between the two halves' own (Section 3.2: intermediate bitwidths between two TCQ quantizers)."""
+    s, T, nt = 4, 256, 8
+    N = 2 * nt * T
+    lay = synth.make_layer(54, 0, synth.TCQHH, 1, N, s)
+    full = oracle.hybrid_lut(lay.lut, lay.tlut_bits).view(np.float16).reshape(-1)
+    v = np.random.default_rng(54).standard_normal((2 * nt, T))
+    st_lo, _ = oracle.tcq_encode_tiles(v[:nt], s, 16, T, 2, full)
+    st_hi, _ = oracle.tcq_encode_tiles(v[nt:], s + 1, 16, T, 2, full)
+    lay.codes = np.concatenate([st_lo.reshape(-1), st_hi.reshape(-1)])[None, :].copy()
+    w = oracle.half_to_double(oracle.decode(lay))[0].reshape(2 * nt, T)
+    mse = ((w - v) ** 2).mean(axis=1)
+    d_lo, d_hi, d_all = mse[:nt].mean(), mse[nt:].mean(), mse.mean()
+    assert d_hi < d_all < d_lo
+    assert 2.0 ** -5 < d_hi and d_lo < 0.1   # between the 2.5-bit rate-distortion bound and scalar 2-bit
