@@ -287,7 +287,8 @@ def main():
         todo = [(3, 0, 1), (3, 0, 4), (3, 0, 8), (2, 0, 1), (1, 0, 1),
                 (4, 0, 1), (4, 1, 1), (4, 2, 1), (4, 3, 1), (4, 3, 8), (4, 3, 16), (4, 2, 8),
                 (5, 0, 1), (5, 1, 1), (5, 2, 1), (5, 3, 1), (5, 2, 8), (5, 3, 8),
-                (6, 0, 1), (6, 1, 1), (6, 2, 1), (6, 3, 1), (6, 1, 8), (6, 4, 1), (6, 5, 1), (6, 6, 1)]
+                (6, 0, 1), (6, 1, 1), (6, 2, 1), (6, 3, 1), (6, 1, 8), (6, 4, 1), (6, 5, 1), (6, 6, 1),
+                (6, 7, 1), (6, 8, 1), (6, 8, 8), (6, 9, 1)]
         for cfg, li, B in todo:
             if (cfg, li, B) == (a.cfg, a.layer, a.batch):
                 continue

@@ -17,6 +17,10 @@
  *           small table tlut[2^tb][2]: h = x(x+1), entry (h >> (15-tb)) mod 2^tb, component 0 negated
  *           when bit 15 of h is set (App. C.3.1 "Codebook construction")
  *
+ *   QP_TCQHH half-TCQ (Section 3.2, App. C.3.2): QP_TCQH with s bits per step on the first N/2 input
+ *           channels and s + 1 on the remaining N/2 (s/2 + 1/4 bits per weight), both halves decoded
+ *           with the one small table that belongs to s + 1
+ *
  * Notation: M = out_features = rows of W^, N = in_features = columns, B = batch.
  *
  * CANONICAL LAYOUT (QP_LAYOUT_CANONICAL).  Row j of W^ is one bitstream of
@@ -26,6 +30,9 @@
  * code_bits*tile bits; inside a tile weight i is LUT[window], the window being
  * the window_bits stream bits from i*code_bits on, taken modulo the tile's length.
  *
+ * For QP_TCQHH a row is the N/512 tiles of the first half (16 s bytes each) followed by the N/512
+ * tiles of the second half (16 (s + 1) bytes each).
+ *
  * NATIVE LAYOUT (QP_LAYOUT_NATIVE), produced by qp_repack; needs M % 16 == 0 and
  * N % 1024 == 0.  The matrix is cut into blocks of 16 rows x 1024 columns, stored
  * block-row-major (all column blocks of rows 0..15, then rows 16..31, ...).  Within
@@ -34,7 +41,9 @@
  * holds for that span (bpw = code_bits/vec).  Those bytes are cut into P = 2*bpw
  * pieces of 16 bytes; piece p of lane l sits at byte (p*64 + l)*16 of the block, so
  * one 128-bit load per lane of a 64-wide wavefront reads 1 KiB contiguously.
- * row_stride is ignored for this layout.
+ * row_stride is ignored for this layout.  QP_TCQHH (needs N % 2048 == 0): the column blocks of the
+ * second half have one piece more than those of the first; a block row is the N/2048 blocks of the
+ * first half followed by the N/2048 blocks of the second.
  *
  * All pointers named "device" are device (HBM) pointers owned by the caller; the
  * library allocates no device memory and keeps no mutable state.  Every entry
@@ -64,7 +73,7 @@ typedef enum {
     QP_ERR_WORKSPACE = 7    /* workspace smaller than qp_linear_workspace_bytes()          */
 } qp_status;
 
-typedef enum { QP_SQ = 0, QP_VQ = 1, QP_TCQ = 2, QP_TCQH = 3 } qp_scheme;
+typedef enum { QP_SQ = 0, QP_VQ = 1, QP_TCQ = 2, QP_TCQH = 3, QP_TCQHH = 4 } qp_scheme;
 typedef enum { QP_LAYOUT_CANONICAL = 0, QP_LAYOUT_NATIVE = 1 } qp_layout;
 
 #define QP_MAX_BATCH 16
@@ -76,6 +85,8 @@ typedef enum { QP_LAYOUT_CANONICAL = 0, QP_LAYOUT_NATIVE = 1 } qp_layout;
  *   QP_TCQH: vec 2, window_bits 16, tile 256, code_bits s = 3..10 (1.5 .. 5 bits per weight),
  *            tlut_bits 9 for s <= 8, 10 for s = 9, 11 for s = 10, the table sizes of App. C.3.1
  *            (lut = the small table, fp16 [2^tlut_bits][2])
+ *   QP_TCQHH: vec 2, window_bits 16, tile 256, code_bits s = 3..9 (1.75 .. 4.75 bits per weight),
+ *            N % 512 == 0, tlut_bits that of s + 1 (9 for s <= 7, 10 for s = 8, 11 for s = 9)
  * Fused layers (QKV, gate+up; Section 4.2) are one qp_weight with M the sum of the
  * members' out_features. */
 typedef struct {
@@ -88,9 +99,9 @@ typedef struct {
     int32_t layout;      /* qp_layout                                                          */
     int64_t row_stride;  /* canonical: bytes between rows of codes, multiple of 16, >= row bytes */
     const void *codes;   /* device, 16-byte aligned                                            */
-    const void *lut;     /* device, fp16, 4-byte aligned: SQ 2^code_bits; VQ 2^code_bits*vec; TCQ 2^L*vec; TCQH 2^tlut_bits*vec */
+    const void *lut;     /* device, fp16, 4-byte aligned: SQ 2^code_bits; VQ 2^code_bits*vec; TCQ 2^L*vec; TCQH, TCQHH 2^tlut_bits*vec */
     const void *scales;  /* device, fp16 [M], 2-byte aligned: per-output-channel factor s      */
-    int32_t tlut_bits;   /* QP_TCQH: log2 of the small table's entries; otherwise 0            */
+    int32_t tlut_bits;   /* QP_TCQH, QP_TCQHH: log2 of the small table's entries; otherwise 0  */
     int32_t reserved;    /* 0                                                                  */
 } qp_weight;
 

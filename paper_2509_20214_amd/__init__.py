@@ -6,12 +6,12 @@ arguments (torch tensors -> device pointers, the current HIP stream).  Every
 step of the path runs in the library's HIP kernels; there is no CPU fallback —
 if the library cannot be loaded, importing `binding` users fail loudly.
 """
-from .binding import (QP_SQ, QP_VQ, QP_TCQ, QP_TCQH, QP_LAYOUT_CANONICAL, QP_LAYOUT_NATIVE, QpError, Weight,
+from .binding import (QP_SQ, QP_VQ, QP_TCQ, QP_TCQH, QP_TCQHH, QP_LAYOUT_CANONICAL, QP_LAYOUT_NATIVE, QpError, Weight,
                       load_library, qp_dequant, qp_hadamard, qp_linear, qp_linear_workspace_bytes,
                       qp_native_bytes, qp_repack, qp_rotate_linear, qp_rotate_linear_workspace_bytes,
                       qp_status_string, qp_validate, qp_version)
 
-__all__ = ["QP_SQ", "QP_VQ", "QP_TCQ", "QP_TCQH", "QP_LAYOUT_CANONICAL", "QP_LAYOUT_NATIVE", "QpError", "Weight",
+__all__ = ["QP_SQ", "QP_VQ", "QP_TCQ", "QP_TCQH", "QP_TCQHH", "QP_LAYOUT_CANONICAL", "QP_LAYOUT_NATIVE", "QpError", "Weight",
            "load_library", "qp_dequant", "qp_hadamard", "qp_linear", "qp_linear_workspace_bytes",
            "qp_native_bytes", "qp_repack", "qp_rotate_linear", "qp_rotate_linear_workspace_bytes",
            "qp_status_string", "qp_validate", "qp_version"]

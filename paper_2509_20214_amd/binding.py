@@ -7,7 +7,7 @@ import os
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libqp.so")
 
-QP_SQ, QP_VQ, QP_TCQ, QP_TCQH = 0, 1, 2, 3
+QP_SQ, QP_VQ, QP_TCQ, QP_TCQH, QP_TCQHH = 0, 1, 2, 3, 4
 QP_LAYOUT_CANONICAL, QP_LAYOUT_NATIVE = 0, 1
 QP_OK = 0
 
@@ -43,6 +43,10 @@ def load_library(build_if_missing: bool = True):
             raise FileNotFoundError(LIB_PATH)
         from . import build as _b
         _b.build()
+    # PyTorch ships its own copy of the HIP runtime.  It must be the one already in the
+    # process when libqp.so resolves libamdhip64: with two runtimes loaded, kernels registered
+    # in one cannot be launched on device pointers and streams that belong to the other.
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
     wp = C.POINTER(qp_weight)

@@ -27,12 +27,23 @@ static qp_status scheme_supported(const qp_weight *w) {
                     w->tlut_bits == (w->code_bits <= 8 ? 9 : w->code_bits == 9 ? 10 : 11))
                        ? QP_OK
                        : QP_ERR_UNSUPPORTED;
+        case QP_TCQHH: {
+            // s on the first half of the input channels, s + 1 on the second; the table of s + 1
+            const int top = w->code_bits + 1;
+            return (w->vec == 2 && w->window_bits == 16 && w->tile == 256 && w->code_bits >= 3 &&
+                    w->code_bits <= 9 && w->tlut_bits == (top <= 8 ? 9 : top == 9 ? 10 : 11))
+                       ? QP_OK
+                       : QP_ERR_UNSUPPORTED;
+        }
         default:
             return QP_ERR_UNSUPPORTED;
     }
 }
 
-static inline int64_t row_bytes(const qp_weight *w) { return (int64_t)w->N / w->vec * w->code_bits / 8; }
+static inline int64_t row_bytes(const qp_weight *w) {
+    if (w->scheme == QP_TCQHH) return (int64_t)w->N / 4 * (2 * w->code_bits + 1) / 8;
+    return (int64_t)w->N / w->vec * w->code_bits / 8;
+}
 static inline int span_bytes(const qp_weight *w) { return 32 * w->code_bits / w->vec; }
 
 extern "C" qp_status qp_validate(const qp_weight *w) {
@@ -42,6 +53,7 @@ extern "C" qp_status qp_validate(const qp_weight *w) {
     if (w->M <= 0 || w->N <= 0) return QP_ERR_SHAPE;
     if (w->N % 8 != 0) return QP_ERR_SHAPE;
     if ((w->scheme == QP_TCQ || w->scheme == QP_TCQH) && w->N % w->tile != 0) return QP_ERR_SHAPE;
+    if (w->scheme == QP_TCQHH && w->N % (2 * w->tile) != 0) return QP_ERR_SHAPE;
     if (!w->codes || !w->lut || !w->scales) return QP_ERR_NULL;
     if (w->layout == QP_LAYOUT_CANONICAL) {
         if (w->row_stride % 16 != 0) return QP_ERR_ALIGN;
@@ -49,6 +61,7 @@ extern "C" qp_status qp_validate(const qp_weight *w) {
         if ((int64_t)w->row_stride * w->M > ((int64_t)1 << 40)) return QP_ERR_SHAPE;
     } else if (w->layout == QP_LAYOUT_NATIVE) {
         if (w->M % 16 != 0 || w->N % 1024 != 0) return QP_ERR_LAYOUT;
+        if (w->scheme == QP_TCQHH && w->N % 2048 != 0) return QP_ERR_LAYOUT;
     } else {
         return QP_ERR_LAYOUT;
     }
@@ -171,6 +184,7 @@ extern "C" qp_status qp_hadamard(const void *x, const int8_t *signs, int32_t B, 
 extern "C" size_t qp_native_bytes(const qp_weight *c) {
     if (!c || scheme_supported(c) != QP_OK) return 0;
     if (c->M <= 0 || c->N <= 0 || c->M % 16 != 0 || c->N % 1024 != 0) return 0;
+    if (c->scheme == QP_TCQHH && c->N % 2048 != 0) return 0;
     return (size_t)c->M * (size_t)row_bytes(c);
 }
 
@@ -189,7 +203,10 @@ extern "C" qp_status qp_repack(const qp_weight *c, qp_weight *native_out, void *
         int64_t ea = (int64_t)c->row_stride * c->M;
         if (a < b + (int64_t)need && b < a + ea) return QP_ERR_ALIGN;
     }
-    s = qp_launch_repack(make_dev(c), span_bytes(c), native_codes, static_cast<hipStream_t>(hip_stream));
+    if (c->scheme == QP_TCQHH)
+        s = qp_launch_repack_half(make_dev(c), c->code_bits, native_codes, static_cast<hipStream_t>(hip_stream));
+    else
+        s = qp_launch_repack(make_dev(c), span_bytes(c), native_codes, static_cast<hipStream_t>(hip_stream));
     if (s != QP_OK) return s;
     *native_out = *c;
     native_out->layout = QP_LAYOUT_NATIVE;

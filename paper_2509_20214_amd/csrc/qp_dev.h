@@ -25,15 +25,20 @@ struct QpW {
 };
 
 // Compile-time facts about a (scheme, code_bits) pair.
+// For QP_TCQHH (half-TCQ) the per-span figures are those of the first half (CB bits per
+// step); the second half has CB + 1 bits per step: 16 bytes more per span, one piece more.
 template <int S, int CB>
 struct QpTraits {
-    static constexpr int V = (S == QP_VQ || S == QP_TCQH) ? 2 : 1;
+    static constexpr int V = (S == QP_VQ || S == QP_TCQH || S == QP_TCQHH) ? 2 : 1;
     static constexpr int BITS8 = 8 * CB / V;           // stream bits that 8 weights advance
     static constexpr int SPAN = 32 * CB / V;           // bytes of a 256-weight span
     static constexpr int PIECES = SPAN / 16;           // 16-byte pieces per span
     // QP_TCQH: the small table has 2^9 pairs up to 4 bits per weight, 2^10 at 4.5, 2^11 at 5
-    static constexpr int TLUT_BITS = (S != QP_TCQH) ? 0 : (CB <= 8) ? 9 : (CB == 9) ? 10 : 11;
-    static constexpr int LUT_HALVES = (S == QP_TCQ) ? 65536 : (S == QP_TCQH) ? (2 << TLUT_BITS) : (1 << CB) * V;
+    // half-TCQ takes the table of its higher bitwidth (App. C.3.2)
+    static constexpr int TOP = (S == QP_TCQHH) ? CB + 1 : CB;
+    static constexpr bool HYBRID = (S == QP_TCQH || S == QP_TCQHH);
+    static constexpr int TLUT_BITS = !HYBRID ? 0 : (TOP <= 8) ? 9 : (TOP == 9) ? 10 : 11;
+    static constexpr int LUT_HALVES = (S == QP_TCQ) ? 65536 : HYBRID ? (2 << TLUT_BITS) : (1 << CB) * V;
     static constexpr int BLOCK_BYTES = 64 * SPAN;      // one 16 x 1024 native block
 };
 
@@ -48,6 +53,24 @@ __device__ __forceinline__ const uint32_t *qp_dword_ptr(const QpW &w, int row, i
     int64_t blk = (int64_t)R * w.nbc + C;
     return reinterpret_cast<const uint32_t *>(w.codes + blk * (64 * SPAN) +
                                               ((((beta >> 4) * 64 + g * 16 + i) << 4) + (beta & 15)));
+}
+
+// Half-TCQ: address of byte `byte` (a multiple of 4) of 256-weight tile `tile` of row `row`.
+// Tiles of the first half (tile < N/512) hold 16 CB bytes, the others 16 (CB + 1).  Native
+// layout: a block row is N/2048 blocks of the first kind followed by N/2048 of the second.
+template <int CB>
+__device__ __forceinline__ const uint32_t *qp_hh_dword_ptr(const QpW &w, int row, int tile, int byte) {
+    const int th = w.N >> 9;   // tiles per half
+    const bool hi = tile >= th;
+    if (w.layout == QP_LAYOUT_CANONICAL) {
+        const int64_t off = hi ? (int64_t)th * (16 * CB) + (int64_t)(tile - th) * (16 * (CB + 1))
+                               : (int64_t)tile * (16 * CB);
+        return reinterpret_cast<const uint32_t *>(w.codes + (int64_t)row * w.row_stride + off + byte);
+    }
+    const int C = tile >> 2, g = tile & 3, i = row & 15, R = row >> 4, h = w.nbc >> 1;
+    const int64_t base = (int64_t)R * h * (1024 * (2 * CB + 1)) +
+                         (hi ? (int64_t)h * (1024 * CB) + (int64_t)(C - h) * (1024 * (CB + 1)) : (int64_t)C * (1024 * CB));
+    return reinterpret_cast<const uint32_t *>(w.codes + base + ((((byte >> 4) * 64 + g * 16 + i) << 4) + (byte & 15)));
 }
 
 // The 64 stream bits that start at the first bit of weight group `grp` (8 weights)
@@ -111,7 +134,24 @@ __device__ __forceinline__ uint32_t qp_hybrid_entry(uint32_t state, const uint32
 template <int S, int CB>
 __device__ __forceinline__ void qp_group_decode(const QpW &w, int row, int grp, const uint16_t *lut,
                                                 uint16_t (&v)[8]) {
-    if constexpr (S == QP_TCQH) {
+    if constexpr (S == QP_TCQHH) {
+        const int tile = grp >> 5, u = grp & 31;
+        const int cb = CB + ((tile >= (w.N >> 9)) ? 1 : 0);   // bits per step of this tile's half
+        const int span4 = 4 * cb;                             // dwords per tile
+        const uint32_t *lut2 = reinterpret_cast<const uint32_t *>(lut);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int bit = (4 * u + c) * cb;
+            const int d0 = bit >> 5, r = bit & 31;
+            const int d1 = (d0 + 1 == span4) ? 0 : d0 + 1;   // tail-biting wrap
+            const uint32_t lo = *qp_hh_dword_ptr<CB>(w, row, tile, d0 * 4);
+            const uint32_t hi = *qp_hh_dword_ptr<CB>(w, row, tile, d1 * 4);
+            const uint32_t state = (uint32_t)(((((uint64_t)hi) << 32) | lo) >> r) & 0xffffu;
+            const uint32_t e = qp_hybrid_entry(state, lut2, w.tlut_bits);
+            v[2 * c] = (uint16_t)e;
+            v[2 * c + 1] = (uint16_t)(e >> 16);
+        }
+    } else if constexpr (S == QP_TCQH) {
         using T = QpTraits<S, CB>;
         const int tile = grp >> 5, u = grp & 31;
         const uint32_t *lut2 = reinterpret_cast<const uint32_t *>(lut);
@@ -167,5 +207,12 @@ __device__ __forceinline__ float qp_half_bits_to_float(uint16_t h) {
         else if ((scheme) == QP_TCQH && (cb) == 8) { CALL(QP_TCQH, 8); }              \
         else if ((scheme) == QP_TCQH && (cb) == 9) { CALL(QP_TCQH, 9); }              \
         else if ((scheme) == QP_TCQH && (cb) == 10) { CALL(QP_TCQH, 10); }            \
+        else if ((scheme) == QP_TCQHH && (cb) == 3) { CALL(QP_TCQHH, 3); }            \
+        else if ((scheme) == QP_TCQHH && (cb) == 4) { CALL(QP_TCQHH, 4); }            \
+        else if ((scheme) == QP_TCQHH && (cb) == 5) { CALL(QP_TCQHH, 5); }            \
+        else if ((scheme) == QP_TCQHH && (cb) == 6) { CALL(QP_TCQHH, 6); }            \
+        else if ((scheme) == QP_TCQHH && (cb) == 7) { CALL(QP_TCQHH, 7); }            \
+        else if ((scheme) == QP_TCQHH && (cb) == 8) { CALL(QP_TCQHH, 8); }            \
+        else if ((scheme) == QP_TCQHH && (cb) == 9) { CALL(QP_TCQHH, 9); }            \
         else return QP_ERR_UNSUPPORTED;                                               \
     } while (0)

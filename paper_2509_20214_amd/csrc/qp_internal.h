@@ -15,6 +15,8 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
 qp_status qp_launch_hadamard(const void *x, const int8_t *signs, int B, int n, int block, int64_t ldx,
                              void *xr, int64_t ldxr, int pack_bp, hipStream_t st);
 qp_status qp_launch_repack(const QpW &src, int span_bytes, void *dst, hipStream_t st);
+// half-TCQ: spans of 16 cb bytes in the first N/2 columns, 16 (cb + 1) in the rest
+qp_status qp_launch_repack_half(const QpW &src, int cb, void *dst, hipStream_t st);
 
 static inline qp_status qp_check_launch() {
     return hipGetLastError() == hipSuccess ? QP_OK : QP_ERR_DEVICE;

@@ -59,18 +59,20 @@ __device__ __forceinline__ uint32_t qp_dw(const u32x4_t (&q)[P], int idx) {
 
 // 32 stream bits starting at `bitpos` (circular when WRAP; otherwise bits past the end
 // of the stream are unspecified).
-template <int P, bool WRAP>
+// PW: pieces that make up the stream (the array may be longer: half-TCQ keeps the units of
+// both halves in one array sized for the longer one).
+template <int P, bool WRAP, int PW = P>
 __device__ __forceinline__ uint32_t qp_bits32(const u32x4_t (&q)[P], int bitpos) {
     const int i0 = bitpos >> 5, r = bitpos & 31;
     if (r == 0) return qp_dw<P>(q, i0);
-    const int i1 = WRAP ? ((i0 + 1) % (4 * P)) : ((i0 + 1 < 4 * P) ? i0 + 1 : i0);
+    const int i1 = WRAP ? ((i0 + 1) % (4 * PW)) : ((i0 + 1 < 4 * PW) ? i0 + 1 : i0);
     return __builtin_amdgcn_alignbit(qp_dw<P>(q, i1), qp_dw<P>(q, i0), r);
 }
 
 // (field << LSH) & (mask << LSH) for the nbits-wide field at `bitpos`: one shift and one
 // AND when the field sits inside a dword, one funnel shift and one AND when it straddles
 // two (a straddling field starts above bit 16 >= LSH, so the funnel can start LSH bits low).
-template <int P, bool WRAP, int LSH>
+template <int P, bool WRAP, int LSH, int PW = P>
 __device__ __forceinline__ uint32_t qp_field_shl(const u32x4_t (&q)[P], int bitpos, int nbits) {
     const int i0 = bitpos >> 5, r = bitpos & 31;
     const uint32_t mask = ((1u << nbits) - 1u) << LSH;
@@ -78,7 +80,7 @@ __device__ __forceinline__ uint32_t qp_field_shl(const u32x4_t (&q)[P], int bitp
         const uint32_t w = qp_dw<P>(q, i0);
         return ((r >= LSH) ? (w >> (r - LSH)) : (w << (LSH - r))) & mask;
     }
-    return qp_bits32<P, WRAP>(q, bitpos - LSH) & mask;
+    return qp_bits32<P, WRAP, PW>(q, bitpos - LSH) & mask;
 }
 
 // (field << LSH) | orv in two vector operations, v_bfe_u32 + v_lshl_or_b32, with the
@@ -276,16 +278,18 @@ struct QpDecTcq {
 // per *two* weights - never collide; 16 and 8 copies for TB = 10 and 11, where only lanes
 // with equal l % COPIES can still meet in a bank.  The per-state work is a 24-bit
 // multiply-add, a bit-field extract and a shift-or.
-template <int K>
+template <int TB>
+struct QpTcqhPre { uint32_t raw[(1 << TB) / 1024 ? (1 << TB) / 1024 : 1]; };
+
+template <int K, int TB = QpTraits<QP_TCQH, K>::TLUT_BITS>
 struct QpDecTcqh {
-    static constexpr int TB = QpTraits<QP_TCQH, K>::TLUT_BITS;
     static constexpr int ENTRIES = 2 << TB;
     static constexpr int COPIES = 32768 / ENTRIES;          // 32, 16, 8
     static constexpr int LSH = (COPIES == 32) ? 7 : (COPIES == 16) ? 6 : 5;
     static constexpr int TAB_BYTES = 131072;
     static constexpr int SMALL_BYTES = 4 << TB;             // staging room for the source
     static constexpr int NSRC = (1 << TB) / 1024 ? (1 << TB) / 1024 : 1;   // source dwords per thread
-    struct Pre { uint32_t raw[NSRC]; };
+    typedef QpTcqhPre<TB> Pre;
     static __device__ __forceinline__ uint32_t lane_const() { return (threadIdx.x & (COPIES - 1)) << 2; }
     static __device__ __forceinline__ void early(uint8_t *, uint16_t *, const uint16_t *) {}
     static __device__ __forceinline__ Pre pre(const uint16_t *g) {  // needs blockDim.x == 1024
@@ -319,7 +323,7 @@ struct QpDecTcqh {
         uint32_t r[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const uint32_t st = qp_field_shl<P, true, 0>(q, (4 * s + c) * K, 16);
+            const uint32_t st = qp_field_shl<P, true, 0, K>(q, (4 * s + c) * K, 16);   // the stream is K pieces long
             uint32_t h, idx, a;
             asm("v_mad_u32_u24 %0, %1, %1, %1" : "=v"(h) : "v"(st));   // x (x + 1), exact: x < 2^16
             asm("v_bfe_u32 %0, %1, %2, %3" : "=v"(idx) : "v"(h), "n"(15 - TB), "n"(TB + 1));
@@ -337,6 +341,22 @@ template <> struct QpDec<QP_TCQH, 7> : QpDecTcqh<7> {};
 template <> struct QpDec<QP_TCQH, 8> : QpDecTcqh<8> {};
 template <> struct QpDec<QP_TCQH, 9> : QpDecTcqh<9> {};
 template <> struct QpDec<QP_TCQH, 10> : QpDecTcqh<10> {};
+
+// Half-TCQ (Section 3.2, App. C.3.2): column blocks of the first half of the input channels
+// carry K bits per step, those of the second half K + 1; one table, that of K + 1.
+// QpDec<QP_TCQHH, K> is the decoder of the second half (it also builds the table); Lo
+// decodes the first half from the same table.
+template <int K>
+struct QpDecHalf : QpDecTcqh<K + 1, QpTraits<QP_TCQHH, K>::TLUT_BITS> {
+    typedef QpDecTcqh<K, QpTraits<QP_TCQHH, K>::TLUT_BITS> Lo;
+};
+template <> struct QpDec<QP_TCQHH, 3> : QpDecHalf<3> {};
+template <> struct QpDec<QP_TCQHH, 4> : QpDecHalf<4> {};
+template <> struct QpDec<QP_TCQHH, 5> : QpDecHalf<5> {};
+template <> struct QpDec<QP_TCQHH, 6> : QpDecHalf<6> {};
+template <> struct QpDec<QP_TCQHH, 7> : QpDecHalf<7> {};
+template <> struct QpDec<QP_TCQHH, 8> : QpDecHalf<8> {};
+template <> struct QpDec<QP_TCQHH, 9> : QpDecHalf<9> {};
 
 template <> struct QpDec<QP_TCQ, 2> : QpDecTcq<2> {};
 template <> struct QpDec<QP_TCQ, 3> : QpDecTcq<3> {};
@@ -365,22 +385,35 @@ struct QpFold {  // acc[0] + shl1(acc[1]) + ... : lane b*TT of every row ends up
 // One unit's loads: the first PF activation fragments, then P coalesced 128-bit pieces
 // of codes.  Straight-line code (no branches) so that the waits the compiler inserts
 // later can name exactly the loads they need.
-template <int P, int PF>
-__device__ __forceinline__ void qp_unit_load(const u32x4_t *blk, const half_t *xu, int xfs, int lane,
+// The P pieces of one unit.  Half-TCQ units of the first half have one piece less: `full`
+// (wave-uniform) says whether the last one exists.
+template <int P, bool OPTIONAL_LAST>
+__device__ __forceinline__ void qp_pieces_load(const u32x4_t *blk, int lane, bool full, u32x4_t (&q)[P]) {
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        if (OPTIONAL_LAST && p == P - 1) {
+            q[p] = u32x4_t{0u, 0u, 0u, 0u};
+            if (full) q[p] = __builtin_nontemporal_load(blk + p * 64 + lane);
+        } else {
+            q[p] = __builtin_nontemporal_load(blk + p * 64 + lane);
+        }
+    }
+}
+
+template <int P, int PF, bool OPTIONAL_LAST>
+__device__ __forceinline__ void qp_unit_load(const u32x4_t *blk, const half_t *xu, int xfs, int lane, bool full,
                                              u32x4_t (&q)[P], half8_t (&xf)[PF]) {
 #pragma unroll
     for (int n = 0; n < PF; ++n) xf[n] = *reinterpret_cast<const half8_t *>(xu + xfs * n);
-#pragma unroll
-    for (int p = 0; p < P; ++p) q[p] = __builtin_nontemporal_load(blk + p * 64 + lane);
+    qp_pieces_load<P, OPTIONAL_LAST>(blk, lane, full, q);
 }
 
 // Decode and multiply one unit; the lane that owns (rows 4g..4g+3, batch row b) returns
 // their partial dot products in v.
-template <int S, int CB, int P, int PF, int TT>
+template <class D, int P, int PF, int TT>
 __device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8_t (&xf)[PF], const half_t *xu,
                                                     int xfs, const uint8_t *tab, uint32_t lc,
-                                                    const typename QpDec<S, CB>::Pre &pre) {
-    using D = QpDec<S, CB>;
+                                                    const typename D::Pre &pre) {
     constexpr int NXF = 32 / TT;
 #ifdef QP_NODECODE  // development builds only: loads without decode, to time the memory side alone
     {
@@ -477,7 +510,11 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
                                                       int x_packed) {
     using T = QpTraits<S, CB>;
     using D = QpDec<S, CB>;
-    constexpr int P = T::PIECES;
+    // Half-TCQ: the units of the second half of the column blocks have P pieces and decode
+    // with D, those of the first half have P - 1 and decode with D::Lo; both kinds share the
+    // piece array, the table and everything else.
+    constexpr bool HH = (S == QP_TCQHH);
+    constexpr int P = HH ? T::PIECES + 1 : T::PIECES;
     constexpr int LB = (BP == 1) ? 0 : (BP == 2) ? 1 : (BP == 4) ? 2 : (BP == 8) ? 3 : 4;
     // steps per activation fragment; 16 accumulators only where the registers allow it
     constexpr int TTMAX = 16;
@@ -488,7 +525,7 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
     __shared__ __attribute__((aligned(16))) uint8_t tab[D::TAB_BYTES];
     // [unit][b][row]; before the first pass the same room stages a table's source
     constexpr int RED_FLOATS = QP_UMAX * 16 * BP;
-    constexpr int SMALL_FLOATS = (S == QP_TCQH) ? (1 << T::TLUT_BITS) : 0;
+    constexpr int SMALL_FLOATS = T::HYBRID ? (1 << T::TLUT_BITS) : 0;
     __shared__ __attribute__((aligned(16))) float red[RED_FLOATS > SMALL_FLOATS ? RED_FLOATS : SMALL_FLOATS];
     QP_T(0);
 
@@ -539,11 +576,25 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
         xf[n] = *reinterpret_cast<const half8_t *>(xu + xfs * n);
 #endif
     }
+    // block (row block rb0 + slot, column block C) of unit u = slot * nbc + C, and whether
+    // it has all P pieces
+    const int hcb = nbc >> 1;   // half-TCQ: column blocks per half
+    auto unit_block = [&](int rb0, int un, int C, bool &full) -> const u32x4_t * {
+        if constexpr (HH) {
+            const int slot = (un * nbc_magic) >> 16;
+            full = __builtin_amdgcn_readfirstlane(C >= hcb);
+            return codes16 + (int64_t)(rb0 + slot) * (hcb * 64 * (2 * CB + 1)) + C * (64 * CB) +
+                   (full ? (C - hcb) * 64 : 0);
+        } else {
+            full = true;
+            return codes16 + ((int64_t)rb0 * nbc + un) * BLK16;
+        }
+    };
     u32x4_t q[P];
+    bool full;
     {
-        const u32x4_t *blk = codes16 + ((int64_t)rb_begin * nbc + uu) * BLK16;
-#pragma unroll
-        for (int p = 0; p < P; ++p) q[p] = __builtin_nontemporal_load(blk + p * 64 + lane);
+        const u32x4_t *blk = unit_block(rb_begin, uu, uu - ((uu * nbc_magic) >> 16) * nbc, full);
+        qp_pieces_load<P, HH>(blk, lane, full, q);
     }
     // the first output this thread stores after the pass: its per-row scale is fetched now
     uint16_t scale_first;
@@ -557,7 +608,13 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
     D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
     QP_T(1);
     if (u < units) {
-        float4_t v = qp_unit_compute<S, CB, P, PF, TT>(q, xf, xu, xfs, tab, lc, pre);
+        float4_t v;
+        if constexpr (HH) {
+            if (full) v = qp_unit_compute<D, P, PF, TT>(q, xf, xu, xfs, tab, lc, pre);
+            else v = qp_unit_compute<typename D::Lo, P, PF, TT>(q, xf, xu, xfs, tab, lc, pre);
+        } else {
+            v = qp_unit_compute<D, P, PF, TT>(q, xf, xu, xfs, tab, lc, pre);
+        }
         if (owner) *reinterpret_cast<float4_t *>(&red[(u * BP + bj) * 16 + 4 * g]) = v;
     }
     QP_T(2);
@@ -570,8 +627,16 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
             const half_t *xu2 = xlane + C * xcs;
             u32x4_t q2[P];
             half8_t xf2[PF];
-            qp_unit_load<P, PF>(codes16 + ((int64_t)rb0 * nbc + u) * BLK16, xu2, xfs, lane, q2, xf2);
-            float4_t v = qp_unit_compute<S, CB, P, PF, TT>(q2, xf2, xu2, xfs, tab, lc, pre);
+            bool full2;
+            const u32x4_t *blk2 = unit_block(rb0, u, C, full2);
+            qp_unit_load<P, PF, HH>(blk2, xu2, xfs, lane, full2, q2, xf2);
+            float4_t v;
+            if constexpr (HH) {
+                if (full2) v = qp_unit_compute<D, P, PF, TT>(q2, xf2, xu2, xfs, tab, lc, pre);
+                else v = qp_unit_compute<typename D::Lo, P, PF, TT>(q2, xf2, xu2, xfs, tab, lc, pre);
+            } else {
+                v = qp_unit_compute<D, P, PF, TT>(q2, xf2, xu2, xfs, tab, lc, pre);
+            }
             if (owner) *reinterpret_cast<float4_t *>(&red[(u * BP + bj) * 16 + 4 * g]) = v;
         }
         qp_pass_store<BP>(w, red, y, ldy, B, rb0, gcount, nbc, scale_first);
@@ -602,7 +667,7 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
     int rb_q = rbk / grid, rb_r = rbk % grid;
     int nbc_magic = (65536 + nbc - 1) / nbc;  // u / nbc == (u * magic) >> 16 for u < 1024
     int nw = units < 16 ? units : 16;
-    if (scheme == QP_TCQ || scheme == QP_TCQH) nw = 16;  // the table staging is written for 1024 threads
+    if (scheme == QP_TCQ || scheme == QP_TCQH || scheme == QP_TCQHH) nw = 16;  // the table staging is written for 1024 threads
     if (nw < 4) nw = 4;
 #define CALL_BP(S, C, BP)                                                                              \
     hipLaunchKernelGGL((k_linear_mfma<S, C, BP>), dim3(grid), dim3(64 * nw), 0, st, w, (const half_t *)x, B, \

@@ -232,7 +232,11 @@ def config_layers(cfg: int, *, small: bool = False):
                 d(3, "tcqh2_q_proj_4096x4096", TCQH, 4096, 4096, 4),
                 d(4, "tcqh4_down_4096x14336", TCQH, 4096, 14336, 8),
                 d(5, "tcqh4.5_down_4096x14336", TCQH, 4096, 14336, 9),
-                d(6, "tcqh5_down_4096x14336", TCQH, 4096, 14336, 10)]
+                d(6, "tcqh5_down_4096x14336", TCQH, 4096, 14336, 10),
+                # half-TCQ: 2 / 2.5 bits and 3 / 3.5 bits on the two halves of the input channels
+                d(7, "tcqhh2.25_down_4096x14336", TCQHH, 4096, 14336, 4),
+                d(8, "tcqhh3.25_down_4096x14336", TCQHH, 4096, 14336, 6),
+                d(9, "tcqhh3.25_gateup_28672x4096", TCQHH, 28672, 4096, 6)]
     raise ValueError(cfg)
 
 

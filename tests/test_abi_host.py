@@ -55,6 +55,17 @@ def desc(**kw):
     (dict(scheme=qp.QP_TCQH, vec=2, code_bits=10, window_bits=16, tile=256, tlut_bits=10, row_stride=640), 3),
     (dict(scheme=qp.QP_TCQH, vec=2, code_bits=11, window_bits=16, tile=256, tlut_bits=11, row_stride=704), 3),
     (dict(scheme=qp.QP_TCQH, vec=1, code_bits=4, window_bits=16, tile=256, tlut_bits=9, row_stride=512), 3),
+    # half-TCQ: s = 4 and 5 bits per step -> 1024/4 * 9/8 = 288 bytes per row; table of s + 1
+    (dict(scheme=qp.QP_TCQHH, vec=2, code_bits=4, window_bits=16, tile=256, tlut_bits=9, row_stride=288), 0),
+    (dict(scheme=qp.QP_TCQHH, vec=2, code_bits=8, window_bits=16, tile=256, tlut_bits=10, row_stride=544), 0),
+    (dict(scheme=qp.QP_TCQHH, vec=2, code_bits=8, window_bits=16, tile=256, tlut_bits=9, row_stride=544), 3),
+    (dict(scheme=qp.QP_TCQHH, vec=2, code_bits=10, window_bits=16, tile=256, tlut_bits=11, row_stride=672), 3),
+    (dict(scheme=qp.QP_TCQHH, vec=2, code_bits=4, window_bits=16, tile=256, tlut_bits=9, row_stride=272), 2),
+    (dict(scheme=qp.QP_TCQHH, vec=2, code_bits=4, window_bits=16, tile=256, tlut_bits=9, N=768, row_stride=224), 2),
+    (dict(scheme=qp.QP_TCQHH, vec=2, code_bits=4, window_bits=16, tile=256, tlut_bits=9, row_stride=288,
+          layout=qp.QP_LAYOUT_NATIVE), 5),
+    (dict(scheme=qp.QP_TCQHH, vec=2, code_bits=4, window_bits=16, tile=256, tlut_bits=9, N=2048, row_stride=576,
+          layout=qp.QP_LAYOUT_NATIVE), 0),
     (dict(M=0), 2),
     (dict(N=1020), 2),
     (dict(codes=0), 1),

@@ -20,6 +20,7 @@ CASES = [  # (cfg, layer index, batches)
     (5, 3, [1, 8]),
     (6, 1, [1, 8]),
     (6, 6, [1]),
+    (6, 8, [1, 8]),
 ]
 
 

@@ -223,3 +223,79 @@ def test_rotate_linear_other_shapes_fall_back_to_two_launches(qp, monkeypatch):
             w = qp.qp_repack(w)
         y = qp.qp_rotate_linear(w, dev(x), dev(sg), 4096)
         assert rel_err(host16(y), want) <= TOL
+
+
+# ----------------------------------------------------------------- half-TCQ
+HH = [(synth.TCQHH, s) for s in range(3, 10)]
+HH_IDS = [f"tcqhh{s / 2 + 0.25}" for s in range(3, 10)]
+
+
+@pytest.mark.parametrize("scheme,cb", HH, ids=HH_IDS)
+@pytest.mark.parametrize("layout,M,N", [("canonical", 40, 1536), ("canonical", 33, 512), ("native", 48, 4096)])
+def test_half_tcq_dequant_bit_exact(qp, scheme, cb, layout, M, N):
+    lay = synth.make_layer(80, cb, scheme, M, N, cb)
+    want = oracle.decode(lay)
+    w = qp.Weight.from_layer(lay)
+    if layout == "native":
+        w = qp.qp_repack(w)
+    assert np.array_equal(host16(qp.qp_dequant(w)), want)
+
+
+def test_half_tcq_repack_layout_is_as_documented(qp):
+    """Per block row: the column blocks of the first half (cb pieces per lane), then those of
+    the second (cb + 1 pieces); inside a block as for every other scheme."""
+    cb, M, N = 4, 32, 4096
+    lay = synth.make_layer(81, 0, synth.TCQHH, M, N, cb)
+    nat = qp.qp_repack(qp.Weight.from_layer(lay)).codes.cpu().numpy()
+    h = N // 2048
+    lo_row = N // 512 * 16 * cb
+    want = np.empty_like(nat)
+    pos = 0
+    for R in range(M // 16):
+        for half in range(2):
+            P = cb + half
+            span = 16 * P
+            for C_ in range(h):
+                for p in range(P):
+                    for l in range(64):
+                        g, i = l >> 4, l & 15
+                        off = half * lo_row + (4 * C_ + g) * span + 16 * p
+                        want[pos + (p * 64 + l) * 16: pos + (p * 64 + l) * 16 + 16] = lay.codes[16 * R + i, off:off + 16]
+                pos += 64 * span
+    assert pos == nat.size
+    assert np.array_equal(nat, want)
+
+
+@pytest.mark.parametrize("scheme,cb", HH, ids=HH_IDS)
+@pytest.mark.parametrize("layout,M,N", [("canonical", 40, 1536), ("native", 48, 4096), ("native-rowwave", 48, 4096),
+                                        ("native", 1040, 2048), ("native", 16, 14336)])
+@pytest.mark.parametrize("B", [1, 2, 3, 8, 16])
+def test_half_tcq_linear_matches_oracle(qp, scheme, cb, layout, M, N, B, monkeypatch):
+    lay = synth.make_layer(82, cb, scheme, M, N, cb)
+    x = synth.make_x(82, B, B, N)
+    want = oracle.linear(lay, x, threads=True)
+    w = qp.Weight.from_layer(lay)
+    if layout.startswith("native"):
+        w = qp.qp_repack(w)
+    monkeypatch.setenv("QP_LINEAR_KERNEL", "rowwave" if layout == "native-rowwave" else "mfma")
+    y = qp.qp_linear(w, dev(x))
+    torch.cuda.synchronize()
+    assert rel_err(host16(y), want) <= TOL
+
+
+@pytest.mark.parametrize("scheme,cb", HH, ids=HH_IDS)
+@pytest.mark.parametrize("B", [1, 4, 13])
+def test_half_tcq_rotate_linear(qp, scheme, cb, B, monkeypatch):
+    M, N, block = 272, 4096, 1024
+    lay = synth.make_layer(83, cb, scheme, M, N, cb)
+    x = synth.make_x(83, B, B, N)
+    sg = synth.make_signs(83, 1, N)
+    want = oracle.linear(lay, oracle.hadamard(x, sg, block), threads=True)
+    w = qp.qp_repack(qp.Weight.from_layer(lay))
+    monkeypatch.setenv("QP_LINEAR_KERNEL", "mfma")
+    xd, sd = dev(x), dev(sg)
+    y2 = qp.qp_linear(w, qp.qp_hadamard(xd, sd, block))
+    y1 = qp.qp_rotate_linear(w, xd, sd, block)
+    torch.cuda.synchronize()
+    assert rel_err(host16(y1), want) <= TOL
+    assert torch.equal(y1, y2)
