@@ -308,6 +308,21 @@ def main():
             del c, g
             torch.cuda.empty_cache()
 
+    # ---------------- dequantize-only kernel on the headline layer (write-bound: 2 bytes per weight)
+    dequant = None
+    if not a.no_cases:
+        lay = head.lay
+        Wout = torch.empty((lay.M, lay.N), dtype=torch.float16, device=dev)
+        g = graph_of(lambda: qp.qp_dequant(head.ring[0], out=Wout), 30)
+        g.replay()
+        us = event_time_us(g, 30, repeats=3)
+        dequant = {"workload": head.desc["name"], "us_per_call": round(us, 2),
+                   "written_GBps": round(lay.M * lay.N * 2 / us / 1e3, 1),
+                   "frac_of_peak": round(lay.M * lay.N * 2 / us / 1e3 / HBM_PEAK_GBS, 4),
+                   "note": "output (112 MiB) fits the 256 MB Infinity Cache"}
+        del g, Wout
+        torch.cuda.empty_cache()
+
     # ---------------- the oracle on this machine's host cores (a reported baseline, not a target)
     cpu = None
     if not a.no_cpu_baseline:
@@ -337,7 +352,7 @@ def main():
         "us_qp_linear": round(lin_us, 3),
         "us_qp_hadamard": round(had_us, 3),
         "linear_weight_GBps": round(head.code_bytes / lin_us / 1e3, 1),
-        "roofline": roofline, "cpu_baseline": cpu, "cases": cases,
+        "roofline": roofline, "cpu_baseline": cpu, "dequant": dequant, "cases": cases,
     }
     print(json.dumps(out))
 

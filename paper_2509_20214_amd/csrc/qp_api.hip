@@ -161,6 +161,15 @@ extern "C" qp_status qp_dequant(const qp_weight *w, void *W_out, void *hip_strea
     if (s != QP_OK) return s;
     if (!W_out) return QP_ERR_NULL;
     if (!aligned(W_out, 16)) return QP_ERR_ALIGN;
+    // Native layout: one block per wavefront with the fused kernel's decoders, unless the layer
+    // has fewer blocks than the chip has CUs (its table set-up would dominate: 1024 x 1024
+    // takes 6.5 us there, 2.9 us on the layout-agnostic kernel).  QP_DEQUANT_KERNEL=generic /
+    // blocks forces one (the tests cover both on native-layout weights of any size).
+    const char *force = getenv("QP_DEQUANT_KERNEL");
+    const bool small = (int64_t)(w->M / 16) * (w->N / 1024) < 256 && !(force && strcmp(force, "blocks") == 0);
+    if (w->layout == QP_LAYOUT_NATIVE && !small && !(force && strcmp(force, "generic") == 0))
+        return qp_launch_dequant_blocks(make_dev(w), w->scheme, w->code_bits, W_out,
+                                        static_cast<hipStream_t>(hip_stream));
     return qp_launch_dequant(make_dev(w), w->scheme, w->code_bits, W_out, static_cast<hipStream_t>(hip_stream));
 }
 

@@ -6,6 +6,8 @@
 #include "qp_dev.h"
 
 qp_status qp_launch_dequant(const QpW &w, int scheme, int cb, void *out, hipStream_t st);
+// native layout only: one 16 x 1024 block per wavefront, the fused kernel's decoders
+qp_status qp_launch_dequant_blocks(const QpW &w, int scheme, int cb, void *out, hipStream_t st);
 qp_status qp_launch_linear_rowwave(const QpW &w, int scheme, int cb, const void *x, int B, int64_t ldx,
                                    void *y, int64_t ldy, hipStream_t st);
 qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x, int B, int64_t ldx, void *y,

@@ -685,3 +685,112 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
 #undef CALL_BP
     return qp_check_launch();
 }
+
+// ------------------------------------------------------------------ dequantize only, native layout
+// Same units, piece loads and table lookups as the fused kernel, without the multiply
+// (Appendix D, dequantization-only kernels).  Write-bound: 2 bytes out per weight.  After
+// step s lane (i, g) holds the 8 weights of row i, columns 256 g + 8 s .. + 7 of its block;
+// storing that directly would scatter 16-byte pieces over 64 cache lines per instruction
+// (measured 2.5 TB/s).  Four steps at a time therefore go through a 4 KiB LDS tile per
+// wavefront (swizzled, conflict-free both ways) so that four neighbouring lanes store the
+// 64 contiguous bytes one lane decoded.  Blocks are dealt round-robin to the decoding
+// wavefronts of the grid; with the 128 KiB trellis tables only 8 of the 16 wavefronts decode
+// (the tiles of 16 would not fit), the others only help staging the table.
+template <int S, int CB>
+__global__ __launch_bounds__(1024) void k_dequant_blocks(QpW w, uint16_t *out, int nblocks) {
+    using T = QpTraits<S, CB>;
+    using D = QpDec<S, CB>;
+    constexpr bool HH = (S == QP_TCQHH);
+    constexpr int P = HH ? T::PIECES + 1 : T::PIECES;
+    constexpr int BLK16 = T::BLOCK_BYTES / 16;
+    constexpr int STAGE_FLOATS = T::HYBRID ? (1 << T::TLUT_BITS) : 512;
+    constexpr int NWD = (D::TAB_BYTES > 65536) ? 8 : 16;   // decoding wavefronts per workgroup
+    __shared__ __attribute__((aligned(16))) uint8_t tab[D::TAB_BYTES];
+    __shared__ __attribute__((aligned(16))) uint8_t tile[NWD * 4096];   // also stages a table's source
+    static_assert(NWD * 4096 >= STAGE_FLOATS * 4, "staging room");
+    D::early(tab, reinterpret_cast<uint16_t *>(tile), w.lut);
+    const typename D::Pre pre = D::pre(w.lut);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int nbc = w.nbc, hcb = nbc >> 1;
+    const u32x4_t *codes16 = reinterpret_cast<const u32x4_t *>(w.codes);
+    const uint32_t lc = D::lane_const();
+    const int nwd = (int)(blockDim.x >> 6) < NWD ? (int)(blockDim.x >> 6) : NWD;
+    const int stride = gridDim.x * nwd;
+    int t = (wave < nwd) ? blockIdx.x * nwd + wave : nblocks;   // a wavefront that does not decode has no block
+
+    u32x4_t q[P];
+    bool full = true;
+    auto issue = [&](int blk) __attribute__((always_inline)) {
+        const bool live = blk < nblocks;
+        const int bc = live ? blk : 0;
+        const int R = bc / nbc, C = bc - R * nbc;
+        const u32x4_t *src;
+        if constexpr (HH) {
+            full = __builtin_amdgcn_readfirstlane(C >= hcb);
+            src = codes16 + (int64_t)R * (hcb * 64 * (2 * CB + 1)) + C * (64 * CB) + (full ? (C - hcb) * 64 : 0);
+        } else {
+            src = codes16 + (int64_t)bc * BLK16;
+        }
+        qp_pieces_load<P, HH>(src, lane, full, q);
+    };
+    issue(t);
+    D::build(tab, reinterpret_cast<uint16_t *>(tile), pre);
+    __syncthreads();   // the staging room becomes the transposition tiles
+    // tile of this wavefront: 64 slots of 64 bytes, slot = decoding lane, chunk c of a slot
+    // at ((c + slot / 2) % 4) * 16 so that eight neighbouring lanes always cover all banks
+    u32x4_t *tl = reinterpret_cast<u32x4_t *>(tile + (wave < nwd ? wave : 0) * 4096);
+    const int wr = lane * 4;                            // in 16-byte units
+    const int rd_slot0 = lane >> 2, rd_c = lane & 3;    // store k reads slot 16 k + lane / 4, chunk lane % 4
+    while (t < nblocks) {
+        const int R = t / nbc, C = t - R * nbc;
+        // lane stores: row rd_slot0 of the block, column group k, chunk rd_c of every four steps
+        uint16_t *dst = out + (int64_t)(R * 16 + rd_slot0) * w.N + C * 1024 + rd_c * 8;
+        const bool hi = full;
+#pragma unroll
+        for (int s4 = 0; s4 < 8; ++s4) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                half8_t a;
+                if constexpr (HH) {
+                    if (hi) a = D::template step<P>(q, 4 * s4 + c, tab, lc, pre);
+                    else a = D::Lo::template step<P>(q, 4 * s4 + c, tab, lc, pre);
+                } else {
+                    a = D::template step<P>(q, 4 * s4 + c, tab, lc, pre);
+                }
+                tl[wr + ((c + (lane >> 1)) & 3)] = __builtin_bit_cast(u32x4_t, a);
+            }
+            __builtin_amdgcn_wave_barrier();   // LDS operations of a wavefront complete in order
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int slot = 16 * k + rd_slot0;
+                const u32x4_t v = tl[slot * 4 + ((rd_c + (slot >> 1)) & 3)];
+                *reinterpret_cast<u32x4_t *>(dst + k * 256 + s4 * 32) = v;
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        t += stride;
+        if (t < nblocks) issue(t);
+    }
+}
+
+qp_status qp_launch_dequant_blocks(const QpW &w, int scheme, int cb, void *out, hipStream_t st) {
+    const int64_t nb64 = (int64_t)(w.M / 16) * w.nbc;
+    if (nb64 > 0x7fffffff) return QP_ERR_SHAPE;
+    const int nblocks = (int)nb64;
+    const bool big_table = (scheme == QP_TCQ || scheme == QP_TCQH || scheme == QP_TCQHH);
+    // small layers: fewer wavefronts per workgroup so that every CU gets some
+    int nw = 16;
+    if (!big_table) {
+        nw = (nblocks + 255) / 256;
+        if (nw < 4) nw = 4;   // the per-scheme table set-up assumes at least four wavefronts
+        if (nw > 16) nw = 16;
+    }
+    const int nwd = big_table ? 8 : nw;
+    int grid = (nblocks + nwd - 1) / nwd;
+    if (grid > 256) grid = 256;
+#define CALL(S, C) \
+    hipLaunchKernelGGL((k_dequant_blocks<S, C>), dim3(grid), dim3(64 * nw), 0, st, w, (uint16_t *)out, nblocks)
+    QP_DISPATCH_SCHEME(scheme, cb, CALL);
+#undef CALL
+    return qp_check_launch();
+}

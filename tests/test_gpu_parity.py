@@ -46,13 +46,18 @@ def rel_err(y_gpu_u16, y_ref):
 
 # ----------------------------------------------------------------- decode
 @pytest.mark.parametrize("scheme,cb", SCHEMES, ids=IDS)
-@pytest.mark.parametrize("layout,M,N", [("canonical", 40, 1280), ("canonical", 33, 256), ("native", 48, 3072)])
-def test_dequant_bit_exact(qp, scheme, cb, layout, M, N):
+@pytest.mark.parametrize("layout,M,N", [("canonical", 40, 1280), ("canonical", 33, 256), ("native", 48, 3072),
+                                        ("native-generic", 48, 3072), ("native", 4128, 2048)])
+def test_dequant_bit_exact(qp, scheme, cb, layout, M, N, monkeypatch):
+    """canonical -> the layout-agnostic kernel; native -> one block per wavefront with the fused
+    kernel's decoders (M = 4128: 516 blocks, more than one per wavefront of the grid and a ragged
+    last round); native-generic -> the layout-agnostic kernel reading the native layout."""
     lay = synth.make_layer(70, scheme * 10 + cb, scheme, M, N, cb)
     want = oracle.decode(lay)
     w = qp.Weight.from_layer(lay)
-    if layout == "native":
+    if layout.startswith("native"):
         w = qp.qp_repack(w)
+    monkeypatch.setenv("QP_DEQUANT_KERNEL", "generic" if layout == "native-generic" else "blocks")
     got = host16(qp.qp_dequant(w))
     assert np.array_equal(got, want)
 
@@ -231,13 +236,15 @@ HH_IDS = [f"tcqhh{s / 2 + 0.25}" for s in range(3, 10)]
 
 
 @pytest.mark.parametrize("scheme,cb", HH, ids=HH_IDS)
-@pytest.mark.parametrize("layout,M,N", [("canonical", 40, 1536), ("canonical", 33, 512), ("native", 48, 4096)])
-def test_half_tcq_dequant_bit_exact(qp, scheme, cb, layout, M, N):
+@pytest.mark.parametrize("layout,M,N", [("canonical", 40, 1536), ("canonical", 33, 512), ("native", 48, 4096),
+                                        ("native-generic", 48, 4096), ("native", 4128, 2048)])
+def test_half_tcq_dequant_bit_exact(qp, scheme, cb, layout, M, N, monkeypatch):
     lay = synth.make_layer(80, cb, scheme, M, N, cb)
     want = oracle.decode(lay)
     w = qp.Weight.from_layer(lay)
-    if layout == "native":
+    if layout.startswith("native"):
         w = qp.qp_repack(w)
+    monkeypatch.setenv("QP_DEQUANT_KERNEL", "generic" if layout == "native-generic" else "blocks")
     assert np.array_equal(host16(qp.qp_dequant(w)), want)
 
 
