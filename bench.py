@@ -40,16 +40,21 @@ def parse():
     p.add_argument("--sweep70b", action="store_true",
                    help="configuration 5: all 80 layers of the 70B-shaped mixed-scheme model resident, "
                         "one decode step through every projection; prints its own JSON line")
+    p.add_argument("--sweep8b", default="", metavar="SCHEME:BITS",
+                   help="Llama-3-8B-shaped model (configuration 4's projections, 32 layers) with one quantizer, "
+                        "e.g. tcq:3, tcqh:6, vq:5, tcqhh:6; prints its own JSON line")
     p.add_argument("--profile-only", action="store_true",
                    help="run a short sequence of the dominant kernel only (for rocprofv3)")
     return p.parse_args()
 
 
-def sweep70b(a, torch, synth, qp, dev, upload, graph_of, event_time_us):
-    """Configuration 5.  Codes are drawn on the device (seeded torch generator: 26 GB through
-    the host would take minutes); tables, scales, activations and signs come from synth."""
+def sweep_model(model, label, torch, synth, qp, dev, upload, graph_of, event_time_us):
+    """One decode step through every projection of a whole model that is resident in HBM.
+    Codes are drawn on the device (seeded torch generator: 26 GB through the host would take
+    minutes); tables, scales, activations and signs come from synth."""
     import oracle
-    model = synth.config5_model(80)
+    two = (synth.VQ, synth.TCQH, synth.TCQHH)
+    trel = (synth.TCQ, synth.TCQH, synth.TCQHH)
     gen = torch.Generator(device=dev)
     gen.manual_seed(5)
     luts = {}
@@ -60,17 +65,18 @@ def sweep70b(a, torch, synth, qp, dev, upload, graph_of, event_time_us):
     for row in model:
         ws = []
         for d in row:
-            vec = 2 if d["scheme"] == synth.VQ else 1
+            vec = 2 if d["scheme"] in two else 1
             rb = synth.row_bytes_for(d["scheme"], d["N"], d["code_bits"], vec)
             key = (d["scheme"], d["code_bits"])
             if key not in luts:
                 tiny = synth.make_layer(5, 500 + len(luts), d["scheme"], 16, 1024, d["code_bits"])
-                luts[key] = upload(tiny.lut)
+                luts[key] = (upload(tiny.lut), tiny.tlut_bits)
             codes = torch.randint(0, 256, (d["M"], rb), dtype=torch.uint8, device=dev, generator=gen)
             scales = upload(synth.rng(5, d["layer"], synth.TENSOR_SCALES).uniform(0.5, 1.5, d["M"]).astype(np.float16))
-            trellis = d["scheme"] == synth.TCQ
+            trellis = d["scheme"] in trel
             can = qp.Weight(d["scheme"], d["M"], d["N"], d["code_bits"], vec, 16 if trellis else 0,
-                            256 if trellis else 0, codes, luts[key].view(torch.int16), scales.view(torch.int16))
+                            256 if trellis else 0, codes, luts[key][0].view(torch.int16), scales.view(torch.int16),
+                            tlut_bits=luts[key][1])
             nat = qp.qp_repack(can)
             ws.append((d, nat))
             total_bytes += d["M"] * rb
@@ -87,13 +93,13 @@ def sweep70b(a, torch, synth, qp, dev, upload, graph_of, event_time_us):
     # rows' codes (copied back from the device generator's output) and multiplies in fp64
     checked = []
     for d, nat, rows, code_rows, scale_rows, lut_dev in sampled.values():
-        vec = 2 if d["scheme"] == synth.VQ else 1
-        trellis = d["scheme"] == synth.TCQ
+        vec = 2 if d["scheme"] in two else 1
+        trellis = d["scheme"] in trel
         sub = synth.Layer(scheme=d["scheme"], M=len(rows), N=d["N"], code_bits=d["code_bits"], vec=vec,
                           window_bits=16 if trellis else 0, tile=256 if trellis else 0,
                           codes=np.ascontiguousarray(code_rows),
-                          lut=lut_dev.cpu().view(torch.int16).numpy().view(np.float16).reshape(-1),
-                          scales=np.ascontiguousarray(scale_rows))
+                          lut=lut_dev[0].cpu().view(torch.int16).numpy().view(np.float16).reshape(-1),
+                          scales=np.ascontiguousarray(scale_rows), tlut_bits=lut_dev[1])
         xh = synth.make_x(5, d["layer"], 2, d["N"])
         y = qp.qp_linear(nat, upload(xh))
         want = oracle.linear(sub, xh)
@@ -102,11 +108,14 @@ def sweep70b(a, torch, synth, qp, dev, upload, graph_of, event_time_us):
         assert err <= 1e-2, (d["name"], err)
         checked.append({"layer": d["name"], "rows": len(rows), "rel_err_vs_oracle": round(err, 6)})
     out_cases = []
+    Ns = sorted({d["N"] for row in model for d in row})
+    Ms = sorted({d["M"] for row in model for d in row})
+    n_proj = sum(len(row) for row in model)
     for B in (1, 8):
-        xs = {N: upload(synth.make_x(5, N, B, N)) for N in (8192, 28672)}
-        sg = {N: upload(synth.make_signs(5, N, N)) for N in (8192, 28672)}
+        xs = {N: upload(synth.make_x(5, N, B, N)) for N in Ns}
+        sg = {N: upload(synth.make_signs(5, N, N)) for N in Ns}
         wsp = {N: torch.empty(2 * 16 * N, dtype=torch.uint8, device=dev) for N in xs}
-        ys = {M: torch.empty((B, M), dtype=torch.float16, device=dev) for M in (10240, 8192, 57344)}
+        ys = {M: torch.empty((B, M), dtype=torch.float16, device=dev) for M in Ms}
 
         def step():
             for ws in layers:
@@ -121,10 +130,10 @@ def sweep70b(a, torch, synth, qp, dev, upload, graph_of, event_time_us):
                           "weight_GBps": round(total_bytes / us / 1e3, 1),
                           "frac_of_peak": round(total_bytes / us / 1e3 / HBM_PEAK_GBS, 4),
                           "steps_per_s": round(1e6 / us, 1)})
-    print(json.dumps({"metric": "configuration 5: one decode step through all 320 quantized projections of the "
-                                "70B-shaped mixed-scheme model (80 layers resident)",
+    print(json.dumps({"metric": f"{label}: one decode step through all {n_proj} quantized projections "
+                                f"({len(model)} decoder layers resident), rotation + fused layer each",
                       "resident_weight_GiB": round(total_bytes / 2**30, 2), "setup_s": round(setup_s, 1),
-                      "launches_per_step": 640, "cases": out_cases, "parity": checked,
+                      "launches_per_step": 2 * n_proj, "cases": out_cases, "parity": checked,
                       "data": "synthetic (codes drawn on the device from a seeded generator)"}))
 
 
@@ -220,7 +229,14 @@ def main():
         return statistics.median(out)
 
     if a.sweep70b:
-        sweep70b(a, torch, synth, qp, dev, upload, graph_of, event_time_us)
+        sweep_model(synth.config5_model(80), "configuration 5, 70B-shaped mixed-scheme model", torch, synth, qp, dev,
+                    upload, graph_of, event_time_us)
+        return
+    if a.sweep8b:
+        name, bits = a.sweep8b.split(":")
+        scheme = {v: k for k, v in synth.SCHEME_NAMES.items()}[name]
+        sweep_model(synth.model_8b(scheme, int(bits)), f"8B-shaped model, every projection {name} code_bits {bits}",
+                    torch, synth, qp, dev, upload, graph_of, event_time_us)
         return
 
     head = Case(a.cfg, a.layer, a.batch)

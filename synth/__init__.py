@@ -258,6 +258,14 @@ def config5_model(n_layers: int = 80):
     return model
 
 
+def model_8b(scheme: int, code_bits: int, n_layers: int = 32):
+    """Llama-3-8B-shaped model (configuration 4's four fused projections per decoder layer) with one
+    quantizer for every projection.  Returns descriptions only (list of lists)."""
+    shapes = [("qkv", 6144, 4096), ("o", 4096, 4096), ("gateup", 28672, 4096), ("down", 4096, 14336)]
+    return [[dict(cfg=4, layer=2000 + 4 * L + i, name=f"L{L}.{SCHEME_NAMES[scheme]}{code_bits}_{nm}", scheme=scheme,
+                  M=M, N=N, code_bits=code_bits) for i, (nm, M, N) in enumerate(shapes)] for L in range(n_layers)]
+
+
 def build(desc: dict) -> Layer:
     return make_layer(desc["cfg"], desc["layer"], desc["scheme"], desc["M"], desc["N"],
                       desc["code_bits"], name=desc["name"])
