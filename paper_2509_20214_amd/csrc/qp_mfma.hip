@@ -310,10 +310,19 @@ struct QpDecTcqh {
             if (i < (1 << TB)) s32[i] = p.raw[k];
         }
         __syncthreads();
-        uint32_t *t32 = reinterpret_cast<uint32_t *>(tab);
-        for (int idx = threadIdx.x; idx < 32768; idx += blockDim.x) {
-            const int e = idx / COPIES;
-            t32[idx] = s32[e & ((1 << TB) - 1)] ^ ((uint32_t)(e >> TB) << 15);
+        // Thread t writes all copies of entries t, t + 1024, ...: COPIES / 4 pieces of 16 bytes
+        // each, in an order rotated by the lane so that eight neighbouring lanes always cover
+        // all 32 banks (a few dozen instructions per thread instead of one per dword).
+        u32x4_t *t4 = reinterpret_cast<u32x4_t *>(tab);
+        constexpr int NP = COPIES / 4;                          // pieces per entry: 8, 4, 2
+        const int rot = (int)(threadIdx.x & 63) >> ((COPIES == 32) ? 0 : (COPIES == 16) ? 1 : 2);
+#pragma unroll
+        for (int m = 0; m < ENTRIES / 1024; ++m) {
+            const int e = m * 1024 + (int)threadIdx.x;
+            const uint32_t v = s32[e & ((1 << TB) - 1)] ^ ((uint32_t)(e >> TB) << 15);
+            const u32x4_t v4 = u32x4_t{v, v, v, v};
+#pragma unroll
+            for (int k = 0; k < NP; ++k) t4[e * NP + ((k + rot) & (NP - 1))] = v4;
         }
         __syncthreads();
     }
@@ -323,9 +332,12 @@ struct QpDecTcqh {
         uint32_t r[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const uint32_t st = qp_field_shl<P, true, 0, K>(q, (4 * s + c) * K, 16);   // the stream is K pieces long
+            // 32 stream bits from the state's first bit on (the stream is K pieces long).  Bits
+            // above the 16 of the state are left in: bits 6..15 of x (x + 1), all that is used,
+            // depend on the low 16 bits of x only.
+            const uint32_t st = qp_bits32<P, true, K>(q, (4 * s + c) * K);
             uint32_t h, idx, a;
-            asm("v_mad_u32_u24 %0, %1, %1, %1" : "=v"(h) : "v"(st));   // x (x + 1), exact: x < 2^16
+            asm("v_mad_u32_u24 %0, %1, %1, %1" : "=v"(h) : "v"(st));   // x (x + 1) modulo 2^32 (24-bit operands)
             asm("v_bfe_u32 %0, %1, %2, %3" : "=v"(idx) : "v"(h), "n"(15 - TB), "n"(TB + 1));
             asm("v_lshl_or_b32 %0, %1, %2, %3" : "=v"(a) : "v"(idx), "n"(LSH), "v"(lc));
             r[c] = *reinterpret_cast<const uint32_t *>(tab + a);
