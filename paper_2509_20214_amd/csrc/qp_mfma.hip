@@ -114,6 +114,16 @@ struct QpBankTable {
     static __device__ __forceinline__ uint32_t lane_const() { return (threadIdx.x & 31u) << 2; }
 };
 
+// The 32 copies of entry e (128 contiguous bytes) as eight 16-byte writes, rotated by the
+// lane so that neighbouring lanes hit different banks.
+__device__ __forceinline__ void qp_bank_table_fill(uint8_t *tab, int e, uint32_t v) {
+    u32x4_t *t4 = reinterpret_cast<u32x4_t *>(tab);
+    const int rot = threadIdx.x & 7;
+    const u32x4_t v4 = u32x4_t{v, v, v, v};
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t4[e * 8 + ((k + rot) & 7)] = v4;
+}
+
 // Uniform (wave-wide) reads of the table's source go through the scalar cache: they do
 // not queue behind the vector loads of the weight stream.
 typedef const uint32_t __attribute__((address_space(4))) qp_cu32;
@@ -144,10 +154,12 @@ struct QpDec<QP_SQ, 4> : QpBankTable<256> {
     static __device__ __forceinline__ void early(uint8_t *tab, uint16_t *small, const uint16_t *g) {
         if (threadIdx.x < 64) qp_scalar_to_lds<2>(qp_scalar_ptr(g), reinterpret_cast<u32x4_t *>(small));
         __syncthreads();
-        uint32_t *t32 = reinterpret_cast<uint32_t *>(tab);
-        for (int idx = threadIdx.x; idx < 256 * 32; idx += blockDim.x) {
-            int e = idx >> 5;
-            t32[idx] = (uint32_t)small[e & 15] | ((uint32_t)small[e >> 4] << 16);
+        // thread e < 256 writes the 32 copies of entry e as eight 16-byte pieces, in an order
+        // rotated by the lane (eight neighbouring lanes cover all banks)
+        if (threadIdx.x < 256) {
+            const int e = threadIdx.x;
+            const uint32_t v = (uint32_t)small[e & 15] | ((uint32_t)small[e >> 4] << 16);
+            qp_bank_table_fill(tab, e, v);
         }
         __syncthreads();
     }
@@ -176,8 +188,7 @@ struct QpDec<QP_VQ, 7> : QpBankTable<128> {
             qp_scalar_to_lds<8>(qp_scalar_ptr(g) + 32 * wave, reinterpret_cast<u32x4_t *>(small) + 8 * wave);
         __syncthreads();
         const uint32_t *s32 = reinterpret_cast<const uint32_t *>(small);
-        uint32_t *t32 = reinterpret_cast<uint32_t *>(tab);
-        for (int idx = threadIdx.x; idx < 128 * 32; idx += blockDim.x) t32[idx] = s32[idx >> 5];
+        if (threadIdx.x < 128) qp_bank_table_fill(tab, threadIdx.x, s32[threadIdx.x]);
         __syncthreads();
     }
     static __device__ __forceinline__ void build(uint8_t *, uint16_t *, const Pre &) {}
