@@ -58,6 +58,10 @@ def lib():
             f.argtypes = [_f64p, C.c_int, C.c_int, C.c_int, C.c_int, _u16p, _u8p]
         L.qpo_tcq_encode_tiles.argtypes = [_f64p, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int,
                                            _u16p, _u8p, _f64p]
+        L.qpo_tcq_encode_constrained.restype = C.c_double
+        L.qpo_tcq_encode_constrained.argtypes = [_f64p, C.c_int, C.c_int, C.c_int, C.c_int, _u16p, C.c_uint32, _u8p]
+        L.qpo_tcq_tile_error.restype = C.c_double
+        L.qpo_tcq_tile_error.argtypes = [_f64p, _u8p, C.c_int, C.c_int, C.c_int, C.c_int, _u16p]
         _lib = L
     return _lib
 
@@ -189,3 +193,21 @@ def tcq_encode_tiles(v, s, L, T, V, lut16):
     lib().qpo_tcq_encode_tiles(v.reshape(-1), nt, s, L, T, V, _u16(lut16).reshape(-1),
                                streams.reshape(-1), errs)
     return streams, errs
+
+
+def tcq_encode_constrained(v, s, L, T, V, lut16, overlap: int):
+    """One tile, the first L - s stream bits fixed to `overlap`: exact optimum for that value.
+    Returns (stream bytes, squared error)."""
+    v = np.ascontiguousarray(v, dtype=np.float64).reshape(-1)
+    assert v.size == T
+    nb = (s * T // V + 7) // 8
+    out = np.zeros(nb + 4, dtype=np.uint8)
+    e = lib().qpo_tcq_encode_constrained(v, s, L, T, V, _u16(lut16).reshape(-1), int(overlap), out)
+    return out[:nb], e
+
+
+def tcq_tile_error(v, stream, s, L, T, V, lut16) -> float:
+    """Squared error between v and the tail-biting decode of one tile's stream."""
+    v = np.ascontiguousarray(v, dtype=np.float64).reshape(-1)
+    st = np.ascontiguousarray(stream, dtype=np.uint8)
+    return lib().qpo_tcq_tile_error(v, st, s, L, T, V, _u16(lut16).reshape(-1))

@@ -232,6 +232,40 @@ double qpo_tcq_encode_viterbi(const double *v, int s, int L, int T, int V, const
     return e;
 }
 
+/* Best tail-biting stream among those whose first L - s bits equal `overlap` (one
+ * constrained Viterbi pass, exact for that value of the shared bits).  Returns its squared
+ * error; DBL_MAX if overlap is out of range.  Used to check an encoder that picked its own
+ * value of the shared bits: its result can be no better than this, and should be no worse. */
+double qpo_tcq_encode_constrained(const double *v, int s, int L, int T, int V, const uint16_t *lut16,
+                                  uint32_t overlap, uint8_t *stream)
+{
+    int n = T / V;
+    int64_t S = (int64_t)1 << L;
+    int nbytes = (s * n + 7) / 8;
+    if (overlap >> (L - s)) return DBL_MAX;
+    double *lut = (double *)malloc(sizeof(double) * (size_t)(S * V));
+    for (int64_t i = 0; i < S * V; ++i) lut[i] = qpo_half_to_double(lut16[i]);
+    uint8_t *back = (uint8_t *)malloc((size_t)n * (size_t)S);
+    double *cost = (double *)malloc(sizeof(double) * 2 * (size_t)S);
+    memset(stream, 0, (size_t)nbytes);
+    viterbi_pass(v, s, L, n, V, lut, (int64_t)overlap, stream, back, cost);
+    double e = tile_error(v, stream, s, L, T, V, lut);
+    free(cost); free(back); free(lut);
+    return e;
+}
+
+/* Squared error of the decode of an arbitrary tile stream against the target. */
+double qpo_tcq_tile_error(const double *v, const uint8_t *stream, int s, int L, int T, int V,
+                          const uint16_t *lut16)
+{
+    int64_t S = (int64_t)1 << L;
+    double *lut = (double *)malloc(sizeof(double) * (size_t)(S * V));
+    for (int64_t i = 0; i < S * V; ++i) lut[i] = qpo_half_to_double(lut16[i]);
+    double e = tile_error(v, stream, s, L, T, V, lut);
+    free(lut);
+    return e;
+}
+
 /* Many tiles at once (threads over tiles when built with OpenMP). */
 void qpo_tcq_encode_tiles(const double *v, int64_t ntiles, int s, int L, int T, int V,
                           const uint16_t *lut16, uint8_t *streams, double *errs)

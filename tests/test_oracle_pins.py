@@ -579,3 +579,45 @@ def test_half_tcq_distortion_between_its_two_bitwidths():
     d_lo, d_hi, d_all = mse[:nt].mean(), mse[nt:].mean(), mse.mean()
     assert d_hi < d_all < d_lo
     assert 2.0 ** -5 < d_hi and d_lo < 0.1   # between the 2.5-bit rate-distortion bound and scalar 2-bit
+
+
+# ------------------------------------------------- constrained trellis pass (encoder checks)
+def test_constrained_pass_against_exhaustive_and_two_pass():
+    """Small trellis (L = 6, s = 2, T = 8, V = 1: 2^16 streams): for every value of the shared
+    L - s bits the constrained pass reaches the exhaustive optimum over the streams that start
+    with those bits; the minimum over all values is the exact tail-biting optimum; and the
+    error it reports is the error of decoding the stream it wrote."""
+    L, s, T, V = 6, 2, 8, 1
+    g = np.random.default_rng(60)
+    lut = g.standard_normal(1 << L).astype(np.float16)
+    v = g.standard_normal(T)
+    lutd = oracle.half_to_double(lut)
+    nbits = s * T
+    best = {}
+    for code in range(1 << nbits):
+        bits = [(code >> p) & 1 for p in range(nbits)]
+        dec = [lutd[sum(bits[(i * s + u) % nbits] << u for u in range(L))] for i in range(T)]
+        e = float(((np.array(dec) - v) ** 2).sum())
+        ov = code & ((1 << (L - s)) - 1)
+        if e < best.get(ov, (np.inf,))[0]:
+            best[ov] = (e, code)
+    errs = []
+    for ov in range(1 << (L - s)):
+        st, e = oracle.tcq_encode_constrained(v, s, L, T, V, lut, ov)
+        assert abs(e - best[ov][0]) < 1e-12
+        assert (int.from_bytes(st.tobytes(), "little") & ((1 << (L - s)) - 1)) == ov
+        assert abs(oracle.tcq_tile_error(v, st, s, L, T, V, lut) - e) < 1e-12
+        errs.append(e)
+    _, e_exact = oracle.tcq_encode(v, s, L, T, V, lut, method="exact")
+    assert abs(min(errs) - e_exact) < 1e-12
+
+
+def test_two_pass_encoder_is_the_constrained_pass_at_its_own_overlap():
+    L, s, T, V = 16, 4, 256, 2
+    tl = synth.tcqh_tlut(61, 0, 9)
+    full = oracle.hybrid_lut(tl, 9).view(np.float16).reshape(-1)
+    v = np.random.default_rng(61).standard_normal(T)
+    st, e = oracle.tcq_encode(v, s, L, T, V, full)
+    ov = int.from_bytes(st[:2].tobytes(), "little") & ((1 << (L - s)) - 1)
+    st2, e2 = oracle.tcq_encode_constrained(v, s, L, T, V, full, ov)
+    assert abs(e - e2) < 1e-12
