@@ -153,6 +153,29 @@ size_t qp_rotate_linear_workspace_bytes(const qp_weight *w, int32_t B);
 qp_status qp_repack(const qp_weight *canonical, qp_weight *native_out, void *native_codes, size_t bytes,
                     void *hip_stream);
 
+/* Quantization: targets -> packed codes, canonical layout (App. C.1 / C.2 / C.3.1 / C.3.2
+ * "Quantization"): the nearest table entry per weight (QP_SQ) or per pair (QP_VQ); for the trellis
+ * schemes, per 256-weight tile, the bitstream whose decode is closest to the targets, found with
+ * the Viterbi algorithm over the 2^16 states, the tail-biting condition met in two passes (an open
+ * pass over the tile rotated by half its length fixes the 16 - s bits that both ends of the stream
+ * share; a second pass constrained to them gives the stream: optimal for those bits).  Half-TCQ
+ * encodes its two halves with their own bitwidths.
+ * w: scheme, shape, code_bits, vec, window_bits, tile, tlut_bits, lut (device, 16-byte aligned) and
+ * row_stride describe the result, layout must be canonical; codes and scales are not read.
+ * Supported: every QP_SQ / QP_VQ / QP_TCQ layer of qp_linear; QP_TCQH with s <= 6; QP_TCQHH with
+ * s <= 5; N % 16 == 0.  W: device fp16 [M, ldw], the weights as they should decode (rotated and
+ * divided by the per-row scale by the caller), 16-byte aligned, ldw % 8 == 0.  codes_out: device,
+ * 16-byte aligned, M * row_stride bytes; only the row's code bytes are written.  tile_err:
+ * optional device fp32 [M, N/256], the squared error of every tile (trellis schemes only; fp32
+ * accumulation).  workspace (trellis schemes): device, 16-byte aligned; any size from one
+ * workgroup's share, qp_encode_workspace_bytes(w) / min(256, tiles), upwards is accepted and decides
+ * how many tiles are encoded at once.  Distances are computed in fp32 from the exact fp16 inputs;
+ * ties go to the lower index. */
+qp_status qp_encode(const qp_weight *w, const void *W, int64_t ldw, void *codes_out, float *tile_err,
+                    void *workspace, size_t workspace_bytes, void *hip_stream);
+/* Workspace that lets qp_encode use the whole chip (0 for QP_SQ / QP_VQ and for bad descriptors). */
+size_t qp_encode_workspace_bytes(const qp_weight *w);
+
 /* Bytes of the native code buffer for this layer, 0 if it has no native form. */
 size_t qp_native_bytes(const qp_weight *canonical);
 

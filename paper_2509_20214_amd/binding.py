@@ -13,7 +13,7 @@ QP_OK = 0
 
 EXPORTS = ["qp_linear", "qp_dequant", "qp_hadamard", "qp_repack", "qp_native_bytes",
            "qp_linear_workspace_bytes", "qp_validate", "qp_status_string", "qp_version",
-           "qp_rotate_linear", "qp_rotate_linear_workspace_bytes"]
+           "qp_rotate_linear", "qp_rotate_linear_workspace_bytes", "qp_encode", "qp_encode_workspace_bytes"]
 
 
 class qp_weight(C.Structure):
@@ -58,6 +58,10 @@ def load_library(build_if_missing: bool = True):
     L.qp_rotate_linear_workspace_bytes.argtypes = [wp, i32]
     L.qp_dequant.restype = C.c_int
     L.qp_dequant.argtypes = [wp, vp, vp]
+    L.qp_encode.restype = C.c_int
+    L.qp_encode.argtypes = [wp, vp, i64, vp, vp, vp, sz, vp]
+    L.qp_encode_workspace_bytes.restype = sz
+    L.qp_encode_workspace_bytes.argtypes = [wp]
     L.qp_hadamard.restype = C.c_int
     L.qp_hadamard.argtypes = [vp, vp, i32, i32, i32, i64, vp, i64, vp]
     L.qp_repack.restype = C.c_int
@@ -166,6 +170,28 @@ def qp_repack(w: Weight, stream=None) -> Weight:
                                     _stream_ptr(stream)), "qp_repack")
     nw.desc = tmp
     return nw
+
+
+def qp_encode(w: Weight, W, tile_err: bool = False, workspace=None, stream=None):
+    """Quantize the fp16 targets W [M, N] into w's own code buffer (canonical layout; the buffer's
+    previous contents are replaced).  Returns the fp32 [M, N/256] tile errors when asked for
+    (trellis schemes), else None."""
+    import torch
+    d = w.desc
+    need = int(load_library().qp_encode_workspace_bytes(C.byref(d)))
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=W.device)
+    err = torch.zeros((d.M, d.N // 256), dtype=torch.float32, device=W.device) if tile_err else None
+    _check(load_library().qp_encode(C.byref(d), W.data_ptr(), W.stride(0), w.codes.data_ptr(),
+                                    err.data_ptr() if err is not None else None,
+                                    workspace.data_ptr() if workspace is not None else None,
+                                    workspace.numel() if workspace is not None else 0, _stream_ptr(stream)),
+           "qp_encode")
+    return err
+
+
+def qp_encode_workspace_bytes(w: Weight) -> int:
+    return int(load_library().qp_encode_workspace_bytes(C.byref(w.desc)))
 
 
 def qp_linear(w: Weight, x, y=None, workspace=None, stream=None):

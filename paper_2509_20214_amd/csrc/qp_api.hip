@@ -224,6 +224,50 @@ extern "C" qp_status qp_repack(const qp_weight *c, qp_weight *native_out, void *
     return QP_OK;
 }
 
+// What the encoders support: every table-lookup scheme; the trellis up to 6 bits per step
+// (the 2^s predecessors of a state must fit one thread's 64 states).
+static qp_status encode_check(const qp_weight *w) {
+    if (!w) return QP_ERR_NULL;
+    qp_status s = scheme_supported(w);
+    if (s != QP_OK) return s;
+    if (w->scheme == QP_TCQH && w->code_bits > 6) return QP_ERR_UNSUPPORTED;
+    if (w->scheme == QP_TCQHH && w->code_bits > 5) return QP_ERR_UNSUPPORTED;
+    if (w->M <= 0 || w->N <= 0) return QP_ERR_SHAPE;
+    if (w->N % 16 != 0) return QP_ERR_SHAPE;
+    if ((w->scheme == QP_TCQ || w->scheme == QP_TCQH) && w->N % 256 != 0) return QP_ERR_SHAPE;
+    if (w->scheme == QP_TCQHH && w->N % 512 != 0) return QP_ERR_SHAPE;
+    if (!w->lut) return QP_ERR_NULL;
+    if (w->layout != QP_LAYOUT_CANONICAL) return QP_ERR_LAYOUT;
+    if (w->row_stride % 16 != 0) return QP_ERR_ALIGN;
+    if (w->row_stride < row_bytes(w)) return QP_ERR_SHAPE;
+    if (!aligned(w->lut, 16)) return QP_ERR_ALIGN;
+    return QP_OK;
+}
+
+extern "C" size_t qp_encode_workspace_bytes(const qp_weight *w) {
+    if (encode_check(w) != QP_OK) return 0;
+    const size_t per_wg = qp_encode_min_workspace(w->scheme, w->code_bits + (w->scheme == QP_TCQHH ? 0 : 0));
+    int64_t tiles = (int64_t)w->M * (w->N / 256);
+    if (w->scheme == QP_TCQHH) tiles /= 2;
+    const int64_t wgs = tiles < 256 ? tiles : 256;
+    return per_wg * (size_t)wgs;
+}
+
+extern "C" qp_status qp_encode(const qp_weight *w, const void *W, int64_t ldw, void *codes_out, float *tile_err,
+                               void *workspace, size_t workspace_bytes, void *hip_stream) {
+    qp_status s = encode_check(w);
+    if (s != QP_OK) return s;
+    if (!W || !codes_out) return QP_ERR_NULL;
+    if (ldw < w->N || ldw % 8 != 0) return QP_ERR_SHAPE;
+    if (!aligned(W, 16) || !aligned(codes_out, 16) || (tile_err && !aligned(tile_err, 4))) return QP_ERR_ALIGN;
+    const size_t per_wg = qp_encode_min_workspace(w->scheme, w->code_bits);
+    if (per_wg && (!workspace || workspace_bytes < per_wg)) return QP_ERR_WORKSPACE;
+    if (per_wg && !aligned(workspace, 16)) return QP_ERR_ALIGN;
+    return qp_launch_encode(w->scheme, w->code_bits, w->M, w->N, static_cast<const uint16_t *>(w->lut), W, ldw,
+                            codes_out, w->row_stride, workspace, workspace_bytes, tile_err,
+                            static_cast<hipStream_t>(hip_stream));
+}
+
 extern "C" const char *qp_status_string(qp_status s) {
     switch (s) {
         case QP_OK: return "ok";

@@ -16,6 +16,11 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
 // qp_launch_linear_mfma reads with x_packed (needs n % 1024 == 0, pack_bp * n halves of room)
 qp_status qp_launch_hadamard(const void *x, const int8_t *signs, int B, int n, int block, int64_t ldx,
                              void *xr, int64_t ldxr, int pack_bp, hipStream_t st);
+// encoders (canonical output); workspace only for the trellis schemes
+qp_status qp_launch_encode(int scheme, int cb, int M, int N, const uint16_t *lut, const void *W, int64_t ldw,
+                           void *codes, int64_t row_stride, void *workspace, size_t workspace_bytes, float *tile_err,
+                           hipStream_t st);
+size_t qp_encode_min_workspace(int scheme, int cb);   // bytes one workgroup needs; 0 for SQ / VQ
 qp_status qp_launch_repack(const QpW &src, int span_bytes, void *dst, hipStream_t st);
 // half-TCQ: spans of 16 cb bytes in the first N/2 columns, 16 (cb + 1) in the rest
 qp_status qp_launch_repack_half(const QpW &src, int cb, void *dst, hipStream_t st);
