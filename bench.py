@@ -339,6 +339,30 @@ def main():
         del g, Wout
         torch.cuda.empty_cache()
 
+    # ---------------- encoder (offline path): 1024 x 4096 Gaussian targets at 2 bits, V = 2 trellis
+    encode = None
+    if not a.no_cases:
+        M_e, N_e, s_e = 1024, 4096, 4
+        lay_e = synth.make_layer(6, 900, synth.TCQH, 16, N_e, s_e)
+        Wt = torch.randn((M_e, N_e), device=dev, generator=torch.Generator(device=dev).manual_seed(6)).half()
+        codes_e = torch.zeros((M_e, lay_e.codes.shape[1]), dtype=torch.uint8, device=dev)
+        we = qp.Weight(synth.TCQH, M_e, N_e, s_e, 2, 16, 256, codes_e, upload(lay_e.lut).view(torch.int16),
+                       torch.full((M_e,), 0x3C00, dtype=torch.int16, device=dev), tlut_bits=lay_e.tlut_bits)
+        ws_e = torch.empty(qp.qp_encode_workspace_bytes(we), dtype=torch.uint8, device=dev)
+        dt = None
+        for _ in range(2):     # the second call is the timed one
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            qp.qp_encode(we, Wt, workspace=ws_e)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+        Wd = qp.qp_dequant(we).float()
+        mse = float(((Wd - Wt.float()) ** 2).mean() / (Wt.float() ** 2).mean())
+        encode = {"workload": "tcqh 2 bit, 1024x4096 N(0,1) targets", "ms": round(dt * 1e3, 1),
+                  "Mweights_per_s": round(M_e * N_e / dt / 1e6, 1), "normalised_mse": round(mse, 5)}
+        del Wt, Wd, ws_e, we, codes_e
+        torch.cuda.empty_cache()
+
     # ---------------- the oracle on this machine's host cores (a reported baseline, not a target)
     cpu = None
     if not a.no_cpu_baseline:
@@ -368,7 +392,7 @@ def main():
         "us_qp_linear": round(lin_us, 3),
         "us_qp_hadamard": round(had_us, 3),
         "linear_weight_GBps": round(head.code_bytes / lin_us / 1e3, 1),
-        "roofline": roofline, "cpu_baseline": cpu, "dequant": dequant, "cases": cases,
+        "roofline": roofline, "cpu_baseline": cpu, "dequant": dequant, "encode": encode, "cases": cases,
     }
     print(json.dumps(out))
 
