@@ -176,6 +176,18 @@ qp_status qp_encode(const qp_weight *w, const void *W, int64_t ldw, void *codes_
 /* Workspace that lets qp_encode use the whole chip (0 for QP_SQ / QP_VQ and for bad descriptors). */
 size_t qp_encode_workspace_bytes(const qp_weight *w);
 
+/* Per-output-channel scale of a (rotated) weight matrix (Section 3.3): for every row j of W,
+ * device fp16 [M, ldw], s[j] = sqrt(mean_i W[j,i]^2) rounded to fp16 (1 for a row of zeros) is
+ * written to scales (device fp16 [M]) and the row is divided by it in place (fp32 arithmetic,
+ * one rounding to fp16), so that what is left is close to N(0,1) and ready for qp_encode.
+ * The whole offline path of a layer with weights W [M, N] is then
+ *   qp_hadamard(W, signs, M, N, block, ...)   rows of W rotated like the activations will be
+ *   qp_row_normalize(...)                      s and W / s
+ *   qp_encode(...), qp_repack(...)
+ * after which qp_rotate_linear(x) = s (x R)(W R / s)^T approximates x W^T.
+ * W 16-byte aligned, N % 8 == 0, ldw % 8 == 0, ldw >= N. */
+qp_status qp_row_normalize(void *W, int64_t ldw, int32_t M, int32_t N, void *scales, void *hip_stream);
+
 /* Bytes of the native code buffer for this layer, 0 if it has no native form. */
 size_t qp_native_bytes(const qp_weight *canonical);
 

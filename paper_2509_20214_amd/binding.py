@@ -13,7 +13,8 @@ QP_OK = 0
 
 EXPORTS = ["qp_linear", "qp_dequant", "qp_hadamard", "qp_repack", "qp_native_bytes",
            "qp_linear_workspace_bytes", "qp_validate", "qp_status_string", "qp_version",
-           "qp_rotate_linear", "qp_rotate_linear_workspace_bytes", "qp_encode", "qp_encode_workspace_bytes"]
+           "qp_rotate_linear", "qp_rotate_linear_workspace_bytes", "qp_encode", "qp_encode_workspace_bytes",
+           "qp_row_normalize"]
 
 
 class qp_weight(C.Structure):
@@ -60,6 +61,8 @@ def load_library(build_if_missing: bool = True):
     L.qp_dequant.argtypes = [wp, vp, vp]
     L.qp_encode.restype = C.c_int
     L.qp_encode.argtypes = [wp, vp, i64, vp, vp, vp, sz, vp]
+    L.qp_row_normalize.restype = C.c_int
+    L.qp_row_normalize.argtypes = [vp, i64, i32, i32, vp, vp]
     L.qp_encode_workspace_bytes.restype = sz
     L.qp_encode_workspace_bytes.argtypes = [wp]
     L.qp_hadamard.restype = C.c_int
@@ -188,6 +191,18 @@ def qp_encode(w: Weight, W, tile_err: bool = False, workspace=None, stream=None)
                                     workspace.numel() if workspace is not None else 0, _stream_ptr(stream)),
            "qp_encode")
     return err
+
+
+def qp_row_normalize(W, scales=None, stream=None):
+    """In place: every row of the fp16 matrix W divided by its root mean square; returns the
+    fp16 scales [M]."""
+    import torch
+    M, N = W.shape
+    if scales is None:
+        scales = torch.empty(M, dtype=torch.float16, device=W.device)
+    _check(load_library().qp_row_normalize(W.data_ptr(), W.stride(0), M, N, scales.data_ptr(), _stream_ptr(stream)),
+           "qp_row_normalize")
+    return scales
 
 
 def qp_encode_workspace_bytes(w: Weight) -> int:

@@ -268,6 +268,13 @@ extern "C" qp_status qp_encode(const qp_weight *w, const void *W, int64_t ldw, v
                             static_cast<hipStream_t>(hip_stream));
 }
 
+extern "C" qp_status qp_row_normalize(void *W, int64_t ldw, int32_t M, int32_t N, void *scales, void *hip_stream) {
+    if (!W || !scales) return QP_ERR_NULL;
+    if (M < 1 || N < 8 || N % 8 != 0 || ldw < N || ldw % 8 != 0) return QP_ERR_SHAPE;
+    if (!aligned(W, 16) || !aligned(scales, 2)) return QP_ERR_ALIGN;
+    return qp_launch_row_normalize(W, ldw, M, N, scales, static_cast<hipStream_t>(hip_stream));
+}
+
 extern "C" const char *qp_status_string(qp_status s) {
     switch (s) {
         case QP_OK: return "ok";

@@ -352,3 +352,40 @@ qp_status qp_launch_encode(int scheme, int cb, int M, int N, const uint16_t *lut
     }
     return QP_ERR_UNSUPPORTED;
 }
+
+// ------------------------------------------------------------------ per-output-channel scale
+// s[j] = sqrt(mean_i W[j, i]^2) rounded to fp16, W[j, :] <- W[j, :] / s[j] (Section 3.3: after
+// the rotation the weights of an output channel are divided by their scale so that they are
+// close to N(0,1), what the code books are fitted to).  One wavefront per row; a row of zeros
+// gets scale 1.
+__global__ __launch_bounds__(1024) void k_row_normalize(half_t *W, int64_t ldw, int M, int N, uint16_t *scales) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int row = blockIdx.x * 16 + wave; row < M; row += gridDim.x * 16) {
+        half_t *w = W + (int64_t)row * ldw;
+        float acc = 0.f;
+        for (int i = lane * 8; i < N; i += 512) {
+            const half8_t h = *reinterpret_cast<const half8_t *>(w + i);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc = __builtin_fmaf((float)h[e], (float)h[e], acc);
+        }
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);
+        half_t s16 = (half_t)sqrtf(acc / (float)N);
+        if ((float)s16 == 0.f) s16 = (half_t)1.0f;
+        if (lane == 0) scales[row] = __builtin_bit_cast(uint16_t, s16);
+        const float inv = 1.0f / (float)s16;
+        for (int i = lane * 8; i < N; i += 512) {
+            half8_t h = *reinterpret_cast<const half8_t *>(w + i);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) h[e] = (half_t)((float)h[e] * inv);
+            *reinterpret_cast<half8_t *>(w + i) = h;
+        }
+    }
+}
+
+qp_status qp_launch_row_normalize(void *W, int64_t ldw, int M, int N, void *scales, hipStream_t st) {
+    int blocks = (M + 15) / 16;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(k_row_normalize, dim3(blocks), dim3(1024), 0, st, (half_t *)W, ldw, M, N, (uint16_t *)scales);
+    return qp_check_launch();
+}

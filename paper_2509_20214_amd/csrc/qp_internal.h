@@ -20,6 +20,7 @@ qp_status qp_launch_hadamard(const void *x, const int8_t *signs, int B, int n, i
 qp_status qp_launch_encode(int scheme, int cb, int M, int N, const uint16_t *lut, const void *W, int64_t ldw,
                            void *codes, int64_t row_stride, void *workspace, size_t workspace_bytes, float *tile_err,
                            hipStream_t st);
+qp_status qp_launch_row_normalize(void *W, int64_t ldw, int M, int N, void *scales, hipStream_t st);
 size_t qp_encode_min_workspace(int scheme, int cb);   // bytes one workgroup needs; 0 for SQ / VQ
 qp_status qp_launch_repack(const QpW &src, int span_bytes, void *dst, hipStream_t st);
 // half-TCQ: spans of 16 cb bytes in the first N/2 columns, 16 (cb + 1) in the rest

@@ -153,3 +153,36 @@ def test_repack_argument_errors_do_not_launch():
         dd = desc(scheme=s, code_bits=cb, vec=v, window_bits=16 if s == qp.QP_TCQ else 0,
                   tile=256 if s == qp.QP_TCQ else 0, row_stride=1024)
         assert L.qp_native_bytes(C.byref(dd)) == want
+
+
+def test_encode_argument_errors_do_not_launch():
+    L = qp.load_library()
+    d = desc(codes=0, scales=0, lut=0x2000)       # codes and scales are not read by the encoder
+    call = lambda dd, W, ldw, out, ws, n: L.qp_encode(C.byref(dd), W, ldw, out, None, ws, n, None)
+    assert L.qp_encode_workspace_bytes(C.byref(d)) == 0          # scalar quantizer: no workspace
+    assert call(d, None, 1024, 0x9000, None, 0) == 1
+    assert call(d, 0x4000, 1024, None, None, 0) == 1
+    assert call(d, 0x4000, 1000, 0x9000, None, 0) == 2
+    assert call(d, 0x4008, 1024, 0x9000, None, 0) == 4
+    assert call(desc(lut=0), 0x4000, 1024, 0x9000, None, 0) == 1
+    assert call(desc(layout=qp.QP_LAYOUT_NATIVE), 0x4000, 1024, 0x9000, None, 0) == 5
+    t = desc(scheme=qp.QP_TCQH, vec=2, code_bits=4, window_bits=16, tile=256, tlut_bits=9, row_stride=256)
+    per_wg = 128 * 4096                                          # 128 steps x 2^12 groups, one byte each
+    assert L.qp_encode_workspace_bytes(C.byref(t)) == per_wg * 64   # 16 rows x 4 tiles
+    assert call(t, 0x4000, 1024, 0x9000, None, 0) == 7
+    assert call(t, 0x4000, 1024, 0x9000, 0x100000, per_wg - 1) == 7
+    assert call(t, 0x4000, 1024, 0x9000, 0x100004, per_wg) == 4
+    t7 = desc(scheme=qp.QP_TCQH, vec=2, code_bits=7, window_bits=16, tile=256, tlut_bits=9, row_stride=448)
+    assert call(t7, 0x4000, 1024, 0x9000, 0x100000, 1 << 30) == 3     # more than 6 bits per step: not built
+    assert L.qp_encode_workspace_bytes(C.byref(t7)) == 0
+    assert L.qp_encode_workspace_bytes(None) == 0
+
+
+def test_row_normalize_argument_errors_do_not_launch():
+    L = qp.load_library()
+    assert L.qp_row_normalize(None, 1024, 4, 1024, 0x5000, None) == 1
+    assert L.qp_row_normalize(0x4000, 1024, 4, 1024, None, None) == 1
+    assert L.qp_row_normalize(0x4000, 1024, 0, 1024, 0x5000, None) == 2
+    assert L.qp_row_normalize(0x4000, 1024, 4, 1020, 0x5000, None) == 2
+    assert L.qp_row_normalize(0x4000, 512, 4, 1024, 0x5000, None) == 2
+    assert L.qp_row_normalize(0x4004, 1024, 4, 1024, 0x5000, None) == 4

@@ -170,3 +170,51 @@ def test_encode_then_linear_end_to_end(qp, monkeypatch):
     exact = oracle.half_to_double(x) @ oracle.half_to_double(Wt).T
     rel = np.linalg.norm(want - exact) / np.linalg.norm(exact)
     assert 0.05 < rel < 0.25, rel     # sqrt(MSE) at 3 bits is about 2^-3 .. 1.5 * 2^-3
+
+
+def test_row_normalize(qp):
+    M, N = 37, 1280
+    W = (np.random.default_rng(96).standard_normal((M, N)) * np.linspace(0.01, 30, M)[:, None]).astype(np.float16)
+    W[5] = 0
+    Wd = torch.zeros((M, N + 64), dtype=torch.float16, device="cuda")
+    Wd[:, :N] = dev16(W)
+    sc = qp.qp_row_normalize(Wd[:, :N])
+    torch.cuda.synchronize()
+    w64 = oracle.half_to_double(W)
+    s_ref = np.sqrt((w64 ** 2).mean(1))
+    s_ref[5] = 1.0
+    s_got = sc.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(s_got - s_ref) <= 2.0 ** -10 * s_ref)          # fp16 rounding of the scale
+    out = Wd[:, :N].cpu().numpy().astype(np.float64)
+    want = w64 / s_got[:, None]
+    assert np.all(np.abs(out - want) <= 2.0 ** -10 * np.abs(want) + 1e-7)
+    assert np.all(Wd[:, N:].cpu().numpy() == 0)                         # nothing written past the row
+    assert np.allclose((out ** 2).mean(1)[np.arange(M) != 5], 1.0, atol=3e-3)
+
+
+def test_offline_path_then_online_path(qp, monkeypatch):
+    """A dense weight matrix through the whole offline path (rotate rows, scale, encode, repack),
+    then the online path on unrotated activations: y approximates x W^T as closely as the
+    quantizer's distortion allows (Section 3.3: X W = (X R)(R^T W))."""
+    s, M, N, B, block = 6, 64, 2048, 3, 1024
+    g = np.random.default_rng(97)
+    Wfull = (g.standard_normal((M, N)) * g.uniform(0.5, 2.0, M)[:, None]).astype(np.float16)
+    Wfull[:, 7] *= 20.0       # an outlier column: what the rotation is there to spread
+    x = synth.make_x(97, 0, B, N)
+    sg = synth.make_signs(97, 0, N)
+    lay = synth.make_layer(97, 0, synth.TCQH, M, N, s)
+    w = qp.Weight.from_layer(lay)
+    sgd = torch.from_numpy(sg).cuda()
+    Wr = qp.qp_hadamard(dev16(Wfull), sgd, block)
+    w.scales.copy_(qp.qp_row_normalize(Wr).view(torch.int16))
+    qp.qp_encode(w, Wr)
+    monkeypatch.setenv("QP_LINEAR_KERNEL", "mfma")
+    y = qp.qp_rotate_linear(qp.qp_repack(w), dev16(x), sgd, block).cpu().numpy().astype(np.float64)
+    exact = oracle.half_to_double(x) @ oracle.half_to_double(Wfull).T
+    rel = np.linalg.norm(y - exact) / np.linalg.norm(exact)
+    assert rel < 0.2, rel          # 3 bits: relative error about sqrt(0.021) = 0.145
+    # and the fp64 chain on the GPU's own codes and scales agrees with the GPU's product
+    lay_g = synth.Layer(**{**lay.__dict__, "codes": w.codes.cpu().numpy(),
+                           "scales": w.scales.cpu().numpy().view(np.float16)})
+    want = oracle.linear(lay_g, oracle.hadamard(x, sg, block))
+    assert np.max(np.abs(y - want)) / np.max(np.abs(want)) <= 1e-2
