@@ -118,7 +118,7 @@ double qpo_tcq_encode_brute(const double *v, int s, int L, int T, int V, const u
  * Returns the path's squared error.
  */
 static double viterbi_pass(const double *v, int s, int L, int n, int V, const double *lut,
-                           int64_t overlap, uint8_t *stream, uint8_t *back /* n * 2^L */,
+                           int64_t overlap, uint8_t *stream, uint16_t *back /* n * 2^L decisions, up to s = 16 bits each */,
                            double *cost /* 2 * 2^L */)
 {
     int64_t S = (int64_t)1 << L;
@@ -149,7 +149,7 @@ static double viterbi_pass(const double *v, int s, int L, int n, int V, const do
                 e += d * d;
             }
             nxt[st] = (bc == DBL_MAX) ? DBL_MAX : bc + e;
-            back[(int64_t)i * S + st] = (uint8_t)bf;
+            back[(int64_t)i * S + st] = (uint16_t)bf;
         }
         double *t = cur; cur = nxt; nxt = t;
     }
@@ -184,7 +184,7 @@ double qpo_tcq_encode_viterbi_exact(const double *v, int s, int L, int T, int V,
     int nbytes = (s * n + 7) / 8;
     double *lut = (double *)malloc(sizeof(double) * (size_t)(S * V));
     for (int64_t i = 0; i < S * V; ++i) lut[i] = qpo_half_to_double(lut16[i]);
-    uint8_t *back = (uint8_t *)malloc((size_t)n * (size_t)S);
+    uint16_t *back = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)n * (size_t)S);
     double *cost = (double *)malloc(sizeof(double) * 2 * (size_t)S);
     uint8_t *cand = (uint8_t *)calloc((size_t)nbytes + 1, 1);
     double best = DBL_MAX;
@@ -211,7 +211,7 @@ double qpo_tcq_encode_viterbi(const double *v, int s, int L, int T, int V, const
     int nbytes = (nbits + 7) / 8;
     double *lut = (double *)malloc(sizeof(double) * (size_t)(S * V));
     for (int64_t i = 0; i < S * V; ++i) lut[i] = qpo_half_to_double(lut16[i]);
-    uint8_t *back = (uint8_t *)malloc((size_t)n * (size_t)S);
+    uint16_t *back = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)n * (size_t)S);
     double *cost = (double *)malloc(sizeof(double) * 2 * (size_t)S);
     double *rot = (double *)malloc(sizeof(double) * (size_t)T);
     uint8_t *tmp = (uint8_t *)calloc((size_t)nbytes + 1, 1);
@@ -245,7 +245,7 @@ double qpo_tcq_encode_constrained(const double *v, int s, int L, int T, int V, c
     if (overlap >> (L - s)) return DBL_MAX;
     double *lut = (double *)malloc(sizeof(double) * (size_t)(S * V));
     for (int64_t i = 0; i < S * V; ++i) lut[i] = qpo_half_to_double(lut16[i]);
-    uint8_t *back = (uint8_t *)malloc((size_t)n * (size_t)S);
+    uint16_t *back = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)n * (size_t)S);
     double *cost = (double *)malloc(sizeof(double) * 2 * (size_t)S);
     memset(stream, 0, (size_t)nbytes);
     viterbi_pass(v, s, L, n, V, lut, (int64_t)overlap, stream, back, cost);

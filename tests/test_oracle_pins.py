@@ -621,3 +621,20 @@ def test_two_pass_encoder_is_the_constrained_pass_at_its_own_overlap():
     ov = int.from_bytes(st[:2].tobytes(), "little") & ((1 << (L - s)) - 1)
     st2, e2 = oracle.tcq_encode_constrained(v, s, L, T, V, full, ov)
     assert abs(e - e2) < 1e-12
+
+
+def test_viterbi_with_more_than_eight_bits_per_step():
+    """s = 9 (4.5 bits per weight at V = 2): 512 predecessors per state, so a decision does not
+    fit a byte.  The error the pass reports must be the error of decoding what it wrote, must not
+    exceed that of the same targets at s = 8 (one bit per step less), and must sit near the
+    rate-distortion bound 2^-9 per weight."""
+    T, V = 256, 2
+    tl10 = synth.tcqh_tlut(62, 0, 10)
+    full10 = oracle.hybrid_lut(tl10, 10).view(np.float16).reshape(-1)
+    v = np.random.default_rng(62).standard_normal(T)
+    st9, e9 = oracle.tcq_encode_constrained(v, 9, 16, T, V, full10, 3)
+    assert abs(oracle.tcq_tile_error(v, st9, 9, 16, T, V, full10) - e9) < 1e-9
+    assert (int.from_bytes(st9[:2].tobytes(), "little") & 0x7F) == 3
+    _, e8 = oracle.tcq_encode_constrained(v, 8, 16, T, V, full10, 3)
+    assert e9 < e8
+    assert 2.0 ** -9 < e9 / T < 4 * 2.0 ** -9
