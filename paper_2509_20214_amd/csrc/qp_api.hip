@@ -224,14 +224,11 @@ extern "C" qp_status qp_repack(const qp_weight *c, qp_weight *native_out, void *
     return QP_OK;
 }
 
-// What the encoders support: every table-lookup scheme; the trellis up to 6 bits per step
-// (the 2^s predecessors of a state must fit one thread's 64 states).
+// What the encoders support: every scheme that qp_linear does.
 static qp_status encode_check(const qp_weight *w) {
     if (!w) return QP_ERR_NULL;
     qp_status s = scheme_supported(w);
     if (s != QP_OK) return s;
-    if (w->scheme == QP_TCQH && w->code_bits > 6) return QP_ERR_UNSUPPORTED;
-    if (w->scheme == QP_TCQHH && w->code_bits > 5) return QP_ERR_UNSUPPORTED;
     if (w->M <= 0 || w->N <= 0) return QP_ERR_SHAPE;
     if (w->N % 16 != 0) return QP_ERR_SHAPE;
     if ((w->scheme == QP_TCQ || w->scheme == QP_TCQH) && w->N % 256 != 0) return QP_ERR_SHAPE;
@@ -263,7 +260,7 @@ extern "C" qp_status qp_encode(const qp_weight *w, const void *W, int64_t ldw, v
     const size_t per_wg = qp_encode_min_workspace(w->scheme, w->code_bits);
     if (per_wg && (!workspace || workspace_bytes < per_wg)) return QP_ERR_WORKSPACE;
     if (per_wg && !aligned(workspace, 16)) return QP_ERR_ALIGN;
-    return qp_launch_encode(w->scheme, w->code_bits, w->M, w->N, static_cast<const uint16_t *>(w->lut), W, ldw,
+    return qp_launch_encode(w->scheme, w->code_bits, w->tlut_bits, w->M, w->N, static_cast<const uint16_t *>(w->lut), W, ldw,
                             codes_out, w->row_stride, workspace, workspace_bytes, tile_err,
                             static_cast<hipStream_t>(hip_stream));
 }

@@ -96,20 +96,29 @@ __global__ __launch_bounds__(256) void k_encode_vq(QpEnc a) {
 // a thread's 64 reads and its neighbours' fall into different banks), and every thread adds
 // the distance of its own 64 states to step i's targets.  Constant terms |v|^2 are left out
 // of the costs and added at the end.
-template <int V, int SB>
+// With more than 6 bits per step a group's 2^s predecessors span 2^(s-6) neighbouring threads
+// (all 64 states of a thread then belong to one group): the group minimum is finished with
+// wavefront shuffles and the decision needs more than a byte from s = 9 on.
+template <int SB> struct QpDecision { typedef uint8_t type; };
+template <> struct QpDecision<9> { typedef uint16_t type; };
+template <> struct QpDecision<10> { typedef uint16_t type; };
+
+template <int V, int SB, int TB>
 __global__ __launch_bounds__(1024) void k_encode_trellis(QpEnc a, int tiles_per_row, int64_t ntiles) {
+    typedef typename QpDecision<SB>::type dec_t;
     constexpr int n = 256 / V;          // steps per tile
     constexpr int F = 1 << SB;          // values of the s fresh bits
     constexpr int G = 65536 >> SB;      // groups = values of the 16 - s shared bits
-    constexpr int GPT = 64 / F;         // groups per thread
+    constexpr int GPT = (F <= 64) ? 64 / F : 1;   // groups per thread (F <= 64)
+    constexpr int NL = (F <= 64) ? 1 : F / 64;    // threads per group (F > 64)
     constexpr int TP = G / 64;          // group g = 64 t' + k lives at [k][t'], t' < TP
     constexpr int TPP = TP + 1;
     constexpr uint32_t LOW = G - 1;
     constexpr int HALF = n / 2;
     constexpr int NW = (n * SB + 31) / 32;   // dwords of a tile's stream
-    static_assert(F <= 64, "a group's predecessors must sit in one thread");
     __shared__ float gm[2][64 * TPP];
-    __shared__ uint32_t tl[V == 2 ? 1024 : 1];
+    constexpr int TLN = 2 << TB;        // hybrid code book with the sign folded in
+    __shared__ uint32_t tl[V == 2 ? TLN : 1];
     __shared__ __attribute__((aligned(16))) half_t vt[256];
     __shared__ uint16_t states[n];
     __shared__ float redv[16];
@@ -121,7 +130,7 @@ __global__ __launch_bounds__(1024) void k_encode_trellis(QpEnc a, int tiles_per_
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int tq = t & (TP - 1);
     const uint32_t st0 = 64u * t;
-    uint8_t *back = a.back + (size_t)blockIdx.x * n * G;
+    dec_t *back = reinterpret_cast<dec_t *>(a.back) + (size_t)blockIdx.x * n * G;
 
     // the values of this thread's 64 states
     uint32_t lv1[V == 1 ? 32 : 1];   // two fp16 values per register
@@ -134,9 +143,9 @@ __global__ __launch_bounds__(1024) void k_encode_trellis(QpEnc a, int tiles_per_
             for (int e = 0; e < 4; ++e) lv1[4 * c + e] = h[e];
         }
     } else {
-        // hybrid code book (App. C.3.1): 1024 entries, the upper 512 with component 0 negated
+        // hybrid code book (App. C.3.1): 2^(TB+1) entries, the upper half with component 0 negated
         const uint32_t *src = reinterpret_cast<const uint32_t *>(a.lut);
-        tl[t] = src[t & 511] ^ ((uint32_t)(t >> 9) << 15);
+        for (int e = t; e < TLN; e += 1024) tl[e] = src[e & ((1 << TB) - 1)] ^ ((uint32_t)(e >> TB) << 15);
     }
     __syncthreads();
 
@@ -157,30 +166,50 @@ __global__ __launch_bounds__(1024) void k_encode_trellis(QpEnc a, int tiles_per_
                 if (iv >= n) iv -= n;
                 if (i > 0) {
                     // group minima of the previous step's costs and the decisions
-                    uint8_t dec[GPT];
+                    if constexpr (F <= 64) {
+                        uint8_t dec[GPT];
 #pragma unroll
-                    for (int j = 0; j < GPT; ++j) {
-                        float bc = cost[j * F];
+                        for (int j = 0; j < GPT; ++j) {
+                            float bc = cost[j * F];
+                            uint32_t bf = 0;
+#pragma unroll
+                            for (int f = 1; f < F; ++f) {
+                                const float cc = cost[j * F + f];
+                                if (cc < bc) { bc = cc; bf = f; }
+                            }
+                            const int g = t * GPT + j;
+                            gm[buf][(g & 63) * TPP + (g >> 6)] = bc;
+                            dec[j] = (uint8_t)bf;
+                        }
+                        uint8_t *brow = reinterpret_cast<uint8_t *>(back) + (size_t)i * G + (size_t)t * GPT;
+                        if constexpr (GPT >= 4) {
+#pragma unroll
+                            for (int j4 = 0; j4 < GPT / 4; ++j4)
+                                reinterpret_cast<uint32_t *>(brow)[j4] =
+                                    (uint32_t)dec[4 * j4] | ((uint32_t)dec[4 * j4 + 1] << 8) |
+                                    ((uint32_t)dec[4 * j4 + 2] << 16) | ((uint32_t)dec[4 * j4 + 3] << 24);
+                        } else {
+#pragma unroll
+                            for (int j = 0; j < GPT; ++j) brow[j] = dec[j];
+                        }
+                    } else {
+                        float bc = cost[0];
                         uint32_t bf = 0;
 #pragma unroll
-                        for (int f = 1; f < F; ++f) {
-                            const float cc = cost[j * F + f];
-                            if (cc < bc) { bc = cc; bf = f; }
+                        for (int k = 1; k < 64; ++k)
+                            if (cost[k] < bc) { bc = cost[k]; bf = k; }
+                        bf += (uint32_t)(t & (NL - 1)) * 64u;
+#pragma unroll
+                        for (int m = 1; m < NL; m <<= 1) {
+                            const float ov = __shfl_xor(bc, m, 64);
+                            const uint32_t oi = __shfl_xor(bf, m, 64);
+                            if (ov < bc || (ov == bc && oi < bf)) { bc = ov; bf = oi; }
                         }
-                        const int g = t * GPT + j;
-                        gm[buf][(g & 63) * TPP + (g >> 6)] = bc;
-                        dec[j] = (uint8_t)bf;
-                    }
-                    uint8_t *brow = back + (size_t)i * G + (size_t)t * GPT;
-                    if constexpr (GPT >= 4) {
-#pragma unroll
-                        for (int j4 = 0; j4 < GPT / 4; ++j4)
-                            reinterpret_cast<uint32_t *>(brow)[j4] = (uint32_t)dec[4 * j4] | ((uint32_t)dec[4 * j4 + 1] << 8) |
-                                                                     ((uint32_t)dec[4 * j4 + 2] << 16) |
-                                                                     ((uint32_t)dec[4 * j4 + 3] << 24);
-                    } else {
-#pragma unroll
-                        for (int j = 0; j < GPT; ++j) brow[j] = dec[j];
+                        if ((t & (NL - 1)) == 0) {
+                            const int g = t / NL;
+                            gm[buf][(g & 63) * TPP + (g >> 6)] = bc;
+                            back[(size_t)i * G + g] = (dec_t)bf;
+                        }
                     }
                     __syncthreads();
                 }
@@ -211,7 +240,7 @@ __global__ __launch_bounds__(1024) void k_encode_trellis(QpEnc a, int tiles_per_
                         } else {
                             const uint32_t st = st0i + k;
                             const uint32_t h = st * (st + 1u);
-                            const half2v l2 = __builtin_bit_cast(half2v, tl[(h >> 6) & 1023u]);
+                            const half2v l2 = __builtin_bit_cast(half2v, tl[(h >> (15 - TB)) & (uint32_t)(TLN - 1)]);
                             cost[k] = __builtin_amdgcn_fdot2(l2, l2, __builtin_amdgcn_fdot2(l2, m2v2, base, false), false);
                         }
                     }
@@ -275,7 +304,9 @@ __global__ __launch_bounds__(1024) void k_encode_trellis(QpEnc a, int tiles_per_
     }
 }
 
-static size_t trellis_back_bytes(int V, int sb) { return (size_t)(256 / V) * (size_t)(65536 >> sb); }
+static size_t trellis_back_bytes(int V, int sb) {
+    return (size_t)(256 / V) * (size_t)(65536 >> sb) * (sb > 8 ? 2 : 1);
+}
 
 // Workgroups that the trellis encoder runs: one per CU, fewer when the workspace is smaller.
 static int trellis_grid(int V, int sb, int64_t ntiles, size_t workspace_bytes) {
@@ -292,25 +323,32 @@ size_t qp_encode_min_workspace(int scheme, int cb) {
     return 0;
 }
 
-static qp_status launch_trellis(int V, int sb, QpEnc a, size_t workspace_bytes, hipStream_t st) {
+static qp_status launch_trellis(int V, int sb, int tb, QpEnc a, size_t workspace_bytes, hipStream_t st) {
     const int tiles_per_row = a.ncols / 256;
     const int64_t ntiles = (int64_t)a.M * tiles_per_row;
     const int grid = trellis_grid(V, sb, ntiles, workspace_bytes);
     if (grid < 1) return QP_ERR_WORKSPACE;
-#define ENC(VV, SS) hipLaunchKernelGGL((k_encode_trellis<VV, SS>), dim3(grid), dim3(1024), 0, st, a, tiles_per_row, ntiles)
-    if (V == 1 && sb == 2) ENC(1, 2);
-    else if (V == 1 && sb == 3) ENC(1, 3);
-    else if (V == 1 && sb == 4) ENC(1, 4);
-    else if (V == 2 && sb == 3) ENC(2, 3);
-    else if (V == 2 && sb == 4) ENC(2, 4);
-    else if (V == 2 && sb == 5) ENC(2, 5);
-    else if (V == 2 && sb == 6) ENC(2, 6);
+#define ENC(VV, SS, TT) \
+    hipLaunchKernelGGL((k_encode_trellis<VV, SS, TT>), dim3(grid), dim3(1024), 0, st, a, tiles_per_row, ntiles)
+    if (V == 1 && sb == 2) ENC(1, 2, 9);
+    else if (V == 1 && sb == 3) ENC(1, 3, 9);
+    else if (V == 1 && sb == 4) ENC(1, 4, 9);
+    else if (V == 2 && sb == 3 && tb == 9) ENC(2, 3, 9);
+    else if (V == 2 && sb == 4 && tb == 9) ENC(2, 4, 9);
+    else if (V == 2 && sb == 5 && tb == 9) ENC(2, 5, 9);
+    else if (V == 2 && sb == 6 && tb == 9) ENC(2, 6, 9);
+    else if (V == 2 && sb == 7 && tb == 9) ENC(2, 7, 9);
+    else if (V == 2 && sb == 8 && tb == 9) ENC(2, 8, 9);
+    else if (V == 2 && sb == 8 && tb == 10) ENC(2, 8, 10);
+    else if (V == 2 && sb == 9 && tb == 10) ENC(2, 9, 10);
+    else if (V == 2 && sb == 9 && tb == 11) ENC(2, 9, 11);
+    else if (V == 2 && sb == 10 && tb == 11) ENC(2, 10, 11);
     else return QP_ERR_UNSUPPORTED;
 #undef ENC
     return qp_check_launch();
 }
 
-qp_status qp_launch_encode(int scheme, int cb, int M, int N, const uint16_t *lut, const void *W, int64_t ldw,
+qp_status qp_launch_encode(int scheme, int cb, int tlut_bits, int M, int N, const uint16_t *lut, const void *W, int64_t ldw,
                            void *codes, int64_t row_stride, void *workspace, size_t workspace_bytes, float *tile_err,
                            hipStream_t st) {
     QpEnc a;
@@ -339,16 +377,16 @@ qp_status qp_launch_encode(int scheme, int cb, int M, int N, const uint16_t *lut
         else hipLaunchKernelGGL(k_encode_vq<7>, dim3(blocks), dim3(256), 0, st, a);
         return qp_check_launch();
     }
-    if (scheme == QP_TCQ) return launch_trellis(1, cb, a, workspace_bytes, st);
-    if (scheme == QP_TCQH) return launch_trellis(2, cb, a, workspace_bytes, st);
+    if (scheme == QP_TCQ) return launch_trellis(1, cb, 9, a, workspace_bytes, st);
+    if (scheme == QP_TCQH) return launch_trellis(2, cb, tlut_bits, a, workspace_bytes, st);
     if (scheme == QP_TCQHH) {
         // two launches on the stream, one per half of the input channels (App. C.3.2 "Quantization")
         a.ncols = N / 2;
-        qp_status s = launch_trellis(2, cb, a, workspace_bytes, st);
+        qp_status s = launch_trellis(2, cb, tlut_bits, a, workspace_bytes, st);
         if (s != QP_OK) return s;
         a.col0 = N / 2;
         a.code_off = (int64_t)(N / 512) * (16 * cb);
-        return launch_trellis(2, cb + 1, a, workspace_bytes, st);
+        return launch_trellis(2, cb + 1, tlut_bits, a, workspace_bytes, st);
     }
     return QP_ERR_UNSUPPORTED;
 }

@@ -172,9 +172,11 @@ def test_encode_argument_errors_do_not_launch():
     assert call(t, 0x4000, 1024, 0x9000, None, 0) == 7
     assert call(t, 0x4000, 1024, 0x9000, 0x100000, per_wg - 1) == 7
     assert call(t, 0x4000, 1024, 0x9000, 0x100004, per_wg) == 4
-    t7 = desc(scheme=qp.QP_TCQH, vec=2, code_bits=7, window_bits=16, tile=256, tlut_bits=9, row_stride=448)
-    assert call(t7, 0x4000, 1024, 0x9000, 0x100000, 1 << 30) == 3     # more than 6 bits per step: not built
-    assert L.qp_encode_workspace_bytes(C.byref(t7)) == 0
+    t10 = desc(scheme=qp.QP_TCQH, vec=2, code_bits=10, window_bits=16, tile=256, tlut_bits=11, row_stride=640)
+    assert L.qp_encode_workspace_bytes(C.byref(t10)) == 128 * 64 * 2 * 64   # two bytes per decision from s = 9 on
+    t11 = desc(scheme=qp.QP_TCQH, vec=2, code_bits=11, window_bits=16, tile=256, tlut_bits=11, row_stride=704)
+    assert call(t11, 0x4000, 1024, 0x9000, 0x100000, 1 << 30) == 3
+    assert L.qp_encode_workspace_bytes(C.byref(t11)) == 0
     assert L.qp_encode_workspace_bytes(None) == 0
 
 

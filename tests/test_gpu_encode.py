@@ -59,7 +59,7 @@ def test_nearest_entry_encoders(qp, scheme, cb, M, N):
 
 
 TRELLIS = [(synth.TCQ, 2), (synth.TCQ, 3), (synth.TCQ, 4), (synth.TCQH, 3), (synth.TCQH, 4), (synth.TCQH, 5),
-           (synth.TCQH, 6)]
+           (synth.TCQH, 6), (synth.TCQH, 7), (synth.TCQH, 8), (synth.TCQH, 9), (synth.TCQH, 10)]
 
 
 def full_table(lay):
@@ -68,8 +68,9 @@ def full_table(lay):
     return oracle.hybrid_lut(lay.lut, lay.tlut_bits).view(np.float16).reshape(-1)
 
 
-def check_tiles(v_tiles, streams, errs_gpu, s, V, table, agree_min):
-    """v_tiles [nt, 256] fp64, streams [nt, bytes] from the GPU."""
+def check_tiles(v_tiles, streams, errs_gpu, s, V, table, agree_min, two_pass=True):
+    """v_tiles [nt, 256] fp64, streams [nt, bytes] from the GPU.  two_pass=False skips the
+    comparison with the oracle's own two-pass encoder (its cost grows with 2^s per state)."""
     nt = v_tiles.shape[0]
     same = 0
     e_true = np.empty(nt)
@@ -82,11 +83,14 @@ def check_tiles(v_tiles, streams, errs_gpu, s, V, table, agree_min):
         # than fp32 rounding of path costs allows
         assert e_true[i] >= e_con - 1e-9
         assert e_true[i] <= e_con * (1 + 2e-4) + 1e-4, (i, e_true[i], e_con)
-        st2, e_two[i] = oracle.tcq_encode(v_tiles[i], s, 16, 256, V, table)
-        ov2 = int.from_bytes(st2[:2].tobytes(), "little") & ((1 << (16 - s)) - 1)
-        same += ov == ov2
+        if two_pass:
+            st2, e_two[i] = oracle.tcq_encode(v_tiles[i], s, 16, 256, V, table)
+            ov2 = int.from_bytes(st2[:2].tobytes(), "little") & ((1 << (16 - s)) - 1)
+            same += ov == ov2
     if errs_gpu is not None:   # what the kernel reports is the error of what it wrote
         assert np.allclose(errs_gpu, e_true, rtol=2e-3, atol=1e-3)
+    if not two_pass:
+        return
     assert same >= agree_min * nt, (same, nt)
     # on the tiles where the shared bits differ the two answers are of the same quality
     assert abs(e_true.mean() - e_two.mean()) <= 0.01 * e_two.mean()
@@ -94,7 +98,8 @@ def check_tiles(v_tiles, streams, errs_gpu, s, V, table, agree_min):
 
 @pytest.mark.parametrize("scheme,s", TRELLIS)
 def test_trellis_encoder(qp, scheme, s):
-    M, N = 5, 512       # 10 tiles, two per row
+    # 10 tiles, two per row; fewer where the oracle's passes get slow (2^s predecessors per state)
+    M, N = (5 if s <= 6 else 2 if s <= 8 else 1), 512
     V = 1 if scheme == synth.TCQ else 2
     lay = synth.make_layer(91, s, scheme, M, N, s)
     Wt = targets(91 * 7 + s, M, N)
@@ -105,14 +110,15 @@ def test_trellis_encoder(qp, scheme, s):
     codes = w.codes.cpu().numpy()
     tb = codes.shape[1] // (N // 256)
     v = oracle.half_to_double(Wt).reshape(M * (N // 256), 256)
-    check_tiles(v, codes.reshape(M * (N // 256), tb), err.cpu().numpy().reshape(-1), s, V, full_table(lay), 0.8)
+    check_tiles(v, codes.reshape(M * (N // 256), tb), err.cpu().numpy().reshape(-1), s, V, full_table(lay), 0.8,
+                two_pass=s <= 7)
     # the GPU decodes its own codes to what the oracle decodes them to, and the distortion is that
     # of a trellis quantizer at this rate (between the rate-distortion bound and twice it)
     lay_g = synth.Layer(**{**lay.__dict__, "codes": codes})
     assert np.array_equal(qp.qp_dequant(w).cpu().view(torch.int16).numpy().view(np.uint16), oracle.decode(lay_g))
-    if scheme == synth.TCQH:   # random Gaussian code book of 2^9 pairs: a sane quantizer at s/2 bits
+    if scheme == synth.TCQH:   # random Gaussian code book of 2^9..2^11 pairs: a sane quantizer at s/2 bits
         mse = ((oracle.half_to_double(oracle.decode(lay_g)) - oracle.half_to_double(Wt)) ** 2).mean()
-        assert 2.0 ** (-s) < mse < 2.5 * 2.0 ** (-s), mse
+        assert 2.0 ** (-s) < mse < 3.0 * 2.0 ** (-s), mse
 
 
 def test_trellis_encoder_small_workspace_and_many_tiles(qp):
@@ -132,10 +138,10 @@ def test_trellis_encoder_small_workspace_and_many_tiles(qp):
         qp.qp_encode(w, dev16(Wt), workspace=ws[: per_wg - 16])
 
 
-@pytest.mark.parametrize("s", [3, 4, 5])
+@pytest.mark.parametrize("s", [3, 4, 5, 8])
 def test_half_tcq_encoder(qp, s):
     """First half of the input channels at s bits per step, second half at s + 1 (App. C.3.2)."""
-    M, N = 3, 1024
+    M, N = (3 if s <= 5 else 1), 1024
     lay = synth.make_layer(93, s, synth.TCQHH, M, N, s)
     Wt = targets(930 + s, M, N)
     w = qp.Weight.from_layer(lay)
@@ -147,9 +153,9 @@ def test_half_tcq_encoder(qp, s):
     e = err.cpu().numpy()
     table = full_table(lay)
     check_tiles(v[:, : N // 2].reshape(-1, 256), np.ascontiguousarray(codes[:, :nb0]).reshape(M * 2, -1),
-                e[:, :2].reshape(-1), s, 2, table, 0.7)
+                e[:, :2].reshape(-1), s, 2, table, 0.7, two_pass=s <= 5)
     check_tiles(v[:, N // 2:].reshape(-1, 256), np.ascontiguousarray(codes[:, nb0:]).reshape(M * 2, -1),
-                e[:, 2:].reshape(-1), s + 1, 2, table, 0.7)
+                e[:, 2:].reshape(-1), s + 1, 2, table, 0.7, two_pass=s <= 5)
 
 
 def test_encode_then_linear_end_to_end(qp, monkeypatch):
