@@ -2,8 +2,8 @@
 """Benchmark of the quantized-linear hot path on one MI355X.
 
 A "step" is one pass of the whole hot path over one batch: rotate x, then the fused
-dequantize-and-multiply on one layer (qp_rotate_linear: one call, and for the headline
-shape one kernel launch; the two-call sequence qp_hadamard + qp_linear is timed beside it).  The headline
+dequantize-and-multiply on one layer (qp_rotate_linear: one call, two kernel launches; the
+two-call sequence qp_hadamard + qp_linear is timed beside it).  The headline
 workload is the 4096x14336 down-projection with the 2.5-bit vector quantizer at
 batch 1 (seeded synthetic codes, LUT, scales and activations).  Weights are taken
 from a ring of distinct device buffers larger than twice the 256 MB Infinity Cache,
@@ -11,7 +11,11 @@ so every step streams its codes from HBM ("cold"); inputs are resident in HBM be
 the timed region starts.  The K timed steps are captured once into a HIP graph and
 replayed, so that the host's per-call overhead does not hide the device time.
 
-Prints ONE JSON line (see the README of the benchmark contract in the design doc).
+Prints ONE JSON line: metric / value / unit (code bytes per second through the whole step),
+the per-kernel times, `roofline` for the dominant kernel (qp_linear: algorithmic bytes over its
+HIP-event time against the 8 TB/s peak), `cpu_baseline` (the oracle on the host cores), the
+dequantize-only kernel, the encoder, and `cases`: the other configurations.  --sweep70b and
+--sweep8b run whole models resident in HBM; --profile-only is the short run that profilers wrap.
 """
 from __future__ import annotations
 
