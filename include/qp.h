@@ -197,6 +197,25 @@ size_t qp_linear_workspace_bytes(const qp_weight *w, int32_t B);
 /* Check a descriptor alone (what qp_linear / qp_dequant check first). */
 qp_status qp_validate(const qp_weight *w);
 
+/* Mixed-scheme selection on the host (Section 4.1 eq. (3) and the fusion-aware form, Section 4.2
+ * eq. (4) with (C1), (C2)): n_classes classes, class c owning the options begin[c] .. begin[c+1]-1
+ * (begin[0] = 0), option o with loss term loss[o] and profiled cost cost[o] >= 0 (latency or
+ * memory).  Exactly one option per class is chosen so that the summed cost stays within budget
+ * and the summed loss is least; choice[c] receives the option's index inside its class.  For the
+ * fusion-aware problem a class is a cluster of layers sharing their input and an option a split
+ * into fused groups with a quantizer per group (its loss: the sum over its layers; its cost: the
+ * sum over its groups), which makes (C1) hold by construction.
+ * Method: dynamic programming over the cost axis cut into `resolution` cells of budget/resolution;
+ * costs are rounded up to whole cells, so the result always satisfies the true budget and is
+ * optimal among the selections whose rounded costs fit - in particular exactly optimal when all
+ * costs are multiples of the cell, and otherwise no worse than the optimum for the budget reduced
+ * by n_classes cells.  Ties go to the lower option index.  All pointers are host pointers;
+ * total_loss / total_cost (optional) receive the sums of the true values.
+ * QP_ERR_UNSUPPORTED: no selection fits.  1 <= resolution <= 2^22. */
+qp_status qp_msq_solve(int32_t n_classes, const int32_t *begin, const double *loss, const double *cost,
+                       double budget, int32_t resolution, int32_t *choice, double *total_loss,
+                       double *total_cost);
+
 const char *qp_status_string(qp_status s);
 int32_t qp_version(void);
 

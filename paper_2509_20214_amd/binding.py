@@ -14,7 +14,7 @@ QP_OK = 0
 EXPORTS = ["qp_linear", "qp_dequant", "qp_hadamard", "qp_repack", "qp_native_bytes",
            "qp_linear_workspace_bytes", "qp_validate", "qp_status_string", "qp_version",
            "qp_rotate_linear", "qp_rotate_linear_workspace_bytes", "qp_encode", "qp_encode_workspace_bytes",
-           "qp_row_normalize"]
+           "qp_row_normalize", "qp_msq_solve"]
 
 
 class qp_weight(C.Structure):
@@ -63,6 +63,9 @@ def load_library(build_if_missing: bool = True):
     L.qp_encode.argtypes = [wp, vp, i64, vp, vp, vp, sz, vp]
     L.qp_row_normalize.restype = C.c_int
     L.qp_row_normalize.argtypes = [vp, i64, i32, i32, vp, vp]
+    L.qp_msq_solve.restype = C.c_int
+    L.qp_msq_solve.argtypes = [i32, C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_double,
+                               i32, C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_double)]
     L.qp_encode_workspace_bytes.restype = sz
     L.qp_encode_workspace_bytes.argtypes = [wp]
     L.qp_hadamard.restype = C.c_int
@@ -203,6 +206,22 @@ def qp_row_normalize(W, scales=None, stream=None):
     _check(load_library().qp_row_normalize(W.data_ptr(), W.stride(0), M, N, scales.data_ptr(), _stream_ptr(stream)),
            "qp_row_normalize")
     return scales
+
+
+def qp_msq_solve(classes, budget: float, resolution: int = 20000):
+    """classes: list of lists of (loss, cost).  Returns (choices, total_loss, total_cost)."""
+    n = len(classes)
+    begin = (C.c_int32 * (n + 1))()
+    flat = [oc for cl in classes for oc in cl]
+    for i, cl in enumerate(classes):
+        begin[i + 1] = begin[i] + len(cl)
+    loss = (C.c_double * len(flat))(*[float(l) for l, _ in flat])
+    cost = (C.c_double * len(flat))(*[float(c) for _, c in flat])
+    choice = (C.c_int32 * n)()
+    tl, tc = C.c_double(), C.c_double()
+    _check(load_library().qp_msq_solve(n, begin, loss, cost, float(budget), int(resolution), choice,
+                                       C.byref(tl), C.byref(tc)), "qp_msq_solve")
+    return list(choice), tl.value, tc.value
 
 
 def qp_encode_workspace_bytes(w: Weight) -> int:
