@@ -47,6 +47,9 @@ def parse():
     p.add_argument("--sweep8b", default="", metavar="SCHEME:BITS",
                    help="Llama-3-8B-shaped model (configuration 4's projections, 32 layers) with one quantizer, "
                         "e.g. tcq:3, tcqh:6, vq:5, tcqhh:6; prints its own JSON line")
+    p.add_argument("--msq", action="store_true",
+                   help="profile every (fusible group, quantizer) of an 8B-shaped block and run the fusion-aware "
+                        "mixed-scheme selection on the measured latencies; prints its own JSON line")
     p.add_argument("--profile-only", action="store_true",
                    help="run a short sequence of the dominant kernel only (for rocprofv3)")
     return p.parse_args()
@@ -139,6 +142,96 @@ def sweep_model(model, label, torch, synth, qp, dev, upload, graph_of, event_tim
                       "resident_weight_GiB": round(total_bytes / 2**30, 2), "setup_s": round(setup_s, 1),
                       "launches_per_step": 2 * n_proj, "cases": out_cases, "parity": checked,
                       "data": "synthetic (codes drawn on the device from a seeded generator)"}))
+
+
+def msq_demo(torch, synth, qp, dev, upload, graph_of, event_time_us):
+    """Fusion-aware mixed-scheme selection (Section 4.2) fed with latencies measured here: for
+    every fusible group of an 8B-shaped block and every quantizer of a palette, the time of
+    qp_rotate_linear (batch 1, cold ring); loss terms = synthetic layer sensitivities x the
+    distortion of the quantizer measured by encoding Gaussian targets with qp_encode."""
+    from paper_2509_20214_amd import msq
+    rows = {"q": 4096, "k": 1024, "v": 1024, "o": 4096, "u": 14336, "g": 14336, "d": 4096}
+    cols = {"q": 4096, "k": 4096, "v": 4096, "o": 4096, "u": 4096, "g": 4096, "d": 14336}
+    palette = [3, 4, 5, 6, 7, 8]                       # TCQH, bits per step; bits per weight = s / 2
+    groups = [g for cl in msq.CLUSTERS for part in msq.set_partitions(cl) for g in part]
+    groups = sorted(set(groups), key=lambda g: (len(g), g))
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(8)
+    # distortion of each quantizer on N(0,1) targets (256 x 4096)
+    dist = []
+    Wt = torch.randn((256, 4096), device=dev, generator=gen).half()
+    for s_ in palette:
+        tiny = synth.make_layer(8, s_, synth.TCQH, 16, 4096, s_)
+        codes = torch.zeros((256, tiny.codes.shape[1]), dtype=torch.uint8, device=dev)
+        w = qp.Weight(synth.TCQH, 256, 4096, s_, 2, 16, 256, codes, upload(tiny.lut).view(torch.int16),
+                      torch.full((256,), 0x3C00, dtype=torch.int16, device=dev), tlut_bits=tiny.tlut_bits)
+        qp.qp_encode(w, Wt)
+        d = float(((qp.qp_dequant(w).float() - Wt.float()) ** 2).mean())
+        dist.append(d)
+    # latency of every (group, quantizer)
+    lat = {}
+    for g in groups:
+        M, N = sum(rows[l] for l in g), cols[g[0]]
+        for qi, s_ in enumerate(palette):
+            tiny = synth.make_layer(8, 100 + s_, synth.TCQH, 16, N, s_)
+            rb = tiny.codes.shape[1]
+            lut = upload(tiny.lut).view(torch.int16)
+            sc = torch.full((M,), 0x3C00, dtype=torch.int16, device=dev)
+            n_ring = max(2, -(-(320 << 20) // (M * rb)))
+            ring = []
+            for _ in range(n_ring):
+                codes = torch.randint(0, 256, (M, rb), dtype=torch.uint8, device=dev, generator=gen)
+                ring.append(qp.qp_repack(qp.Weight(synth.TCQH, M, N, s_, 2, 16, 256, codes, lut, sc,
+                                                   tlut_bits=tiny.tlut_bits)))
+            x = upload(synth.make_x(8, N, 1, N))
+            sg = upload(synth.make_signs(8, N, N))
+            y = torch.empty((1, M), dtype=torch.float16, device=dev)
+            ws = torch.empty(qp.qp_rotate_linear_workspace_bytes(ring[0], 1), dtype=torch.uint8, device=dev)
+            i = [0]
+
+            def f():
+                qp.qp_rotate_linear(ring[i[0] % n_ring], x, sg, synth.hadamard_block(N), y=y, workspace=ws)
+                i[0] += 1
+
+            gr = graph_of(f, 100)
+            gr.replay()
+            lat[(g, qi)] = event_time_us(gr, 100, repeats=3)
+            del gr, ring
+            torch.cuda.empty_cache()
+    # one block's worth of classes, replicated for 32 blocks with seeded sensitivities
+    n_blocks = 32
+    sens = synth.rng(8, 0, 77).uniform(0.5, 2.0, size=(n_blocks, 7))
+    names = ("q", "k", "v", "o", "u", "g", "d")
+    loss = {(b, l): [float(sens[b, j] * rows[l] * cols[l] * d) for d in dist]
+            for b in range(n_blocks) for j, l in enumerate(names)}
+    cost = {(b, g): [lat[(g, qi)] for qi in range(len(palette))] for b in range(n_blocks) for g in groups}
+    top = len(palette) - 1
+    fused_lo = n_blocks * sum(min(lat[(cl, qi)] for qi in range(len(palette))) for cl in msq.CLUSTERS)
+    fused_hi = n_blocks * sum(lat[(cl, top)] for cl in msq.CLUSTERS)
+    plain_lo = n_blocks * sum(min(lat[((l,), qi)] for qi in range(len(palette))) for l in names)
+    plain_hi = n_blocks * sum(lat[((l,), top)] for l in names)
+    budgets = [fused_lo + f * (fused_hi - fused_lo) for f in (0.25, 0.5, 0.75)] + \
+              [plain_lo + f * (plain_hi - plain_lo) for f in (0.25, 0.75)]
+    out = []
+    for budget in budgets:
+        row = {"budget_us_per_token": round(budget, 1)}
+        for fusion in (True, False):
+            try:
+                sel, tl, tc = msq.solve(n_blocks, len(palette), loss, cost, budget, fusion=fusion)
+            except qp.QpError:
+                row["fusion_aware" if fusion else "per_layer"] = None
+                continue
+            bits = sum(sum(rows[l] * cols[l] for l in g) * palette[q] / 2 for (b, g), q in sel.items()) / \
+                (n_blocks * sum(rows[l] * cols[l] for l in names))
+            row["fusion_aware" if fusion else "per_layer"] = {
+                "loss_proxy": round(tl / 1e6, 3), "us_per_token": round(tc, 1), "mean_bits": round(bits, 3),
+                "fused_groups": sum(1 for (b, g) in sel if len(g) > 1), "launch_pairs": len(sel)}
+        out.append(row)
+    print(json.dumps({"metric": "fusion-aware mixed-scheme selection on measured latencies: 32 8B-shaped blocks, "
+                                "TCQH palette 1.5..4 bits, batch 1",
+                      "palette_bits": [s_ / 2 for s_ in palette], "distortion": [round(d, 5) for d in dist],
+                      "latency_us": {"+".join(g): [round(lat[(g, qi)], 2) for qi in range(len(palette))] for g in groups},
+                      "selections": out, "data": "synthetic (seeded sensitivities; codes drawn on the device)"}))
 
 
 def main():
@@ -235,6 +328,9 @@ def main():
     if a.sweep70b:
         sweep_model(synth.config5_model(80), "configuration 5, 70B-shaped mixed-scheme model", torch, synth, qp, dev,
                     upload, graph_of, event_time_us)
+        return
+    if a.msq:
+        msq_demo(torch, synth, qp, dev, upload, graph_of, event_time_us)
         return
     if a.sweep8b:
         name, bits = a.sweep8b.split(":")
