@@ -119,7 +119,7 @@ extern "C" qp_status qp_linear(const qp_weight *w, const void *x, int32_t B, int
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     QpW d = make_dev(w);
     if (use_rowwave(w)) return qp_launch_linear_rowwave(d, w->scheme, w->code_bits, x, B, ldx, y, ldy, st);
-    return qp_launch_linear_mfma(d, w->scheme, w->code_bits, x, B, ldx, y, ldy, 0, st);
+    return qp_launch_linear_mfma(d, w->scheme, w->code_bits, x, B, ldx, y, ldy, 0, nullptr, 0, st);
 }
 
 static inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -151,9 +151,15 @@ extern "C" qp_status qp_rotate_linear(const qp_weight *w, const void *x, const i
         if (s != QP_OK) return s;
         return qp_launch_linear_rowwave(d, w->scheme, w->code_bits, workspace, B, w->N, y, ldy, st);
     }
+    // Batch 1 and one rotation block (N a power of two up to 8192): the layer's kernel rotates
+    // the activations itself while its first weights are on their way - every workgroup repeats
+    // the small transform, and the second launch is saved.  QP_ROTATE=split forces two launches.
+    const char *force = getenv("QP_ROTATE");
+    if (B == 1 && block == w->N && block >= 1024 && block <= 8192 && !(force && strcmp(force, "split") == 0))
+        return qp_launch_linear_mfma(d, w->scheme, w->code_bits, x, 1, ldx, y, ldy, 0, signs, block, st);
     s = qp_launch_hadamard(x, signs, B, w->N, block, ldx, workspace, w->N, pow2_at_least(B), st);
     if (s != QP_OK) return s;
-    return qp_launch_linear_mfma(d, w->scheme, w->code_bits, workspace, B, w->N, y, ldy, 1, st);
+    return qp_launch_linear_mfma(d, w->scheme, w->code_bits, workspace, B, w->N, y, ldy, 1, nullptr, 0, st);
 }
 
 extern "C" qp_status qp_dequant(const qp_weight *w, void *W_out, void *hip_stream) {

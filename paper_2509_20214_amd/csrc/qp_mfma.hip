@@ -34,6 +34,7 @@
 // wavefronts, each unit's partial sums go to LDS, and after a barrier the workgroup
 // adds them up in a fixed order, applies the per-row scale and stores fp16.
 #include "qp_internal.h"
+#include "qp_fwht.h"
 
 #define QP_UMAX 32  // units per pass
 
@@ -527,10 +528,30 @@ __device__ __forceinline__ void qp_pass_store(const QpW &w, const float *red, ha
     __syncthreads();
 }
 
+// Shapes of the LDS arrays of the fused kernel.
 template <int S, int CB, int BP>
-__global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, int B, int64_t ldx, half_t *y,
-                                                      int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic,
-                                                      int x_packed) {
+struct QpLinLds {
+    using T = QpTraits<S, CB>;
+    using D = QpDec<S, CB>;
+    static constexpr int RED_FLOATS = QP_UMAX * 16 * BP;
+    static constexpr int SMALL_FLOATS = T::HYBRID ? (1 << T::TLUT_BITS) : 0;
+    static constexpr int RED = RED_FLOATS > SMALL_FLOATS ? RED_FLOATS : SMALL_FLOATS;
+    // in-kernel rotation (batch 1, one Hadamard block of at most 8192): the rotated
+    // activations (fp16) and the transform's transposition scratch (8192 + 256 floats),
+    // which borrows the table's room where that is large enough and still unused
+    static constexpr int ROT_MAX = 8192;
+    static constexpr int ROT_SCRATCH_FLOATS = ROT_MAX + ROT_MAX / 32;
+    static constexpr bool ROT = (BP == 1);
+    static constexpr bool SCRATCH_IN_TAB = D::TAB_BYTES >= ROT_SCRATCH_FLOATS * 4;
+};
+
+// XL: the activations are rotated here (Section 3.3), by the workgroup itself, into LDS, and
+// the B-operand fragments are read from there; otherwise they come from global memory.
+template <int S, int CB, int BP, bool XL>
+__device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, int B, int64_t ldx, half_t *y,
+                                               int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic,
+                                               int x_packed, const int8_t *signs, int rot_block, float rot_norm, uint8_t *tab,
+                                               float *red, half_t *xr_lds, float *rot_buf) {
     using T = QpTraits<S, CB>;
     using D = QpDec<S, CB>;
     // Half-TCQ: the units of the second half of the column blocks have P pieces and decode
@@ -545,11 +566,6 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
     constexpr int NXF = 32 / TT;                     // activation fragments per unit
     constexpr int PF = (NXF < 8) ? NXF : 8;          // fragments kept in flight
     constexpr int BLK16 = T::BLOCK_BYTES / 16;
-    __shared__ __attribute__((aligned(16))) uint8_t tab[D::TAB_BYTES];
-    // [unit][b][row]; before the first pass the same room stages a table's source
-    constexpr int RED_FLOATS = QP_UMAX * 16 * BP;
-    constexpr int SMALL_FLOATS = T::HYBRID ? (1 << T::TLUT_BITS) : 0;
-    __shared__ __attribute__((aligned(16))) float red[RED_FLOATS > SMALL_FLOATS ? RED_FLOATS : SMALL_FLOATS];
     QP_T(0);
 
     // ---- first pass, straight-line up to the first loads ------------------------------
@@ -585,19 +601,25 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
     // Activations either row-major [B, ldx] (fragment n of column block C: 16 bytes per lane
     // at row bj, column 1024 C + 256 g + 8 (TT n + tj)) or already in fragment order
     // (x_packed: fragment n of column block C is the 1 KiB at ((C NXF + n) 64 + lane) 16).
-    const half_t *xlane = x_packed ? x + 8 * lane : x + (int64_t)(xlive ? bj : 0) * ldx + 256 * g + 8 * tj;
-    const int xcs = x_packed ? 1024 * BP : 1024;   // halves between column blocks
-    const int xfs = x_packed ? 512 : 8 * TT;       // halves between fragments
+    // XL: fragment order in LDS, written by the rotation below.
+    const half_t *xlane = XL ? xr_lds + 8 * lane
+                             : (x_packed ? x + 8 * lane : x + (int64_t)(xlive ? bj : 0) * ldx + 256 * g + 8 * tj);
+    const int xcs = (XL || x_packed) ? 1024 * BP : 1024;   // halves between column blocks
+    const int xfs = (XL || x_packed) ? 512 : 8 * TT;       // halves between fragments
     const bool owner = (tj == 0) && xlive;  // lane (g, b*TT) ends up with rows 4g..4g+3 of batch row b
     half8_t xf[PF];
     const half_t *xu = xlane + (uu - ((uu * nbc_magic) >> 16) * nbc) * xcs;   // column block = uu % nbc
+    // XL: the unrotated activations and their signs are requested first, ahead of the weights
+    float rv[16];
+    if constexpr (XL) {
+        const int t = threadIdx.x;
+        if (rot_block == 1024) qp_fwht_fetch<4>(t < 256, t, x, signs, reinterpret_cast<float(&)[4]>(rv));
+        else if (rot_block == 2048) qp_fwht_fetch<8>(t < 256, t, x, signs, reinterpret_cast<float(&)[8]>(rv));
+        else if (rot_block == 4096) qp_fwht_fetch<8>(t < 512, t, x, signs, reinterpret_cast<float(&)[8]>(rv));
+        else qp_fwht_fetch<16>(t < 512, t, x, signs, rv);
+    } else {
 #pragma unroll
-    for (int n = 0; n < PF; ++n) {
-#ifdef QP_NOX
-        xf[n] = half8_t{0, 0, 0, 0, 0, 0, 0, 0};
-#else
-        xf[n] = *reinterpret_cast<const half8_t *>(xu + xfs * n);
-#endif
+        for (int n = 0; n < PF; ++n) xf[n] = *reinterpret_cast<const half8_t *>(xu + xfs * n);
     }
     // block (row block rb0 + slot, column block C) of unit u = slot * nbc + C, and whether
     // it has all P pieces
@@ -628,6 +650,21 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
     }
     const uint32_t lc = D::lane_const();
     QP_T(7);
+    if constexpr (XL) {
+        // The weight loads of the first unit are in flight; meanwhile the first 64 W threads
+        // of the workgroup rotate the one block of activations (same arithmetic as the
+        // stand-alone kernel, so the same bits), everybody meets at the barriers.
+        const float norm = rot_norm;   // computed on the host, like the stand-alone kernel's
+        auto put = [&](int idx, half_t val) { xr_lds[qp_xr_index(0, idx, 0, 1)] = val; };
+        const int t = threadIdx.x;
+        if (rot_block == 1024) qp_fwht_finish<4, 4>(t < 256, t, reinterpret_cast<float(&)[4]>(rv), norm, rot_buf, put);
+        else if (rot_block == 2048) qp_fwht_finish<8, 4>(t < 256, t, reinterpret_cast<float(&)[8]>(rv), norm, rot_buf, put);
+        else if (rot_block == 4096) qp_fwht_finish<8, 8>(t < 512, t, reinterpret_cast<float(&)[8]>(rv), norm, rot_buf, put);
+        else qp_fwht_finish<16, 8>(t < 512, t, rv, norm, rot_buf, put);
+        __syncthreads();
+#pragma unroll
+        for (int n = 0; n < PF; ++n) xf[n] = *reinterpret_cast<const half8_t *>(xu + xfs * n);
+    }
     D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
     QP_T(1);
     if (u < units) {
@@ -678,8 +715,32 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
     QP_T(6);
 }
 
+
+template <int S, int CB, int BP>
+__global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, int B, int64_t ldx, half_t *y,
+                                                      int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic,
+                                                      int x_packed, const int8_t *signs, int rot_block, float rot_norm) {
+    using L = QpLinLds<S, CB, BP>;
+    using D = QpDec<S, CB>;
+    __shared__ __attribute__((aligned(16))) uint8_t tab[D::TAB_BYTES];
+    // [unit][b][row]; before the first pass the same room stages a table's source
+    __shared__ __attribute__((aligned(16))) float red[L::RED];
+    if constexpr (L::ROT) {
+        __shared__ __attribute__((aligned(16))) half_t xr_lds[L::ROT_MAX];
+        __shared__ __attribute__((aligned(16))) float rot_own[L::SCRATCH_IN_TAB ? 1 : L::ROT_SCRATCH_FLOATS];
+        float *rot_buf = L::SCRATCH_IN_TAB ? reinterpret_cast<float *>(tab) : rot_own;
+        if (rot_block > 0) {
+            qp_linear_body<S, CB, BP, true>(w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
+                                            rot_block, rot_norm, tab, red, xr_lds, rot_buf);
+            return;
+        }
+    }
+    qp_linear_body<S, CB, BP, false>(w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs, rot_block,
+                                     rot_norm, tab, red, nullptr, nullptr);
+}
+
 qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x, int B, int64_t ldx, void *y,
-                                int64_t ldy, int x_packed, hipStream_t st) {
+                                int64_t ldy, int x_packed, const int8_t *signs, int rot_block, hipStream_t st) {
     const int nbc = w.nbc, rbk = w.M / 16;
     if (nbc < 1 || nbc > QP_UMAX) return QP_ERR_UNSUPPORTED;
     int grid = rbk < 256 ? rbk : 256;
@@ -692,9 +753,15 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
     int nw = units < 16 ? units : 16;
     if (scheme == QP_TCQ || scheme == QP_TCQH || scheme == QP_TCQHH) nw = 16;  // the table staging is written for 1024 threads
     if (nw < 4) nw = 4;
+    const float rot_norm = rot_block > 0 ? 1.0f / sqrtf((float)rot_block) : 0.f;
+    if (rot_block > 0) {
+        // in-kernel rotation: batch 1, one block; up to 8 wavefronts transform it
+        if (B != 1 || rot_block != w.N || rot_block > 8192 || rot_block < 1024) return QP_ERR_UNSUPPORTED;
+        if (nw < 8) nw = 8;
+    }
 #define CALL_BP(S, C, BP)                                                                              \
     hipLaunchKernelGGL((k_linear_mfma<S, C, BP>), dim3(grid), dim3(64 * nw), 0, st, w, (const half_t *)x, B, \
-                       ldx, (half_t *)y, ldy, G, rb_q, rb_r, nbc_magic, x_packed)
+                       ldx, (half_t *)y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs, rot_block, rot_norm)
 #define CALL(S, C)                                   \
     do {                                             \
         if (B <= 1) CALL_BP(S, C, 1);                \

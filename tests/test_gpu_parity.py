@@ -306,3 +306,42 @@ def test_half_tcq_rotate_linear(qp, scheme, cb, B, monkeypatch):
     torch.cuda.synchronize()
     assert rel_err(host16(y1), want) <= TOL
     assert torch.equal(y1, y2)
+
+
+# ------------------------------------------- rotation inside the layer's kernel (batch 1, one block)
+ALL = SCHEMES + HH
+ALL_IDS = IDS + HH_IDS
+
+
+@pytest.mark.parametrize("scheme,cb", ALL, ids=ALL_IDS)
+@pytest.mark.parametrize("M,N", [(272, 2048), (48, 4096), (1040, 4096), (32, 8192)])
+def test_rotate_linear_in_kernel_rotation(qp, scheme, cb, M, N, monkeypatch):
+    """Batch 1 and one Hadamard block: qp_rotate_linear is a single launch whose workgroups
+    rotate the activations themselves.  Same bits as rotation kernel + layer kernel, and the
+    fp64 chain within tolerance; the split path stays available (QP_ROTATE=split)."""
+    lay = synth.make_layer(84, scheme * 10 + cb, scheme, M, N, cb)
+    x = synth.make_x(84, N, 1, N)
+    sg = synth.make_signs(84, N, N)
+    want = oracle.linear(lay, oracle.hadamard(x, sg, N, fast=True), threads=True)
+    w = qp.qp_repack(qp.Weight.from_layer(lay))
+    monkeypatch.setenv("QP_LINEAR_KERNEL", "mfma")
+    xd, sd = dev(x), dev(sg)
+    y_two = qp.qp_linear(w, qp.qp_hadamard(xd, sd, N))
+    y_one = qp.qp_rotate_linear(w, xd, sd, N)
+    monkeypatch.setenv("QP_ROTATE", "split")
+    y_split = qp.qp_rotate_linear(w, xd, sd, N)
+    torch.cuda.synchronize()
+    assert rel_err(host16(y_one), want) <= TOL
+    assert torch.equal(y_one, y_two)
+    assert torch.equal(y_split, y_two)
+
+
+def test_rotate_linear_in_kernel_rotation_block_1024(qp, monkeypatch):
+    lay = synth.make_layer(85, 0, synth.VQ, 4096, 1024, 5)
+    x = synth.make_x(85, 0, 1, 1024)
+    sg = synth.make_signs(85, 0, 1024)
+    w = qp.qp_repack(qp.Weight.from_layer(lay))
+    monkeypatch.setenv("QP_LINEAR_KERNEL", "mfma")
+    y = qp.qp_rotate_linear(w, dev(x), dev(sg), 1024)
+    assert rel_err(host16(y), oracle.linear(lay, oracle.hadamard(x, sg, 1024), threads=True)) <= TOL
+    assert torch.equal(y, qp.qp_linear(w, qp.qp_hadamard(dev(x), dev(sg), 1024)))
