@@ -140,7 +140,7 @@ def sweep_model(model, label, torch, synth, qp, dev, upload, graph_of, event_tim
     print(json.dumps({"metric": f"{label}: one decode step through all {n_proj} quantized projections "
                                 f"({len(model)} decoder layers resident), rotation + fused layer each",
                       "resident_weight_GiB": round(total_bytes / 2**30, 2), "setup_s": round(setup_s, 1),
-                      "launches_per_step": 2 * n_proj, "cases": out_cases, "parity": checked,
+                      "qp_rotate_linear_calls_per_step": n_proj, "cases": out_cases, "parity": checked,
                       "data": "synthetic (codes drawn on the device from a seeded generator)"}))
 
 

@@ -133,11 +133,14 @@ qp_status qp_hadamard(const void *x, const int8_t *signs, int32_t B, int32_t n, 
 
 /* Rotation and fused layer in one call (Section 3.3: with QKV and gate+up fused into one
  * layer each, every online rotation feeds exactly one linear layer).  Same result, bit for
- * bit, as qp_hadamard(x, signs, B, N, block, ...) followed by qp_linear on its output: it
- * enqueues those two kernels, with the rotated activations (fp16) passing through the
- * workspace in whatever order the layer's kernel reads them best (for the native layout:
- * the order of its matrix-core operand fragments, so that its activation loads stay
- * contiguous at every batch size).  x: device fp16 [B, ldx], unrotated, 16-byte aligned, ldx % 8 == 0;
+ * bit, as qp_hadamard(x, signs, B, N, block, ...) followed by qp_linear on its output.
+ * Two kernels are enqueued, with the rotated activations (fp16) passing through the workspace
+ * in whatever order the layer's kernel reads them best (for the native layout: the order of
+ * its matrix-core operand fragments, so that its activation loads stay contiguous at every
+ * batch size) - or one kernel, at batch 1 on the native layout when block == N is a power of
+ * two between 1024 and 8192: its workgroups then rotate the activations themselves while
+ * their first weights are on the way, and the workspace is not touched.
+ * x: device fp16 [B, ldx], unrotated, 16-byte aligned, ldx % 8 == 0;
  * signs: device int8 [N], 16-byte aligned.  workspace: device, 256-byte aligned, at least
  * qp_rotate_linear_workspace_bytes(w, B) bytes; contents on entry and exit are unspecified. */
 qp_status qp_rotate_linear(const qp_weight *w, const void *x, const int8_t *signs, int32_t block, int32_t B,
