@@ -33,6 +33,8 @@
 // row blocks; the G * (N / 1024) units of a pass are dealt round-robin to the
 // wavefronts, each unit's partial sums go to LDS, and after a barrier the workgroup
 // adds them up in a fixed order, applies the per-row scale and stores fp16.
+#include <cstdlib>
+
 #include "qp_internal.h"
 #include "qp_fwht.h"
 
@@ -432,13 +434,33 @@ __device__ __forceinline__ void qp_unit_load(const u32x4_t *blk, const half_t *x
     qp_pieces_load<P, OPTIONAL_LAST>(blk, lane, full, q);
 }
 
+// Two wavefronts per unit (trellis schemes, few units per workgroup): half H decodes steps
+// 16 H .. 16 H + 15 and only needs the pieces that hold its windows - those of its own half of
+// the stream plus, the windows being 16 bits wide, the piece after it (for the second half: the
+// first piece, by tail-biting).  The others stay zero and are never looked at.
+template <int S, int CB, int P, int H>
+__device__ __forceinline__ void qp_half_pieces_load(const u32x4_t *blk, int lane, u32x4_t (&q)[P]) {
+    constexpr int V = QpTraits<S, CB>::V;
+    constexpr int ELEMS = 128 / V;                       // windows per half
+    constexpr int TOTAL = 128 * P;                       // stream bits of the lane
+    constexpr int START = H * ELEMS * CB, END = START + (ELEMS - 1) * CB + 16;   // [START, END)
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        const bool need = (128 * p < END && 128 * p + 128 > START) || (END > TOTAL && 128 * p < END - TOTAL);
+        if (need) q[p] = __builtin_nontemporal_load(blk + p * 64 + lane);
+        else q[p] = u32x4_t{0u, 0u, 0u, 0u};
+    }
+}
+
 // Decode and multiply one unit; the lane that owns (rows 4g..4g+3, batch row b) returns
 // their partial dot products in v.
-template <class D, int P, int PF, int TT>
+// S0, S1: the steps done here (a whole unit, or one half of it when two wavefronts share a
+// unit); xf[i] holds fragment S0 / TT + i on entry.
+template <class D, int P, int PF, int TT, int S0 = 0, int S1 = 32>
 __device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8_t (&xf)[PF], const half_t *xu,
                                                     int xfs, const uint8_t *tab, uint32_t lc,
                                                     const typename D::Pre &pre) {
-    constexpr int NXF = 32 / TT;
+    constexpr int N0 = S0 / TT, N1 = S1 / TT;   // fragments N0 .. N1 - 1
 #ifdef QP_NODECODE  // development builds only: loads without decode, to time the memory side alone
     {
         uint32_t z = 0;
@@ -462,10 +484,10 @@ __device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8
     for (int t = 0; t < NACC; ++t) acc[t] = float4_t{0.f, 0.f, 0.f, 0.f};
     u32x4_t masked[NM];
 #pragma unroll
-    for (int s = 0; s < 32; ++s) {
+    for (int s = S0; s < S1; ++s) {
         const int n = s / TT, t = s % TT;
         if (t == 0) {
-            const u32x4_t raw = __builtin_bit_cast(u32x4_t, xf[n % PF]);
+            const u32x4_t raw = __builtin_bit_cast(u32x4_t, xf[(n - N0) % PF]);
             if constexpr (NM == 1) {
                 masked[0] = raw;
             } else {
@@ -476,8 +498,8 @@ __device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8
                     for (int r = 0; r < 4; ++r) masked[m][r] = keep ? raw[r] : 0u;
                 }
             }
-            if (n + PF < NXF)  // the raw fragment is spent: refill its slot
-                xf[n % PF] = *reinterpret_cast<const half8_t *>(xu + xfs * (n + PF));
+            if (n + PF < N1)  // the raw fragment is spent: refill its slot
+                xf[(n - N0) % PF] = *reinterpret_cast<const half8_t *>(xu + xfs * (n + PF));
         }
         half8_t a = D::template step<P>(q, s, tab, lc, pre);
         acc[t % NACC] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, __builtin_bit_cast(half8_t, masked[t / NACC]),
@@ -547,7 +569,7 @@ struct QpLinLds {
 
 // XL: the activations are rotated here (Section 3.3), by the workgroup itself, into LDS, and
 // the B-operand fragments are read from there; otherwise they come from global memory.
-template <int S, int CB, int BP, bool XL>
+template <int S, int CB, int BP, bool XL, bool SPLIT>
 __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, int B, int64_t ldx, half_t *y,
                                                int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic,
                                                int x_packed, const int8_t *signs, int rot_block, float rot_norm, uint8_t *tab,
@@ -564,7 +586,11 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     constexpr int TTMAX = 16;
     constexpr int TT = (16 / BP < TTMAX) ? 16 / BP : TTMAX;
     constexpr int NXF = 32 / TT;                     // activation fragments per unit
-    constexpr int PF = (NXF < 8) ? NXF : 8;          // fragments kept in flight
+    // SPLIT: a unit is shared by two wavefronts, each decoding 16 of its 32 steps; the work
+    // items of a pass are then the half units, item u = 2 * unit + half.
+    constexpr int SPL = SPLIT ? 2 : 1;
+    static_assert(!SPLIT || (!HH && NXF >= 2 && NXF <= 4), "half units: trellis schemes, batch <= 2");
+    constexpr int PF = SPLIT ? NXF / 2 : ((NXF < 8) ? NXF : 8);   // fragments kept in flight
     constexpr int BLK16 = T::BLOCK_BYTES / 16;
     QP_T(0);
 
@@ -587,11 +613,13 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     const u32x4_t *codes16 = reinterpret_cast<const u32x4_t *>(w.codes);
 
     int gcount = (rb_end - rb_begin < G) ? (rb_end - rb_begin) : G;
-    int units = gcount * nbc;
+    int units = gcount * nbc * SPL;   // work items of the pass
     int u = wave;
-    // A wavefront without a unit loads unit 0 as well, to keep this code free of branches;
+    // A wavefront without an item loads item 0 as well, to keep this code free of branches;
     // it only skips the arithmetic.
-    const int uu = (u < units) ? u : 0;
+    const int uw = (u < units) ? u : 0;
+    const int uu = uw / SPL;                                        // its unit
+    const bool half1 = SPLIT && __builtin_amdgcn_readfirstlane(uw & 1);   // its half of the unit
     // Activation fragments first: they hit in L2, come back early, and - loads returning in
     // issue order - let step 0 start as soon as the first piece of codes has landed.
     const int g = lane >> 4, j = lane & 15;
@@ -609,6 +637,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     const bool owner = (tj == 0) && xlive;  // lane (g, b*TT) ends up with rows 4g..4g+3 of batch row b
     half8_t xf[PF];
     const half_t *xu = xlane + (uu - ((uu * nbc_magic) >> 16) * nbc) * xcs;   // column block = uu % nbc
+    const int xn0 = half1 ? PF : 0;   // first fragment of this item
     // XL: the unrotated activations and their signs are requested first, ahead of the weights
     float rv[16];
     if constexpr (XL) {
@@ -619,7 +648,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
         else qp_fwht_fetch<16>(t < 512, t, x, signs, rv);
     } else {
 #pragma unroll
-        for (int n = 0; n < PF; ++n) xf[n] = *reinterpret_cast<const half8_t *>(xu + xfs * n);
+        for (int n = 0; n < PF; ++n) xf[n] = *reinterpret_cast<const half8_t *>(xu + xfs * (xn0 + n));
     }
     // block (row block rb0 + slot, column block C) of unit u = slot * nbc + C, and whether
     // it has all P pieces
@@ -639,7 +668,12 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     bool full;
     {
         const u32x4_t *blk = unit_block(rb_begin, uu, uu - ((uu * nbc_magic) >> 16) * nbc, full);
-        qp_pieces_load<P, HH>(blk, lane, full, q);
+        if constexpr (SPLIT) {
+            if (half1) qp_half_pieces_load<S, CB, P, 1>(blk, lane, q);
+            else qp_half_pieces_load<S, CB, P, 0>(blk, lane, q);
+        } else {
+            qp_pieces_load<P, HH>(blk, lane, full, q);
+        }
     }
     // the first output this thread stores after the pass: its per-row scale is fetched now
     uint16_t scale_first;
@@ -663,13 +697,16 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
         else qp_fwht_finish<16, 8>(t < 512, t, rv, norm, rot_buf, put);
         __syncthreads();
 #pragma unroll
-        for (int n = 0; n < PF; ++n) xf[n] = *reinterpret_cast<const half8_t *>(xu + xfs * n);
+        for (int n = 0; n < PF; ++n) xf[n] = *reinterpret_cast<const half8_t *>(xu + xfs * (xn0 + n));
     }
     D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
     QP_T(1);
     if (u < units) {
         float4_t v;
-        if constexpr (HH) {
+        if constexpr (SPLIT) {
+            if (half1) v = qp_unit_compute<D, P, PF, TT, 16, 32>(q, xf, xu, xfs, tab, lc, pre);
+            else v = qp_unit_compute<D, P, PF, TT, 0, 16>(q, xf, xu, xfs, tab, lc, pre);
+        } else if constexpr (HH) {
             if (full) v = qp_unit_compute<D, P, PF, TT>(q, xf, xu, xfs, tab, lc, pre);
             else v = qp_unit_compute<typename D::Lo, P, PF, TT>(q, xf, xu, xfs, tab, lc, pre);
         } else {
@@ -683,14 +720,30 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     while (true) {
         // ---- remaining units of this pass ----------------------------------------------
         for (; u < units; u += nw) {
-            const int C = u - ((u * nbc_magic) >> 16) * nbc;
+            const int ub = u / SPL;
+            const bool h2 = SPLIT && __builtin_amdgcn_readfirstlane(u & 1);
+            const int C = ub - ((ub * nbc_magic) >> 16) * nbc;
             const half_t *xu2 = xlane + C * xcs;
             u32x4_t q2[P];
             half8_t xf2[PF];
             bool full2;
-            const u32x4_t *blk2 = unit_block(rb0, u, C, full2);
-            qp_unit_load<P, PF, HH>(blk2, xu2, xfs, lane, full2, q2, xf2);
+            const u32x4_t *blk2 = unit_block(rb0, ub, C, full2);
             float4_t v;
+            if constexpr (SPLIT) {
+                const int n0 = h2 ? PF : 0;
+#pragma unroll
+                for (int n = 0; n < PF; ++n) xf2[n] = *reinterpret_cast<const half8_t *>(xu2 + xfs * (n0 + n));
+                if (h2) {
+                    qp_half_pieces_load<S, CB, P, 1>(blk2, lane, q2);
+                    v = qp_unit_compute<D, P, PF, TT, 16, 32>(q2, xf2, xu2, xfs, tab, lc, pre);
+                } else {
+                    qp_half_pieces_load<S, CB, P, 0>(blk2, lane, q2);
+                    v = qp_unit_compute<D, P, PF, TT, 0, 16>(q2, xf2, xu2, xfs, tab, lc, pre);
+                }
+                if (owner) *reinterpret_cast<float4_t *>(&red[(u * BP + bj) * 16 + 4 * g]) = v;
+                continue;
+            }
+            qp_unit_load<P, PF, HH>(blk2, xu2, xfs, lane, full2, q2, xf2);
             if constexpr (HH) {
                 if (full2) v = qp_unit_compute<D, P, PF, TT>(q2, xf2, xu2, xfs, tab, lc, pre);
                 else v = qp_unit_compute<typename D::Lo, P, PF, TT>(q2, xf2, xu2, xfs, tab, lc, pre);
@@ -699,12 +752,12 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
             }
             if (owner) *reinterpret_cast<float4_t *>(&red[(u * BP + bj) * 16 + 4 * g]) = v;
         }
-        qp_pass_store<BP>(w, red, y, ldy, B, rb0, gcount, nbc, scale_first);
+        qp_pass_store<BP>(w, red, y, ldy, B, rb0, gcount, nbc * SPL, scale_first);
         // ---- next pass ------------------------------------------------------------------
         rb0 += G;
         if (rb0 >= rb_end) break;
         gcount = (rb_end - rb0 < G) ? (rb_end - rb0) : G;
-        units = gcount * nbc;
+        units = gcount * nbc * SPL;
         u = wave;
         {
             const int o = threadIdx.x;
@@ -716,7 +769,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
 }
 
 
-template <int S, int CB, int BP>
+template <int S, int CB, int BP, bool SPLIT>
 __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, int B, int64_t ldx, half_t *y,
                                                       int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic,
                                                       int x_packed, const int8_t *signs, int rot_block, float rot_norm) {
@@ -730,13 +783,32 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
         __shared__ __attribute__((aligned(16))) float rot_own[L::SCRATCH_IN_TAB ? 1 : L::ROT_SCRATCH_FLOATS];
         float *rot_buf = L::SCRATCH_IN_TAB ? reinterpret_cast<float *>(tab) : rot_own;
         if (rot_block > 0) {
-            qp_linear_body<S, CB, BP, true>(w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
+            qp_linear_body<S, CB, BP, true, SPLIT>(w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
                                             rot_block, rot_norm, tab, red, xr_lds, rot_buf);
             return;
         }
     }
-    qp_linear_body<S, CB, BP, false>(w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs, rot_block,
+    qp_linear_body<S, CB, BP, false, SPLIT>(w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs, rot_block,
                                      rot_norm, tab, red, nullptr, nullptr);
+}
+
+// Half units exist for the trellis schemes at batch <= 2 (the kernels that are bound by their
+// own decode work when a workgroup has few units).
+template <int S, int CB, int BP>
+static void qp_launch_one(bool split, int grid, int nw, hipStream_t st, const QpW &w, const void *x, int B,
+                          int64_t ldx, void *y, int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic, int x_packed,
+                          const int8_t *signs, int rot_block, float rot_norm) {
+    constexpr bool CAN_SPLIT = (S == QP_TCQ || S == QP_TCQH) && BP <= 2;
+    if constexpr (CAN_SPLIT) {
+        if (split) {
+            hipLaunchKernelGGL((k_linear_mfma<S, CB, BP, true>), dim3(grid), dim3(64 * nw), 0, st, w,
+                               (const half_t *)x, B, ldx, (half_t *)y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
+                               rot_block, rot_norm);
+            return;
+        }
+    }
+    hipLaunchKernelGGL((k_linear_mfma<S, CB, BP, false>), dim3(grid), dim3(64 * nw), 0, st, w, (const half_t *)x, B,
+                       ldx, (half_t *)y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs, rot_block, rot_norm);
 }
 
 qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x, int B, int64_t ldx, void *y,
@@ -750,6 +822,18 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
     int units = G * nbc;
     int rb_q = rbk / grid, rb_r = rbk % grid;
     int nbc_magic = (65536 + nbc - 1) / nbc;  // u / nbc == (u * magic) >> 16 for u < 1024
+    // Two wavefronts per unit where a pass has no more units than the workgroup has
+    // wavefronts: the decode work of the trellis schemes then spreads over all SIMDs.  Measured:
+    // 3 .. 5 % faster from 6 units per workgroup on (4096x14336: 14 units, 6144x4096: 6), a few
+    // per cent slower at 4 units (4096x4096), where the second copy of the shared pieces costs
+    // more than the idle SIMDs.  QP_LINEAR_SPLIT=0 / 1 switches it off / on wherever it is legal.
+    const bool can_split = (scheme == QP_TCQ || scheme == QP_TCQH) && B <= 2 && units <= 16;
+    bool split = can_split && units >= 6;
+    {
+        const char *e = getenv("QP_LINEAR_SPLIT");
+        if (e && e[0] == '0') split = false;
+        if (e && e[0] == '1') split = can_split;
+    }
     int nw = units < 16 ? units : 16;
     if (scheme == QP_TCQ || scheme == QP_TCQH || scheme == QP_TCQHH) nw = 16;  // the table staging is written for 1024 threads
     if (nw < 4) nw = 4;
@@ -759,9 +843,9 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
         if (B != 1 || rot_block != w.N || rot_block > 8192 || rot_block < 1024) return QP_ERR_UNSUPPORTED;
         if (nw < 8) nw = 8;
     }
-#define CALL_BP(S, C, BP)                                                                              \
-    hipLaunchKernelGGL((k_linear_mfma<S, C, BP>), dim3(grid), dim3(64 * nw), 0, st, w, (const half_t *)x, B, \
-                       ldx, (half_t *)y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs, rot_block, rot_norm)
+#define CALL_BP(S, C, BP) \
+    qp_launch_one<S, C, BP>(split, grid, nw, st, w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs, \
+                            rot_block, rot_norm)
 #define CALL(S, C)                                   \
     do {                                             \
         if (B <= 1) CALL_BP(S, C, 1);                \

@@ -345,3 +345,23 @@ def test_rotate_linear_in_kernel_rotation_block_1024(qp, monkeypatch):
     y = qp.qp_rotate_linear(w, dev(x), dev(sg), 1024)
     assert rel_err(host16(y), oracle.linear(lay, oracle.hadamard(x, sg, 1024), threads=True)) <= TOL
     assert torch.equal(y, qp.qp_linear(w, qp.qp_hadamard(dev(x), dev(sg), 1024)))
+
+
+@pytest.mark.parametrize("scheme,cb", [(synth.TCQ, 2), (synth.TCQ, 3), (synth.TCQ, 4)] +
+                         [(synth.TCQH, s) for s in range(3, 11)],
+                         ids=["tcq2", "tcq3", "tcq4"] + [f"tcqh{s / 2}" for s in range(3, 11)])
+@pytest.mark.parametrize("M,N,B", [(48, 4096, 1), (1040, 2048, 2), (16, 14336, 1), (272, 3072, 2)])
+@pytest.mark.parametrize("split", ["0", "1"])
+def test_linear_two_wavefronts_per_unit(qp, scheme, cb, M, N, B, split, monkeypatch):
+    """The trellis kernels at batch <= 2 exist in two forms: one wavefront per 16 x 1024 unit, or
+    two, each decoding half of its steps from only the pieces it needs.  Both forms, at unit
+    counts on either side of the automatic choice."""
+    lay = synth.make_layer(86, scheme * 10 + cb, scheme, M, N, cb)
+    x = synth.make_x(86, B, B, N)
+    want = oracle.linear(lay, x, threads=True)
+    w = qp.qp_repack(qp.Weight.from_layer(lay))
+    monkeypatch.setenv("QP_LINEAR_KERNEL", "mfma")
+    monkeypatch.setenv("QP_LINEAR_SPLIT", split)
+    y = qp.qp_linear(w, dev(x))
+    torch.cuda.synchronize()
+    assert rel_err(host16(y), want) <= TOL
