@@ -390,7 +390,7 @@ def main():
     achieved = head.alg_bytes / (lin_us * 1e-6) / 1e9
     # HBM bytes per launch from the committed rocprofv3 --pmc runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0,
     # factors from a plain copy of known size; profiles/qp_linear_pmc_*.md): only for the workload profiled
-    traffic = (18301 + 8) * 1024 if (a.cfg, a.layer, a.batch) == (3, 0, 1) else None
+    traffic = (18324 + 8) * 1024 if (a.cfg, a.layer, a.batch) == (3, 0, 1) else None
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "kernel": "qp_linear", "us_per_launch": round(lin_us, 3),
