@@ -8,7 +8,7 @@
  *
  *        y[b, j] = s[j] * sum_i xr[b, i] * W^[j, i]          (Section 3.3)
  *
- * with W^ given by one of three quantizer families (Section 3.2, Appendix C):
+ * with W^ given by one of the quantizer families of the paper (Section 3.2, Appendix C):
  *   QP_SQ   non-uniform scalar quantizer:  W^[j,i]           = LUT[code]          (App. C.1 "Dequantization")
  *   QP_VQ   2-D vector quantizer:          (W^[j,2m],W^[j,2m+1]) = LUT[code]      (App. C.2 "Dequantization")
  *   QP_TCQ  bitshift trellis, tail-biting: W^[j,tT+i]        = LUT[r_t[ik : ik+L]] (App. C.3.1 "Dequantization")
@@ -16,7 +16,6 @@
  *           (W^[j,tT+2i], W^[j,tT+2i+1]) = LUT[r_t[is : is+16]], with the 2^16 x 2 LUT *computed* from a
  *           small table tlut[2^tb][2]: h = x(x+1), entry (h >> (15-tb)) mod 2^tb, component 0 negated
  *           when bit 15 of h is set (App. C.3.1 "Codebook construction")
- *
  *   QP_TCQHH half-TCQ (Section 3.2, App. C.3.2): QP_TCQH with s bits per step on the first N/2 input
  *           channels and s + 1 on the remaining N/2 (s/2 + 1/4 bits per weight), both halves decoded
  *           with the one small table that belongs to s + 1
@@ -165,9 +164,9 @@ qp_status qp_repack(const qp_weight *canonical, qp_weight *native_out, void *nat
  * encodes its two halves with their own bitwidths.
  * w: scheme, shape, code_bits, vec, window_bits, tile, tlut_bits, lut (device, 16-byte aligned) and
  * row_stride describe the result, layout must be canonical; codes and scales are not read.
- * Supported: every QP_SQ / QP_VQ / QP_TCQ layer of qp_linear; QP_TCQH with s <= 6; QP_TCQHH with
- * s <= 5; N % 16 == 0.  W: device fp16 [M, ldw], the weights as they should decode (rotated and
- * divided by the per-row scale by the caller), 16-byte aligned, ldw % 8 == 0.  codes_out: device,
+ * Supported: every layer that qp_linear supports; N % 16 == 0.  W: device fp16 [M, ldw], the
+ * weights as they should decode (rotated and divided by the per-row scale by the caller),
+ * 16-byte aligned, ldw % 8 == 0.  codes_out: device,
  * 16-byte aligned, M * row_stride bytes; only the row's code bytes are written.  tile_err:
  * optional device fp32 [M, N/256], the squared error of every tile (trellis schemes only; fp32
  * accumulation).  workspace (trellis schemes): device, 16-byte aligned; any size from one
