@@ -149,12 +149,14 @@ __device__ __forceinline__ void qp_scalar_to_lds(qp_cu32 *src, u32x4_t *dst) {
 
 template <>
 struct QpDec<QP_SQ, 4> : QpBankTable<256> {
-    struct Pre {};
-    static __device__ __forceinline__ Pre pre(const uint16_t *) { return Pre{}; }
-    // tab[e] = (LUT[e & 15], LUT[e >> 4]): the two weights of one code byte.  Built at
-    // kernel start, before any vector load is queued: the 32-byte source comes through
-    // scalar registers into `small`, then every thread writes its share of the copies.
-    static __device__ __forceinline__ void early(uint8_t *tab, uint16_t *small, const uint16_t *g) {
+    // tab[e] = (LUT[e & 15], LUT[e >> 4]): the two weights of one code byte.  The 32-byte
+    // source comes through scalar registers (the scalar path does not queue behind vector
+    // loads) into `small`, then 256 threads write the copies.  When: see QP_TABLE_LATE.
+    struct Pre { const uint16_t *g; };
+    static __device__ __forceinline__ Pre pre(const uint16_t *g) { return Pre{g}; }
+    static __device__ __forceinline__ void early(uint8_t *tab, uint16_t *small, const uint16_t *g) { table(tab, small, g); }
+    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *small, const Pre &p) { table(tab, small, p.g); }
+    static __device__ __forceinline__ void table(uint8_t *tab, uint16_t *small, const uint16_t *g) {
         if (threadIdx.x < 64) qp_scalar_to_lds<2>(qp_scalar_ptr(g), reinterpret_cast<u32x4_t *>(small));
         __syncthreads();
         // thread e < 256 writes the 32 copies of entry e as eight 16-byte pieces, in an order
@@ -166,7 +168,6 @@ struct QpDec<QP_SQ, 4> : QpBankTable<256> {
         }
         __syncthreads();
     }
-    static __device__ __forceinline__ void build(uint8_t *, uint16_t *, const Pre &) {}
     template <int P>
     static __device__ __forceinline__ half8_t step(const u32x4_t (&q)[P], int s, const uint8_t *tab, uint32_t lc,
                                                    const Pre &) {
@@ -182,10 +183,12 @@ struct QpDec<QP_SQ, 4> : QpBankTable<256> {
 
 template <>
 struct QpDec<QP_VQ, 7> : QpBankTable<128> {
-    struct Pre {};
-    static __device__ __forceinline__ Pre pre(const uint16_t *) { return Pre{}; }
-    // 512-byte source: the first four wavefronts bring 128 bytes each.
-    static __device__ __forceinline__ void early(uint8_t *tab, uint16_t *small, const uint16_t *g) {
+    // 512-byte source through the scalar path: the first four wavefronts bring 128 bytes each.
+    struct Pre { const uint16_t *g; };
+    static __device__ __forceinline__ Pre pre(const uint16_t *g) { return Pre{g}; }
+    static __device__ __forceinline__ void early(uint8_t *tab, uint16_t *small, const uint16_t *g) { table(tab, small, g); }
+    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *small, const Pre &p) { table(tab, small, p.g); }
+    static __device__ __forceinline__ void table(uint8_t *tab, uint16_t *small, const uint16_t *g) {
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
         if (wave < 4)
             qp_scalar_to_lds<8>(qp_scalar_ptr(g) + 32 * wave, reinterpret_cast<u32x4_t *>(small) + 8 * wave);
@@ -194,7 +197,6 @@ struct QpDec<QP_VQ, 7> : QpBankTable<128> {
         if (threadIdx.x < 128) qp_bank_table_fill(tab, threadIdx.x, s32[threadIdx.x]);
         __syncthreads();
     }
-    static __device__ __forceinline__ void build(uint8_t *, uint16_t *, const Pre &) {}
     template <int P>
     static __device__ __forceinline__ half8_t step(const u32x4_t (&q)[P], int s, const uint8_t *tab, uint32_t lc,
                                                    const Pre &) {
@@ -387,6 +389,16 @@ template <> struct QpDec<QP_TCQHH, 9> : QpDecHalf<9> {};
 template <> struct QpDec<QP_TCQ, 2> : QpDecTcq<2> {};
 template <> struct QpDec<QP_TCQ, 3> : QpDecTcq<3> {};
 template <> struct QpDec<QP_TCQ, 4> : QpDecTcq<4> {};
+
+// Decoders whose workgroup-wide table can be built either before the first loads are issued
+// (early) or after (build) define both to do the same thing; the kernel calls exactly one.
+// Early delays the first loads by the scalar fetch and two barriers; late makes every
+// wavefront wait at a barrier until the slowest one has issued its loads.  Measured (SQ 4 bit):
+// late wins for workgroups with few units (4096x4096: 5.8 -> 4.4 us), early for many
+// (4096x14336: 8.2 vs 9.3 us).
+template <class D> struct QpTableMovable { static constexpr bool value = false; };
+template <> struct QpTableMovable<QpDec<QP_SQ, 4>> { static constexpr bool value = true; };
+template <> struct QpTableMovable<QpDec<QP_VQ, 7>> { static constexpr bool value = true; };
 
 // ------------------------------------------------------------------ DPP fold
 // v + (src shifted towards lane 0 by N lanes inside each row of 16 lanes).
@@ -599,7 +611,10 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     // early barrier, before any vector load is queued); a per-wavefront table only fetches
     // its source here and is written once the weight loads are in flight; the trellis
     // table's source is requested first so that it can be waited for alone.
-    D::early(tab, reinterpret_cast<uint16_t *>(red), w.lut);
+    // (a table that can be built at either point: late when the workgroup has few units)
+    constexpr bool MOVABLE = QpTableMovable<D>::value;
+    const bool table_late = MOVABLE && (rb_q + (rb_r ? 1 : 0)) * w.nbc <= 8;
+    if (!MOVABLE || !table_late) D::early(tab, reinterpret_cast<uint16_t *>(red), w.lut);
     const typename D::Pre pre = D::pre(w.lut);
 
     const int nw = blockDim.x >> 6;
@@ -699,7 +714,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
 #pragma unroll
         for (int n = 0; n < PF; ++n) xf[n] = *reinterpret_cast<const half8_t *>(xu + xfs * (xn0 + n));
     }
-    D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
+    if (!MOVABLE || table_late) D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
     QP_T(1);
     if (u < units) {
         float4_t v;
@@ -908,7 +923,7 @@ __global__ __launch_bounds__(1024) void k_dequant_blocks(QpW w, uint16_t *out, i
         qp_pieces_load<P, HH>(src, lane, full, q);
     };
     issue(t);
-    D::build(tab, reinterpret_cast<uint16_t *>(tile), pre);
+    if (!QpTableMovable<D>::value) D::build(tab, reinterpret_cast<uint16_t *>(tile), pre);
     __syncthreads();   // the staging room becomes the transposition tiles
     // tile of this wavefront: 64 slots of 64 bytes, slot = decoding lane, chunk c of a slot
     // at ((c + slot / 2) % 4) * 16 so that eight neighbouring lanes always cover all banks
