@@ -13,9 +13,9 @@
 // One coalesced 16-byte load per lane then serves TT consecutive steps; step s0 + t
 // accumulates into its own accumulator acc[t], of which only the columns with
 // j % TT == t are meaningful.  Summing those columns over t at the end (a DPP fold
-// inside each row of 16 lanes) gives the dot products.  TT = 16 / Bp (capped at 8 for
-// the schemes whose pieces need the registers) with Bp
-// the batch rounded up to a power of two.
+// inside each row of 16 lanes) gives the dot products.  TT = 16 / Bp with Bp the batch
+// rounded up to a power of two; the TT steps of a fragment share min(TT, 4) accumulators
+// through column-masked copies of the fragment.
 //
 // Table lookups per scheme:
 //   SQ 4 bit : one LDS read per *byte* of codes returns two weights (merged table,
@@ -28,6 +28,15 @@
 //              AND per code but ran 2x slower: the permute path has a lower rate.)
 //   TCQ      : the 2^16-entry fp16 table, 128 KiB of LDS, read with ds_read_u16.
 //   TCQH     : computed code book, 1024-entry bank-replicated table (see QpDecTcqh).
+//   half-TCQ : TCQH with one 16-byte piece more per lane in the column blocks of the second
+//              half of the input channels; a wavefront picks the decoder of its unit's half.
+//
+// Variants of the same kernel: the activations come row-major from global memory, in
+// fragment order from global memory (written that way by the rotation kernel), or - batch 1,
+// one Hadamard block - are rotated by the workgroup itself into LDS while its first weights
+// are in flight (qp_fwht.h); for the trellis schemes at batch <= 2 a unit can be shared by two
+// wavefronts that decode half of its steps each.  The file ends with the dequantize-only
+// kernel for the native layout, which reuses the units, loads and decoders.
 //
 // A workgroup owns a contiguous range of 16-row blocks and walks it in passes of G
 // row blocks; the G * (N / 1024) units of a pass are dealt round-robin to the

@@ -365,3 +365,44 @@ def test_linear_two_wavefronts_per_unit(qp, scheme, cb, M, N, B, split, monkeypa
     y = qp.qp_linear(w, dev(x))
     torch.cuda.synchronize()
     assert rel_err(host16(y), want) <= TOL
+
+
+def test_calls_captured_in_a_hip_graph_replay_identically(qp, monkeypatch):
+    """The library only enqueues kernels (no allocation, no memset, no synchronisation), so a
+    sequence of its calls can be captured once and replayed: three replays, with eager work in
+    between, each equal to the eager results."""
+    monkeypatch.setenv("QP_LINEAR_KERNEL", "mfma")
+    lay_a = synth.make_layer(87, 0, synth.TCQH, 272, 4096, 5)
+    lay_b = synth.make_layer(87, 1, synth.VQ, 4096, 3072, 5)
+    wa, wb = qp.qp_repack(qp.Weight.from_layer(lay_a)), qp.qp_repack(qp.Weight.from_layer(lay_b))
+    sga, sgb = dev(synth.make_signs(87, 0, 4096)), dev(synth.make_signs(87, 1, 3072))
+    xa, xb = dev(synth.make_x(87, 0, 1, 4096)), dev(synth.make_x(87, 1, 3, 3072))
+    ya = torch.empty((1, 272), dtype=torch.float16, device="cuda")
+    yb = torch.empty((3, 4096), dtype=torch.float16, device="cuda")
+    ws = torch.empty(max(qp.qp_rotate_linear_workspace_bytes(wa, 1), qp.qp_rotate_linear_workspace_bytes(wb, 3)),
+                     dtype=torch.uint8, device="cuda")
+    W = torch.empty((272, 4096), dtype=torch.float16, device="cuda")
+
+    def work():
+        qp.qp_rotate_linear(wa, xa, sga, 4096, y=ya, workspace=ws)      # one launch (in-kernel rotation)
+        qp.qp_rotate_linear(wb, xb, sgb, 1024, y=yb, workspace=ws)      # two launches through the workspace
+        qp.qp_dequant(wa, out=W)
+
+    work()
+    torch.cuda.synchronize()
+    want = (ya.clone(), yb.clone(), W.clone())
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(g, stream=s):
+            work()
+    torch.cuda.current_stream().wait_stream(s)
+    for rep in range(3):
+        ya.zero_(); yb.zero_(); W.zero_(); ws.fill_(rep)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ya, want[0]) and torch.equal(yb, want[1]) and torch.equal(W, want[2]), rep
+        _ = qp.qp_linear(wb, xb)          # eager work between the replays
+        torch.cuda.synchronize()
