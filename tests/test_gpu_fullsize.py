@@ -15,8 +15,12 @@ CASES = [  # (cfg, layer index, batches)
     (2, 0, [1]),
     (3, 0, [1, 4, 8]),
     (4, 0, [1, 16]),
+    (4, 1, [1, 4]),
+    (4, 2, [1, 8]),
     (4, 3, [1, 2, 8]),
+    (5, 0, [1]),
     (5, 1, [1]),
+    (5, 2, [1, 8]),
     (5, 3, [1, 8]),
     (6, 1, [1, 8]),
     (6, 6, [1]),
