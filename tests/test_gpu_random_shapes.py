@@ -1,0 +1,72 @@
+"""Seeded random shapes for the fused layer on the native layout: column-block counts from 1 to 32,
+row-block counts on both sides of the workgroup count (one row block per workgroup, several with a
+ragged last pass, fewer than 256 in all), every batch size, every scheme; checked on sampled output
+rows against the oracle, through qp_linear and through the single-call step."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+SCHEMES = [(synth.SQ, 4), (synth.VQ, 5), (synth.VQ, 7), (synth.TCQ, 2), (synth.TCQ, 3), (synth.TCQ, 4)] + \
+          [(synth.TCQH, s) for s in range(3, 11)] + [(synth.TCQHH, s) for s in range(3, 10)]
+
+
+def cases():
+    g = np.random.default_rng(2024)
+    out = []
+    for k in range(60):
+        scheme, cb = SCHEMES[k % len(SCHEMES)]
+        nbc = int(g.choice([1, 2, 3, 4, 5, 6, 7, 8, 11, 14, 16, 24, 28, 32]))
+        if scheme == synth.TCQHH and nbc % 2:
+            nbc += 1
+        rbk = int(g.choice([1, 3, 17, 100, 255, 256, 257, 300, 511, 700, 1500]))
+        if rbk * nbc > 60000:       # keep the layer below ~1 G weights
+            rbk = max(1, 60000 // nbc)
+        B = int(g.integers(1, 17))
+        out.append((k, scheme, cb, rbk * 16, nbc * 1024, B))
+    return out
+
+
+@pytest.fixture(scope="module")
+def qp():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2509_20214_amd as m
+    m.load_library()
+    return m
+
+
+def dev(a):
+    if a.dtype == np.float16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.float16)
+    return torch.from_numpy(a).cuda()
+
+
+@pytest.mark.parametrize("k,scheme,cb,M,N,B", cases(),
+                         ids=[f"{k}-{synth.SCHEME_NAMES[s]}{cb}-{M}x{N}-b{B}" for k, s, cb, M, N, B in cases()])
+def test_random_shape(qp, k, scheme, cb, M, N, B, monkeypatch):
+    lay = synth.make_layer(88, k, scheme, M, N, cb)
+    x = synth.make_x(88, k, B, N)
+    block = synth.hadamard_block(N)
+    if block > 16384:       # the rotation supports blocks up to 16384
+        block = 1024
+    sg = synth.make_signs(88, k, N)
+    w = qp.qp_repack(qp.Weight.from_layer(lay))
+    monkeypatch.setenv("QP_LINEAR_KERNEL", "mfma")
+    xd, sd = dev(x), dev(sg)
+    xr = qp.qp_hadamard(xd, sd, block)
+    y = qp.qp_linear(w, xr)
+    y_step = qp.qp_rotate_linear(w, xd, sd, block)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y_step)
+    g = np.random.default_rng(k)
+    rows = sorted(set(int(r) for r in g.integers(0, M, size=20)) | {0, M - 1, min(M - 1, 16 * (M // 32))})
+    sub = synth.Layer(**{**lay.__dict__, "codes": lay.codes[rows], "scales": lay.scales[rows], "M": len(rows)})
+    want = oracle.linear(sub, xr.cpu().view(torch.int16).numpy().view(np.uint16))
+    got = y[:, torch.tensor(rows, device="cuda")].cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(got - want)) / np.max(np.abs(want)) <= 1e-2
+    assert torch.isfinite(y.float()).all()
