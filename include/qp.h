@@ -40,7 +40,9 @@
  * holds for that span (bpw = code_bits/vec).  Those bytes are cut into P = 2*bpw
  * pieces of 16 bytes; piece p of lane l sits at byte (p*64 + l)*16 of the block, so
  * one 128-bit load per lane of a 64-wide wavefront reads 1 KiB contiguously.
- * row_stride is ignored for this layout.  QP_TCQHH (needs N % 2048 == 0): the column blocks of the
+ * row_stride is ignored for this layout.  It is the layout the kernels are fastest on; layers
+ * made of whole blocks run the same matrix-core kernel from the canonical layout too, some
+ * 25 % slower, anything else a layout-agnostic kernel.  QP_TCQHH (needs N % 2048 == 0): the column blocks of the
  * second half have one piece more than those of the first; a block row is the N/2048 blocks of the
  * first half followed by the N/2048 blocks of the second.
  *

@@ -90,7 +90,7 @@ extern "C" size_t qp_linear_workspace_bytes(const qp_weight *w, int32_t B) {
 }
 
 // Which kernel runs a layer.  QP_LINEAR_KERNEL=rowwave / mfma forces one (used by the tests
-// to cover both on native-layout weights of any size); anything else lets the shape decide.
+// to cover both on weights of any size); anything else lets the shape decide.
 // The matrix-core kernel pays a fixed table-build and reduction cost per workgroup; below
 // one 16x1024 block per CU (measured: 1024x1024 runs 3.2 us on the row kernel, 6.4 us on
 // the block kernel) the row kernel is the faster one.
@@ -98,9 +98,12 @@ static bool use_rowwave(const qp_weight *w) {
     const int nbc = w->N / 1024;
     const char *force = getenv("QP_LINEAR_KERNEL");
     const int64_t blocks = (int64_t)(w->M / 16) * nbc;
-    bool rowwave = (w->layout != QP_LAYOUT_NATIVE) || nbc > 32 || blocks < 256 ||
-                   (force && strcmp(force, "rowwave") == 0);
-    if (force && strcmp(force, "mfma") == 0 && w->layout == QP_LAYOUT_NATIVE && nbc <= 32) rowwave = false;
+    // the block kernel needs whole 16 x 1024 blocks; it reads them from either layout (in the
+    // canonical one a lane's pieces are consecutive in its row instead of one KiB per piece)
+    const bool fits = w->M % 16 == 0 && w->N % 1024 == 0 && nbc <= 32 &&
+                      !(w->scheme == QP_TCQHH && w->N % 2048 != 0);
+    bool rowwave = !fits || blocks < 256 || (force && strcmp(force, "rowwave") == 0);
+    if (force && strcmp(force, "mfma") == 0 && fits) rowwave = false;
     return rowwave;
 }
 

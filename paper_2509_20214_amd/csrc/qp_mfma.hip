@@ -435,24 +435,27 @@ struct QpFold {  // acc[0] + shl1(acc[1]) + ... : lane b*TT of every row ends up
 // The P pieces of one unit.  Half-TCQ units of the first half have one piece less: `full`
 // (wave-uniform) says whether the last one exists.
 template <int P, bool OPTIONAL_LAST>
-__device__ __forceinline__ void qp_pieces_load(const u32x4_t *blk, int lane, bool full, u32x4_t (&q)[P]) {
+// src: the lane's first piece; ps: distance between its pieces in 16-byte units (64 in the
+// native layout, where a piece of all 64 lanes is one contiguous KiB; 1 in the canonical one,
+// where the lane's pieces follow each other in its row).
+__device__ __forceinline__ void qp_pieces_load(const u32x4_t *src, int ps, bool full, u32x4_t (&q)[P]) {
 #pragma unroll
     for (int p = 0; p < P; ++p) {
         if (OPTIONAL_LAST && p == P - 1) {
             q[p] = u32x4_t{0u, 0u, 0u, 0u};
-            if (full) q[p] = __builtin_nontemporal_load(blk + p * 64 + lane);
+            if (full) q[p] = __builtin_nontemporal_load(src + p * ps);
         } else {
-            q[p] = __builtin_nontemporal_load(blk + p * 64 + lane);
+            q[p] = __builtin_nontemporal_load(src + p * ps);
         }
     }
 }
 
 template <int P, int PF, bool OPTIONAL_LAST>
-__device__ __forceinline__ void qp_unit_load(const u32x4_t *blk, const half_t *xu, int xfs, int lane, bool full,
+__device__ __forceinline__ void qp_unit_load(const u32x4_t *src, int ps, const half_t *xu, int xfs, bool full,
                                              u32x4_t (&q)[P], half8_t (&xf)[PF]) {
 #pragma unroll
     for (int n = 0; n < PF; ++n) xf[n] = *reinterpret_cast<const half8_t *>(xu + xfs * n);
-    qp_pieces_load<P, OPTIONAL_LAST>(blk, lane, full, q);
+    qp_pieces_load<P, OPTIONAL_LAST>(src, ps, full, q);
 }
 
 // Two wavefronts per unit (trellis schemes, few units per workgroup): half H decodes steps
@@ -460,7 +463,7 @@ __device__ __forceinline__ void qp_unit_load(const u32x4_t *blk, const half_t *x
 // the stream plus, the windows being 16 bits wide, the piece after it (for the second half: the
 // first piece, by tail-biting).  The others stay zero and are never looked at.
 template <int S, int CB, int P, int H>
-__device__ __forceinline__ void qp_half_pieces_load(const u32x4_t *blk, int lane, u32x4_t (&q)[P]) {
+__device__ __forceinline__ void qp_half_pieces_load(const u32x4_t *src, int ps, u32x4_t (&q)[P]) {
     constexpr int V = QpTraits<S, CB>::V;
     constexpr int ELEMS = 128 / V;                       // windows per half
     constexpr int TOTAL = 128 * P;                       // stream bits of the lane
@@ -468,7 +471,7 @@ __device__ __forceinline__ void qp_half_pieces_load(const u32x4_t *blk, int lane
 #pragma unroll
     for (int p = 0; p < P; ++p) {
         const bool need = (128 * p < END && 128 * p + 128 > START) || (END > TOTAL && 128 * p < END - TOTAL);
-        if (need) q[p] = __builtin_nontemporal_load(blk + p * 64 + lane);
+        if (need) q[p] = __builtin_nontemporal_load(src + p * ps);
         else q[p] = u32x4_t{0u, 0u, 0u, 0u};
     }
 }
@@ -677,15 +680,28 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     // block (row block rb0 + slot, column block C) of unit u = slot * nbc + C, and whether
     // it has all P pieces
     const int hcb = nbc >> 1;   // half-TCQ: column blocks per half
+    // First piece of this lane for unit un = slot * nbc + C of the pass that starts at row block rb0.
+    const bool canonical = w.layout == QP_LAYOUT_CANONICAL;
+    const int ps = canonical ? 1 : 64;
     auto unit_block = [&](int rb0, int un, int C, bool &full) -> const u32x4_t * {
+        const int slot = (un * nbc_magic) >> 16;
+        if constexpr (HH) full = __builtin_amdgcn_readfirstlane(C >= hcb);
+        else full = true;
+        if (canonical) {
+            // row 16 (rb0 + slot) + i of the bitstream; its span for columns 1024 C + 256 g ..
+            int64_t off;
+            if constexpr (HH)
+                off = full ? (int64_t)hcb * (64 * CB) + (int64_t)((C - hcb) * 4 + (lane >> 4)) * (16 * (CB + 1))
+                           : (int64_t)(C * 4 + (lane >> 4)) * (16 * CB);
+            else
+                off = (int64_t)(C * 4 + (lane >> 4)) * T::SPAN;
+            return reinterpret_cast<const u32x4_t *>(w.codes + ((int64_t)(rb0 + slot) * 16 + (lane & 15)) * w.row_stride + off);
+        }
         if constexpr (HH) {
-            const int slot = (un * nbc_magic) >> 16;
-            full = __builtin_amdgcn_readfirstlane(C >= hcb);
             return codes16 + (int64_t)(rb0 + slot) * (hcb * 64 * (2 * CB + 1)) + C * (64 * CB) +
-                   (full ? (C - hcb) * 64 : 0);
+                   (full ? (C - hcb) * 64 : 0) + lane;
         } else {
-            full = true;
-            return codes16 + ((int64_t)rb0 * nbc + un) * BLK16;
+            return codes16 + ((int64_t)rb0 * nbc + un) * BLK16 + lane;
         }
     };
     u32x4_t q[P];
@@ -693,10 +709,10 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     {
         const u32x4_t *blk = unit_block(rb_begin, uu, uu - ((uu * nbc_magic) >> 16) * nbc, full);
         if constexpr (SPLIT) {
-            if (half1) qp_half_pieces_load<S, CB, P, 1>(blk, lane, q);
-            else qp_half_pieces_load<S, CB, P, 0>(blk, lane, q);
+            if (half1) qp_half_pieces_load<S, CB, P, 1>(blk, ps, q);
+            else qp_half_pieces_load<S, CB, P, 0>(blk, ps, q);
         } else {
-            qp_pieces_load<P, HH>(blk, lane, full, q);
+            qp_pieces_load<P, HH>(blk, ps, full, q);
         }
     }
     // the first output this thread stores after the pass: its per-row scale is fetched now
@@ -758,16 +774,16 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
 #pragma unroll
                 for (int n = 0; n < PF; ++n) xf2[n] = *reinterpret_cast<const half8_t *>(xu2 + xfs * (n0 + n));
                 if (h2) {
-                    qp_half_pieces_load<S, CB, P, 1>(blk2, lane, q2);
+                    qp_half_pieces_load<S, CB, P, 1>(blk2, ps, q2);
                     v = qp_unit_compute<D, P, PF, TT, 16, 32>(q2, xf2, xu2, xfs, tab, lc, pre);
                 } else {
-                    qp_half_pieces_load<S, CB, P, 0>(blk2, lane, q2);
+                    qp_half_pieces_load<S, CB, P, 0>(blk2, ps, q2);
                     v = qp_unit_compute<D, P, PF, TT, 0, 16>(q2, xf2, xu2, xfs, tab, lc, pre);
                 }
                 if (owner) *reinterpret_cast<float4_t *>(&red[(u * BP + bj) * 16 + 4 * g]) = v;
                 continue;
             }
-            qp_unit_load<P, PF, HH>(blk2, xu2, xfs, lane, full2, q2, xf2);
+            qp_unit_load<P, PF, HH>(blk2, ps, xu2, xfs, full2, q2, xf2);
             if constexpr (HH) {
                 if (full2) v = qp_unit_compute<D, P, PF, TT>(q2, xf2, xu2, xfs, tab, lc, pre);
                 else v = qp_unit_compute<typename D::Lo, P, PF, TT>(q2, xf2, xu2, xfs, tab, lc, pre);
@@ -929,7 +945,7 @@ __global__ __launch_bounds__(1024) void k_dequant_blocks(QpW w, uint16_t *out, i
         } else {
             src = codes16 + (int64_t)bc * BLK16;
         }
-        qp_pieces_load<P, HH>(src, lane, full, q);
+        qp_pieces_load<P, HH>(src + lane, 64, full, q);
     };
     issue(t);
     if (!QpTableMovable<D>::value) D::build(tab, reinterpret_cast<uint16_t *>(tile), pre);

@@ -406,3 +406,27 @@ def test_calls_captured_in_a_hip_graph_replay_identically(qp, monkeypatch):
         assert torch.equal(ya, want[0]) and torch.equal(yb, want[1]) and torch.equal(W, want[2]), rep
         _ = qp.qp_linear(wb, xb)          # eager work between the replays
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("scheme,cb", ALL, ids=ALL_IDS)
+@pytest.mark.parametrize("M,N,B", [(48, 4096, 1), (1040, 2048, 3), (16, 14336, 8), (272, 6144, 16)])
+def test_block_kernel_on_canonical_layout(qp, scheme, cb, M, N, B, monkeypatch):
+    """The matrix-core kernel reads whole 16 x 1024 blocks straight from the canonical bitstream
+    (no repack; a padded row stride included) with the same result as from the native layout."""
+    lay = synth.make_layer(89, scheme * 10 + cb, scheme, M, N, cb)
+    x = synth.make_x(89, B, B, N)
+    want = oracle.linear(lay, x, threads=True)
+    monkeypatch.setenv("QP_LINEAR_KERNEL", "mfma")
+    w = qp.Weight.from_layer(lay)
+    y = qp.qp_linear(w, dev(x))
+    y_nat = qp.qp_linear(qp.qp_repack(w), dev(x))
+    # the same codes in a buffer with 48 bytes of padding per row
+    rb = lay.codes.shape[1]
+    padded = torch.zeros((M, rb + 48), dtype=torch.uint8, device="cuda")
+    padded[:, :rb] = dev(lay.codes)
+    wp = qp.Weight(scheme, M, N, cb, lay.vec, lay.window_bits, lay.tile, padded, w.lut, w.scales,
+                   row_stride=rb + 48, tlut_bits=lay.tlut_bits)
+    y_pad = qp.qp_linear(wp, dev(x))
+    torch.cuda.synchronize()
+    assert rel_err(host16(y), want) <= TOL
+    assert torch.equal(y, y_nat) and torch.equal(y_pad, y_nat)
