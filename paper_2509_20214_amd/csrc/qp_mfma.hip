@@ -227,21 +227,14 @@ struct QpDec<QP_VQ, 5> {
     // registers while its weight loads are in flight: no wavefront ever waits for another
     // one before it can start decoding.
     static constexpr int TAB_BYTES = 16 * 128;
-    struct Pre { u32x4_t raw[8]; };  // wave-uniform: lives in 32 scalar registers
+    // The table's source is fetched (scalar path) only when the copy is written, after the
+    // wavefront's weight loads have been issued: held in 32 scalar registers from the start of
+    // the kernel it gets spilled, and the spill waits for the fetch in front of the first loads.
+    struct Pre { const uint16_t *g; };
     static __device__ __forceinline__ void early(uint8_t *, uint16_t *, const uint16_t *) {}
-    static __device__ __forceinline__ Pre pre(const uint16_t *g) {
-        qp_cu32 *l32 = qp_scalar_ptr(g);
-        Pre p;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) p.raw[k] = u32x4_t{l32[4 * k], l32[4 * k + 1], l32[4 * k + 2], l32[4 * k + 3]};
-        return p;
-    }
+    static __device__ __forceinline__ Pre pre(const uint16_t *g) { return Pre{g}; }
     static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *, const Pre &p) {
-        if ((threadIdx.x & 63) == 0) {
-            u32x4_t *t4 = reinterpret_cast<u32x4_t *>(tab) + (threadIdx.x >> 6) * 8;
-#pragma unroll
-            for (int k = 0; k < 8; ++k) t4[k] = p.raw[k];
-        }
+        qp_scalar_to_lds<8>(qp_scalar_ptr(p.g), reinterpret_cast<u32x4_t *>(tab) + (threadIdx.x >> 6) * 8);
     }
     static __device__ __forceinline__ uint32_t lane_const() { return (threadIdx.x >> 6) << 7; }
     template <int P>
