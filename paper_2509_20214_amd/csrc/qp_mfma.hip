@@ -18,12 +18,15 @@
 // through column-masked copies of the fragment.
 //
 // Table lookups per scheme:
-//   SQ 4 bit : one LDS read per *byte* of codes returns two weights (merged table,
-//              256 entries of half2).  The table is replicated once per LDS bank
-//              (entry e of copy c at dword 32 e + c) and lane l only reads copy
-//              l % 32, so no two lanes of a pass ever collide in a bank.
-//   VQ 7 bit : same bank-replicated table, 128 entries of half2.
-//   VQ 5 bit : 32 entries of half2 = one dword per LDS bank, conflict-free as it is.
+//   SQ 4 bit, VQ 5 and 7 bit : one vector operation per code (two weights): an SDWA shift
+//              drops the 8 stream bits that start at the code into byte 1 of a lane's address
+//              register; the 256-row table holds one copy of every row per LDS bank, so no
+//              two lanes ever collide (QpDecByte).  SQ: a code byte = two 4-bit codes, merged
+//              table of half2.  Measured issue cost on this chip, 4 wavefronts per SIMD:
+//              2.3 clocks for VOP2 (shift, and, xor), 3.8 for VOP3 / SDWA / DPP forms, so
+//              one SDWA per code beats bit-field extract + shift-or (7.6) and shift + and (4.6).
+//   VQ 5 bit, small layers : 32 entries of half2 = one dword per bank, conflict-free as it
+//              is; a private copy per wavefront, no workgroup barrier (QpDecVq5Private).
 //              (Keeping the table in a VGPR and fetching it with ds_bpermute saves the
 //              AND per code but ran 2x slower: the permute path has a lower rate.)
 //   TCQ      : the 2^16-entry fp16 table, 128 KiB of LDS, read with ds_read_u16.
@@ -34,7 +37,8 @@
 // Variants of the same kernel: the activations come row-major from global memory, in
 // fragment order from global memory (written that way by the rotation kernel), or - batch 1,
 // one Hadamard block - are rotated by the workgroup itself into LDS while its first weights
-// are in flight (qp_fwht.h); for the trellis schemes at batch <= 2 a unit can be shared by two
+// are in flight (qp_fwht.h; a kernel instance of its own, so that the plain one does not carry
+// the transform's LDS arrays); for the trellis schemes at batch <= 2 a unit can be shared by two
 // wavefronts that decode half of its steps each.  The file ends with the dequantize-only
 // kernel for the native layout, which reuses the units, loads and decoders.
 //
@@ -43,11 +47,20 @@
 // wavefronts, each unit's partial sums go to LDS, and after a barrier the workgroup
 // adds them up in a fixed order, applies the per-row scale and stores fp16.
 #include <cstdlib>
+#include <type_traits>
 
 #include "qp_internal.h"
 #include "qp_fwht.h"
 
-#define QP_UMAX 32  // units per pass
+#define QP_NBC_MAX 32  // column blocks of a layer (N <= 32 * 1024)
+// Units per pass: between two passes the workgroup meets at barriers to add up and store, and
+// every wavefront starts the next pass in step with the others (all waiting for their loads,
+// then all decoding).  The longer a pass, the more the wavefronts drift apart and overlap one
+// another's loads with decode; the room for partial sums (16 BP floats per unit) sets the limit.
+#ifndef QP_UMAX_SMALL_BATCH
+#define QP_UMAX_SMALL_BATCH 128
+#endif
+constexpr int qp_umax(int BP) { return BP == 1 ? QP_UMAX_SMALL_BATCH : (BP <= 4 ? 64 : 32); }
 
 #ifdef QP_TRACE  // development builds only: per-wavefront timestamps of the kernel's phases
 __device__ uint64_t *qp_trace_buf;
@@ -119,23 +132,6 @@ __device__ __forceinline__ uint32_t qp_field_addr(const u32x4_t (&q)[P], int bit
 template <int S, int CB>
 struct QpDec;
 
-// Bank-replicated table of half2 entries: dword 32 e + c holds entry e for c = 0..31.
-template <int ENTRIES>
-struct QpBankTable {
-    static constexpr int TAB_BYTES = ENTRIES * 128;
-    static __device__ __forceinline__ uint32_t lane_const() { return (threadIdx.x & 31u) << 2; }
-};
-
-// The 32 copies of entry e (128 contiguous bytes) as eight 16-byte writes, rotated by the
-// lane so that neighbouring lanes hit different banks.
-__device__ __forceinline__ void qp_bank_table_fill(uint8_t *tab, int e, uint32_t v) {
-    u32x4_t *t4 = reinterpret_cast<u32x4_t *>(tab);
-    const int rot = threadIdx.x & 7;
-    const u32x4_t v4 = u32x4_t{v, v, v, v};
-#pragma unroll
-    for (int k = 0; k < 8; ++k) t4[e * 8 + ((k + rot) & 7)] = v4;
-}
-
 // Uniform (wave-wide) reads of the table's source go through the scalar cache: they do
 // not queue behind the vector loads of the weight stream.
 typedef const uint32_t __attribute__((address_space(4))) qp_cu32;
@@ -156,80 +152,113 @@ __device__ __forceinline__ void qp_scalar_to_lds(qp_cu32 *src, u32x4_t *dst) {
     }
 }
 
-template <>
-struct QpDec<QP_SQ, 4> : QpBankTable<256> {
-    // tab[e] = (LUT[e & 15], LUT[e >> 4]): the two weights of one code byte.  The 32-byte
-    // source comes through scalar registers (the scalar path does not queue behind vector
-    // loads) into `small`, then 256 threads write the copies.  When: see QP_TABLE_LATE.
-    struct Pre { const uint16_t *g; };
-    static __device__ __forceinline__ Pre pre(const uint16_t *g) { return Pre{g}; }
-    static __device__ __forceinline__ void early(uint8_t *tab, uint16_t *small, const uint16_t *g) { table(tab, small, g); }
-    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *small, const Pre &p) { table(tab, small, p.g); }
-    static __device__ __forceinline__ void table(uint8_t *tab, uint16_t *small, const uint16_t *g) {
-        if (threadIdx.x < 64) qp_scalar_to_lds<2>(qp_scalar_ptr(g), reinterpret_cast<u32x4_t *>(small));
-        __syncthreads();
-        // thread e < 256 writes the 32 copies of entry e as eight 16-byte pieces, in an order
-        // rotated by the lane (eight neighbouring lanes cover all banks)
-        if (threadIdx.x < 256) {
-            const int e = threadIdx.x;
-            const uint32_t v = (uint32_t)small[e & 15] | ((uint32_t)small[e >> 4] << 16);
-            qp_bank_table_fill(tab, e, v);
-        }
-        __syncthreads();
-    }
-    template <int P>
-    static __device__ __forceinline__ half8_t step(const u32x4_t (&q)[P], int s, const uint8_t *tab, uint32_t lc,
-                                                   const Pre &) {
-        uint32_t r[4];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            uint32_t a = qp_field_addr<P, false, 7>(q, 32 * s + 8 * c, 8, lc);
-            r[c] = *reinterpret_cast<const uint32_t *>(tab + a);
-        }
-        return __builtin_bit_cast(half8_t, u32x4_t{r[0], r[1], r[2], r[3]});
-    }
+// ---- byte-window decoders (SQ 4 bit, VQ 5 and 7 bit) ---------------------------------------
+// A code of at most 8 bits costs ONE vector operation: an SDWA shift (or move) drops the 8
+// stream bits that start at the code's first bit into byte 1 of an address register whose
+// byte 0 holds 4 (lane % 32) for good.  The table therefore has 256 rows of 256 bytes, row b
+// holding 32 copies (one per LDS bank, so lookups never collide) of the entry of window b;
+// window bits above the code belong to the next code and are ignored by replicating the
+// entry over them (row b = entry b mod 2^CB).  The upper half of every row is unused.
+// The address registers are written read-modify-write, so a lane keeps eight of them.
+struct QpLane8 {
+    uint32_t a[8];
 };
 
-template <>
-struct QpDec<QP_VQ, 7> : QpBankTable<128> {
-    // 512-byte source through the scalar path: the first four wavefronts bring 128 bytes each.
+template <int SEL>
+__device__ __forceinline__ void qp_byte1_from_byte(uint32_t &a, uint32_t w) {
+    if constexpr (SEL == 0) asm("v_mov_b32_sdwa %0, %1 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_0" : "+v"(a) : "v"(w));
+    else if constexpr (SEL == 1) asm("v_mov_b32_sdwa %0, %1 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_1" : "+v"(a) : "v"(w));
+    else if constexpr (SEL == 2) asm("v_mov_b32_sdwa %0, %1 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_2" : "+v"(a) : "v"(w));
+    else asm("v_mov_b32_sdwa %0, %1 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_3" : "+v"(a) : "v"(w));
+}
+
+// byte 1 of `a` <- stream bits [BITPOS, BITPOS + 8) (bits past the lane's stream read as anything)
+template <int P, int BITPOS, int NBITS>
+__device__ __forceinline__ void qp_window8(const u32x4_t (&q)[P], uint32_t &a) {
+    constexpr int i0 = BITPOS >> 5, r = BITPOS & 31;
+    if constexpr (r + NBITS <= 32) {
+        const uint32_t w = qp_dw<P>(q, i0);
+        if constexpr ((r & 7) == 0) {
+            qp_byte1_from_byte<r / 8>(a, w);
+        } else {
+            // the shift amount sits in a scalar register: SDWA encodings take no constants
+            asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:BYTE_1 dst_unused:UNUSED_PRESERVE src0_sel:DWORD src1_sel:DWORD"
+                : "+v"(a)
+                : "s"(r), "v"(w));
+        }
+    } else {
+        const uint32_t w = qp_bits32<P, false>(q, BITPOS);
+        qp_byte1_from_byte<0>(a, w);
+    }
+}
+
+template <int S, int CB>
+struct QpDecByte {
+    static constexpr bool BYTE_WINDOW = true;
+    static constexpr int TAB_BYTES = 65536;
+    static constexpr int SRC_BYTES = (S == QP_SQ) ? 32 : (4 << CB);   // the table's source in global memory
+    typedef QpLane8 Lane;
     struct Pre { const uint16_t *g; };
     static __device__ __forceinline__ Pre pre(const uint16_t *g) { return Pre{g}; }
+    static __device__ __forceinline__ Lane lane_const() {
+        Lane l;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) l.a[k] = (threadIdx.x & 31u) << 2;
+        return l;
+    }
     static __device__ __forceinline__ void early(uint8_t *tab, uint16_t *small, const uint16_t *g) { table(tab, small, g); }
     static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *small, const Pre &p) { table(tab, small, p.g); }
+    // The source comes through scalar registers (the scalar path does not queue behind the
+    // vector loads of the weight stream) into `small`; then every thread writes 32 bytes of a row.
     static __device__ __forceinline__ void table(uint8_t *tab, uint16_t *small, const uint16_t *g) {
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        if (wave < 4)
-            qp_scalar_to_lds<8>(qp_scalar_ptr(g) + 32 * wave, reinterpret_cast<u32x4_t *>(small) + 8 * wave);
+        if constexpr (SRC_BYTES <= 128) {
+            if (wave == 0) qp_scalar_to_lds<SRC_BYTES / 16>(qp_scalar_ptr(g), reinterpret_cast<u32x4_t *>(small));
+        } else {
+            if (wave < SRC_BYTES / 128)
+                qp_scalar_to_lds<8>(qp_scalar_ptr(g) + 32 * wave, reinterpret_cast<u32x4_t *>(small) + 8 * wave);
+        }
         __syncthreads();
         const uint32_t *s32 = reinterpret_cast<const uint32_t *>(small);
-        if (threadIdx.x < 128) qp_bank_table_fill(tab, threadIdx.x, s32[threadIdx.x]);
+        u32x4_t *t4 = reinterpret_cast<u32x4_t *>(tab);
+        for (int idx = threadIdx.x; idx < 1024; idx += blockDim.x) {
+            const int b = idx >> 2, part = idx & 3;
+            uint32_t v;
+            if constexpr (S == QP_SQ) v = (uint32_t)small[b & 15] | ((uint32_t)small[b >> 4] << 16);   // two weights per code byte
+            else v = s32[b & ((1 << CB) - 1)];
+            const u32x4_t v4 = u32x4_t{v, v, v, v};
+            const int flip = (idx >> 3) & 1;   // neighbouring rows start on different banks
+            t4[b * 16 + part * 2 + flip] = v4;
+            t4[b * 16 + part * 2 + (flip ^ 1)] = v4;
+        }
         __syncthreads();
     }
-    template <int P>
-    static __device__ __forceinline__ half8_t step(const u32x4_t (&q)[P], int s, const uint8_t *tab, uint32_t lc,
-                                                   const Pre &) {
+    template <int P, int SI>
+    static __device__ __forceinline__ half8_t step_at(const u32x4_t (&q)[P], const uint8_t *tab, Lane &l) {
+        constexpr int CODE = (S == QP_SQ) ? 8 : CB;   // stream bits per lookup (two weights)
         uint32_t r[4];
+        qp_window8<P, 4 * CODE * SI + 0 * CODE, CODE>(q, l.a[4 * (SI & 1) + 0]);
+        qp_window8<P, 4 * CODE * SI + 1 * CODE, CODE>(q, l.a[4 * (SI & 1) + 1]);
+        qp_window8<P, 4 * CODE * SI + 2 * CODE, CODE>(q, l.a[4 * (SI & 1) + 2]);
+        qp_window8<P, 4 * CODE * SI + 3 * CODE, CODE>(q, l.a[4 * (SI & 1) + 3]);
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            uint32_t a = qp_field_addr<P, false, 7>(q, 28 * s + 7 * c, 7, lc);
-            r[c] = *reinterpret_cast<const uint32_t *>(tab + a);
-        }
+        for (int c = 0; c < 4; ++c) r[c] = *reinterpret_cast<const uint32_t *>(tab + l.a[4 * (SI & 1) + c]);
         return __builtin_bit_cast(half8_t, u32x4_t{r[0], r[1], r[2], r[3]});
     }
 };
+template <> struct QpDec<QP_SQ, 4> : QpDecByte<QP_SQ, 4> {};
+template <> struct QpDec<QP_VQ, 5> : QpDecByte<QP_VQ, 5> {};
+template <> struct QpDec<QP_VQ, 7> : QpDecByte<QP_VQ, 7> {};
 
-template <>
-struct QpDec<QP_VQ, 5> {
-    // 32 entries of half2 = 32 dwords = one per LDS bank: two lanes either read the same
-    // entry (broadcast) or different banks, so the plain table is already conflict-free.
-    // Every wavefront keeps a private copy (16 x 128 bytes), filled from 32 scalar
-    // registers while its weight loads are in flight: no wavefront ever waits for another
-    // one before it can start decoding.
+// VQ 5 bit, small layers: 32 entries of half2 = one dword per LDS bank, conflict-free
+// as it is (two lanes either read the same entry or different banks), so every wavefront keeps
+// a private copy (16 x 128 bytes), filled from scalar registers once its weight loads are in
+// flight.  Two vector operations per code instead of one, but no workgroup barrier in front of
+// the decode - which counts when a workgroup only has one unit per wavefront.
+struct QpDecVq5Private {
+    static constexpr bool BYTE_WINDOW = false;
     static constexpr int TAB_BYTES = 16 * 128;
-    // The table's source is fetched (scalar path) only when the copy is written, after the
-    // wavefront's weight loads have been issued: held in 32 scalar registers from the start of
-    // the kernel it gets spilled, and the spill waits for the fetch in front of the first loads.
+    typedef uint32_t Lane;
     struct Pre { const uint16_t *g; };
     static __device__ __forceinline__ void early(uint8_t *, uint16_t *, const uint16_t *) {}
     static __device__ __forceinline__ Pre pre(const uint16_t *g) { return Pre{g}; }
@@ -252,6 +281,7 @@ struct QpDec<QP_VQ, 5> {
 
 template <int K>
 struct QpDecTcq {
+    static constexpr bool BYTE_WINDOW = false;
     static constexpr int TAB_BYTES = 131072;
     static constexpr int PRE = 8;  // 128 KiB / (1024 threads * 16 bytes)
     struct Pre { u32x4_t raw[PRE]; };
@@ -274,6 +304,7 @@ struct QpDecTcq {
         for (int k = 0; k < PRE; ++k) t4[k * 1024 + threadIdx.x] = p.raw[k];
         __syncthreads();
     }
+    typedef uint32_t Lane;
     static __device__ __forceinline__ uint32_t lane_const() { return 0; }
     template <int P>
     static __device__ __forceinline__ half8_t step(const u32x4_t (&q)[P], int s, const uint8_t *tab, uint32_t,
@@ -301,6 +332,7 @@ struct QpTcqhPre { uint32_t raw[(1 << TB) / 1024 ? (1 << TB) / 1024 : 1]; };
 
 template <int K, int TB = QpTraits<QP_TCQH, K>::TLUT_BITS>
 struct QpDecTcqh {
+    static constexpr bool BYTE_WINDOW = false;
     static constexpr int ENTRIES = 2 << TB;
     static constexpr int COPIES = 32768 / ENTRIES;          // 32, 16, 8
     static constexpr int LSH = (COPIES == 32) ? 7 : (COPIES == 16) ? 6 : 5;
@@ -308,6 +340,7 @@ struct QpDecTcqh {
     static constexpr int SMALL_BYTES = 4 << TB;             // staging room for the source
     static constexpr int NSRC = (1 << TB) / 1024 ? (1 << TB) / 1024 : 1;   // source dwords per thread
     typedef QpTcqhPre<TB> Pre;
+    typedef uint32_t Lane;
     static __device__ __forceinline__ uint32_t lane_const() { return (threadIdx.x & (COPIES - 1)) << 2; }
     static __device__ __forceinline__ void early(uint8_t *, uint16_t *, const uint16_t *) {}
     static __device__ __forceinline__ Pre pre(const uint16_t *g) {  // needs blockDim.x == 1024
@@ -401,6 +434,30 @@ template <> struct QpDec<QP_TCQ, 4> : QpDecTcq<4> {};
 template <class D> struct QpTableMovable { static constexpr bool value = false; };
 template <> struct QpTableMovable<QpDec<QP_SQ, 4>> { static constexpr bool value = true; };
 template <> struct QpTableMovable<QpDec<QP_VQ, 7>> { static constexpr bool value = true; };
+template <> struct QpTableMovable<QpDec<QP_VQ, 5>> { static constexpr bool value = true; };
+
+// ALT selects the second form of a kernel where there is one: two wavefronts per unit for the
+// V = 1 and V = 2 trellis, the per-wavefront table for VQ 5 bit.
+template <int S, int CB, bool ALT> struct QpDecSel { typedef QpDec<S, CB> type; };
+template <> struct QpDecSel<QP_VQ, 5, true> { typedef QpDecVq5Private type; };
+constexpr bool qp_alt_splits(int S) { return S == QP_TCQ || S == QP_TCQH; }
+
+// Step SI of a unit with the step index as a compile-time constant (the byte-window decoders
+// pick their instruction forms from it).
+template <class D, int P, int SI>
+__device__ __forceinline__ half8_t qp_step(const u32x4_t (&q)[P], const uint8_t *tab, typename D::Lane &lc,
+                                           const typename D::Pre &pre) {
+    if constexpr (D::BYTE_WINDOW) return D::template step_at<P, SI>(q, tab, lc);
+    else return D::template step<P>(q, SI, tab, lc, pre);
+}
+
+template <int B, int E, class F>
+__device__ __forceinline__ void qp_static_for(F &&f) {
+    if constexpr (B < E) {
+        f(std::integral_constant<int, B>{});
+        qp_static_for<B + 1, E>(f);
+    }
+}
 
 // ------------------------------------------------------------------ DPP fold
 // v + (src shifted towards lane 0 by N lanes inside each row of 16 lanes).
@@ -432,6 +489,14 @@ template <int P, bool OPTIONAL_LAST>
 // native layout, where a piece of all 64 lanes is one contiguous KiB; 1 in the canonical one,
 // where the lane's pieces follow each other in its row).
 __device__ __forceinline__ void qp_pieces_load(const u32x4_t *src, int ps, bool full, u32x4_t (&q)[P]) {
+#ifdef QP_NOLOAD  // development builds only: decode without the weight stream, to time the compute side alone
+    {
+        const uint32_t h = (uint32_t)(uintptr_t)src * 2654435761u;
+#pragma unroll
+        for (int p = 0; p < P; ++p) q[p] = u32x4_t{h + p, h ^ (0x9e3779b9u * (p + 1)), h * (2 * p + 3), ~h + 7 * p};
+        return;
+    }
+#endif
 #pragma unroll
     for (int p = 0; p < P; ++p) {
         if (OPTIONAL_LAST && p == P - 1) {
@@ -475,7 +540,7 @@ __device__ __forceinline__ void qp_half_pieces_load(const u32x4_t *src, int ps, 
 // unit); xf[i] holds fragment S0 / TT + i on entry.
 template <class D, int P, int PF, int TT, int S0 = 0, int S1 = 32>
 __device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8_t (&xf)[PF], const half_t *xu,
-                                                    int xfs, const uint8_t *tab, uint32_t lc,
+                                                    int xfs, const uint8_t *tab, typename D::Lane &lc,
                                                     const typename D::Pre &pre) {
     constexpr int N0 = S0 / TT, N1 = S1 / TT;   // fragments N0 .. N1 - 1
 #ifdef QP_NODECODE  // development builds only: loads without decode, to time the memory side alone
@@ -500,10 +565,10 @@ __device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8
 #pragma unroll
     for (int t = 0; t < NACC; ++t) acc[t] = float4_t{0.f, 0.f, 0.f, 0.f};
     u32x4_t masked[NM];
-#pragma unroll
-    for (int s = S0; s < S1; ++s) {
-        const int n = s / TT, t = s % TT;
-        if (t == 0) {
+    qp_static_for<S0, S1>([&](auto sc) __attribute__((always_inline)) {
+        constexpr int s = decltype(sc)::value;
+        constexpr int n = s / TT, t = s % TT;
+        if constexpr (t == 0) {
             const u32x4_t raw = __builtin_bit_cast(u32x4_t, xf[(n - N0) % PF]);
             if constexpr (NM == 1) {
                 masked[0] = raw;
@@ -515,17 +580,17 @@ __device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8
                     for (int r = 0; r < 4; ++r) masked[m][r] = keep ? raw[r] : 0u;
                 }
             }
-            if (n + PF < N1)  // the raw fragment is spent: refill its slot
+            if constexpr (n + PF < N1)  // the raw fragment is spent: refill its slot
                 xf[(n - N0) % PF] = *reinterpret_cast<const half8_t *>(xu + xfs * (n + PF));
         }
-        half8_t a = D::template step<P>(q, s, tab, lc, pre);
+        half8_t a = qp_step<D, P, s>(q, tab, lc, pre);
         acc[t % NACC] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, __builtin_bit_cast(half8_t, masked[t / NACC]),
                                                                acc[t % NACC], 0, 0, 0);
 #ifdef QP_TRACE
-        if (s == 0) QP_T(3);
-        if (s == 27) QP_T(4);
+        if constexpr (s == 0) QP_T(3);
+        if constexpr (s == 27) QP_T(4);
 #endif
-    }
+    });
     float4_t v = acc[0];
     QpFold<NACC>::run(v, acc);   // lanes with t % NACC == 0 now hold their group's sum
 #pragma unroll
@@ -568,11 +633,10 @@ __device__ __forceinline__ void qp_pass_store(const QpW &w, const float *red, ha
 }
 
 // Shapes of the LDS arrays of the fused kernel.
-template <int S, int CB, int BP>
+template <class D, int S, int CB, int BP>
 struct QpLinLds {
     using T = QpTraits<S, CB>;
-    using D = QpDec<S, CB>;
-    static constexpr int RED_FLOATS = QP_UMAX * 16 * BP;
+    static constexpr int RED_FLOATS = qp_umax(BP) * 16 * BP;
     static constexpr int SMALL_FLOATS = T::HYBRID ? (1 << T::TLUT_BITS) : 0;
     static constexpr int RED = RED_FLOATS > SMALL_FLOATS ? RED_FLOATS : SMALL_FLOATS;
     // in-kernel rotation (batch 1, one Hadamard block of at most 8192): the rotated
@@ -581,18 +645,22 @@ struct QpLinLds {
     static constexpr int ROT_MAX = 8192;
     static constexpr int ROT_SCRATCH_FLOATS = ROT_MAX + ROT_MAX / 32;
     static constexpr bool ROT = (BP == 1);
-    static constexpr bool SCRATCH_IN_TAB = D::TAB_BYTES >= ROT_SCRATCH_FLOATS * 4;
+    // (not a table that may be built before the rotation runs)
+    static constexpr bool SCRATCH_IN_TAB = !QpTableMovable<D>::value && D::TAB_BYTES >= ROT_SCRATCH_FLOATS * 4;
 };
 
 // XL: the activations are rotated here (Section 3.3), by the workgroup itself, into LDS, and
 // the B-operand fragments are read from there; otherwise they come from global memory.
-template <int S, int CB, int BP, bool XL, bool SPLIT>
+template <int S, int CB, int BP, bool XL, bool ALT>
 __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, int B, int64_t ldx, half_t *y,
                                                int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic,
-                                               int x_packed, const int8_t *signs, int rot_block, float rot_norm, uint8_t *tab,
+                                               int x_flags, const int8_t *signs, int rot_block, float rot_norm, uint8_t *tab,
                                                float *red, half_t *xr_lds, float *rot_buf) {
+    const int x_packed = x_flags & 0xff;   // activations in fragment order
+    const int late_max = x_flags >> 8;     // a movable table is built after the first loads up to this many units
     using T = QpTraits<S, CB>;
-    using D = QpDec<S, CB>;
+    using D = typename QpDecSel<S, CB, ALT>::type;
+    constexpr bool SPLIT = ALT && qp_alt_splits(S);
     // Half-TCQ: the units of the second half of the column blocks have P pieces and decode
     // with D, those of the first half have P - 1 and decode with D::Lo; both kinds share the
     // piece array, the table and everything else.
@@ -618,7 +686,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     // table's source is requested first so that it can be waited for alone.
     // (a table that can be built at either point: late when the workgroup has few units)
     constexpr bool MOVABLE = QpTableMovable<D>::value;
-    const bool table_late = MOVABLE && (rb_q + (rb_r ? 1 : 0)) * w.nbc <= 8;
+    const bool table_late = MOVABLE && (rb_q + (rb_r ? 1 : 0)) * w.nbc <= late_max;
     if (!MOVABLE || !table_late) D::early(tab, reinterpret_cast<uint16_t *>(red), w.lut);
     const typename D::Pre pre = D::pre(w.lut);
 
@@ -715,7 +783,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
         const int i = o & 15, slot = o >> (4 + LB);
         scale_first = w.scales[(slot < gcount) ? (rb_begin + slot) * 16 + i : 0];
     }
-    const uint32_t lc = D::lane_const();
+    typename D::Lane lc = D::lane_const();
     QP_T(7);
     if constexpr (XL) {
         // The weight loads of the first unit are in flight; meanwhile the first 64 W threads
@@ -802,55 +870,79 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
 }
 
 
-template <int S, int CB, int BP, bool SPLIT>
+// XL (batch 1 only): the workgroup rotates the activations itself; a kernel of its own, so that the
+// plain kernel does not carry the transform's LDS arrays and more workgroups fit a compute unit.
+template <int S, int CB, int BP, bool SPLIT, bool XL>
 __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, int B, int64_t ldx, half_t *y,
                                                       int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic,
                                                       int x_packed, const int8_t *signs, int rot_block, float rot_norm) {
-    using L = QpLinLds<S, CB, BP>;
-    using D = QpDec<S, CB>;
+    using D = typename QpDecSel<S, CB, SPLIT>::type;
+    using L = QpLinLds<D, S, CB, BP>;
+    static_assert(!XL || L::ROT, "in-kernel rotation: batch 1");
     __shared__ __attribute__((aligned(16))) uint8_t tab[D::TAB_BYTES];
     // [unit][b][row]; before the first pass the same room stages a table's source
     __shared__ __attribute__((aligned(16))) float red[L::RED];
-    if constexpr (L::ROT) {
+    if constexpr (XL) {
         __shared__ __attribute__((aligned(16))) half_t xr_lds[L::ROT_MAX];
         __shared__ __attribute__((aligned(16))) float rot_own[L::SCRATCH_IN_TAB ? 1 : L::ROT_SCRATCH_FLOATS];
         float *rot_buf = L::SCRATCH_IN_TAB ? reinterpret_cast<float *>(tab) : rot_own;
-        if (rot_block > 0) {
-            qp_linear_body<S, CB, BP, true, SPLIT>(w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
-                                            rot_block, rot_norm, tab, red, xr_lds, rot_buf);
-            return;
-        }
+        qp_linear_body<S, CB, BP, true, SPLIT>(w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
+                                               rot_block, rot_norm, tab, red, xr_lds, rot_buf);
+    } else {
+        qp_linear_body<S, CB, BP, false, SPLIT>(w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
+                                                rot_block, rot_norm, tab, red, nullptr, nullptr);
     }
-    qp_linear_body<S, CB, BP, false, SPLIT>(w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs, rot_block,
-                                     rot_norm, tab, red, nullptr, nullptr);
 }
 
 // Half units exist for the trellis schemes at batch <= 2 (the kernels that are bound by their
 // own decode work when a workgroup has few units).
-template <int S, int CB, int BP>
-static void qp_launch_one(bool split, int grid, int nw, hipStream_t st, const QpW &w, const void *x, int B,
-                          int64_t ldx, void *y, int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic, int x_packed,
-                          const int8_t *signs, int rot_block, float rot_norm) {
-    constexpr bool CAN_SPLIT = (S == QP_TCQ || S == QP_TCQH) && BP <= 2;
-    if constexpr (CAN_SPLIT) {
-        if (split) {
-            hipLaunchKernelGGL((k_linear_mfma<S, CB, BP, true>), dim3(grid), dim3(64 * nw), 0, st, w,
+template <int S, int CB, int BP, bool SPLIT>
+static void qp_launch_xl(int grid, int nw, hipStream_t st, const QpW &w, const void *x, int B, int64_t ldx, void *y,
+                         int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic, int x_packed, const int8_t *signs,
+                         int rot_block, float rot_norm) {
+    if constexpr (BP == 1) {
+        if (rot_block > 0) {
+            hipLaunchKernelGGL((k_linear_mfma<S, CB, BP, SPLIT, true>), dim3(grid), dim3(64 * nw), 0, st, w,
                                (const half_t *)x, B, ldx, (half_t *)y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
                                rot_block, rot_norm);
             return;
         }
     }
-    hipLaunchKernelGGL((k_linear_mfma<S, CB, BP, false>), dim3(grid), dim3(64 * nw), 0, st, w, (const half_t *)x, B,
-                       ldx, (half_t *)y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs, rot_block, rot_norm);
+    hipLaunchKernelGGL((k_linear_mfma<S, CB, BP, SPLIT, false>), dim3(grid), dim3(64 * nw), 0, st, w,
+                       (const half_t *)x, B, ldx, (half_t *)y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
+                       rot_block, rot_norm);
+}
+
+template <int S, int CB, int BP>
+static void qp_launch_one(bool split, int grid, int nw, hipStream_t st, const QpW &w, const void *x, int B,
+                          int64_t ldx, void *y, int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic, int x_packed,
+                          const int8_t *signs, int rot_block, float rot_norm) {
+    constexpr bool CAN_SPLIT = (qp_alt_splits(S) && BP <= 2) || (S == QP_VQ && CB == 5);
+    if constexpr (CAN_SPLIT) {
+        if (split) {
+            qp_launch_xl<S, CB, BP, true>(grid, nw, st, w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed,
+                                          signs, rot_block, rot_norm);
+            return;
+        }
+    }
+    qp_launch_xl<S, CB, BP, false>(grid, nw, st, w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
+                                   rot_block, rot_norm);
 }
 
 qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x, int B, int64_t ldx, void *y,
                                 int64_t ldy, int x_packed, const int8_t *signs, int rot_block, hipStream_t st) {
     const int nbc = w.nbc, rbk = w.M / 16;
-    if (nbc < 1 || nbc > QP_UMAX) return QP_ERR_UNSUPPORTED;
-    int grid = rbk < 256 ? rbk : 256;
+    if (nbc < 1 || nbc > QP_NBC_MAX) return QP_ERR_UNSUPPORTED;
+    const int umax = qp_umax(B <= 1 ? 1 : B <= 2 ? 2 : B <= 4 ? 4 : B <= 8 ? 8 : 16);
+    // Development hooks: workgroups per compute unit and wavefronts per workgroup.
+    int wg_per_cu = 1, nw_forced = 0;
+    if (const char *e = getenv("QP_LINEAR_WG_PER_CU")) wg_per_cu = atoi(e) > 0 ? atoi(e) : 1;
+    if (const char *e = getenv("QP_LINEAR_NW")) nw_forced = atoi(e);
+    const bool big_table = (scheme == QP_TCQ || scheme == QP_TCQH || scheme == QP_TCQHH);
+    if (big_table) { wg_per_cu = 1; nw_forced = 0; }
+    int grid = rbk < 256 * wg_per_cu ? rbk : 256 * wg_per_cu;
     int rb_per_wg = (rbk + grid - 1) / grid;
-    int G = QP_UMAX / nbc;
+    int G = umax / nbc;
     if (G > rb_per_wg) G = rb_per_wg;
     int units = G * nbc;
     int rb_q = rbk / grid, rb_r = rbk % grid;
@@ -867,8 +959,11 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
         if (e && e[0] == '0') split = false;
         if (e && e[0] == '1') split = can_split;
     }
+    // VQ 5 bit: the per-wavefront table while a workgroup has at most one unit per wavefront
+    if (scheme == QP_VQ && cb == 5 && rb_per_wg * nbc <= 16) split = true;
     int nw = units < 16 ? units : 16;
     if (scheme == QP_TCQ || scheme == QP_TCQH || scheme == QP_TCQHH) nw = 16;  // the table staging is written for 1024 threads
+    if (nw_forced >= 4 && nw_forced <= 16 && nw_forced < nw) nw = nw_forced;
     if (nw < 4) nw = 4;
     const float rot_norm = rot_block > 0 ? 1.0f / sqrtf((float)rot_block) : 0.f;
     if (rot_block > 0) {
@@ -876,8 +971,14 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
         if (B != 1 || rot_block != w.N || rot_block > 8192 || rot_block < 1024) return QP_ERR_UNSUPPORTED;
         if (nw < 8) nw = 8;
     }
+    // A table that the whole workgroup shares is built after the first loads have been issued when
+    // the workgroup has few units, and at batch >= 4 with row-major activations (whose many
+    // small loads then start earlier); before them otherwise.
+    int late_max = (!x_packed && B >= 4) ? 1024 : 8;
+    if (const char *e = getenv("QP_TABLE_LATE_MAX")) late_max = atoi(e);
+    const int x_flags = (x_packed ? 1 : 0) | (late_max << 8);
 #define CALL_BP(S, C, BP) \
-    qp_launch_one<S, C, BP>(split, grid, nw, st, w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs, \
+    qp_launch_one<S, C, BP>(split, grid, nw, st, w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_flags, signs, \
                             rot_block, rot_norm)
 #define CALL(S, C)                                   \
     do {                                             \
@@ -920,7 +1021,7 @@ __global__ __launch_bounds__(1024) void k_dequant_blocks(QpW w, uint16_t *out, i
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int nbc = w.nbc, hcb = nbc >> 1;
     const u32x4_t *codes16 = reinterpret_cast<const u32x4_t *>(w.codes);
-    const uint32_t lc = D::lane_const();
+    typename D::Lane lc = D::lane_const();
     const int nwd = (int)(blockDim.x >> 6) < NWD ? (int)(blockDim.x >> 6) : NWD;
     const int stride = gridDim.x * nwd;
     int t = (wave < nwd) ? blockIdx.x * nwd + wave : nblocks;   // a wavefront that does not decode has no block
@@ -953,19 +1054,19 @@ __global__ __launch_bounds__(1024) void k_dequant_blocks(QpW w, uint16_t *out, i
         // lane stores: row rd_slot0 of the block, column group k, chunk rd_c of every four steps
         uint16_t *dst = out + (int64_t)(R * 16 + rd_slot0) * w.N + C * 1024 + rd_c * 8;
         const bool hi = full;
-#pragma unroll
-        for (int s4 = 0; s4 < 8; ++s4) {
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
+        qp_static_for<0, 8>([&](auto s4c) __attribute__((always_inline)) {
+            constexpr int s4 = decltype(s4c)::value;
+            qp_static_for<0, 4>([&](auto cc) __attribute__((always_inline)) {
+                constexpr int c = decltype(cc)::value;
                 half8_t a;
                 if constexpr (HH) {
-                    if (hi) a = D::template step<P>(q, 4 * s4 + c, tab, lc, pre);
-                    else a = D::Lo::template step<P>(q, 4 * s4 + c, tab, lc, pre);
+                    if (hi) a = qp_step<D, P, 4 * s4 + c>(q, tab, lc, pre);
+                    else a = qp_step<typename D::Lo, P, 4 * s4 + c>(q, tab, lc, pre);
                 } else {
-                    a = D::template step<P>(q, 4 * s4 + c, tab, lc, pre);
+                    a = qp_step<D, P, 4 * s4 + c>(q, tab, lc, pre);
                 }
                 tl[wr + ((c + (lane >> 1)) & 3)] = __builtin_bit_cast(u32x4_t, a);
-            }
+            });
             __builtin_amdgcn_wave_barrier();   // LDS operations of a wavefront complete in order
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -974,7 +1075,7 @@ __global__ __launch_bounds__(1024) void k_dequant_blocks(QpW w, uint16_t *out, i
                 *reinterpret_cast<u32x4_t *>(dst + k * 256 + s4 * 32) = v;
             }
             __builtin_amdgcn_wave_barrier();
-        }
+        });
         t += stride;
         if (t < nblocks) issue(t);
     }
