@@ -334,9 +334,14 @@ template <int K, int TB = QpTraits<QP_TCQH, K>::TLUT_BITS>
 struct QpDecTcqh {
     static constexpr bool BYTE_WINDOW = false;
     static constexpr int ENTRIES = 2 << TB;
+#ifdef QP_TCQH_TABLE_128K
     static constexpr int COPIES = 32768 / ENTRIES;          // 32, 16, 8
-    static constexpr int LSH = (COPIES == 32) ? 7 : (COPIES == 16) ? 6 : 5;
     static constexpr int TAB_BYTES = 131072;
+#else
+    static constexpr int COPIES = 16384 / ENTRIES;          // 16, 8, 4
+    static constexpr int TAB_BYTES = 65536;
+#endif
+    static constexpr int LSH = (COPIES == 32) ? 7 : (COPIES == 16) ? 6 : (COPIES == 8) ? 5 : 4;
     static constexpr int SMALL_BYTES = 4 << TB;             // staging room for the source
     static constexpr int NSRC = (1 << TB) / 1024 ? (1 << TB) / 1024 : 1;   // source dwords per thread
     typedef QpTcqhPre<TB> Pre;
@@ -365,8 +370,8 @@ struct QpDecTcqh {
         // each, in an order rotated by the lane so that eight neighbouring lanes always cover
         // all 32 banks (a few dozen instructions per thread instead of one per dword).
         u32x4_t *t4 = reinterpret_cast<u32x4_t *>(tab);
-        constexpr int NP = COPIES / 4;                          // pieces per entry: 8, 4, 2
-        const int rot = (int)(threadIdx.x & 63) >> ((COPIES == 32) ? 0 : (COPIES == 16) ? 1 : 2);
+        constexpr int NP = COPIES / 4;                          // pieces per entry
+        const int rot = (int)(threadIdx.x & 63) >> ((NP == 8) ? 0 : (NP == 4) ? 1 : 2);
 #pragma unroll
         for (int m = 0; m < ENTRIES / 1024; ++m) {
             const int e = m * 1024 + (int)threadIdx.x;
@@ -386,11 +391,22 @@ struct QpDecTcqh {
             // 32 stream bits from the state's first bit on (the stream is K pieces long).  Bits
             // above the 16 of the state are left in: bits 6..15 of x (x + 1), all that is used,
             // depend on the low 16 bits of x only.
-            const uint32_t st = qp_bits32<P, true, K>(q, (4 * s + c) * K);
-            uint32_t h, idx, a;
+            const int bitpos = (4 * s + c) * K, rr = bitpos & 31;
+            uint32_t st, h, a;
+            // a window that lies inside one dword only needs a plain shift (half the issue cost
+            // of the funnel shift)
+            if (rr != 0 && rr <= 16) st = qp_dw<P>(q, bitpos >> 5) >> rr;
+            else st = qp_bits32<P, true, K>(q, bitpos);
             asm("v_mad_u32_u24 %0, %1, %1, %1" : "=v"(h) : "v"(st));   // x (x + 1) modulo 2^32 (24-bit operands)
+#ifdef QP_TCQH_TABLE_128K
+            uint32_t idx;
             asm("v_bfe_u32 %0, %1, %2, %3" : "=v"(idx) : "v"(h), "n"(15 - TB), "n"(TB + 1));
             asm("v_lshl_or_b32 %0, %1, %2, %3" : "=v"(a) : "v"(idx), "n"(LSH), "v"(lc));
+#else
+            // the index field of h already sits where the row number of the address does
+            static_assert(LSH == 15 - TB, "row stride = 2^(15 - TB) bytes");
+            asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(a) : "v"(h), "s"((ENTRIES - 1) << LSH), "v"(lc));
+#endif
             r[c] = *reinterpret_cast<const uint32_t *>(tab + a);
         }
         return __builtin_bit_cast(half8_t, u32x4_t{r[0], r[1], r[2], r[3]});
@@ -565,6 +581,12 @@ __device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8
 #pragma unroll
     for (int t = 0; t < NACC; ++t) acc[t] = float4_t{0.f, 0.f, 0.f, 0.f};
     u32x4_t masked[NM];
+    uint32_t keep[NM];
+#pragma unroll
+    for (int m = 0; m < NM; ++m) {
+        keep[m] = (lane_t / NACC) == m ? 0xffffffffu : 0u;
+        asm volatile("" : "+v"(keep[m]));   // stays a register: the compiler would turn the AND back into a select
+    }
     qp_static_for<S0, S1>([&](auto sc) __attribute__((always_inline)) {
         constexpr int s = decltype(sc)::value;
         constexpr int n = s / TT, t = s % TT;
@@ -575,9 +597,8 @@ __device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8
             } else {
 #pragma unroll
                 for (int m = 0; m < NM; ++m) {
-                    const bool keep = (lane_t / NACC) == m;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) masked[m][r] = keep ? raw[r] : 0u;
+                    for (int r = 0; r < 4; ++r) masked[m][r] = raw[r] & keep[m];   // (an AND issues in 2.3 clocks, a select in 3.8)
                 }
             }
             if constexpr (n + PF < N1)  // the raw fragment is spent: refill its slot
@@ -1093,7 +1114,7 @@ qp_status qp_launch_dequant_blocks(const QpW &w, int scheme, int cb, void *out, 
         if (nw < 4) nw = 4;   // the per-scheme table set-up assumes at least four wavefronts
         if (nw > 16) nw = 16;
     }
-    const int nwd = big_table ? 8 : nw;
+    const int nwd = (scheme == QP_TCQ) ? 8 : nw;   // decoding wavefronts: see NWD in the kernel
     int grid = (nblocks + nwd - 1) / nwd;
     if (grid > 256) grid = 256;
 #define CALL(S, C) \
