@@ -68,7 +68,7 @@ extern "C" void qp_debug_set_trace(void *p) { (void)hipMemcpyToSymbol(HIP_SYMBOL
 #define QP_T(slot)                                                                                   \
     do {                                                                                             \
         if ((threadIdx.x & 63) == 0)                                                                 \
-            qp_trace_buf[((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 8 + (slot)] = __builtin_amdgcn_s_memtime(); \
+            qp_trace_buf[((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 16 + (slot)] = __builtin_amdgcn_s_memtime(); \
     } while (0)
 #else
 #define QP_T(slot)
@@ -500,6 +500,10 @@ struct QpFold {  // acc[0] + shl1(acc[1]) + ... : lane b*TT of every row ends up
 // later can name exactly the loads they need.
 // The P pieces of one unit.  Half-TCQ units of the first half have one piece less: `full`
 // (wave-uniform) says whether the last one exists.
+// One 16-byte piece of the weight stream: read once, never reused, hence non-temporal (measured
+// 5 - 8 % faster than plain loads on large layers; the sc0 policy on top changes nothing).
+__device__ __forceinline__ u32x4_t qp_stream_load(const u32x4_t *p) { return __builtin_nontemporal_load(p); }
+
 template <int P, bool OPTIONAL_LAST>
 // src: the lane's first piece; ps: distance between its pieces in 16-byte units (64 in the
 // native layout, where a piece of all 64 lanes is one contiguous KiB; 1 in the canonical one,
@@ -517,9 +521,9 @@ __device__ __forceinline__ void qp_pieces_load(const u32x4_t *src, int ps, bool 
     for (int p = 0; p < P; ++p) {
         if (OPTIONAL_LAST && p == P - 1) {
             q[p] = u32x4_t{0u, 0u, 0u, 0u};
-            if (full) q[p] = __builtin_nontemporal_load(src + p * ps);
+            if (full) q[p] = qp_stream_load(src + p * ps);
         } else {
-            q[p] = __builtin_nontemporal_load(src + p * ps);
+            q[p] = qp_stream_load(src + p * ps);
         }
     }
 }
@@ -545,7 +549,7 @@ __device__ __forceinline__ void qp_half_pieces_load(const u32x4_t *src, int ps, 
 #pragma unroll
     for (int p = 0; p < P; ++p) {
         const bool need = (128 * p < END && 128 * p + 128 > START) || (END > TOTAL && 128 * p < END - TOTAL);
-        if (need) q[p] = __builtin_nontemporal_load(src + p * ps);
+        if (need) q[p] = qp_stream_load(src + p * ps);
         else q[p] = u32x4_t{0u, 0u, 0u, 0u};
     }
 }
@@ -709,6 +713,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     constexpr bool MOVABLE = QpTableMovable<D>::value;
     const bool table_late = MOVABLE && (rb_q + (rb_r ? 1 : 0)) * w.nbc <= late_max;
     if (!MOVABLE || !table_late) D::early(tab, reinterpret_cast<uint16_t *>(red), w.lut);
+    QP_T(13);
     const typename D::Pre pre = D::pre(w.lut);
 
     const int nw = blockDim.x >> 6;
@@ -788,6 +793,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     };
     u32x4_t q[P];
     bool full;
+    QP_T(14);
     {
         const u32x4_t *blk = unit_block(rb_begin, uu, uu - ((uu * nbc_magic) >> 16) * nbc, full);
         if constexpr (SPLIT) {
@@ -839,6 +845,9 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     QP_T(2);
     int rb0 = rb_begin;
     u += nw;
+#ifdef QP_TRACE
+    uint64_t tr_wait = 0, tr_dec = 0, tr_units = 0;
+#endif
     while (true) {
         // ---- remaining units of this pass ----------------------------------------------
         for (; u < units; u += nw) {
@@ -866,6 +875,12 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
                 continue;
             }
             qp_unit_load<P, PF, HH>(blk2, ps, xu2, xfs, full2, q2, xf2);
+            QP_T(8);
+#ifdef QP_TRACE
+            const uint64_t tr_a = __builtin_amdgcn_s_memtime();
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            const uint64_t tr_b = __builtin_amdgcn_s_memtime();
+#endif
             if constexpr (HH) {
                 if (full2) v = qp_unit_compute<D, P, PF, TT>(q2, xf2, xu2, xfs, tab, lc, pre);
                 else v = qp_unit_compute<typename D::Lo, P, PF, TT>(q2, xf2, xu2, xfs, tab, lc, pre);
@@ -873,6 +888,12 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
                 v = qp_unit_compute<D, P, PF, TT>(q2, xf2, xu2, xfs, tab, lc, pre);
             }
             if (owner) *reinterpret_cast<float4_t *>(&red[(u * BP + bj) * 16 + 4 * g]) = v;
+            QP_T(9);
+#ifdef QP_TRACE
+            tr_wait += tr_b - tr_a;
+            tr_dec += __builtin_amdgcn_s_memtime() - tr_b;
+            tr_units += 1;
+#endif
         }
         qp_pass_store<BP>(w, red, y, ldy, B, rb0, gcount, nbc * SPL, scale_first);
         // ---- next pass ------------------------------------------------------------------
@@ -888,6 +909,12 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
         }
     }
     QP_T(6);
+#ifdef QP_TRACE
+    if ((threadIdx.x & 63) == 0) {
+        uint64_t *tb = &qp_trace_buf[((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 16];
+        tb[10] = tr_wait; tb[11] = tr_dec; tb[12] = tr_units;
+    }
+#endif
 }
 
 
