@@ -18,6 +18,8 @@ _u8p = np.ctypeslib.ndpointer(dtype=np.uint8, flags="C_CONTIGUOUS")
 _u16p = np.ctypeslib.ndpointer(dtype=np.uint16, flags="C_CONTIGUOUS")
 _i8p = np.ctypeslib.ndpointer(dtype=np.int8, flags="C_CONTIGUOUS")
 _f64p = np.ctypeslib.ndpointer(dtype=np.float64, flags="C_CONTIGUOUS")
+_i32p = np.ctypeslib.ndpointer(dtype=np.int32, flags="C_CONTIGUOUS")
+_i64p = np.ctypeslib.ndpointer(dtype=np.int64, flags="C_CONTIGUOUS")
 
 
 def lib():
@@ -50,6 +52,13 @@ def lib():
                                       C.c_int, C.c_int, _u16p, _u16p, _f64p, C.c_int, C.c_int,
                                       C.c_int, _f64p, C.c_int]
         L.qpo_hybrid_lut.argtypes = [_u16p, C.c_int, _u16p]
+        L.qpo_kmeans_assign.restype = C.c_double
+        L.qpo_kmeans_assign.argtypes = [_f64p, C.c_int64, C.c_int, _f64p, C.c_int, _i32p]
+        L.qpo_kmeans_update.restype = C.c_double
+        L.qpo_kmeans_update.argtypes = [_f64p, C.c_int64, C.c_int, _i32p, _f64p, C.c_int, _f64p, _i64p]
+        L.qpo_kmeans.restype = C.c_int
+        L.qpo_kmeans.argtypes = [_f64p, C.c_int64, C.c_int, _f64p, C.c_int, C.c_int, C.c_double,
+                                 C.POINTER(C.c_double)]
         L.qpo_num_threads.restype = C.c_int
         L.qpo_rtn_sq.argtypes = [_f64p, C.c_int64, C.c_int, _u16p, _u8p]
         L.qpo_rtn_vq.argtypes = [_f64p, C.c_int64, C.c_int, C.c_int, _u16p, _u8p]
@@ -211,3 +220,37 @@ def tcq_tile_error(v, stream, s, L, T, V, lut16) -> float:
     v = np.ascontiguousarray(v, dtype=np.float64).reshape(-1)
     st = np.ascontiguousarray(stream, dtype=np.uint8)
     return lib().qpo_tcq_tile_error(v, st, s, L, T, V, _u16(lut16).reshape(-1))
+
+
+def _samples(x) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    return x.reshape(-1, 1) if x.ndim == 1 else x
+
+
+def kmeans_assign(x, centres):
+    """(assignment int32 [n], inertia) of one assignment step (ties: the lowest index)."""
+    x = _samples(x)
+    m = np.ascontiguousarray(_samples(centres))
+    a = np.empty(x.shape[0], dtype=np.int32)
+    inertia = lib().qpo_kmeans_assign(x, x.shape[0], x.shape[1], m, m.shape[0], a)
+    return a, float(inertia)
+
+
+def kmeans_update(x, assign, centres):
+    """(new centres, counts, total squared movement) of one update step."""
+    x = _samples(x)
+    m = np.ascontiguousarray(_samples(centres))
+    out = np.empty_like(m)
+    count = np.empty(m.shape[0], dtype=np.int64)
+    moved = lib().qpo_kmeans_update(x, x.shape[0], x.shape[1], np.ascontiguousarray(assign, dtype=np.int32), m,
+                                    m.shape[0], out, count)
+    return out, count, float(moved)
+
+
+def kmeans(x, init, max_iter: int = 300, tol: float = 1e-6):
+    """Lloyd's algorithm from `init`: (centres, updates made, inertia of the last assignment)."""
+    x = _samples(x)
+    m = np.array(_samples(init), dtype=np.float64, order="C", copy=True)
+    inertia = C.c_double(0.0)
+    it = lib().qpo_kmeans(x, x.shape[0], x.shape[1], m, m.shape[0], int(max_iter), float(tol), C.byref(inertia))
+    return m, int(it), float(inertia.value)

@@ -5,7 +5,7 @@ import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SOURCES = ["qpo.c", "qpo_encode.c"]
+SOURCES = ["qpo.c", "qpo_encode.c", "qpo_kmeans.c"]
 LIB = os.path.join(HERE, "libqpo.so")
 
 
