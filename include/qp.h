@@ -192,6 +192,25 @@ size_t qp_encode_workspace_bytes(const qp_weight *w);
  * W 16-byte aligned, N % 8 == 0, ldw % 8 == 0, ldw >= N. */
 qp_status qp_row_normalize(void *W, int64_t ldw, int32_t M, int32_t N, void *scales, void *hip_stream);
 
+/* Code book construction by Lloyd's algorithm (App. C.1 / C.2 / C.3.1 "Codebook construction":
+ * k-means of standard Gaussian samples; k = 2^b scalar levels, k = 2^(2b) 2-D points, or the
+ * 2^tlut_bits pairs of the trellis quantizer's small table).  samples: device fp32 [n, d], d = 1
+ * or 2, 4 d -byte aligned; centres: device fp32 [k, d], on entry the start (the caller's choice:
+ * the paper does not fix it), on return the result; 1 <= k <= 4096.  Each iteration assigns every
+ * sample to its nearest centre (fp32 distances, d = fma(dy, dy, dx dx); ties go to the lower index)
+ * and moves every centre to the mean of its samples (fp32 partial sums per workgroup, added in a
+ * fixed order in fp64; a centre without samples stays); the run ends with the update whose total
+ * squared movement is <= tol, at the latest after max_iter (>= 1) updates.  All iterations are
+ * enqueued at once; no host synchronisation.  Optional outputs (device, may be NULL): assign_out
+ * int32 [n], the cluster of every sample at the last assignment step; centres_f16 fp16 [k, d],
+ * the centres rounded to nearest even (the table format of qp_weight.lut); stats_out double [3]:
+ * inertia of the last assignment step (sum of squared distances), updates made, movement of the
+ * last update.  workspace: device, 16-byte aligned, qp_kmeans_workspace_bytes(k, d) bytes. */
+qp_status qp_kmeans(const void *samples, int64_t n, int32_t d, void *centres, int32_t k, int32_t max_iter,
+                    float tol, void *workspace, size_t workspace_bytes, int32_t *assign_out, void *centres_f16,
+                    double *stats_out, void *hip_stream);
+size_t qp_kmeans_workspace_bytes(int32_t k, int32_t d);   /* 0 for unsupported k, d */
+
 /* Bytes of the native code buffer for this layer, 0 if it has no native form. */
 size_t qp_native_bytes(const qp_weight *canonical);
 

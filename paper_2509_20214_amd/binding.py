@@ -14,7 +14,7 @@ QP_OK = 0
 EXPORTS = ["qp_linear", "qp_dequant", "qp_hadamard", "qp_repack", "qp_native_bytes",
            "qp_linear_workspace_bytes", "qp_validate", "qp_status_string", "qp_version",
            "qp_rotate_linear", "qp_rotate_linear_workspace_bytes", "qp_encode", "qp_encode_workspace_bytes",
-           "qp_row_normalize", "qp_msq_solve"]
+           "qp_row_normalize", "qp_msq_solve", "qp_kmeans", "qp_kmeans_workspace_bytes"]
 
 
 class qp_weight(C.Structure):
@@ -68,6 +68,10 @@ def load_library(build_if_missing: bool = True):
                                i32, C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_double)]
     L.qp_encode_workspace_bytes.restype = sz
     L.qp_encode_workspace_bytes.argtypes = [wp]
+    L.qp_kmeans.restype = C.c_int
+    L.qp_kmeans.argtypes = [vp, i64, i32, vp, i32, i32, C.c_float, vp, sz, vp, vp, vp, vp]
+    L.qp_kmeans_workspace_bytes.restype = sz
+    L.qp_kmeans_workspace_bytes.argtypes = [i32, i32]
     L.qp_hadamard.restype = C.c_int
     L.qp_hadamard.argtypes = [vp, vp, i32, i32, i32, i64, vp, i64, vp]
     L.qp_repack.restype = C.c_int
@@ -206,6 +210,36 @@ def qp_row_normalize(W, scales=None, stream=None):
     _check(load_library().qp_row_normalize(W.data_ptr(), W.stride(0), M, N, scales.data_ptr(), _stream_ptr(stream)),
            "qp_row_normalize")
     return scales
+
+
+def qp_kmeans_workspace_bytes(k: int, d: int) -> int:
+    return int(load_library().qp_kmeans_workspace_bytes(k, d))
+
+
+def qp_kmeans(samples, centres, max_iter: int = 300, tol: float = 1e-6, assign=None, centres_f16=None,
+              stats=None, workspace=None, stream=None):
+    """Lloyd's algorithm on the device.  samples: fp32 [n] or [n, d]; centres: fp32 [k] or [k, d], start
+    on entry, result on return (in place).  Optional device outputs: assign int32 [n], centres_f16
+    fp16 like centres, stats float64 [3] (inertia of the last assignment, updates made, last
+    movement).  Returns centres; nothing is synchronised."""
+    import torch
+    n = samples.shape[0]
+    d = 1 if samples.dim() == 1 else samples.shape[1]
+    k = centres.shape[0]
+    if not (samples.is_contiguous() and centres.is_contiguous()):
+        raise ValueError("samples and centres must be contiguous")
+    if samples.dtype != torch.float32 or centres.dtype != torch.float32:
+        raise ValueError("samples and centres must be float32")
+    nbytes = qp_kmeans_workspace_bytes(k, d)
+    if workspace is None:
+        workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=samples.device)
+    _check(load_library().qp_kmeans(samples.data_ptr(), n, d, centres.data_ptr(), k, int(max_iter), float(tol),
+                                    workspace.data_ptr(), workspace.numel(),
+                                    assign.data_ptr() if assign is not None else None,
+                                    centres_f16.data_ptr() if centres_f16 is not None else None,
+                                    stats.data_ptr() if stats is not None else None, _stream_ptr(stream)),
+           "qp_kmeans")
+    return centres
 
 
 def qp_msq_solve(classes, budget: float, resolution: int = 20000):

@@ -281,6 +281,28 @@ extern "C" qp_status qp_row_normalize(void *W, int64_t ldw, int32_t M, int32_t N
     return qp_launch_row_normalize(W, ldw, M, N, scales, static_cast<hipStream_t>(hip_stream));
 }
 
+extern "C" size_t qp_kmeans_workspace_bytes(int32_t k, int32_t d) {
+    if (k < 1 || k > 4096 || (d != 1 && d != 2)) return 0;
+    return qp_kmeans_workspace(k, d);
+}
+
+extern "C" qp_status qp_kmeans(const void *samples, int64_t n, int32_t d, void *centres, int32_t k, int32_t max_iter,
+                               float tol, void *workspace, size_t workspace_bytes, int32_t *assign_out,
+                               void *centres_f16, double *stats_out, void *hip_stream) {
+    if (!samples || !centres || !workspace) return QP_ERR_NULL;
+    if (d != 1 && d != 2) return QP_ERR_UNSUPPORTED;
+    if (k < 1 || k > 4096) return QP_ERR_UNSUPPORTED;
+    if (n < 1 || max_iter < 1 || !(tol >= 0.0f)) return QP_ERR_SHAPE;
+    if (!aligned(samples, 4 * d) || !aligned(centres, 4 * d) || !aligned(workspace, 16) ||
+        (assign_out && !aligned(assign_out, 4)) || (centres_f16 && !aligned(centres_f16, 2 * d)) ||
+        (stats_out && !aligned(stats_out, 8)))
+        return QP_ERR_ALIGN;
+    if (workspace_bytes < qp_kmeans_workspace(k, d)) return QP_ERR_WORKSPACE;
+    return qp_launch_kmeans(static_cast<const float *>(samples), n, d, static_cast<float *>(centres), k, max_iter, tol,
+                            workspace, assign_out, static_cast<uint16_t *>(centres_f16), stats_out,
+                            static_cast<hipStream_t>(hip_stream));
+}
+
 extern "C" const char *qp_status_string(qp_status s) {
     switch (s) {
         case QP_OK: return "ok";

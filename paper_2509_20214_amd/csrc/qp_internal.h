@@ -26,6 +26,12 @@ qp_status qp_launch_repack(const QpW &src, int span_bytes, void *dst, hipStream_
 // half-TCQ: spans of 16 cb bytes in the first N/2 columns, 16 (cb + 1) in the rest
 qp_status qp_launch_repack_half(const QpW &src, int cb, void *dst, hipStream_t st);
 
+// Lloyd's algorithm (code book construction); workspace of qp_kmeans_workspace(k, d) bytes
+size_t qp_kmeans_workspace(int k, int d);
+qp_status qp_launch_kmeans(const float *x, int64_t n, int d, float *centres, int k, int max_iter, float tol,
+                           void *workspace, int32_t *assign_out, uint16_t *centres_f16, double *stats_out,
+                           hipStream_t st);
+
 static inline qp_status qp_check_launch() {
     return hipGetLastError() == hipSuccess ? QP_OK : QP_ERR_DEVICE;
 }

@@ -188,3 +188,18 @@ def test_row_normalize_argument_errors_do_not_launch():
     assert L.qp_row_normalize(0x4000, 1024, 4, 1020, 0x5000, None) == 2
     assert L.qp_row_normalize(0x4000, 512, 4, 1024, 0x5000, None) == 2
     assert L.qp_row_normalize(0x4004, 1024, 4, 1024, 0x5000, None) == 4
+
+
+def test_kmeans_rejects_bad_arguments_on_the_host():
+    L = qp.load_library()
+    ws = qp.qp_kmeans_workspace_bytes(16, 2)
+    assert ws > 0 and qp.qp_kmeans_workspace_bytes(0, 2) == 0 and qp.qp_kmeans_workspace_bytes(16, 3) == 0
+    assert qp.qp_kmeans_workspace_bytes(4097, 1) == 0
+    call = lambda **kw: L.qp_kmeans(*[kw.get(k, v) for k, v in dict(
+        samples=0x1000, n=100, d=2, centres=0x2000, k=16, max_iter=10, tol=1e-6, workspace=0x3000, workspace_bytes=ws,
+        assign=None, c16=None, stats=None, stream=None).items()])
+    assert call(samples=None) == 1 and call(centres=None) == 1 and call(workspace=None) == 1
+    assert call(d=3) == 3 and call(k=0) == 3 and call(k=5000) == 3
+    assert call(n=0) == 2 and call(max_iter=0) == 2 and call(tol=-1.0) == 2
+    assert call(samples=0x1004) == 4 and call(workspace=0x3008) == 4 and call(stats=0x4004) == 4
+    assert call(workspace_bytes=ws - 1) == 7

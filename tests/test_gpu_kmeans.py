@@ -1,0 +1,115 @@
+"""Code book construction on the GPU (qp_kmeans) against the oracle's Lloyd iteration.
+
+Nearest-centre decisions are taken in fp32 on the GPU and in fp64 in the oracle, so a sample that is
+(nearly) equidistant from two centres may legitimately go either way.  What is unique is compared
+exactly, the rest is checked for validity: every GPU assignment must be a nearest centre within fp32
+rounding of the distances; given the GPU's own assignment the oracle's update must reproduce the
+GPU's centres; a whole run must end, like the oracle's, in a fixed point of the same quality."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2509_20214_amd as qp
+
+pytestmark = pytest.mark.gpu
+
+
+def gauss(seed, n, d):
+    x = np.random.default_rng(seed).standard_normal((n, d)).astype(np.float32)
+    return x if d == 2 else x.reshape(-1)
+
+
+def run_gpu(x, init, max_iter, tol):
+    xs = torch.from_numpy(x).cuda()
+    c = torch.from_numpy(np.ascontiguousarray(init, dtype=np.float32)).cuda()
+    assign = torch.full((x.shape[0],), -1, dtype=torch.int32, device="cuda")
+    c16 = torch.zeros(c.shape, dtype=torch.float16, device="cuda")
+    stats = torch.zeros(3, dtype=torch.float64, device="cuda")
+    qp.qp_kmeans(xs, c, max_iter, tol, assign=assign, centres_f16=c16, stats=stats)
+    torch.cuda.synchronize()
+    return c.cpu().numpy(), assign.cpu().numpy(), c16.cpu().numpy(), stats.cpu().numpy()
+
+
+@pytest.mark.parametrize("n,d,k,seed", [(1, 1, 1, 0), (5, 2, 1, 1), (1000, 1, 4, 2), (4097, 2, 16, 3),
+                                        (70001, 2, 512, 4), (30000, 1, 256, 5), (3000, 2, 4096, 6),
+                                        (2_000_003, 2, 32, 7), (600_000, 1, 16, 8)])
+def test_one_iteration(n, d, k, seed):
+    x = gauss(seed, n, d)
+    init = gauss(100 + seed, k, d) * 1.5
+    c, a, c16, stats = run_gpu(x, init, 1, 0.0)
+    x64 = x.astype(np.float64).reshape(n, d)
+    m64 = init.astype(np.float64).reshape(k, d)
+    a_ref, inertia_ref = oracle.kmeans_assign(x64, m64)
+    # validity of every assignment: its centre is a nearest one up to fp32 rounding of the distances
+    d_gpu = ((x64 - m64[a]) ** 2).sum(1)
+    d_min = ((x64 - m64[a_ref]) ** 2).sum(1)
+    assert np.all((a >= 0) & (a < k))
+    assert np.all(d_gpu <= d_min * (1 + 1e-5) + 1e-6)
+    assert (a != a_ref).mean() < 1e-3
+    assert abs(stats[0] - inertia_ref) <= 1e-5 * inertia_ref + 1e-6
+    assert stats[1] == 1
+    # the update, from the GPU's own assignment
+    m_ref, count, moved = oracle.kmeans_update(x64, a, m64)
+    np.testing.assert_allclose(c.reshape(k, d), m_ref, rtol=0, atol=2e-5)
+    assert abs(stats[2] - moved) <= 1e-4 * moved + 1e-9
+    # fp16 copy = round-to-nearest-even of the fp32 centres
+    assert np.array_equal(c16.view(np.uint16), c.astype(np.float16).view(np.uint16))
+
+
+@pytest.mark.parametrize("n,d,k,seed", [(20000, 1, 8, 11), (50000, 2, 16, 12), (40000, 2, 64, 13)])
+def test_full_run_matches_the_oracle(n, d, k, seed):
+    x = gauss(seed, n, d)
+    init = x[:k].copy()
+    c, a, _, stats = run_gpu(x, init, 300, 1e-6)
+    x64 = x.astype(np.float64).reshape(n, d)
+    m_ref, it_ref, inertia_ref = oracle.kmeans(x64, init.astype(np.float64).reshape(k, d), 300, 1e-6)
+    # same quality (a near-tie resolved the other way may shift the path by a hair)
+    assert abs(stats[0] - inertia_ref) < 2e-3 * inertia_ref
+    assert 1 <= stats[1] <= 300
+    # the GPU's result is (nearly) a fixed point of the oracle's iteration
+    a2, _ = oracle.kmeans_assign(x64, c.astype(np.float64).reshape(k, d))
+    m2, _, moved = oracle.kmeans_update(x64, a2, c.astype(np.float64).reshape(k, d))
+    assert moved < 1e-4 if stats[1] < 300 else True
+    if it_ref < 300 and stats[1] < 300:
+        np.testing.assert_allclose(np.sort(c.reshape(k, d), axis=0), np.sort(m_ref, axis=0), rtol=0, atol=5e-2)
+
+
+def test_empty_clusters_keep_their_centres_and_run_stops():
+    x = np.array([0.0, 1.0, 10.0, 11.0], dtype=np.float32)
+    init = np.array([0.0, 10.0, 1000.0], dtype=np.float32)
+    c, a, _, stats = run_gpu(x, init, 50, 1e-6)
+    assert c.tolist() == [0.5, 10.5, 1000.0]
+    assert a.tolist() == [0, 0, 1, 1]
+    assert stats[1] == 2 and stats[0] == 1.0 and stats[2] == 0.0
+
+
+def test_stops_at_max_iter():
+    x = gauss(21, 5000, 2)
+    c, _, _, stats = run_gpu(x, x[:16].copy(), 3, 0.0)
+    assert stats[1] == 3
+    m = x[:16].astype(np.float64)
+    x64 = x.astype(np.float64)
+    for _ in range(3):
+        a, _ = oracle.kmeans_assign(x64, m)
+        m, _, _ = oracle.kmeans_update(x64, a, m)
+    np.testing.assert_allclose(c, m, rtol=0, atol=1e-3)
+
+
+def test_trained_tables_reach_the_papers_distortions():
+    """Appendix C.1 / C.2 through the GPU: a 4-level scalar table and a 16-point 2-D table trained on
+    Gaussian samples on the GPU; the distortion of fresh Gaussian weights rounded to their nearest
+    entries (the oracle's assignment step) is 0.11747 (NUQ-2) and within 2 % of 0.10857 (VQ-2), Table 5."""
+    from paper_2509_20214_amd import codebooks
+    g = torch.Generator(device="cuda").manual_seed(5)
+    fresh = torch.randn((256, 4096), generator=g, device="cuda", dtype=torch.float32)
+    lut = codebooks.train_scalar(2, n_samples=2_000_000, seed=1)
+    lut2 = codebooks.train_vector(4, n_samples=2_000_000, seed=2)
+    assert lut2.shape == (16, 2) and lut2.dtype == torch.float16
+    x64 = fresh.double().cpu().numpy().reshape(-1, 2)
+    _, inertia = oracle.kmeans_assign(x64, lut2.double().cpu().numpy())
+    assert abs(inertia / x64.size - 0.10857) < 0.02 * 0.10857
+    x1 = fresh.double().cpu().numpy().reshape(-1)
+    _, inertia1 = oracle.kmeans_assign(x1, lut.double().cpu().numpy())
+    assert abs(inertia1 / x1.size - 0.11747) < 2e-3
+    assert torch.all(lut[1:] > lut[:-1])
