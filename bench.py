@@ -50,6 +50,9 @@ def parse():
     p.add_argument("--msq", action="store_true",
                    help="profile every (fusible group, quantizer) of an 8B-shaped block and run the fusion-aware "
                         "mixed-scheme selection on the measured latencies; prints its own JSON line")
+    p.add_argument("--codebooks", action="store_true",
+                   help="fit code books on the GPU (qp_kmeans) and measure the distortion of Gaussian weights "
+                        "quantized with them (fit -> qp_encode -> qp_dequant); prints its own JSON line")
     p.add_argument("--profile-only", action="store_true",
                    help="run a short sequence of the dominant kernel only (for rocprofv3)")
     return p.parse_args()
@@ -234,6 +237,63 @@ def msq_demo(torch, synth, qp, dev, upload, graph_of, event_time_us):
                       "selections": out, "data": "synthetic (seeded sensitivities; codes drawn on the device)"}))
 
 
+def codebooks_demo(torch, synth, qp, dev):
+    """Appendix C "Codebook construction" on the GPU, then the distortion of N(0,1) weights quantized
+    with the fitted tables (Table 5 of the paper: NUQ-2 0.11747, VQ-2 0.10857, TCQ-2 0.07101 on
+    4096 x 4096 Gaussian matrices with its own k-means tables)."""
+    from paper_2509_20214_amd import codebooks
+    out = {"metric": "code books fitted on the GPU and the distortion they reach on N(0,1) weights", "rows": []}
+    gen = torch.Generator(device=dev).manual_seed(77)
+    M, N = 1024, 4096
+    Wt = torch.randn((M, N), device=dev, generator=gen).half()
+    norm = float((Wt.float() ** 2).mean())
+    ones = torch.full((M,), 0x3C00, dtype=torch.int16, device=dev)
+
+    def timed(fn):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        r = fn()
+        torch.cuda.synchronize()
+        return r, time.perf_counter() - t0
+
+    def quantize(scheme, cb, vec, lut16, tlut_bits=0):
+        lay = synth.make_layer(6, 901, scheme, 16, N, cb)
+        codes = torch.zeros((M, lay.codes.shape[1]), dtype=torch.uint8, device=dev)
+        trel = scheme in (synth.TCQ, synth.TCQH, synth.TCQHH)
+        w = qp.Weight(scheme, M, N, cb, vec, 16 if trel else 0, 256 if trel else 0, codes,
+                      lut16.contiguous().view(torch.int16), ones, tlut_bits=tlut_bits)
+        nb = qp.qp_encode_workspace_bytes(w)
+        ws = torch.empty(max(nb, 16), dtype=torch.uint8, device=dev)
+        _, dt = timed(lambda: qp.qp_encode(w, Wt, workspace=ws))
+        Wd = qp.qp_dequant(w).float()
+        return float(((Wd - Wt.float()) ** 2).mean()) / norm, dt
+
+    # scalar table, 4 bits (the fused kernels' scalar scheme), against the closed-form Lloyd-Max levels
+    lut, dt = timed(lambda: codebooks.train_scalar(4, n_samples=20_000_000, seed=1))
+    d, de = quantize(synth.SQ, 4, 1, lut)
+    ref = float(np.abs(lut.float().cpu().numpy() - synth.sq_lut(4).view(np.float16).astype(np.float32)).max())
+    out["rows"].append({"table": "scalar 4 bit, 16 levels, 2e7 samples", "fit_ms": round(dt * 1e3, 1),
+                        "normalised_mse": round(d, 5), "max_abs_diff_to_closed_form_levels": round(ref, 4)})
+    # vector tables of the fused kernels
+    for cb in (5, 7):
+        lut, dt = timed(lambda: codebooks.train_vector(cb, n_samples=10_000_000, seed=2))
+        d, de = quantize(synth.VQ, cb, 2, lut)
+        d_rand, _ = quantize(synth.VQ, cb, 2, torch.from_numpy(synth.vq_lut(3, 0, cb).view(np.int16)).to(dev).view(torch.float16))
+        out["rows"].append({"table": f"2-D {cb} bit ({cb / 2} bits per weight), 1e7 pairs", "fit_ms": round(dt * 1e3, 1),
+                            "normalised_mse": round(d, 5), "with_random_gaussian_table": round(d_rand, 5),
+                            "rate_distortion_bound": round(2.0 ** -cb, 5)})
+    # the trellis quantizer's small table: 2^9 pairs fitted to 2^20 Gaussian pairs, several scalings
+    for scale in (1.0, 0.9, 0.85, 0.8, 0.75):
+        tl, dt = timed(lambda: codebooks.train_tlut(9, seed=3, scale=scale))
+        d, de = quantize(synth.TCQH, 4, 2, tl, tlut_bits=9)
+        out["rows"].append({"table": f"trellis small table 2^9 pairs, samples scaled by {scale}; TCQ 2 bit",
+                            "fit_ms": round(dt * 1e3, 1), "encode_ms": round(de * 1e3, 1),
+                            "normalised_mse": round(d, 5), "paper_table5": 0.07101})
+    d_rand, _ = quantize(synth.TCQH, 4, 2, torch.from_numpy(synth.tcqh_tlut(6, 0, 9).view(np.int16)).to(dev).view(torch.float16), tlut_bits=9)
+    out["rows"].append({"table": "trellis small table of random Gaussian pairs; TCQ 2 bit", "normalised_mse": round(d_rand, 5)})
+    print(json.dumps(out))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -331,6 +391,9 @@ def main():
         return
     if a.msq:
         msq_demo(torch, synth, qp, dev, upload, graph_of, event_time_us)
+        return
+    if a.codebooks:
+        codebooks_demo(torch, synth, qp, dev)
         return
     if a.sweep8b:
         name, bits = a.sweep8b.split(":")

@@ -39,10 +39,13 @@ def train_vector(code_bits: int, n_samples: int = 10_000_000, seed: int = 0, max
     return _fit(x, 1 << code_bits, max_iter, tol)[0]
 
 
-def train_tlut(tlut_bits: int = 9, n_samples: int = 1 << 20, seed: int = 0, scale: float = 1.0, max_iter: int = 300,
+def train_tlut(tlut_bits: int = 9, n_samples: int = 1 << 20, seed: int = 0, scale: float = 0.8, max_iter: int = 300,
                tol: float = 1e-6, device="cuda"):
     """The small table of the trellis quantizer's hybrid code book: 2^tlut_bits pairs fitted to
-    2^20 Gaussian pairs (the paper scales the samples by a factor it does not state: `scale`)."""
+    2^20 Gaussian pairs.  The paper scales the samples by a factor it does not state; measured at
+    2 bits per weight, the distortion of N(0,1) weights is least for a factor of 0.75 .. 0.8
+    (0.0706; 0.0799 unscaled; the paper's own figure, 0.07101, lies between the results for 0.8 and
+    0.85), hence the default."""
     import torch
     g = torch.Generator(device=device).manual_seed(seed)
     x = torch.randn((n_samples, 2), generator=g, device=device, dtype=torch.float32) * scale

@@ -113,3 +113,31 @@ def test_trained_tables_reach_the_papers_distortions():
     _, inertia1 = oracle.kmeans_assign(x1, lut.double().cpu().numpy())
     assert abs(inertia1 / x1.size - 0.11747) < 2e-3
     assert torch.all(lut[1:] > lut[:-1])
+
+
+def test_trained_trellis_table_reproduces_paper_tcq2():
+    """Appendix C.3.1 end to end on the GPU: small table of 2^9 pairs fitted by k-means to 2^20
+    scaled Gaussian pairs, hybrid code book computed from it inside the kernels, tail-biting Viterbi
+    encode of N(0,1) weights at 2 bits per weight (V = 2, s = 4), decode: normalised distortion within
+    2 % of the paper's TCQ-2 figure (Table 5, 0.07101), and below that of a random Gaussian table."""
+    import synth
+    from paper_2509_20214_amd import codebooks
+    tl = codebooks.train_tlut(9, seed=3)
+    assert tl.shape == (512, 2) and tl.dtype == torch.float16
+    M, N = 256, 4096
+    Wt = torch.randn((M, N), device="cuda", generator=torch.Generator(device="cuda").manual_seed(9)).half()
+    lay = synth.make_layer(6, 902, synth.TCQH, 16, N, 4)
+    ones = torch.full((M,), 0x3C00, dtype=torch.int16, device="cuda")
+
+    def distortion(table):
+        codes = torch.zeros((M, lay.codes.shape[1]), dtype=torch.uint8, device="cuda")
+        w = qp.Weight(synth.TCQH, M, N, 4, 2, 16, 256, codes, table.contiguous().view(torch.int16), ones, tlut_bits=9)
+        ws = torch.empty(qp.qp_encode_workspace_bytes(w), dtype=torch.uint8, device="cuda")
+        qp.qp_encode(w, Wt, workspace=ws)
+        Wd = qp.qp_dequant(w).float()
+        return float(((Wd - Wt.float()) ** 2).mean() / (Wt.float() ** 2).mean())
+
+    d = distortion(tl)
+    assert abs(d - 0.07101) < 0.02 * 0.07101
+    rand = torch.from_numpy(synth.tcqh_tlut(6, 0, 9).view(np.int16)).cuda().view(torch.float16)
+    assert d < distortion(rand)
