@@ -28,6 +28,13 @@ def cases():
             rbk = max(1, 60000 // nbc)
         B = int(g.integers(1, 17))
         out.append((k, scheme, cb, rbk * 16, nbc * 1024, B))
+    # Chosen by hand: many units per workgroup, i.e. the workgroup-wide byte-window table of VQ 5 bit
+    # (small layers use a per-wavefront table instead) and passes of more than 32 units at small batch.
+    extra = [(synth.VQ, 5, 40, 20, 1), (synth.VQ, 5, 600, 8, 2), (synth.VQ, 5, 1100, 28, 5), (synth.VQ, 5, 300, 24, 16),
+             (synth.SQ, 4, 2000, 8, 1), (synth.VQ, 7, 1300, 32, 1), (synth.TCQH, 6, 2600, 8, 1),
+             (synth.TCQ, 3, 3000, 16, 2), (synth.TCQHH, 5, 1000, 14, 1), (synth.SQ, 4, 900, 28, 4)]
+    for j, (scheme, cb, rbk, nbc, B) in enumerate(extra):
+        out.append((100 + j, scheme, cb, rbk * 16, nbc * 1024, B))
     return out
 
 
