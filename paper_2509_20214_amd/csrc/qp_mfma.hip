@@ -712,7 +712,6 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     // (a table that can be built at either point: late when the workgroup has few units)
     constexpr bool MOVABLE = QpTableMovable<D>::value;
     const bool table_late = MOVABLE && (rb_q + (rb_r ? 1 : 0)) * w.nbc <= late_max;
-    if (!MOVABLE || !table_late) D::early(tab, reinterpret_cast<uint16_t *>(red), w.lut);
     QP_T(13);
     const typename D::Pre pre = D::pre(w.lut);
 
@@ -800,7 +799,20 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
             if (half1) qp_half_pieces_load<S, CB, P, 1>(blk, ps, q);
             else qp_half_pieces_load<S, CB, P, 0>(blk, ps, q);
         } else {
-            qp_pieces_load<P, HH>(blk, ps, full, q);
+            if constexpr (MOVABLE && !HH) {
+                // A table shared by the workgroup that is built "before the loads" is built with the
+                // activation fragments and the first piece(s) already on their way: the scalar fetch
+                // of its source, two barriers and 32 KiB of LDS writes take over a microsecond, the
+                // few early requests are accepted without back-pressure, and - loads returning in
+                // order - step 0 can start as soon as the table stands.
+                // (measured with one, two and three pieces ahead of the build: one is best)
+                q[0] = qp_stream_load(blk);
+                if (!table_late) D::early(tab, reinterpret_cast<uint16_t *>(red), w.lut);
+#pragma unroll
+                for (int p = 1; p < P; ++p) q[p] = qp_stream_load(blk + p * ps);
+            } else {
+                qp_pieces_load<P, HH>(blk, ps, full, q);
+            }
         }
     }
     // the first output this thread stores after the pass: its per-row scale is fetched now
