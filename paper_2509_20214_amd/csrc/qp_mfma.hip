@@ -25,8 +25,9 @@
 //              table of half2.  Measured issue cost on this chip, 4 wavefronts per SIMD:
 //              2.3 clocks for VOP2 (shift, and, xor), 3.8 for VOP3 / SDWA / DPP forms, so
 //              one SDWA per code beats bit-field extract + shift-or (7.6) and shift + and (4.6).
-//   VQ 5 bit, small layers : 32 entries of half2 = one dword per bank, conflict-free as it
-//              is; a private copy per wavefront, no workgroup barrier (QpDecVq5Private).
+//   VQ 5 bit, small layers, batch 3-4 and 9-16 : 32 entries of half2 = one dword per bank,
+//              conflict-free as it is; a private copy per wavefront, no workgroup barrier
+//              (QpDecVq5Private).
 //              (Keeping the table in a VGPR and fetching it with ds_bpermute saves the
 //              AND per code but ran 2x slower: the permute path has a lower rate.)
 //   TCQ      : the 2^16-entry fp16 table, 128 KiB of LDS, read with ds_read_u16.
@@ -250,7 +251,7 @@ template <> struct QpDec<QP_SQ, 4> : QpDecByte<QP_SQ, 4> {};
 template <> struct QpDec<QP_VQ, 5> : QpDecByte<QP_VQ, 5> {};
 template <> struct QpDec<QP_VQ, 7> : QpDecByte<QP_VQ, 7> {};
 
-// VQ 5 bit, small layers: 32 entries of half2 = one dword per LDS bank, conflict-free
+// VQ 5 bit, small layers at some batch sizes: 32 entries of half2 = one dword per LDS bank, conflict-free
 // as it is (two lanes either read the same entry or different banks), so every wavefront keeps
 // a private copy (16 x 128 bytes), filled from scalar registers once its weight loads are in
 // flight.  Two vector operations per code instead of one, but no workgroup barrier in front of
@@ -977,7 +978,7 @@ template <int S, int CB, int BP>
 static void qp_launch_one(bool split, int grid, int nw, hipStream_t st, const QpW &w, const void *x, int B,
                           int64_t ldx, void *y, int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic, int x_packed,
                           const int8_t *signs, int rot_block, float rot_norm) {
-    constexpr bool CAN_SPLIT = (qp_alt_splits(S) && BP <= 2) || (S == QP_VQ && CB == 5);
+    constexpr bool CAN_SPLIT = (qp_alt_splits(S) && BP <= 2) || (S == QP_VQ && CB == 5 && (BP == 4 || BP == 16));
     if constexpr (CAN_SPLIT) {
         if (split) {
             qp_launch_xl<S, CB, BP, true>(grid, nw, st, w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed,
@@ -1019,8 +1020,15 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
         if (e && e[0] == '0') split = false;
         if (e && e[0] == '1') split = can_split;
     }
-    // VQ 5 bit: the per-wavefront table while a workgroup has at most one unit per wavefront
-    if (scheme == QP_VQ && cb == 5 && rb_per_wg * nbc <= 16) split = true;
+    // VQ 5 bit: the per-wavefront table while a workgroup has at most one unit per wavefront, at the
+    // batch sizes where it measured faster than the workgroup's byte-window table (4096x14336,
+    // us per call, per-wavefront / shared: batch 1 7.3 / 6.7, 2 7.35 / 7.07, 3 7.7 / 7.9, 4 7.8 / 8.7,
+    // 8 10.85 / 10.1, 16 with fragment-order activations 14.05 / 15.4).
+    if (scheme == QP_VQ && cb == 5 && rb_per_wg * nbc <= 16 && ((B > 2 && B <= 4) || (B > 8 && x_packed))) {
+        split = true;
+        const char *e = getenv("QP_LINEAR_SPLIT");
+        if (e && e[0] == '0') split = false;
+    }
     int nw = units < 16 ? units : 16;
     if (scheme == QP_TCQ || scheme == QP_TCQH || scheme == QP_TCQHH) nw = 16;  // the table staging is written for 1024 threads
     if (nw_forced >= 4 && nw_forced <= 16 && nw_forced < nw) nw = nw_forced;
