@@ -541,15 +541,19 @@ __device__ __forceinline__ void qp_unit_load(const u32x4_t *src, int ps, const h
 // 16 H .. 16 H + 15 and only needs the pieces that hold its windows - those of its own half of
 // the stream plus, the windows being 16 bits wide, the piece after it (for the second half: the
 // first piece, by tail-biting).  The others stay zero and are never looked at.
-template <int S, int CB, int P, int H>
+// PHASE 0: everything; 1: only the piece that holds the half's first window; 2: the others.
+template <int S, int CB, int P, int H, int PHASE = 0>
 __device__ __forceinline__ void qp_half_pieces_load(const u32x4_t *src, int ps, u32x4_t (&q)[P]) {
     constexpr int V = QpTraits<S, CB>::V;
     constexpr int ELEMS = 128 / V;                       // windows per half
     constexpr int TOTAL = 128 * P;                       // stream bits of the lane
     constexpr int START = H * ELEMS * CB, END = START + (ELEMS - 1) * CB + 16;   // [START, END)
+    constexpr int FIRST = START / 128;
 #pragma unroll
     for (int p = 0; p < P; ++p) {
         const bool need = (128 * p < END && 128 * p + 128 > START) || (END > TOTAL && 128 * p < END - TOTAL);
+        if (PHASE == 1 && p != FIRST) continue;
+        if (PHASE == 2 && p == FIRST) continue;
         if (need) q[p] = qp_stream_load(src + p * ps);
         else q[p] = u32x4_t{0u, 0u, 0u, 0u};
     }
@@ -712,6 +716,8 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     // table's source is requested first so that it can be waited for alone.
     // (a table that can be built at either point: late when the workgroup has few units)
     constexpr bool MOVABLE = QpTableMovable<D>::value;
+    // (not with the in-kernel rotation, whose scratch borrows the table's room first)
+    constexpr bool MID_BUILD = !MOVABLE && !XL && (S == QP_TCQ || S == QP_TCQH || S == QP_TCQHH);
     const bool table_late = MOVABLE && (rb_q + (rb_r ? 1 : 0)) * w.nbc <= late_max;
     QP_T(13);
     const typename D::Pre pre = D::pre(w.lut);
@@ -796,7 +802,33 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     QP_T(14);
     {
         const u32x4_t *blk = unit_block(rb_begin, uu, uu - ((uu * nbc_magic) >> 16) * nbc, full);
-        if constexpr (SPLIT) {
+        if constexpr (MID_BUILD) {
+            // The trellis tables (64 / 128 KiB of LDS writes, two barriers) are built with the activation
+            // fragments and the first piece already requested and the other pieces still to be asked
+            // for: every wavefront reaches the barriers without waiting in the load queue, and the
+            // first data arrives while the table is written (5 - 7 % on 4096x4096 and 28672x4096).
+            if constexpr (SPLIT) {
+                if (half1) qp_half_pieces_load<S, CB, P, 1, 1>(blk, ps, q);
+                else qp_half_pieces_load<S, CB, P, 0, 1>(blk, ps, q);
+            } else {
+                q[0] = qp_stream_load(blk);
+            }
+            D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
+            if constexpr (SPLIT) {
+                if (half1) qp_half_pieces_load<S, CB, P, 1, 2>(blk, ps, q);
+                else qp_half_pieces_load<S, CB, P, 0, 2>(blk, ps, q);
+            } else {
+#pragma unroll
+                for (int p = 1; p < P; ++p) {
+                    if (HH && p == P - 1) {   // half-TCQ: the last piece only exists in the second half
+                        q[p] = u32x4_t{0u, 0u, 0u, 0u};
+                        if (full) q[p] = qp_stream_load(blk + p * ps);
+                    } else {
+                        q[p] = qp_stream_load(blk + p * ps);
+                    }
+                }
+            }
+        } else if constexpr (SPLIT) {
             if (half1) qp_half_pieces_load<S, CB, P, 1>(blk, ps, q);
             else qp_half_pieces_load<S, CB, P, 0>(blk, ps, q);
         } else {
@@ -840,7 +872,9 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
 #pragma unroll
         for (int n = 0; n < PF; ++n) xf[n] = *reinterpret_cast<const half8_t *>(xu + xfs * (xn0 + n));
     }
-    if (!MOVABLE || table_late) D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
+    if constexpr (!MID_BUILD) {
+        if (!MOVABLE || table_late) D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
+    }
     QP_T(1);
     if (u < units) {
         float4_t v;
