@@ -676,7 +676,9 @@ struct QpLinLds {
     static constexpr int ROT_SCRATCH_FLOATS = ROT_MAX + ROT_MAX / 32;
     static constexpr bool ROT = (BP == 1);
     // (not a table that may be built before the rotation runs)
-    static constexpr bool SCRATCH_IN_TAB = !QpTableMovable<D>::value && D::TAB_BYTES >= ROT_SCRATCH_FLOATS * 4;
+    // (only the 128 KiB table leaves no room for a scratch of its own; a table that may be built
+    // before the rotation runs cannot lend its room)
+    static constexpr bool SCRATCH_IN_TAB = !QpTableMovable<D>::value && D::TAB_BYTES > 65536;
 };
 
 // XL: the activations are rotated here (Section 3.3), by the workgroup itself, into LDS, and
@@ -716,8 +718,9 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     // table's source is requested first so that it can be waited for alone.
     // (a table that can be built at either point: late when the workgroup has few units)
     constexpr bool MOVABLE = QpTableMovable<D>::value;
-    // (not with the in-kernel rotation, whose scratch borrows the table's room first)
-    constexpr bool MID_BUILD = !MOVABLE && !XL && (S == QP_TCQ || S == QP_TCQH || S == QP_TCQHH);
+    // (not where the in-kernel rotation's scratch borrows the table's room first)
+    constexpr bool MID_BUILD = !MOVABLE && !(XL && QpLinLds<D, S, CB, BP>::SCRATCH_IN_TAB) &&
+                               (S == QP_TCQ || S == QP_TCQH || S == QP_TCQHH);
     const bool table_late = MOVABLE && (rb_q + (rb_r ? 1 : 0)) * w.nbc <= late_max;
     QP_T(13);
     const typename D::Pre pre = D::pre(w.lut);
