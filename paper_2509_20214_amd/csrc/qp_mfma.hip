@@ -54,6 +54,9 @@
 #include "qp_fwht.h"
 
 #define QP_NBC_MAX 32  // column blocks of a layer (N <= 32 * 1024)
+#ifndef QP_COLMAJOR_MIN_BP
+#define QP_COLMAJOR_MIN_BP 4
+#endif
 // Units per pass: between two passes the workgroup meets at barriers to add up and store, and
 // every wavefront starts the next pass in step with the others (all waiting for their loads,
 // then all decoding).  The longer a pass, the more the wavefronts drift apart and overlap one
@@ -707,7 +710,11 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     // items of a pass are then the half units, item u = 2 * unit + half.
     constexpr int SPL = SPLIT ? 2 : 1;
     static_assert(!SPLIT || (!HH && NXF >= 2 && NXF <= 4), "half units: trellis schemes, batch <= 2");
-    constexpr int PF = SPLIT ? NXF / 2 : ((NXF < 8) ? NXF : 8);   // fragments kept in flight
+#ifndef QP_PF_MAX16
+#define QP_PF_MAX16 8
+#endif
+    constexpr int PFMAX = (BP == 16) ? QP_PF_MAX16 : 8;
+    constexpr int PF = SPLIT ? NXF / 2 : ((NXF < PFMAX) ? NXF : PFMAX);   // fragments kept in flight
     constexpr int BLK16 = T::BLOCK_BYTES / 16;
     QP_T(0);
 
@@ -726,7 +733,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     const typename D::Pre pre = D::pre(w.lut);
 
     const int nw = blockDim.x >> 6;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int nbc = w.nbc;
     // balanced contiguous partition of the row blocks over the workgroups: the first rb_r
     // workgroups take rb_q + 1 blocks, the others rb_q
@@ -737,10 +744,20 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
 
     int gcount = (rb_end - rb_begin < G) ? (rb_end - rb_begin) : G;
     int units = gcount * nbc * SPL;   // work items of the pass
-    int u = wave;
+    // Which unit the k-th work item of a pass is.  Batch >= 4: column blocks first, so that the
+    // wavefronts that run side by side work on the same column block of different row blocks and
+    // share its activation fragments (2 KiB per batch row and unit) in the L1.
+    constexpr bool COLMAJOR = (BP >= QP_COLMAJOR_MIN_BP) && !SPLIT;
+    auto unit_of = [&](int k, int gc) __attribute__((always_inline)) -> int {
+        if constexpr (!COLMAJOR) return k;
+        const int C = k / gc;
+        return (k - C * gc) * nbc + C;
+    };
+    int k = wave;                                  // work item of this wavefront in the pass
+    int u = (k < units) ? unit_of(k, gcount) : 0;  // its unit
     // A wavefront without an item loads item 0 as well, to keep this code free of branches;
     // it only skips the arithmetic.
-    const int uw = (u < units) ? u : 0;
+    const int uw = u;
     const int uu = uw / SPL;                                        // its unit
     const bool half1 = SPLIT && __builtin_amdgcn_readfirstlane(uw & 1);   // its half of the unit
     // Activation fragments first: they hit in L2, come back early, and - loads returning in
@@ -879,7 +896,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
         if (!MOVABLE || table_late) D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
     }
     QP_T(1);
-    if (u < units) {
+    if (k < units) {
         float4_t v;
         if constexpr (SPLIT) {
             if (half1) v = qp_unit_compute<D, P, PF, TT, 16, 32>(q, xf, xu, xfs, tab, lc, pre);
@@ -894,13 +911,14 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     }
     QP_T(2);
     int rb0 = rb_begin;
-    u += nw;
+    k += nw;
 #ifdef QP_TRACE
     uint64_t tr_wait = 0, tr_dec = 0, tr_units = 0;
 #endif
     while (true) {
         // ---- remaining units of this pass ----------------------------------------------
-        for (; u < units; u += nw) {
+        for (; k < units; k += nw) {
+            u = unit_of(k, gcount);
             const int ub = u / SPL;
             const bool h2 = SPLIT && __builtin_amdgcn_readfirstlane(u & 1);
             const int C = ub - ((ub * nbc_magic) >> 16) * nbc;
@@ -951,7 +969,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
         if (rb0 >= rb_end) break;
         gcount = (rb_end - rb0 < G) ? (rb_end - rb0) : G;
         units = gcount * nbc * SPL;
-        u = wave;
+        k = wave;
         {
             const int o = threadIdx.x;
             const int i = o & 15, slot = o >> (4 + LB);
@@ -1123,7 +1141,7 @@ __global__ __launch_bounds__(1024) void k_dequant_blocks(QpW w, uint16_t *out, i
     static_assert(NWD * 4096 >= STAGE_FLOATS * 4, "staging room");
     D::early(tab, reinterpret_cast<uint16_t *>(tile), w.lut);
     const typename D::Pre pre = D::pre(w.lut);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int nbc = w.nbc, hcb = nbc >> 1;
     const u32x4_t *codes16 = reinterpret_cast<const u32x4_t *>(w.codes);
     typename D::Lane lc = D::lane_const();
