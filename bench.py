@@ -336,6 +336,8 @@ def main():
             self.xr = torch.empty_like(self.x)
             self.y = torch.empty((B, lay.M), dtype=torch.float16, device=dev)
             self.ws = torch.empty(qp.qp_rotate_linear_workspace_bytes(nat, B), dtype=torch.uint8, device=dev)
+            need = qp.qp_linear_workspace_bytes(nat, B)   # the layer's own optional scratch (large layers, batch > 4)
+            self.lin_ws = torch.empty(need, dtype=torch.uint8, device=dev) if need else False
             self.i = 0
             # algorithmic bytes of one qp_linear launch: codes + scales + x + y + one LUT
             self.alg_bytes = lay.code_bytes + 2 * lay.M + 2 * B * lay.N + 2 * B * lay.M + 2 * lay.lut.size
@@ -348,11 +350,11 @@ def main():
 
         def step_two_calls(self):
             qp.qp_hadamard(self.x, self.signs, self.block, out=self.xr)
-            qp.qp_linear(self.ring[self.i % len(self.ring)], self.xr, y=self.y)
+            qp.qp_linear(self.ring[self.i % len(self.ring)], self.xr, y=self.y, workspace=self.lin_ws)
             self.i += 1
 
         def linear_only(self):
-            qp.qp_linear(self.ring[self.i % len(self.ring)], self.xr, y=self.y)
+            qp.qp_linear(self.ring[self.i % len(self.ring)], self.xr, y=self.y, workspace=self.lin_ws)
             self.i += 1
 
         def hadamard_only(self):

@@ -111,8 +111,12 @@ typedef struct {
  * not rotate), 16-byte aligned with ldx % 8 == 0, ldx >= N.  y: device fp16
  * [B, ldy], ldy >= M; written for all b < B, j < M, rounded to nearest even from
  * the fp32 value s[j]*acc.  1 <= B <= QP_MAX_BATCH.  Accumulation is fp32; the
- * summation order is unspecified.  workspace: device scratch of at least
- * qp_linear_workspace_bytes(w, B) bytes (may be NULL when that is 0). */
+ * summation order is unspecified.  workspace: optional device scratch, 256-byte aligned, of
+ * at least qp_linear_workspace_bytes(w, B) bytes (0 for most layers and batch sizes): given
+ * one, large layers at batch > 4 first copy the activations into the order in which their
+ * kernel reads them (one more small launch, the layer itself up to twice as fast at batch
+ * 9 - 16).  NULL, too small or misaligned: the activations are read where they are.  Same
+ * result, bit for bit, either way; the workspace's contents on exit are unspecified. */
 qp_status qp_linear(const qp_weight *w, const void *x, int32_t B, int64_t ldx, void *y, int64_t ldy,
                     void *workspace, size_t workspace_bytes, void *hip_stream);
 

@@ -263,12 +263,17 @@ def qp_encode_workspace_bytes(w: Weight) -> int:
 
 
 def qp_linear(w: Weight, x, y=None, workspace=None, stream=None):
-    """y[b, j] = s[j] * sum_i x[b, i] W^[j, i].  x: fp16 [B, N] (row stride = x.stride(0))."""
+    """y[b, j] = s[j] * sum_i x[b, i] W^[j, i].  x: fp16 [B, N] (row stride = x.stride(0)).
+    workspace: uint8 tensor of qp_linear_workspace_bytes(w, B) bytes, None (allocated here when the
+    layer wants one) or False (none: the layer reads x in place; same result)."""
     import torch
     B = x.shape[0]
     if y is None:
         y = torch.empty((B, w.M), dtype=torch.float16, device=x.device)
-    ws_ptr, ws_bytes = (None, 0) if workspace is None else (workspace.data_ptr(), workspace.numel() * workspace.element_size())
+    if workspace is None:   # allocate what the layer asks for (usually nothing); workspace=False: none
+        need = qp_linear_workspace_bytes(w, B)
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device) if need else False
+    ws_ptr, ws_bytes = (None, 0) if workspace is False else (workspace.data_ptr(), workspace.numel() * workspace.element_size())
     _check(load_library().qp_linear(C.byref(w.desc), x.data_ptr(), B, x.stride(0), y.data_ptr(), y.stride(0),
                                     ws_ptr, ws_bytes, _stream_ptr(stream)), "qp_linear")
     return y

@@ -83,12 +83,6 @@ static QpW make_dev(const qp_weight *w) {
     return d;
 }
 
-extern "C" size_t qp_linear_workspace_bytes(const qp_weight *w, int32_t B) {
-    (void)w;
-    (void)B;
-    return 0;
-}
-
 // Which kernel runs a layer.  QP_LINEAR_KERNEL=rowwave / mfma forces one (used by the tests
 // to cover both on weights of any size); anything else lets the shape decide.
 // The matrix-core kernel pays a fixed table-build and reduction cost per workgroup; below
@@ -109,6 +103,28 @@ static bool use_rowwave(const qp_weight *w) {
 
 static inline int pow2_at_least(int B) { return B <= 1 ? 1 : B <= 2 ? 2 : B <= 4 ? 4 : B <= 8 ? 8 : 16; }
 
+static inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// Whether qp_linear first copies the activations into the fragment order of the matrix-core
+// kernel (one more small launch; every activation load of the layer is then a contiguous KiB
+// instead of 16 - 64 byte pieces of 8 - 16 rows).  Measured, layer alone, row-major / copied:
+// batch 16 VQ 5 bit 57344x8192 130 / 67 us, 4096x14336 23.6 / 13.1 us, TCQ 3 bit 4096x14336
+// 29 / 22 us; batch 9 VQ 7 bit 8192x28672 55 / 41 us, but 4096x4096 6.3 / 8.1 us; batch 8 VQ 7 bit
+// 8192x28672 38 / 31 us, SQ 57344x8192 62 / 52 us, but VQ 7 bit 10240x8192 14.6 / 16 us and the
+// V = 1 trellis (bound by its table lookups) never at batch <= 8.
+static bool pack_pays(const qp_weight *w, int B) {
+    if (use_rowwave(w)) return false;
+    const int64_t weights = (int64_t)w->M * w->N;
+    if (B > 8) return weights >= ((int64_t)1 << 25);
+    if (B > 4) return w->scheme != QP_TCQ && weights >= ((int64_t)1 << 27);
+    return false;
+}
+
+extern "C" size_t qp_linear_workspace_bytes(const qp_weight *w, int32_t B) {
+    if (!w || B < 1 || B > QP_MAX_BATCH || w->N <= 0 || w->M <= 0) return 0;
+    return pack_pays(w, B) ? round256((size_t)pow2_at_least(B) * (size_t)w->N * 2) : 0;
+}
+
 extern "C" qp_status qp_linear(const qp_weight *w, const void *x, int32_t B, int64_t ldx, void *y, int64_t ldy,
                                void *workspace, size_t workspace_bytes, void *hip_stream) {
     qp_status s = qp_validate(w);
@@ -117,15 +133,19 @@ extern "C" qp_status qp_linear(const qp_weight *w, const void *x, int32_t B, int
     if (B < 1 || B > QP_MAX_BATCH) return QP_ERR_SHAPE;
     if (ldx < w->N || ldy < w->M || ldx % 8 != 0) return QP_ERR_SHAPE;
     if (!aligned(x, 16) || !aligned(y, 2)) return QP_ERR_ALIGN;
-    size_t need = qp_linear_workspace_bytes(w, B);
-    if (need && (!workspace || workspace_bytes < need)) return QP_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     QpW d = make_dev(w);
     if (use_rowwave(w)) return qp_launch_linear_rowwave(d, w->scheme, w->code_bits, x, B, ldx, y, ldy, st);
+    // The workspace is optional: without one (or with one that is too small or not 256-byte
+    // aligned) the layer reads the activations where they are - same result, bit for bit.
+    const size_t need = qp_linear_workspace_bytes(w, B);
+    if (need && workspace && workspace_bytes >= need && aligned(workspace, 256)) {
+        s = qp_launch_pack_x(x, B, w->N, ldx, workspace, pow2_at_least(B), st);
+        if (s != QP_OK) return s;
+        return qp_launch_linear_mfma(d, w->scheme, w->code_bits, workspace, B, w->N, y, ldy, 1, nullptr, 0, st);
+    }
     return qp_launch_linear_mfma(d, w->scheme, w->code_bits, x, B, ldx, y, ldy, 0, nullptr, 0, st);
 }
-
-static inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 extern "C" size_t qp_rotate_linear_workspace_bytes(const qp_weight *w, int32_t B) {
     if (!w || B < 1 || B > QP_MAX_BATCH || w->N <= 0) return 0;

@@ -73,3 +73,23 @@ qp_status qp_launch_hadamard(const void *x, const int8_t *signs, int B, int n, i
                        (const half_t *)x, signs, n, block, ldx, (half_t *)xr, ldxr, norm, pack_bp);
     return qp_check_launch();
 }
+
+// Activations that are already rotated, copied from [B, ldx] into the fragment order of the
+// matrix-core kernel (qp_xr_index): one thread per 16-byte piece, reads coalesced along the
+// row.  The batch columns B .. pack_bp - 1 of the destination stay unwritten: the layer's kernel
+// drops whatever it computes from them.
+__global__ __launch_bounds__(256) void k_pack_x(const half_t *x, int B, int n, int64_t ldx, half_t *xp, int pack_bp) {
+    const int pieces = n >> 3;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)B * pieces) return;
+    const int b = (int)(i / pieces), c8 = (int)(i - (int64_t)b * pieces);
+    const u32x4_t v = *reinterpret_cast<const u32x4_t *>(x + (int64_t)b * ldx + 8 * c8);
+    *reinterpret_cast<u32x4_t *>(xp + qp_xr_index(b, 8 * c8, 0, pack_bp)) = v;
+}
+
+qp_status qp_launch_pack_x(const void *x, int B, int n, int64_t ldx, void *xp, int pack_bp, hipStream_t st) {
+    const int64_t total = (int64_t)B * (n >> 3);
+    hipLaunchKernelGGL(k_pack_x, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const half_t *)x, B, n, ldx,
+                       (half_t *)xp, pack_bp);
+    return qp_check_launch();
+}

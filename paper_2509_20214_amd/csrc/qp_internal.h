@@ -16,6 +16,7 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
 // qp_launch_linear_mfma reads with x_packed (needs n % 1024 == 0, pack_bp * n halves of room)
 qp_status qp_launch_hadamard(const void *x, const int8_t *signs, int B, int n, int block, int64_t ldx,
                              void *xr, int64_t ldxr, int pack_bp, hipStream_t st);
+qp_status qp_launch_pack_x(const void *x, int B, int n, int64_t ldx, void *xp, int pack_bp, hipStream_t st);
 // encoders (canonical output); workspace only for the trellis schemes
 qp_status qp_launch_encode(int scheme, int cb, int tlut_bits, int M, int N, const uint16_t *lut, const void *W, int64_t ldw,
                            void *codes, int64_t row_stride, void *workspace, size_t workspace_bytes, float *tile_err,

@@ -105,6 +105,23 @@ def test_linear_argument_errors_do_not_launch():
     assert L.qp_dequant(C.byref(d), 0x5004, None) == 4
 
 
+def test_linear_workspace_sizes():
+    """Host logic only: which layers and batch sizes want the optional workspace, and how much."""
+    L = qp.load_library()
+    big = desc(scheme=qp.QP_VQ, vec=2, code_bits=7, M=8192, N=16384, row_stride=7168)       # 2^27 weights
+    mid = desc(scheme=qp.QP_VQ, vec=2, code_bits=5, M=8192, N=4096, row_stride=1280)        # 2^25
+    small = desc(scheme=qp.QP_VQ, vec=2, code_bits=5, M=4096, N=4096, row_stride=1280)      # 2^24
+    tcq = desc(scheme=qp.QP_TCQ, code_bits=3, window_bits=16, tile=256, M=8192, N=16384, row_stride=6144)
+    tiny = desc()                                                                            # row kernel
+    ws = lambda d, B: L.qp_linear_workspace_bytes(C.byref(d), B)
+    assert [ws(big, B) for B in (1, 4, 5, 8, 9, 16)] == [0, 0, 8 * 16384 * 2, 8 * 16384 * 2, 16 * 16384 * 2, 16 * 16384 * 2]
+    assert [ws(mid, B) for B in (1, 8, 9, 16)] == [0, 0, 16 * 4096 * 2, 16 * 4096 * 2]
+    assert [ws(small, B) for B in (8, 16)] == [0, 0]
+    assert [ws(tcq, B) for B in (5, 8, 9)] == [0, 0, 16 * 16384 * 2]
+    assert [ws(tiny, B) for B in (1, 16)] == [0, 0]
+    assert ws(big, 0) == 0 and ws(big, 17) == 0 and L.qp_linear_workspace_bytes(None, 8) == 0
+
+
 def test_hadamard_argument_errors_do_not_launch():
     L = qp.load_library()
     call = lambda x, s, B, n, blk, ldx, xr, ldxr: L.qp_hadamard(x, s, B, n, blk, ldx, xr, ldxr, None)
