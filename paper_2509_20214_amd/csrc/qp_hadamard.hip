@@ -75,21 +75,30 @@ qp_status qp_launch_hadamard(const void *x, const int8_t *signs, int B, int n, i
 }
 
 // Activations that are already rotated, copied from [B, ldx] into the fragment order of the
-// matrix-core kernel (qp_xr_index): one thread per 16-byte piece, reads coalesced along the
-// row.  The batch columns B .. pack_bp - 1 of the destination stay unwritten: the layer's kernel
-// drops whatever it computes from them.
-__global__ __launch_bounds__(256) void k_pack_x(const half_t *x, int B, int n, int64_t ldx, half_t *xp, int pack_bp) {
-    const int pieces = n >> 3;
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= (int64_t)B * pieces) return;
-    const int b = (int)(i / pieces), c8 = (int)(i - (int64_t)b * pieces);
-    const u32x4_t v = *reinterpret_cast<const u32x4_t *>(x + (int64_t)b * ldx + 8 * c8);
-    *reinterpret_cast<u32x4_t *>(xp + qp_xr_index(b, 8 * c8, 0, pack_bp)) = v;
+// matrix-core kernel (the inverse of qp_xr_index): one thread per 16-byte piece of the
+// destination, so that every wavefront writes one whole fragment (a contiguous KiB) and reads
+// 64 pieces of 16 bytes whose cache lines its neighbours read next (x is small and stays in L2;
+// the other way round - coalesced reads, scattered 16-byte writes - took twice as long).
+// The batch columns B .. pack_bp - 1 are written as zeros.
+__global__ __launch_bounds__(256) void k_pack_x(const half_t *x, int B, int nbc, int64_t ldx, half_t *xp, int lt) {
+    // destination piece d = (C * NXF + n) * 64 + 16 g + (b << lt) + t, TT = 1 << lt steps per fragment
+    const int d = blockIdx.x * blockDim.x + threadIdx.x;
+    const int nxf_log = 5 - lt;
+    if (d >= (nbc << (nxf_log + 6))) return;
+    const int lane = d & 63, frag = d >> 6;
+    const int n = frag & ((1 << nxf_log) - 1), C = frag >> nxf_log;
+    const int g = lane >> 4, j = lane & 15;
+    const int b = j >> lt, t = j & ((1 << lt) - 1);
+    u32x4_t v = u32x4_t{0u, 0u, 0u, 0u};
+    if (b < B) v = *reinterpret_cast<const u32x4_t *>(x + (int64_t)b * ldx + 1024 * C + 256 * g + 8 * ((n << lt) + t));
+    reinterpret_cast<u32x4_t *>(xp)[d] = v;
 }
 
 qp_status qp_launch_pack_x(const void *x, int B, int n, int64_t ldx, void *xp, int pack_bp, hipStream_t st) {
-    const int64_t total = (int64_t)B * (n >> 3);
-    hipLaunchKernelGGL(k_pack_x, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const half_t *)x, B, n, ldx,
-                       (half_t *)xp, pack_bp);
+    const int lt = 4 - __builtin_ctz(pack_bp);   // log2 of the steps per fragment, 16 / pack_bp
+    const int nbc = n / 1024;
+    const int total = nbc << (5 - lt + 6);
+    hipLaunchKernelGGL(k_pack_x, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const half_t *)x, B, nbc, ldx,
+                       (half_t *)xp, lt);
     return qp_check_launch();
 }
