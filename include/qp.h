@@ -113,7 +113,7 @@ typedef struct {
  * the fp32 value s[j]*acc.  1 <= B <= QP_MAX_BATCH.  Accumulation is fp32; the
  * summation order is unspecified.  workspace: optional device scratch, 256-byte aligned, of
  * at least qp_linear_workspace_bytes(w, B) bytes (0 for most layers and batch sizes): given
- * one, large layers at batch > 1 first copy the activations into the order in which their
+ * one, large layers at batch > 4 first copy the activations into the order in which their
  * kernel reads them (one more small launch, the layer itself up to twice as fast at batch
  * 9 - 16).  NULL, too small or misaligned: the activations are read where they are.  Same
  * result, bit for bit, either way; the workspace's contents on exit are unspecified. */

@@ -111,17 +111,16 @@ static inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 // batch 16 VQ 5 bit 57344x8192 130 / 67 us, 4096x14336 23.6 / 13.1 us, TCQ 3 bit 4096x14336
 // 29 / 22 us; batch 9 VQ 7 bit 8192x28672 55 / 41 us, but 4096x4096 6.3 / 8.1 us; batch 8 VQ 7 bit
 // 8192x28672 38 / 31 us, SQ 57344x8192 62 / 52 us, but VQ 7 bit 10240x8192 14.6 / 16 us and the
-// V = 1 trellis (bound by its table lookups) never at batch <= 8; batch 4 VQ 7 bit 8192x28672
-// 27.4 / 25.4 us, 28672x4096 14.3 / 15.6 us; batch 2 57344x8192 VQ 7 bit 45.9 / 41.8 us, TCQH 6 bit
-// 52.5 / 46.9 us, but 8192x28672 within +-4 %.
+// V = 1 trellis (bound by its table lookups) never at batch <= 8.  At batch 1 - 4 the largest
+// layers seem to gain 4 - 10 % as well, but a plain copy of x in front of the unchanged kernel
+// gains the same: launches of large kernels back to back cost more than the same launches with
+// any small kernel between them - an effect of the launch sequence, not of the layout.
 static bool pack_pays(const qp_weight *w, int B) {
     if (use_rowwave(w)) return false;
     if (const char *e = getenv("QP_LINEAR_PACK")) return e[0] == '1';   // development hook: always / never
     const int64_t weights = (int64_t)w->M * w->N;
     if (B > 8) return weights >= ((int64_t)1 << 25);
-    if (w->scheme == QP_TCQ) return false;
-    if (B > 2) return weights >= ((int64_t)1 << 27);
-    if (B > 1) return weights >= ((int64_t)1 << 28);
+    if (B > 4) return w->scheme != QP_TCQ && weights >= ((int64_t)1 << 27);
     return false;
 }
 

@@ -114,10 +114,7 @@ def test_linear_workspace_sizes():
     tcq = desc(scheme=qp.QP_TCQ, code_bits=3, window_bits=16, tile=256, M=8192, N=16384, row_stride=6144)
     tiny = desc()                                                                            # row kernel
     ws = lambda d, B: L.qp_linear_workspace_bytes(C.byref(d), B)
-    assert [ws(big, B) for B in (1, 4, 5, 8, 9, 16)] == [0, 4 * 16384 * 2, 8 * 16384 * 2, 8 * 16384 * 2, 16 * 16384 * 2, 16 * 16384 * 2]
-    assert ws(big, 2) == 0 and ws(big, 3) == 4 * 16384 * 2                                   # batch 2 only from 2^28 weights on
-    huge = desc(scheme=qp.QP_SQ, M=32768, N=8192, row_stride=4096)                           # 2^28
-    assert ws(huge, 1) == 0 and ws(huge, 2) == 2 * 8192 * 2
+    assert [ws(big, B) for B in (1, 4, 5, 8, 9, 16)] == [0, 0, 8 * 16384 * 2, 8 * 16384 * 2, 16 * 16384 * 2, 16 * 16384 * 2]
     assert [ws(mid, B) for B in (1, 8, 9, 16)] == [0, 0, 16 * 4096 * 2, 16 * 4096 * 2]
     assert [ws(small, B) for B in (8, 16)] == [0, 0]
     assert [ws(tcq, B) for B in (5, 8, 9)] == [0, 0, 16 * 16384 * 2]
