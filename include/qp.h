@@ -78,6 +78,7 @@ typedef enum { QP_SQ = 0, QP_VQ = 1, QP_TCQ = 2, QP_TCQH = 3, QP_TCQHH = 4 } qp_
 typedef enum { QP_LAYOUT_CANONICAL = 0, QP_LAYOUT_NATIVE = 1 } qp_layout;
 
 #define QP_MAX_BATCH 16
+#define QP_MAX_LDX (1 << 26)   /* largest row stride of the activations, in elements */
 
 /* One quantized layer.  Supported set:
  *   QP_SQ : vec 1, code_bits 4                       (16-entry fp16 LUT)
@@ -108,7 +109,7 @@ typedef struct {
 
 /* Fused dequantize-and-multiply (Section 3.3 "Kernel implementation"; the fused
  * kernels of Appendix D).  x: device fp16 [B, ldx] (already rotated; this call does
- * not rotate), 16-byte aligned with ldx % 8 == 0, ldx >= N.  y: device fp16
+ * not rotate), 16-byte aligned with ldx % 8 == 0, N <= ldx <= QP_MAX_LDX.  y: device fp16
  * [B, ldy], ldy >= M; written for all b < B, j < M, rounded to nearest even from
  * the fp32 value s[j]*acc.  1 <= B <= QP_MAX_BATCH.  Accumulation is fp32; the
  * summation order is unspecified.  workspace: optional device scratch, 256-byte aligned, of
@@ -145,7 +146,7 @@ qp_status qp_hadamard(const void *x, const int8_t *signs, int32_t B, int32_t n, 
  * batch size) - or one kernel, at batch 1 on the native layout when block == N is a power of
  * two between 1024 and 8192: its workgroups then rotate the activations themselves while
  * their first weights are on the way, and the workspace is not touched.
- * x: device fp16 [B, ldx], unrotated, 16-byte aligned, ldx % 8 == 0;
+ * x: device fp16 [B, ldx], unrotated, 16-byte aligned, ldx % 8 == 0, N <= ldx <= QP_MAX_LDX;
  * signs: device int8 [N], 16-byte aligned.  workspace: device, 256-byte aligned, at least
  * qp_rotate_linear_workspace_bytes(w, B) bytes; contents on entry and exit are unspecified. */
 qp_status qp_rotate_linear(const qp_weight *w, const void *x, const int8_t *signs, int32_t block, int32_t B,

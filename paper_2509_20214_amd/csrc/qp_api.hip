@@ -135,7 +135,7 @@ extern "C" qp_status qp_linear(const qp_weight *w, const void *x, int32_t B, int
     if (s != QP_OK) return s;
     if (!x || !y) return QP_ERR_NULL;
     if (B < 1 || B > QP_MAX_BATCH) return QP_ERR_SHAPE;
-    if (ldx < w->N || ldy < w->M || ldx % 8 != 0) return QP_ERR_SHAPE;
+    if (ldx < w->N || ldx > QP_MAX_LDX || ldy < w->M || ldx % 8 != 0) return QP_ERR_SHAPE;
     if (!aligned(x, 16) || !aligned(y, 2)) return QP_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     QpW d = make_dev(w);
@@ -163,7 +163,7 @@ extern "C" qp_status qp_rotate_linear(const qp_weight *w, const void *x, const i
     if (s != QP_OK) return s;
     if (!x || !signs || !y || !workspace) return QP_ERR_NULL;
     if (B < 1 || B > QP_MAX_BATCH) return QP_ERR_SHAPE;
-    if (ldx < w->N || ldy < w->M || ldx % 8 != 0) return QP_ERR_SHAPE;
+    if (ldx < w->N || ldx > QP_MAX_LDX || ldy < w->M || ldx % 8 != 0) return QP_ERR_SHAPE;
     if (block < 2 || block > 16384 || (block & (block - 1)) != 0 || w->N % block != 0) return QP_ERR_SHAPE;
     if (!aligned(x, 16) || !aligned(y, 2) || !aligned(workspace, 256) || !aligned(signs, 16)) return QP_ERR_ALIGN;
     if (workspace_bytes < qp_rotate_linear_workspace_bytes(w, B)) return QP_ERR_WORKSPACE;

@@ -532,11 +532,41 @@ __device__ __forceinline__ void qp_pieces_load(const u32x4_t *src, int ps, bool 
     }
 }
 
-template <int P, int PF, bool OPTIONAL_LAST>
-__device__ __forceinline__ void qp_unit_load(const u32x4_t *src, int ps, const half_t *xu, int xfs, bool full,
+// Where a unit's activation fragments are.
+// Batch 5 - 16, global memory (QpXBuf): a buffer descriptor over the whole activation array, the
+// unit's column block and the fragment number as a wave-uniform byte offset (scalar registers)
+// and the lane's own byte offset, which is the same for every fragment, column block and unit -
+// one vector register and no vector address arithmetic per load, where a flat 64-bit address
+// costs a register pair and an add each.  These kernels sit at the register limit and load 16
+// to 32 fragments per unit (fragment-order activations at batch 16: 57344x8192 VQ 5 bit
+// 66 -> 57 us, 4096x14336 SQ 18.3 -> 13.9 us); at batch <= 4 there are 2 - 8 loads per unit and
+// the flat form (QpXPtr: the lane's own pointer, also used for the copy in LDS that the in-kernel
+// rotation leaves) measured the same or better.
+struct QpXBuf {
+    static constexpr bool TIE_REFILLS = true;
+    __amdgpu_buffer_rsrc_t rsrc;
+    int soff;      // bytes to the unit's column block
+    uint32_t lo;   // the lane's bytes
+    int xfs;       // bytes between fragments
+    __device__ __forceinline__ half8_t frag(int n, uint32_t lane_off) const {
+        return __builtin_bit_cast(half8_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)lane_off, soff + xfs * n, 0));
+    }
+    __device__ __forceinline__ half8_t frag(int n) const { return frag(n, lo); }
+};
+struct QpXPtr {
+    static constexpr bool TIE_REFILLS = false;
+    const half_t *p;   // the lane's first fragment of the unit
+    uint32_t lo;       // unused (0)
+    int xfs;           // halves between fragments
+    __device__ __forceinline__ half8_t frag(int n, uint32_t) const { return frag(n); }
+    __device__ __forceinline__ half8_t frag(int n) const { return *reinterpret_cast<const half8_t *>(p + xfs * n); }
+};
+
+template <int P, int PF, bool OPTIONAL_LAST, class XS>
+__device__ __forceinline__ void qp_unit_load(const u32x4_t *src, int ps, const XS &xs, bool full,
                                              u32x4_t (&q)[P], half8_t (&xf)[PF]) {
 #pragma unroll
-    for (int n = 0; n < PF; ++n) xf[n] = *reinterpret_cast<const half8_t *>(xu + xfs * n);
+    for (int n = 0; n < PF; ++n) xf[n] = xs.frag(n);
     qp_pieces_load<P, OPTIONAL_LAST>(src, ps, full, q);
 }
 
@@ -566,9 +596,9 @@ __device__ __forceinline__ void qp_half_pieces_load(const u32x4_t *src, int ps, 
 // their partial dot products in v.
 // S0, S1: the steps done here (a whole unit, or one half of it when two wavefronts share a
 // unit); xf[i] holds fragment S0 / TT + i on entry.
-template <class D, int P, int PF, int TT, int S0 = 0, int S1 = 32>
-__device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8_t (&xf)[PF], const half_t *xu,
-                                                    int xfs, const uint8_t *tab, typename D::Lane &lc,
+template <class D, int P, int PF, int TT, int S0 = 0, int S1 = 32, class XS>
+__device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8_t (&xf)[PF], const XS &xs,
+                                                    const uint8_t *tab, typename D::Lane &lc,
                                                     const typename D::Pre &pre) {
     constexpr int N0 = S0 / TT, N1 = S1 / TT;   // fragments N0 .. N1 - 1
 #ifdef QP_NODECODE  // development builds only: loads without decode, to time the memory side alone
@@ -594,6 +624,7 @@ __device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8
     for (int t = 0; t < NACC; ++t) acc[t] = float4_t{0.f, 0.f, 0.f, 0.f};
     u32x4_t masked[NM];
     uint32_t keep[NM];
+    uint32_t xlo = xs.lo, dep = 0;
 #pragma unroll
     for (int m = 0; m < NM; ++m) {
         keep[m] = (lane_t / NACC) == m ? 0xffffffffu : 0u;
@@ -613,10 +644,17 @@ __device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8
                     for (int r = 0; r < 4; ++r) masked[m][r] = raw[r] & keep[m];   // (an AND issues in 2.3 clocks, a select in 3.8)
                 }
             }
-            if constexpr (n + PF < N1)  // the raw fragment is spent: refill its slot
-                xf[(n - N0) % PF] = *reinterpret_cast<const half8_t *>(xu + xfs * (n + PF));
+            if constexpr (n + PF < N1) {  // the raw fragment is spent: refill its slot
+                // One step per fragment (batch 9 - 16): the refill is tied to the previous step's
+                // decoded operand.  Left free, the scheduler hoists the refills of many steps to the
+                // top of the unit, runs out of registers and spills fragments - and a spill store
+                // waits for every load in flight.
+                if constexpr (TT == 1 && n > N0 && XS::TIE_REFILLS) asm volatile("" : "+v"(xlo) : "v"(dep));
+                xf[(n - N0) % PF] = xs.frag(n + PF, xlo);
+            }
         }
         half8_t a = qp_step<D, P, s>(q, tab, lc, pre);
+        if constexpr (TT == 1 && XS::TIE_REFILLS) dep = __builtin_bit_cast(u32x4_t, a)[3];
         acc[t % NACC] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, __builtin_bit_cast(half8_t, masked[t / NACC]),
                                                                acc[t % NACC], 0, 0, 0);
 #ifdef QP_TRACE
@@ -770,13 +808,27 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     // at row bj, column 1024 C + 256 g + 8 (TT n + tj)) or already in fragment order
     // (x_packed: fragment n of column block C is the 1 KiB at ((C NXF + n) 64 + lane) 16).
     // XL: fragment order in LDS, written by the rotation below.
+    // (not for the V = 1 trellis: bound by its table lookups, and with the buffer form the compiler's
+    // register allocation at batch 9 - 16 came out worse for 2 and 4 bits - 19.7 -> 23.7 us, 24.7 -> 36.4 us)
+    constexpr bool XBUF = !XL && BP >= 8 && S != QP_TCQ;
+    // the lane's part of the address: a 32-bit byte offset (the host checks that it fits) or its pointer
+    const uint32_t xlo = x_packed ? 16u * lane : 2u * ((uint32_t)(xlive ? bj : 0) * (uint32_t)ldx + 256u * g + 8u * tj);
     const half_t *xlane = XL ? xr_lds + 8 * lane
                              : (x_packed ? x + 8 * lane : x + (int64_t)(xlive ? bj : 0) * ldx + 256 * g + 8 * tj);
     const int xcs = (XL || x_packed) ? 1024 * BP : 1024;   // halves between column blocks
     const int xfs = (XL || x_packed) ? 512 : 8 * TT;       // halves between fragments
+    // extent of the activations in bytes: a load beyond it would return zeros instead of faulting
+    const uint32_t xbytes = x_packed ? (uint32_t)nbc * (2048u * BP) : 2u * ((uint32_t)(B - 1) * (uint32_t)ldx + 1024u * (uint32_t)nbc);
+    auto x_at = [&](int C) __attribute__((always_inline)) {
+        if constexpr (XBUF)
+            return QpXBuf{__builtin_amdgcn_make_buffer_rsrc(const_cast<half_t *>(x), 0, (int)xbytes, 0x00020000),
+                          2 * C * xcs, xlo, 2 * xfs};
+        else
+            return QpXPtr{xlane + C * xcs, 0u, xfs};
+    };
     const bool owner = (tj == 0) && xlive;  // lane (g, b*TT) ends up with rows 4g..4g+3 of batch row b
     half8_t xf[PF];
-    const half_t *xu = xlane + (uu - ((uu * nbc_magic) >> 16) * nbc) * xcs;   // column block = uu % nbc
+    const auto xu = x_at(uu - ((uu * nbc_magic) >> 16) * nbc);   // column block = uu % nbc
     const int xn0 = half1 ? PF : 0;   // first fragment of this item
     // XL: the unrotated activations and their signs are requested first, ahead of the weights
     float rv[16];
@@ -788,7 +840,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
         else qp_fwht_fetch<16>(t < 512, t, x, signs, rv);
     } else {
 #pragma unroll
-        for (int n = 0; n < PF; ++n) xf[n] = *reinterpret_cast<const half8_t *>(xu + xfs * (xn0 + n));
+        for (int n = 0; n < PF; ++n) xf[n] = xu.frag(xn0 + n);
     }
     // block (row block rb0 + slot, column block C) of unit u = slot * nbc + C, and whether
     // it has all P pieces
@@ -890,7 +942,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
         else qp_fwht_finish<16, 8>(t < 512, t, rv, norm, rot_buf, put);
         __syncthreads();
 #pragma unroll
-        for (int n = 0; n < PF; ++n) xf[n] = *reinterpret_cast<const half8_t *>(xu + xfs * (xn0 + n));
+        for (int n = 0; n < PF; ++n) xf[n] = xu.frag(xn0 + n);
     }
     if constexpr (!MID_BUILD) {
         if (!MOVABLE || table_late) D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
@@ -899,13 +951,13 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     if (k < units) {
         float4_t v;
         if constexpr (SPLIT) {
-            if (half1) v = qp_unit_compute<D, P, PF, TT, 16, 32>(q, xf, xu, xfs, tab, lc, pre);
-            else v = qp_unit_compute<D, P, PF, TT, 0, 16>(q, xf, xu, xfs, tab, lc, pre);
+            if (half1) v = qp_unit_compute<D, P, PF, TT, 16, 32>(q, xf, xu, tab, lc, pre);
+            else v = qp_unit_compute<D, P, PF, TT, 0, 16>(q, xf, xu, tab, lc, pre);
         } else if constexpr (HH) {
-            if (full) v = qp_unit_compute<D, P, PF, TT>(q, xf, xu, xfs, tab, lc, pre);
-            else v = qp_unit_compute<typename D::Lo, P, PF, TT>(q, xf, xu, xfs, tab, lc, pre);
+            if (full) v = qp_unit_compute<D, P, PF, TT>(q, xf, xu, tab, lc, pre);
+            else v = qp_unit_compute<typename D::Lo, P, PF, TT>(q, xf, xu, tab, lc, pre);
         } else {
-            v = qp_unit_compute<D, P, PF, TT>(q, xf, xu, xfs, tab, lc, pre);
+            v = qp_unit_compute<D, P, PF, TT>(q, xf, xu, tab, lc, pre);
         }
         if (owner) *reinterpret_cast<float4_t *>(&red[(u * BP + bj) * 16 + 4 * g]) = v;
     }
@@ -922,7 +974,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
             const int ub = u / SPL;
             const bool h2 = SPLIT && __builtin_amdgcn_readfirstlane(u & 1);
             const int C = ub - ((ub * nbc_magic) >> 16) * nbc;
-            const half_t *xu2 = xlane + C * xcs;
+            const auto xu2 = x_at(C);
             u32x4_t q2[P];
             half8_t xf2[PF];
             bool full2;
@@ -931,18 +983,18 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
             if constexpr (SPLIT) {
                 const int n0 = h2 ? PF : 0;
 #pragma unroll
-                for (int n = 0; n < PF; ++n) xf2[n] = *reinterpret_cast<const half8_t *>(xu2 + xfs * (n0 + n));
+                for (int n = 0; n < PF; ++n) xf2[n] = xu2.frag(n0 + n);
                 if (h2) {
                     qp_half_pieces_load<S, CB, P, 1>(blk2, ps, q2);
-                    v = qp_unit_compute<D, P, PF, TT, 16, 32>(q2, xf2, xu2, xfs, tab, lc, pre);
+                    v = qp_unit_compute<D, P, PF, TT, 16, 32>(q2, xf2, xu2, tab, lc, pre);
                 } else {
                     qp_half_pieces_load<S, CB, P, 0>(blk2, ps, q2);
-                    v = qp_unit_compute<D, P, PF, TT, 0, 16>(q2, xf2, xu2, xfs, tab, lc, pre);
+                    v = qp_unit_compute<D, P, PF, TT, 0, 16>(q2, xf2, xu2, tab, lc, pre);
                 }
                 if (owner) *reinterpret_cast<float4_t *>(&red[(u * BP + bj) * 16 + 4 * g]) = v;
                 continue;
             }
-            qp_unit_load<P, PF, HH>(blk2, ps, xu2, xfs, full2, q2, xf2);
+            qp_unit_load<P, PF, HH>(blk2, ps, xu2, full2, q2, xf2);
             QP_T(8);
 #ifdef QP_TRACE
             const uint64_t tr_a = __builtin_amdgcn_s_memtime();
@@ -950,10 +1002,10 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
             const uint64_t tr_b = __builtin_amdgcn_s_memtime();
 #endif
             if constexpr (HH) {
-                if (full2) v = qp_unit_compute<D, P, PF, TT>(q2, xf2, xu2, xfs, tab, lc, pre);
-                else v = qp_unit_compute<typename D::Lo, P, PF, TT>(q2, xf2, xu2, xfs, tab, lc, pre);
+                if (full2) v = qp_unit_compute<D, P, PF, TT>(q2, xf2, xu2, tab, lc, pre);
+                else v = qp_unit_compute<typename D::Lo, P, PF, TT>(q2, xf2, xu2, tab, lc, pre);
             } else {
-                v = qp_unit_compute<D, P, PF, TT>(q2, xf2, xu2, xfs, tab, lc, pre);
+                v = qp_unit_compute<D, P, PF, TT>(q2, xf2, xu2, tab, lc, pre);
             }
             if (owner) *reinterpret_cast<float4_t *>(&red[(u * BP + bj) * 16 + 4 * g]) = v;
             QP_T(9);

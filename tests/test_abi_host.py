@@ -99,6 +99,7 @@ def test_linear_argument_errors_do_not_launch():
     assert call(0x4000, 17, 1024, 0x5000, 16) == 2
     assert call(0x4000, 1, 1000, 0x5000, 16) == 2
     assert call(0x4000, 1, 1028, 0x5000, 16) == 2
+    assert call(0x4000, 1, (1 << 26) + 8, 0x5000, 16) == 2      # row stride beyond QP_MAX_LDX
     assert call(0x4000, 1, 1024, 0x5000, 8) == 2
     assert call(0x4008, 1, 1024, 0x5000, 16) == 4
     assert L.qp_dequant(C.byref(d), None, None) == 1
