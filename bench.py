@@ -465,9 +465,9 @@ def main():
     cases = []
     if not a.no_cases:
         del g_lin, g_had
-        todo = [(3, 0, 1), (3, 0, 4), (3, 0, 8), (2, 0, 1), (1, 0, 1),
+        todo = [(3, 0, 1), (3, 0, 4), (3, 0, 8), (3, 0, 16), (2, 0, 1), (1, 0, 1),
                 (4, 0, 1), (4, 1, 1), (4, 2, 1), (4, 3, 1), (4, 3, 8), (4, 3, 16), (4, 2, 8),
-                (5, 0, 1), (5, 1, 1), (5, 2, 1), (5, 3, 1), (5, 2, 8), (5, 3, 8),
+                (5, 0, 1), (5, 1, 1), (5, 2, 1), (5, 3, 1), (5, 2, 8), (5, 3, 8), (5, 3, 16),
                 (6, 0, 1), (6, 1, 1), (6, 2, 1), (6, 3, 1), (6, 1, 8), (6, 4, 1), (6, 5, 1), (6, 6, 1),
                 (6, 7, 1), (6, 8, 1), (6, 8, 8), (6, 9, 1)]
         for cfg, li, B in todo:
