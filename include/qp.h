@@ -47,7 +47,9 @@
  * first half followed by the N/2048 blocks of the second.
  *
  * All pointers named "device" are device (HBM) pointers owned by the caller; the
- * library allocates no device memory and keeps no mutable state.  Every entry
+ * library allocates no device memory.  Its only mutable state is the table of process-wide
+ * tuning options behind qp_set_option (kernel choices for tests and measurements; the defaults
+ * are the measured best choices and nothing reads the process environment).  Every entry
  * point validates its arguments on the host first and returns a QP_ERR_* code
  * without touching the device when they are bad; it then only enqueues kernels on
  * the given hipStream_t (passed as void*; NULL is the default stream) and returns
@@ -219,8 +221,45 @@ size_t qp_kmeans_workspace_bytes(int32_t k, int32_t d);   /* 0 for unsupported k
 /* Bytes of the native code buffer for this layer, 0 if it has no native form. */
 size_t qp_native_bytes(const qp_weight *canonical);
 
-/* Scratch bytes qp_linear needs for (w, B); 0 when no cross-workgroup reduction is used. */
+/* Bytes of the optional workspace with which qp_linear runs (w, B) fastest: room for a copy of the
+ * activations in the order the layer's kernel reads them (see qp_linear), a multiple of 256;
+ * 0 where no copy is made (most layers at batch <= 4, small layers, bad arguments). */
 size_t qp_linear_workspace_bytes(const qp_weight *w, int32_t B);
+
+/* Process-wide tuning options (Appendix E.2 profiles every kernel on its own: these switches say
+ * which of the library's kernels that is).  They exist for tests, which must reach every kernel
+ * with layers of any size, and for measurements; the defaults are the measured best choices.
+ * Plain integers read on the host when a call is dispatched - no environment variable is read and
+ * a call costs nothing for them.  Set them while no other thread is inside the library;
+ * qp_linear_workspace_bytes / qp_linear (and the rotate pair) must see the same values.
+ *   QP_OPT_LINEAR_KERNEL   0 by shape (default), 1 one wavefront per row, 2 the 16 x 1024 block kernel
+ *                          wherever the layer consists of whole blocks
+ *   QP_OPT_DEQUANT_KERNEL  0 by shape, 1 layout-agnostic kernel, 2 block kernel (native layout)
+ *   QP_OPT_ROTATE_SPLIT    1: qp_rotate_linear never rotates inside the layer's kernel
+ *   QP_OPT_LINEAR_PACK     -1 by shape, 0 qp_linear never asks for a workspace, 1 always (block kernel)
+ *   QP_OPT_LINEAR_SPLIT    -1 by shape, 0 / 1 the alternative form of the block kernel off / on where
+ *                          it exists (two wavefronts per unit; per-wavefront table for 5-bit VQ)
+ *   QP_OPT_WG_PER_CU       workgroups per compute unit of the block kernel (SQ / VQ; default 1)
+ *   QP_OPT_NW              0 by shape, 4..16 wavefronts per workgroup of the block kernel (SQ / VQ)
+ *   QP_OPT_TABLE_LATE_MAX  -1 by shape; units per workgroup up to which a shared table is built
+ *                          after the first loads
+ * qp_set_option: QP_ERR_UNSUPPORTED for an unknown option, QP_ERR_SHAPE for a value outside its
+ * range; qp_get_option returns the current value (INT32_MIN for an unknown option);
+ * qp_reset_options restores every default. */
+typedef enum {
+    QP_OPT_LINEAR_KERNEL = 0,
+    QP_OPT_DEQUANT_KERNEL = 1,
+    QP_OPT_ROTATE_SPLIT = 2,
+    QP_OPT_LINEAR_PACK = 3,
+    QP_OPT_LINEAR_SPLIT = 4,
+    QP_OPT_WG_PER_CU = 5,
+    QP_OPT_NW = 6,
+    QP_OPT_TABLE_LATE_MAX = 7,
+    QP_OPT_COUNT = 8
+} qp_option;
+qp_status qp_set_option(int32_t option, int32_t value);
+int32_t qp_get_option(int32_t option);
+void qp_reset_options(void);
 
 /* Check a descriptor alone (what qp_linear / qp_dequant check first). */
 qp_status qp_validate(const qp_weight *w);

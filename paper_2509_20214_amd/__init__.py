@@ -6,12 +6,13 @@ arguments (torch tensors -> device pointers, the current HIP stream).  Every
 step of the path runs in the library's HIP kernels; there is no CPU fallback —
 if the library cannot be loaded, importing `binding` users fail loudly.
 """
+from .binding import *  # noqa: F401,F403  (the option constants QP_OPT_*, QP_KERNEL_*, QP_DEQUANT_*)
 from .binding import (QP_SQ, QP_VQ, QP_TCQ, QP_TCQH, QP_TCQHH, QP_LAYOUT_CANONICAL, QP_LAYOUT_NATIVE, QpError, Weight,
                       load_library, qp_dequant, qp_hadamard, qp_linear, qp_linear_workspace_bytes,
                       qp_encode, qp_encode_workspace_bytes, qp_kmeans, qp_kmeans_workspace_bytes, qp_msq_solve, qp_row_normalize, qp_native_bytes, qp_repack, qp_rotate_linear, qp_rotate_linear_workspace_bytes,
-                      qp_status_string, qp_validate, qp_version)
+                      qp_status_string, qp_validate, qp_version, qp_set_option, qp_get_option, qp_reset_options)
 
 __all__ = ["QP_SQ", "QP_VQ", "QP_TCQ", "QP_TCQH", "QP_TCQHH", "QP_LAYOUT_CANONICAL", "QP_LAYOUT_NATIVE", "QpError", "Weight",
            "load_library", "qp_dequant", "qp_hadamard", "qp_linear", "qp_linear_workspace_bytes",
            "qp_encode", "qp_encode_workspace_bytes", "qp_kmeans", "qp_kmeans_workspace_bytes", "qp_msq_solve", "qp_row_normalize", "qp_native_bytes", "qp_repack", "qp_rotate_linear", "qp_rotate_linear_workspace_bytes",
-           "qp_status_string", "qp_validate", "qp_version"]
+           "qp_status_string", "qp_validate", "qp_version", "qp_set_option", "qp_get_option", "qp_reset_options"]

@@ -14,7 +14,14 @@ QP_OK = 0
 EXPORTS = ["qp_linear", "qp_dequant", "qp_hadamard", "qp_repack", "qp_native_bytes",
            "qp_linear_workspace_bytes", "qp_validate", "qp_status_string", "qp_version",
            "qp_rotate_linear", "qp_rotate_linear_workspace_bytes", "qp_encode", "qp_encode_workspace_bytes",
-           "qp_row_normalize", "qp_msq_solve", "qp_kmeans", "qp_kmeans_workspace_bytes"]
+           "qp_row_normalize", "qp_msq_solve", "qp_kmeans", "qp_kmeans_workspace_bytes",
+           "qp_set_option", "qp_get_option", "qp_reset_options"]
+
+# qp_option (include/qp.h)
+QP_OPT_LINEAR_KERNEL, QP_OPT_DEQUANT_KERNEL, QP_OPT_ROTATE_SPLIT, QP_OPT_LINEAR_PACK = 0, 1, 2, 3
+QP_OPT_LINEAR_SPLIT, QP_OPT_WG_PER_CU, QP_OPT_NW, QP_OPT_TABLE_LATE_MAX = 4, 5, 6, 7
+QP_KERNEL_AUTO, QP_KERNEL_ROW, QP_KERNEL_BLOCK = 0, 1, 2            # values of QP_OPT_LINEAR_KERNEL
+QP_DEQUANT_AUTO, QP_DEQUANT_GENERIC, QP_DEQUANT_BLOCKS = 0, 1, 2    # values of QP_OPT_DEQUANT_KERNEL
 
 
 class qp_weight(C.Structure):
@@ -86,6 +93,12 @@ def load_library(build_if_missing: bool = True):
     L.qp_status_string.argtypes = [C.c_int]
     L.qp_version.restype = i32
     L.qp_version.argtypes = []
+    L.qp_set_option.restype = C.c_int
+    L.qp_set_option.argtypes = [i32, i32]
+    L.qp_get_option.restype = i32
+    L.qp_get_option.argtypes = [i32]
+    L.qp_reset_options.restype = None
+    L.qp_reset_options.argtypes = []
     _lib = L
     return L
 
@@ -96,6 +109,18 @@ def qp_status_string(code: int) -> str:
 
 def qp_version() -> int:
     return int(load_library().qp_version())
+
+
+def qp_set_option(option: int, value: int) -> None:
+    _check(load_library().qp_set_option(int(option), int(value)), "qp_set_option")
+
+
+def qp_get_option(option: int) -> int:
+    return int(load_library().qp_get_option(int(option)))
+
+
+def qp_reset_options() -> None:
+    load_library().qp_reset_options()
 
 
 def _stream_ptr(stream):
@@ -316,3 +341,4 @@ def qp_rotate_linear(w: Weight, x, signs, block: int, y=None, workspace=None, st
                                            y.data_ptr(), y.stride(0), workspace.data_ptr(),
                                            workspace.numel(), _stream_ptr(stream)), "qp_rotate_linear")
     return y
+

@@ -1,11 +1,47 @@
 // C ABI: host-side validation and dispatch.  No device memory is allocated here and
 // no call synchronises with the device.
-#include <cstdlib>
+#include <atomic>
+#include <climits>
 #include <cstring>
 
 #include "qp_internal.h"
 
-#define QP_VERSION 100
+#define QP_VERSION 200
+
+// ------------------------------------------------------------------ tuning options
+// Plain process-wide integers (relaxed atomics: a read is an ordinary load); nothing here or
+// elsewhere in the library reads the environment.
+struct QpOptSpec { int32_t def, lo, hi; };
+static const QpOptSpec kOptSpec[QP_OPT_COUNT] = {
+    {0, 0, 2},       // QP_OPT_LINEAR_KERNEL
+    {0, 0, 2},       // QP_OPT_DEQUANT_KERNEL
+    {0, 0, 1},       // QP_OPT_ROTATE_SPLIT
+    {-1, -1, 1},     // QP_OPT_LINEAR_PACK
+    {-1, -1, 1},     // QP_OPT_LINEAR_SPLIT
+    {1, 1, 4},       // QP_OPT_WG_PER_CU
+    {0, 0, 16},      // QP_OPT_NW
+    {-1, -1, 4096},  // QP_OPT_TABLE_LATE_MAX
+};
+static std::atomic<int32_t> g_opt[QP_OPT_COUNT] = {{0}, {0}, {0}, {-1}, {-1}, {1}, {0}, {-1}};
+
+int32_t qp_opt(int option) { return g_opt[option].load(std::memory_order_relaxed); }
+
+extern "C" qp_status qp_set_option(int32_t option, int32_t value) {
+    if (option < 0 || option >= QP_OPT_COUNT) return QP_ERR_UNSUPPORTED;
+    if (value < kOptSpec[option].lo || value > kOptSpec[option].hi) return QP_ERR_SHAPE;
+    if (option == QP_OPT_NW && value != 0 && value < 4) return QP_ERR_SHAPE;
+    g_opt[option].store(value, std::memory_order_relaxed);
+    return QP_OK;
+}
+
+extern "C" int32_t qp_get_option(int32_t option) {
+    if (option < 0 || option >= QP_OPT_COUNT) return INT32_MIN;
+    return qp_opt(option);
+}
+
+extern "C" void qp_reset_options(void) {
+    for (int o = 0; o < QP_OPT_COUNT; ++o) g_opt[o].store(kOptSpec[o].def, std::memory_order_relaxed);
+}
 
 static inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
@@ -83,21 +119,21 @@ static QpW make_dev(const qp_weight *w) {
     return d;
 }
 
-// Which kernel runs a layer.  QP_LINEAR_KERNEL=rowwave / mfma forces one (used by the tests
-// to cover both on weights of any size); anything else lets the shape decide.
+// Which kernel runs a layer.  QP_OPT_LINEAR_KERNEL = 1 / 2 forces the row / the block kernel (used
+// by the tests to cover both on weights of any size); 0 lets the shape decide.
 // The matrix-core kernel pays a fixed table-build and reduction cost per workgroup; below
 // one 16x1024 block per CU (measured: 1024x1024 runs 3.2 us on the row kernel, 6.4 us on
 // the block kernel) the row kernel is the faster one.
 static bool use_rowwave(const qp_weight *w) {
     const int nbc = w->N / 1024;
-    const char *force = getenv("QP_LINEAR_KERNEL");
+    const int force = qp_opt(QP_OPT_LINEAR_KERNEL);
     const int64_t blocks = (int64_t)(w->M / 16) * nbc;
     // the block kernel needs whole 16 x 1024 blocks; it reads them from either layout (in the
     // canonical one a lane's pieces are consecutive in its row instead of one KiB per piece)
     const bool fits = w->M % 16 == 0 && w->N % 1024 == 0 && nbc <= 32 &&
                       !(w->scheme == QP_TCQHH && w->N % 2048 != 0);
-    bool rowwave = !fits || blocks < 256 || (force && strcmp(force, "rowwave") == 0);
-    if (force && strcmp(force, "mfma") == 0 && fits) rowwave = false;
+    bool rowwave = !fits || blocks < 256 || force == 1;
+    if (force == 2 && fits) rowwave = false;
     return rowwave;
 }
 
@@ -117,7 +153,7 @@ static inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 // any small kernel between them - an effect of the launch sequence, not of the layout.
 static bool pack_pays(const qp_weight *w, int B) {
     if (use_rowwave(w)) return false;
-    if (const char *e = getenv("QP_LINEAR_PACK")) return e[0] == '1';   // development hook: always / never
+    if (const int force = qp_opt(QP_OPT_LINEAR_PACK); force >= 0) return force == 1;   // always / never
     const int64_t weights = (int64_t)w->M * w->N;
     if (B > 8) return weights >= ((int64_t)1 << 25);
     if (B > 4) return w->scheme != QP_TCQ && weights >= ((int64_t)1 << 27);
@@ -180,9 +216,8 @@ extern "C" qp_status qp_rotate_linear(const qp_weight *w, const void *x, const i
     }
     // Batch 1 and one rotation block (N a power of two up to 8192): the layer's kernel rotates
     // the activations itself while its first weights are on their way - every workgroup repeats
-    // the small transform, and the second launch is saved.  QP_ROTATE=split forces two launches.
-    const char *force = getenv("QP_ROTATE");
-    if (B == 1 && block == w->N && block >= 1024 && block <= 8192 && !(force && strcmp(force, "split") == 0))
+    // the small transform, and the second launch is saved.  QP_OPT_ROTATE_SPLIT forces two launches.
+    if (B == 1 && block == w->N && block >= 1024 && block <= 8192 && !qp_opt(QP_OPT_ROTATE_SPLIT))
         return qp_launch_linear_mfma(d, w->scheme, w->code_bits, x, 1, ldx, y, ldy, 0, signs, block, st);
     s = qp_launch_hadamard(x, signs, B, w->N, block, ldx, workspace, w->N, pow2_at_least(B), st);
     if (s != QP_OK) return s;
@@ -196,11 +231,11 @@ extern "C" qp_status qp_dequant(const qp_weight *w, void *W_out, void *hip_strea
     if (!aligned(W_out, 16)) return QP_ERR_ALIGN;
     // Native layout: one block per wavefront with the fused kernel's decoders, unless the layer
     // has fewer blocks than the chip has CUs (its table set-up would dominate: 1024 x 1024
-    // takes 6.5 us there, 2.9 us on the layout-agnostic kernel).  QP_DEQUANT_KERNEL=generic /
-    // blocks forces one (the tests cover both on native-layout weights of any size).
-    const char *force = getenv("QP_DEQUANT_KERNEL");
-    const bool small = (int64_t)(w->M / 16) * (w->N / 1024) < 256 && !(force && strcmp(force, "blocks") == 0);
-    if (w->layout == QP_LAYOUT_NATIVE && !small && !(force && strcmp(force, "generic") == 0))
+    // takes 6.5 us there, 2.9 us on the layout-agnostic kernel).  QP_OPT_DEQUANT_KERNEL = 1 / 2
+    // forces the layout-agnostic / the block kernel (the tests cover both on weights of any size).
+    const int force = qp_opt(QP_OPT_DEQUANT_KERNEL);
+    const bool small = (int64_t)(w->M / 16) * (w->N / 1024) < 256 && force != 2;
+    if (w->layout == QP_LAYOUT_NATIVE && !small && force != 1)
         return qp_launch_dequant_blocks(make_dev(w), w->scheme, w->code_bits, W_out,
                                         static_cast<hipStream_t>(hip_stream));
     return qp_launch_dequant(make_dev(w), w->scheme, w->code_bits, W_out, static_cast<hipStream_t>(hip_stream));
@@ -276,7 +311,7 @@ static qp_status encode_check(const qp_weight *w) {
 
 extern "C" size_t qp_encode_workspace_bytes(const qp_weight *w) {
     if (encode_check(w) != QP_OK) return 0;
-    const size_t per_wg = qp_encode_min_workspace(w->scheme, w->code_bits + (w->scheme == QP_TCQHH ? 0 : 0));
+    const size_t per_wg = qp_encode_min_workspace(w->scheme, w->code_bits);
     int64_t tiles = (int64_t)w->M * (w->N / 256);
     if (w->scheme == QP_TCQHH) tiles /= 2;
     const int64_t wgs = tiles < 256 ? tiles : 256;

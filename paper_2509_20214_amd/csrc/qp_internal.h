@@ -33,6 +33,9 @@ qp_status qp_launch_kmeans(const float *x, int64_t n, int d, float *centres, int
                            void *workspace, int32_t *assign_out, uint16_t *centres_f16, double *stats_out,
                            hipStream_t st);
 
+// current value of a tuning option (qp_option); defined beside qp_set_option
+int32_t qp_opt(int option);
+
 static inline qp_status qp_check_launch() {
     return hipGetLastError() == hipSuccess ? QP_OK : QP_ERR_DEVICE;
 }

@@ -47,7 +47,6 @@
 // row blocks; the G * (N / 1024) units of a pass are dealt round-robin to the
 // wavefronts, each unit's partial sums go to LDS, and after a barrier the workgroup
 // adds them up in a fixed order, applies the per-row scale and stores fp16.
-#include <cstdlib>
 #include <type_traits>
 
 #include "qp_internal.h"
@@ -64,18 +63,44 @@
 #ifndef QP_UMAX_SMALL_BATCH
 #define QP_UMAX_SMALL_BATCH 128
 #endif
+#ifdef QP_TRACE   // (the timestamps take 2 KiB of LDS; the 128 KiB trellis table leaves room for 28 units at batch 16 then)
+constexpr int qp_umax(int BP) { return BP == 1 ? QP_UMAX_SMALL_BATCH : (BP <= 4 ? 64 : BP <= 8 ? 32 : 28); }
+#else
 constexpr int qp_umax(int BP) { return BP == 1 ? QP_UMAX_SMALL_BATCH : (BP <= 4 ? 64 : 32); }
+#endif
 
 #ifdef QP_TRACE  // development builds only: per-wavefront timestamps of the kernel's phases
+// Kept in LDS while the kernel runs (a store to global memory would queue behind the weight loads and
+// disturb what it measures) and written out by each wavefront when it ends.
 __device__ uint64_t *qp_trace_buf;
 extern "C" void qp_debug_set_trace(void *p) { (void)hipMemcpyToSymbol(HIP_SYMBOL(qp_trace_buf), &p, sizeof(p)); }
+__shared__ uint64_t qp_trace_lds[16 * 16];
+// ticks of s_memtime against the 100 MHz constant clock: out[0..1] ticks, out[2..3] 10 ns units
+__global__ void k_debug_calibrate(uint64_t *out) {
+    const uint64_t t0 = __builtin_amdgcn_s_memtime(), r0 = __builtin_amdgcn_s_memrealtime();
+    for (int i = 0; i < 20000; ++i) __builtin_amdgcn_s_sleep(8);
+    const uint64_t t1 = __builtin_amdgcn_s_memtime(), r1 = __builtin_amdgcn_s_memrealtime();
+    if (threadIdx.x == 0) { out[0] = t0; out[1] = t1; out[2] = r0; out[3] = r1; }
+}
+extern "C" void qp_debug_calibrate(void *out) { hipLaunchKernelGGL(k_debug_calibrate, dim3(1), dim3(64), 0, 0, (uint64_t *)out); }
 #define QP_T(slot)                                                                                   \
     do {                                                                                             \
-        if ((threadIdx.x & 63) == 0)                                                                 \
-            qp_trace_buf[((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 16 + (slot)] = __builtin_amdgcn_s_memtime(); \
+        if ((threadIdx.x & 63) == 0) qp_trace_lds[(threadIdx.x >> 6) * 16 + (slot)] = __builtin_amdgcn_s_memtime(); \
+    } while (0)
+#define QP_T_INIT()                                                                                  \
+    do {                                                                                             \
+        if ((threadIdx.x & 63) < 16) qp_trace_lds[(threadIdx.x >> 6) * 16 + (threadIdx.x & 15)] = 0;    \
+    } while (0)
+#define QP_T_FLUSH()                                                                                 \
+    do {                                                                                             \
+        if ((threadIdx.x & 63) < 16)                                                                 \
+            qp_trace_buf[((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 16 + (threadIdx.x & 15)] =    \
+                qp_trace_lds[(threadIdx.x >> 6) * 16 + (threadIdx.x & 15)];                          \
     } while (0)
 #else
 #define QP_T(slot)
+#define QP_T_INIT()
+#define QP_T_FLUSH()
 #endif
 
 // ------------------------------------------------------------------ bit fields
@@ -754,6 +779,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     constexpr int PFMAX = (BP == 16) ? QP_PF_MAX16 : 8;
     constexpr int PF = SPLIT ? NXF / 2 : ((NXF < PFMAX) ? NXF : PFMAX);   // fragments kept in flight
     constexpr int BLK16 = T::BLOCK_BYTES / 16;
+    QP_T_INIT();
     QP_T(0);
 
     // ---- first pass, straight-line up to the first loads ------------------------------
@@ -1031,9 +1057,10 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     QP_T(6);
 #ifdef QP_TRACE
     if ((threadIdx.x & 63) == 0) {
-        uint64_t *tb = &qp_trace_buf[((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 16];
+        uint64_t *tb = &qp_trace_lds[(threadIdx.x >> 6) * 16];
         tb[10] = tr_wait; tb[11] = tr_dec; tb[12] = tr_units;
     }
+    QP_T_FLUSH();
 #endif
 }
 
@@ -1102,10 +1129,8 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
     const int nbc = w.nbc, rbk = w.M / 16;
     if (nbc < 1 || nbc > QP_NBC_MAX) return QP_ERR_UNSUPPORTED;
     const int umax = qp_umax(B <= 1 ? 1 : B <= 2 ? 2 : B <= 4 ? 4 : B <= 8 ? 8 : 16);
-    // Development hooks: workgroups per compute unit and wavefronts per workgroup.
-    int wg_per_cu = 1, nw_forced = 0;
-    if (const char *e = getenv("QP_LINEAR_WG_PER_CU")) wg_per_cu = atoi(e) > 0 ? atoi(e) : 1;
-    if (const char *e = getenv("QP_LINEAR_NW")) nw_forced = atoi(e);
+    // Tuning options: workgroups per compute unit and wavefronts per workgroup.
+    int wg_per_cu = qp_opt(QP_OPT_WG_PER_CU), nw_forced = qp_opt(QP_OPT_NW);
     const bool big_table = (scheme == QP_TCQ || scheme == QP_TCQH || scheme == QP_TCQHH);
     if (big_table) { wg_per_cu = 1; nw_forced = 0; }
     int grid = rbk < 256 * wg_per_cu ? rbk : 256 * wg_per_cu;
@@ -1119,22 +1144,18 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
     // wavefronts: the decode work of the trellis schemes then spreads over all SIMDs.  Measured:
     // 3 .. 5 % faster from 6 units per workgroup on (4096x14336: 14 units, 6144x4096: 6), a few
     // per cent slower at 4 units (4096x4096), where the second copy of the shared pieces costs
-    // more than the idle SIMDs.  QP_LINEAR_SPLIT=0 / 1 switches it off / on wherever it is legal.
+    // more than the idle SIMDs.  QP_OPT_LINEAR_SPLIT = 0 / 1 switches it off / on wherever it is legal.
+    const int split_opt = qp_opt(QP_OPT_LINEAR_SPLIT);
     const bool can_split = (scheme == QP_TCQ || scheme == QP_TCQH) && B <= 2 && units <= 16;
     bool split = can_split && units >= 6;
-    {
-        const char *e = getenv("QP_LINEAR_SPLIT");
-        if (e && e[0] == '0') split = false;
-        if (e && e[0] == '1') split = can_split;
-    }
+    if (split_opt == 0) split = false;
+    if (split_opt == 1) split = can_split;
     // VQ 5 bit: the per-wavefront table while a workgroup has at most one unit per wavefront, at the
     // batch sizes where it measured faster than the workgroup's byte-window table (4096x14336,
     // us per call, per-wavefront / shared: batch 1 7.3 / 6.7, 2 7.35 / 7.07, 3 7.7 / 7.9, 4 7.8 / 8.7,
     // 8 10.85 / 10.1, 16 with fragment-order activations 14.05 / 15.4).
     if (scheme == QP_VQ && cb == 5 && rb_per_wg * nbc <= 16 && ((B > 2 && B <= 4) || (B > 8 && x_packed))) {
-        split = true;
-        const char *e = getenv("QP_LINEAR_SPLIT");
-        if (e && e[0] == '0') split = false;
+        split = split_opt != 0;
     }
     int nw = units < 16 ? units : 16;
     if (scheme == QP_TCQ || scheme == QP_TCQH || scheme == QP_TCQHH) nw = 16;  // the table staging is written for 1024 threads
@@ -1150,7 +1171,7 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
     // the workgroup has few units, and at batch >= 4 with row-major activations (whose many
     // small loads then start earlier); before them otherwise.
     int late_max = (!x_packed && B >= 4) ? 1024 : 8;
-    if (const char *e = getenv("QP_TABLE_LATE_MAX")) late_max = atoi(e);
+    if (const int forced = qp_opt(QP_OPT_TABLE_LATE_MAX); forced >= 0) late_max = forced;
     const int x_flags = (x_packed ? 1 : 0) | (late_max << 8);
 #define CALL_BP(S, C, BP) \
     qp_launch_one<S, C, BP>(split, grid, nw, st, w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_flags, signs, \

@@ -25,7 +25,7 @@ def test_library_loads_and_exports_every_declared_symbol():
     assert set(syms) == set(binding.EXPORTS)
     for s in syms:
         assert hasattr(L, s), s
-    assert qp.qp_version() >= 100
+    assert qp.qp_version() >= 200
     assert qp.qp_status_string(0) == "ok"
     for code in range(1, 8):
         assert qp.qp_status_string(code) not in ("ok", "unknown status")
@@ -221,3 +221,25 @@ def test_kmeans_rejects_bad_arguments_on_the_host():
     assert call(n=0) == 2 and call(max_iter=0) == 2 and call(tol=-1.0) == 2
     assert call(samples=0x1004) == 4 and call(workspace=0x3008) == 4 and call(stats=0x4004) == 4
     assert call(workspace_bytes=ws - 1) == 7
+
+
+def test_options_are_plain_integers_with_ranges():
+    """qp_set_option / qp_get_option / qp_reset_options: host state only, no device needed."""
+    L = qp.load_library()
+    defaults = [L.qp_get_option(o) for o in range(8)]
+    assert defaults == [0, 0, 0, -1, -1, 1, 0, -1]
+    try:
+        assert L.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, 2) == 0 and L.qp_get_option(qp.QP_OPT_LINEAR_KERNEL) == 2
+        assert L.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, 3) == 2          # out of range: QP_ERR_SHAPE, value kept
+        assert L.qp_get_option(qp.QP_OPT_LINEAR_KERNEL) == 2
+        assert L.qp_set_option(qp.QP_OPT_NW, 2) == 2 and L.qp_set_option(qp.QP_OPT_NW, 8) == 0
+        assert L.qp_set_option(99, 0) == 3 and L.qp_set_option(-1, 0) == 3  # QP_ERR_UNSUPPORTED
+        assert L.qp_get_option(99) == -2 ** 31
+        # the forced kernel shows in what qp_linear_workspace_bytes answers (block kernel + always pack)
+        w = desc(M=16, N=1024)
+        assert L.qp_linear_workspace_bytes(C.byref(w), 16) == 0
+        L.qp_set_option(qp.QP_OPT_LINEAR_PACK, 1)
+        assert L.qp_linear_workspace_bytes(C.byref(w), 16) == 16 * 1024 * 2
+    finally:
+        L.qp_reset_options()
+    assert [L.qp_get_option(o) for o in range(8)] == defaults

@@ -13,15 +13,6 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 
-@pytest.fixture(scope="module")
-def qp():
-    if not torch.cuda.is_available():
-        pytest.skip("no GPU")
-    import paper_2509_20214_amd as m
-    m.load_library()
-    return m
-
-
 def dev16(a):
     return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda().view(torch.float16)
 
@@ -158,7 +149,7 @@ def test_half_tcq_encoder(qp, s):
                 e[:, 2:].reshape(-1), s + 1, 2, table, 0.7, two_pass=s <= 5)
 
 
-def test_encode_then_linear_end_to_end(qp, monkeypatch):
+def test_encode_then_linear_end_to_end(qp):
     """Quantize a Gaussian matrix on the GPU, repack, multiply: the product differs from the
     product with the unquantized matrix by what the quantizer's distortion predicts."""
     s, M, N, B = 6, 48, 2048, 4
@@ -168,7 +159,7 @@ def test_encode_then_linear_end_to_end(qp, monkeypatch):
     w.scales.fill_(0x3C00)   # fp16 1.0: the check is about W^, not the scales
     qp.qp_encode(w, dev16(Wt))
     x = synth.make_x(94, 0, B, N)
-    monkeypatch.setenv("QP_LINEAR_KERNEL", "mfma")
+    qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_BLOCK)
     y = qp.qp_linear(qp.qp_repack(w), dev16(x)).cpu().numpy().astype(np.float64)
     lay_g = synth.Layer(**{**lay.__dict__, "codes": w.codes.cpu().numpy(), "scales": np.ones(M, dtype=np.float16)})
     want = oracle.linear(lay_g, x)
@@ -198,7 +189,7 @@ def test_row_normalize(qp):
     assert np.allclose((out ** 2).mean(1)[np.arange(M) != 5], 1.0, atol=3e-3)
 
 
-def test_offline_path_then_online_path(qp, monkeypatch):
+def test_offline_path_then_online_path(qp):
     """A dense weight matrix through the whole offline path (rotate rows, scale, encode, repack),
     then the online path on unrotated activations: y approximates x W^T as closely as the
     quantizer's distortion allows (Section 3.3: X W = (X R)(R^T W))."""
@@ -214,7 +205,7 @@ def test_offline_path_then_online_path(qp, monkeypatch):
     Wr = qp.qp_hadamard(dev16(Wfull), sgd, block)
     w.scales.copy_(qp.qp_row_normalize(Wr).view(torch.int16))
     qp.qp_encode(w, Wr)
-    monkeypatch.setenv("QP_LINEAR_KERNEL", "mfma")
+    qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_BLOCK)
     y = qp.qp_rotate_linear(qp.qp_repack(w), dev16(x), sgd, block).cpu().numpy().astype(np.float64)
     exact = oracle.half_to_double(x) @ oracle.half_to_double(Wfull).T
     rel = np.linalg.norm(y - exact) / np.linalg.norm(exact)

@@ -28,15 +28,6 @@ CASES = [  # (cfg, layer index, batches)
 ]
 
 
-@pytest.fixture(scope="module")
-def qp():
-    if not torch.cuda.is_available():
-        pytest.skip("no GPU")
-    import paper_2509_20214_amd as m
-    m.load_library()
-    return m
-
-
 def sample_rows(M, k=24, seed=0):
     g = np.random.default_rng(seed)
     rows = set(int(r) for r in g.integers(0, M, size=k))

@@ -17,15 +17,6 @@ CASES = [(synth.SQ, 4, 4096, 8192, 9), (synth.VQ, 5, 4096, 8192, 16), (synth.VQ,
          (synth.VQ, 7, 8192, 16384, 8), (synth.SQ, 4, 16384, 8192, 5), (synth.TCQH, 5, 8192, 16384, 7)]
 
 
-@pytest.fixture(scope="module")
-def qp():
-    if not torch.cuda.is_available():
-        pytest.skip("no GPU")
-    import paper_2509_20214_amd as m
-    m.load_library()
-    return m
-
-
 def dev(a):
     if a.dtype == np.float16:
         return torch.from_numpy(a.view(np.int16)).cuda().view(torch.float16)

@@ -20,15 +20,6 @@ IDS = ["sq4", "vq5", "vq7", "tcq2", "tcq3", "tcq4", "tcqh1.5", "tcqh2", "tcqh2.5
 TOL = 1e-2
 
 
-@pytest.fixture(scope="module")
-def qp():
-    if not torch.cuda.is_available():
-        pytest.skip("no GPU")
-    import paper_2509_20214_amd as m
-    m.load_library()
-    return m
-
-
 def dev(a):
     if a.dtype == np.float16:
         return torch.from_numpy(a.view(np.int16)).cuda().view(torch.float16)
@@ -48,7 +39,7 @@ def rel_err(y_gpu_u16, y_ref):
 @pytest.mark.parametrize("scheme,cb", SCHEMES, ids=IDS)
 @pytest.mark.parametrize("layout,M,N", [("canonical", 40, 1280), ("canonical", 33, 256), ("native", 48, 3072),
                                         ("native-generic", 48, 3072), ("native", 4128, 2048)])
-def test_dequant_bit_exact(qp, scheme, cb, layout, M, N, monkeypatch):
+def test_dequant_bit_exact(qp, scheme, cb, layout, M, N):
     """canonical -> the layout-agnostic kernel; native -> one block per wavefront with the fused
     kernel's decoders (M = 4128: 516 blocks, more than one per wavefront of the grid and a ragged
     last round); native-generic -> the layout-agnostic kernel reading the native layout."""
@@ -57,7 +48,7 @@ def test_dequant_bit_exact(qp, scheme, cb, layout, M, N, monkeypatch):
     w = qp.Weight.from_layer(lay)
     if layout.startswith("native"):
         w = qp.qp_repack(w)
-    monkeypatch.setenv("QP_DEQUANT_KERNEL", "generic" if layout == "native-generic" else "blocks")
+    qp.qp_set_option(qp.QP_OPT_DEQUANT_KERNEL, qp.QP_DEQUANT_GENERIC if layout == "native-generic" else qp.QP_DEQUANT_BLOCKS)
     got = host16(qp.qp_dequant(w))
     assert np.array_equal(got, want)
 
@@ -86,7 +77,7 @@ def test_repack_layout_is_as_documented(qp):
 @pytest.mark.parametrize("layout,M,N", [("canonical", 40, 1280), ("native", 48, 3072), ("native-rowwave", 48, 3072),
                                         ("native", 1040, 2048), ("native", 16, 14336)])
 @pytest.mark.parametrize("B", [1, 2, 3, 4, 5, 8, 13, 16])
-def test_linear_matches_oracle(qp, scheme, cb, layout, M, N, B, monkeypatch):
+def test_linear_matches_oracle(qp, scheme, cb, layout, M, N, B):
     """canonical -> one wavefront per row; native -> the matrix-core kernel (several row
     blocks per workgroup at M=1040, 14 column blocks at N=14336); native-rowwave -> the
     row kernel reading the native layout."""
@@ -97,7 +88,7 @@ def test_linear_matches_oracle(qp, scheme, cb, layout, M, N, B, monkeypatch):
     if layout.startswith("native"):
         w = qp.qp_repack(w)
     # small test layers would be routed to the row kernel by size: force the one under test
-    monkeypatch.setenv("QP_LINEAR_KERNEL", "rowwave" if layout == "native-rowwave" else "mfma")
+    qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_ROW if layout == "native-rowwave" else qp.QP_KERNEL_BLOCK)
     y = qp.qp_linear(w, dev(x))
     torch.cuda.synchronize()
     assert rel_err(host16(y), want) <= TOL
@@ -162,7 +153,7 @@ def test_hadamard_in_place_and_strided(qp):
 
 # ---------------------------------------------------------------- chained
 @pytest.mark.parametrize("scheme,cb", SCHEMES, ids=IDS)
-def test_rotation_then_linear_matches_fp64_chain(qp, scheme, cb, monkeypatch):
+def test_rotation_then_linear_matches_fp64_chain(qp, scheme, cb):
     """Whole hot path: rotate x on the GPU, multiply on the GPU; the oracle stays in
     fp64 from the fp16 x to the end."""
     M, N, B = 64, 2048, 2
@@ -173,8 +164,8 @@ def test_rotation_then_linear_matches_fp64_chain(qp, scheme, cb, monkeypatch):
     want = oracle.linear(lay, oracle.hadamard(x, sg, block))
     w = qp.qp_repack(qp.Weight.from_layer(lay))
     xr = qp.qp_hadamard(dev(x), dev(sg), block)
-    for kernel in ("mfma", "rowwave"):
-        monkeypatch.setenv("QP_LINEAR_KERNEL", kernel)
+    for kernel in (qp.QP_KERNEL_BLOCK, qp.QP_KERNEL_ROW):
+        qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, kernel)
         y = qp.qp_linear(w, xr)
         assert rel_err(host16(y), want) <= TOL
 
@@ -182,7 +173,7 @@ def test_rotation_then_linear_matches_fp64_chain(qp, scheme, cb, monkeypatch):
 # ---------------------------------------------------- rotation fused into the launch
 @pytest.mark.parametrize("scheme,cb", SCHEMES, ids=IDS)
 @pytest.mark.parametrize("B", [1, 2, 3, 4, 8, 13, 16])
-def test_rotate_linear_matches_oracle_and_unfused(qp, scheme, cb, B, monkeypatch):
+def test_rotate_linear_matches_oracle_and_unfused(qp, scheme, cb, B):
     """One call = rotation + layer; the rotated activations pass through the workspace in the
     block kernel's own fragment order.  Must equal the two-call sequence (row-major
     activations) bit for bit - same arithmetic, fp16 rotated activations in between - and
@@ -193,7 +184,7 @@ def test_rotate_linear_matches_oracle_and_unfused(qp, scheme, cb, B, monkeypatch
     sg = synth.make_signs(78, 1, N)
     want = oracle.linear(lay, oracle.hadamard(x, sg, block), threads=True)
     w = qp.qp_repack(qp.Weight.from_layer(lay))
-    monkeypatch.setenv("QP_LINEAR_KERNEL", "mfma")
+    qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_BLOCK)
     xd, sd = dev(x), dev(sg)
     y2 = qp.qp_linear(w, qp.qp_hadamard(xd, sd, block))
     ws = torch.empty(qp.qp_rotate_linear_workspace_bytes(w, B), dtype=torch.uint8, device="cuda")
@@ -204,7 +195,7 @@ def test_rotate_linear_matches_oracle_and_unfused(qp, scheme, cb, B, monkeypatch
         assert torch.equal(y1, y2)
 
 
-def test_rotate_linear_strided_x(qp, monkeypatch):
+def test_rotate_linear_strided_x(qp):
     lay = synth.make_layer(79, 2, synth.VQ, 256, 2048, 5)
     B, ldx = 2, 2048 + 64
     x = synth.make_x(79, 2, B, 2048)
@@ -212,12 +203,12 @@ def test_rotate_linear_strided_x(qp, monkeypatch):
     want = oracle.linear(lay, oracle.hadamard(x, sg, 1024))
     buf = torch.zeros((B, ldx), dtype=torch.float16, device="cuda")
     buf[:, :2048] = dev(x)
-    monkeypatch.setenv("QP_LINEAR_KERNEL", "mfma")
+    qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_BLOCK)
     y = qp.qp_rotate_linear(qp.qp_repack(qp.Weight.from_layer(lay)), buf[:, :2048], dev(sg), 1024)
     assert rel_err(host16(y), want) <= TOL
 
 
-def test_rotate_linear_other_shapes_fall_back_to_two_launches(qp, monkeypatch):
+def test_rotate_linear_other_shapes_fall_back_to_two_launches(qp):
     lay = synth.make_layer(79, 0, synth.VQ, 64, 4096, 5)
     x = synth.make_x(79, 0, 2, 4096)
     sg = synth.make_signs(79, 0, 4096)
@@ -238,13 +229,13 @@ HH_IDS = [f"tcqhh{s / 2 + 0.25}" for s in range(3, 10)]
 @pytest.mark.parametrize("scheme,cb", HH, ids=HH_IDS)
 @pytest.mark.parametrize("layout,M,N", [("canonical", 40, 1536), ("canonical", 33, 512), ("native", 48, 4096),
                                         ("native-generic", 48, 4096), ("native", 4128, 2048)])
-def test_half_tcq_dequant_bit_exact(qp, scheme, cb, layout, M, N, monkeypatch):
+def test_half_tcq_dequant_bit_exact(qp, scheme, cb, layout, M, N):
     lay = synth.make_layer(80, cb, scheme, M, N, cb)
     want = oracle.decode(lay)
     w = qp.Weight.from_layer(lay)
     if layout.startswith("native"):
         w = qp.qp_repack(w)
-    monkeypatch.setenv("QP_DEQUANT_KERNEL", "generic" if layout == "native-generic" else "blocks")
+    qp.qp_set_option(qp.QP_OPT_DEQUANT_KERNEL, qp.QP_DEQUANT_GENERIC if layout == "native-generic" else qp.QP_DEQUANT_BLOCKS)
     assert np.array_equal(host16(qp.qp_dequant(w)), want)
 
 
@@ -277,14 +268,14 @@ def test_half_tcq_repack_layout_is_as_documented(qp):
 @pytest.mark.parametrize("layout,M,N", [("canonical", 40, 1536), ("native", 48, 4096), ("native-rowwave", 48, 4096),
                                         ("native", 1040, 2048), ("native", 16, 14336)])
 @pytest.mark.parametrize("B", [1, 2, 3, 8, 16])
-def test_half_tcq_linear_matches_oracle(qp, scheme, cb, layout, M, N, B, monkeypatch):
+def test_half_tcq_linear_matches_oracle(qp, scheme, cb, layout, M, N, B):
     lay = synth.make_layer(82, cb, scheme, M, N, cb)
     x = synth.make_x(82, B, B, N)
     want = oracle.linear(lay, x, threads=True)
     w = qp.Weight.from_layer(lay)
     if layout.startswith("native"):
         w = qp.qp_repack(w)
-    monkeypatch.setenv("QP_LINEAR_KERNEL", "rowwave" if layout == "native-rowwave" else "mfma")
+    qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_ROW if layout == "native-rowwave" else qp.QP_KERNEL_BLOCK)
     y = qp.qp_linear(w, dev(x))
     torch.cuda.synchronize()
     assert rel_err(host16(y), want) <= TOL
@@ -292,14 +283,14 @@ def test_half_tcq_linear_matches_oracle(qp, scheme, cb, layout, M, N, B, monkeyp
 
 @pytest.mark.parametrize("scheme,cb", HH, ids=HH_IDS)
 @pytest.mark.parametrize("B", [1, 4, 13])
-def test_half_tcq_rotate_linear(qp, scheme, cb, B, monkeypatch):
+def test_half_tcq_rotate_linear(qp, scheme, cb, B):
     M, N, block = 272, 4096, 1024
     lay = synth.make_layer(83, cb, scheme, M, N, cb)
     x = synth.make_x(83, B, B, N)
     sg = synth.make_signs(83, 1, N)
     want = oracle.linear(lay, oracle.hadamard(x, sg, block), threads=True)
     w = qp.qp_repack(qp.Weight.from_layer(lay))
-    monkeypatch.setenv("QP_LINEAR_KERNEL", "mfma")
+    qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_BLOCK)
     xd, sd = dev(x), dev(sg)
     y2 = qp.qp_linear(w, qp.qp_hadamard(xd, sd, block))
     y1 = qp.qp_rotate_linear(w, xd, sd, block)
@@ -315,20 +306,20 @@ ALL_IDS = IDS + HH_IDS
 
 @pytest.mark.parametrize("scheme,cb", ALL, ids=ALL_IDS)
 @pytest.mark.parametrize("M,N", [(272, 2048), (48, 4096), (1040, 4096), (32, 8192)])
-def test_rotate_linear_in_kernel_rotation(qp, scheme, cb, M, N, monkeypatch):
+def test_rotate_linear_in_kernel_rotation(qp, scheme, cb, M, N):
     """Batch 1 and one Hadamard block: qp_rotate_linear is a single launch whose workgroups
     rotate the activations themselves.  Same bits as rotation kernel + layer kernel, and the
-    fp64 chain within tolerance; the split path stays available (QP_ROTATE=split)."""
+    fp64 chain within tolerance; the split path stays available (QP_OPT_ROTATE_SPLIT)."""
     lay = synth.make_layer(84, scheme * 10 + cb, scheme, M, N, cb)
     x = synth.make_x(84, N, 1, N)
     sg = synth.make_signs(84, N, N)
     want = oracle.linear(lay, oracle.hadamard(x, sg, N, fast=True), threads=True)
     w = qp.qp_repack(qp.Weight.from_layer(lay))
-    monkeypatch.setenv("QP_LINEAR_KERNEL", "mfma")
+    qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_BLOCK)
     xd, sd = dev(x), dev(sg)
     y_two = qp.qp_linear(w, qp.qp_hadamard(xd, sd, N))
     y_one = qp.qp_rotate_linear(w, xd, sd, N)
-    monkeypatch.setenv("QP_ROTATE", "split")
+    qp.qp_set_option(qp.QP_OPT_ROTATE_SPLIT, 1)
     y_split = qp.qp_rotate_linear(w, xd, sd, N)
     torch.cuda.synchronize()
     assert rel_err(host16(y_one), want) <= TOL
@@ -336,12 +327,12 @@ def test_rotate_linear_in_kernel_rotation(qp, scheme, cb, M, N, monkeypatch):
     assert torch.equal(y_split, y_two)
 
 
-def test_rotate_linear_in_kernel_rotation_block_1024(qp, monkeypatch):
+def test_rotate_linear_in_kernel_rotation_block_1024(qp):
     lay = synth.make_layer(85, 0, synth.VQ, 4096, 1024, 5)
     x = synth.make_x(85, 0, 1, 1024)
     sg = synth.make_signs(85, 0, 1024)
     w = qp.qp_repack(qp.Weight.from_layer(lay))
-    monkeypatch.setenv("QP_LINEAR_KERNEL", "mfma")
+    qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_BLOCK)
     y = qp.qp_rotate_linear(w, dev(x), dev(sg), 1024)
     assert rel_err(host16(y), oracle.linear(lay, oracle.hadamard(x, sg, 1024), threads=True)) <= TOL
     assert torch.equal(y, qp.qp_linear(w, qp.qp_hadamard(dev(x), dev(sg), 1024)))
@@ -352,7 +343,7 @@ def test_rotate_linear_in_kernel_rotation_block_1024(qp, monkeypatch):
                          ids=["tcq2", "tcq3", "tcq4"] + [f"tcqh{s / 2}" for s in range(3, 11)])
 @pytest.mark.parametrize("M,N,B", [(48, 4096, 1), (1040, 2048, 2), (16, 14336, 1), (272, 3072, 2)])
 @pytest.mark.parametrize("split", ["0", "1"])
-def test_linear_two_wavefronts_per_unit(qp, scheme, cb, M, N, B, split, monkeypatch):
+def test_linear_two_wavefronts_per_unit(qp, scheme, cb, M, N, B, split):
     """The trellis kernels at batch <= 2 exist in two forms: one wavefront per 16 x 1024 unit, or
     two, each decoding half of its steps from only the pieces it needs.  Both forms, at unit
     counts on either side of the automatic choice."""
@@ -360,18 +351,18 @@ def test_linear_two_wavefronts_per_unit(qp, scheme, cb, M, N, B, split, monkeypa
     x = synth.make_x(86, B, B, N)
     want = oracle.linear(lay, x, threads=True)
     w = qp.qp_repack(qp.Weight.from_layer(lay))
-    monkeypatch.setenv("QP_LINEAR_KERNEL", "mfma")
-    monkeypatch.setenv("QP_LINEAR_SPLIT", split)
+    qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_BLOCK)
+    qp.qp_set_option(qp.QP_OPT_LINEAR_SPLIT, int(split))
     y = qp.qp_linear(w, dev(x))
     torch.cuda.synchronize()
     assert rel_err(host16(y), want) <= TOL
 
 
-def test_calls_captured_in_a_hip_graph_replay_identically(qp, monkeypatch):
+def test_calls_captured_in_a_hip_graph_replay_identically(qp):
     """The library only enqueues kernels (no allocation, no memset, no synchronisation), so a
     sequence of its calls can be captured once and replayed: three replays, with eager work in
     between, each equal to the eager results."""
-    monkeypatch.setenv("QP_LINEAR_KERNEL", "mfma")
+    qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_BLOCK)
     lay_a = synth.make_layer(87, 0, synth.TCQH, 272, 4096, 5)
     lay_b = synth.make_layer(87, 1, synth.VQ, 4096, 3072, 5)
     wa, wb = qp.qp_repack(qp.Weight.from_layer(lay_a)), qp.qp_repack(qp.Weight.from_layer(lay_b))
@@ -410,13 +401,13 @@ def test_calls_captured_in_a_hip_graph_replay_identically(qp, monkeypatch):
 
 @pytest.mark.parametrize("scheme,cb", ALL, ids=ALL_IDS)
 @pytest.mark.parametrize("M,N,B", [(48, 4096, 1), (1040, 2048, 3), (16, 14336, 8), (272, 6144, 16)])
-def test_block_kernel_on_canonical_layout(qp, scheme, cb, M, N, B, monkeypatch):
+def test_block_kernel_on_canonical_layout(qp, scheme, cb, M, N, B):
     """The matrix-core kernel reads whole 16 x 1024 blocks straight from the canonical bitstream
     (no repack; a padded row stride included) with the same result as from the native layout."""
     lay = synth.make_layer(89, scheme * 10 + cb, scheme, M, N, cb)
     x = synth.make_x(89, B, B, N)
     want = oracle.linear(lay, x, threads=True)
-    monkeypatch.setenv("QP_LINEAR_KERNEL", "mfma")
+    qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_BLOCK)
     w = qp.Weight.from_layer(lay)
     y = qp.qp_linear(w, dev(x))
     y_nat = qp.qp_linear(qp.qp_repack(w), dev(x))

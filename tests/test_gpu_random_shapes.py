@@ -38,15 +38,6 @@ def cases():
     return out
 
 
-@pytest.fixture(scope="module")
-def qp():
-    if not torch.cuda.is_available():
-        pytest.skip("no GPU")
-    import paper_2509_20214_amd as m
-    m.load_library()
-    return m
-
-
 def dev(a):
     if a.dtype == np.float16:
         return torch.from_numpy(a.view(np.int16)).cuda().view(torch.float16)
@@ -55,7 +46,7 @@ def dev(a):
 
 @pytest.mark.parametrize("k,scheme,cb,M,N,B", cases(),
                          ids=[f"{k}-{synth.SCHEME_NAMES[s]}{cb}-{M}x{N}-b{B}" for k, s, cb, M, N, B in cases()])
-def test_random_shape(qp, k, scheme, cb, M, N, B, monkeypatch):
+def test_random_shape(qp, k, scheme, cb, M, N, B):
     lay = synth.make_layer(88, k, scheme, M, N, cb)
     x = synth.make_x(88, k, B, N)
     block = synth.hadamard_block(N)
@@ -63,7 +54,7 @@ def test_random_shape(qp, k, scheme, cb, M, N, B, monkeypatch):
         block = 1024
     sg = synth.make_signs(88, k, N)
     w = qp.qp_repack(qp.Weight.from_layer(lay))
-    monkeypatch.setenv("QP_LINEAR_KERNEL", "mfma")
+    qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_BLOCK)
     xd, sd = dev(x), dev(sg)
     xr = qp.qp_hadamard(xd, sd, block)
     y = qp.qp_linear(w, xr)
