@@ -49,7 +49,8 @@
  * All pointers named "device" are device (HBM) pointers owned by the caller; the
  * library allocates no device memory.  Its only mutable state is the table of process-wide
  * tuning options behind qp_set_option (kernel choices for tests and measurements; the defaults
- * are the measured best choices and nothing reads the process environment).  Every entry
+ * are the measured best choices and nothing reads the process environment) and the fixed
+ * scratch array of qp_rotate_linear_static.  Every entry
  * point validates its arguments on the host first and returns a QP_ERR_* code
  * without touching the device when they are bad; it then only enqueues kernels on
  * the given hipStream_t (passed as void*; NULL is the default stream) and returns
@@ -155,6 +156,20 @@ qp_status qp_rotate_linear(const qp_weight *w, const void *x, const int8_t *sign
                            int64_t ldx, void *y, int64_t ldy, void *workspace, size_t workspace_bytes,
                            void *hip_stream);
 size_t qp_rotate_linear_workspace_bytes(const qp_weight *w, int32_t B);
+
+/* qp_rotate_linear for callers that cannot allocate device memory or hand in a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * without the workspace, same kernels, same result bit for bit; the rotated activations pass
+ * through a fixed array of qp_rotate_linear_static_max_bytes() = 1 MiB of device memory that
+ * belongs to the library (one per GPU, held until the process ends).  Nothing is allocated or
+ * freed, here or in any routine this calls.  Layers with qp_rotate_linear_workspace_bytes(w, B)
+ * above that size (N > 32768 at batch 16) are refused with QP_ERR_WORKSPACE; QP_ERR_DEVICE if the
+ * array's address cannot be obtained on the current device.  All calls on one GPU share the
+ * array: calls that overlap in time on one GPU (two streams, two threads) race on it and must be
+ * serialised by the caller; calls that follow each other on one stream are safe. */
+qp_status qp_rotate_linear_static(const qp_weight *w, const void *x, const int8_t *signs, int32_t block,
+                                  int32_t B, int64_t ldx, void *y, int64_t ldy, void *hip_stream);
+size_t qp_rotate_linear_static_max_bytes(void);
 
 /* One-time conversion canonical -> native.  `canonical` describes device codes in
  * canonical layout; native_codes is a device buffer of `bytes` >=

@@ -15,7 +15,8 @@ EXPORTS = ["qp_linear", "qp_dequant", "qp_hadamard", "qp_repack", "qp_native_byt
            "qp_linear_workspace_bytes", "qp_validate", "qp_status_string", "qp_version",
            "qp_rotate_linear", "qp_rotate_linear_workspace_bytes", "qp_encode", "qp_encode_workspace_bytes",
            "qp_row_normalize", "qp_msq_solve", "qp_kmeans", "qp_kmeans_workspace_bytes",
-           "qp_set_option", "qp_get_option", "qp_reset_options"]
+           "qp_set_option", "qp_get_option", "qp_reset_options", "qp_rotate_linear_static",
+           "qp_rotate_linear_static_max_bytes"]
 
 # qp_option (include/qp.h)
 QP_OPT_LINEAR_KERNEL, QP_OPT_DEQUANT_KERNEL, QP_OPT_ROTATE_SPLIT, QP_OPT_LINEAR_PACK = 0, 1, 2, 3
@@ -62,6 +63,10 @@ def load_library(build_if_missing: bool = True):
     L.qp_linear.argtypes = [wp, vp, i32, i64, vp, i64, vp, sz, vp]
     L.qp_rotate_linear.restype = C.c_int
     L.qp_rotate_linear.argtypes = [wp, vp, vp, i32, i32, i64, vp, i64, vp, sz, vp]
+    L.qp_rotate_linear_static.restype = C.c_int
+    L.qp_rotate_linear_static.argtypes = [wp, vp, vp, i32, i32, i64, vp, i64, vp]
+    L.qp_rotate_linear_static_max_bytes.restype = sz
+    L.qp_rotate_linear_static_max_bytes.argtypes = []
     L.qp_rotate_linear_workspace_bytes.restype = sz
     L.qp_rotate_linear_workspace_bytes.argtypes = [wp, i32]
     L.qp_dequant.restype = C.c_int
@@ -342,3 +347,16 @@ def qp_rotate_linear(w: Weight, x, signs, block: int, y=None, workspace=None, st
                                            workspace.numel(), _stream_ptr(stream)), "qp_rotate_linear")
     return y
 
+
+def qp_rotate_linear_static_max_bytes() -> int:
+    return int(load_library().qp_rotate_linear_static_max_bytes())
+
+
+def qp_rotate_linear_static(w: Weight, x, signs, block: int, y, stream=None):
+    """qp_rotate_linear through the library's own fixed scratch array: nothing is allocated, so the
+    output y (fp16 [B, M]) must be passed in."""
+    B = x.shape[0]
+    _check(load_library().qp_rotate_linear_static(C.byref(w.desc), x.data_ptr(), signs.data_ptr(), block, B,
+                                                  x.stride(0), y.data_ptr(), y.stride(0), _stream_ptr(stream)),
+           "qp_rotate_linear_static")
+    return y

@@ -224,6 +224,46 @@ extern "C" qp_status qp_rotate_linear(const qp_weight *w, const void *x, const i
     return qp_launch_linear_mfma(d, w->scheme, w->code_bits, workspace, B, w->N, y, ldy, 1, nullptr, 0, st);
 }
 
+// ------------------------------------------------------------------ the entry point that allocates nothing
+// qp_rotate_linear for callers that cannot allocate: the rotated activations pass through this fixed
+// array instead of a caller's workspace.  One copy per GPU, there until the process ends.  The array's
+// name is only a handle on the host; its device address is looked up once per device.
+#define QP_STATIC_SCRATCH_BYTES ((size_t)QP_MAX_BATCH * 32 * 1024 * 2)   // batch 16 x N = 32768 fp16
+#define QP_MAX_DEVICES 64
+static __device__ __align__(256) unsigned char scratch[QP_STATIC_SCRATCH_BYTES];
+static std::atomic<void *> g_scratch_ptr[QP_MAX_DEVICES];
+
+// Device address of `scratch` on the current device; nullptr when it cannot be had.
+static void *scratch_address() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= QP_MAX_DEVICES) return nullptr;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    g_scratch_ptr[dev].store(p, std::memory_order_release);   // (two threads racing here store the same address)
+    return p;
+}
+
+extern "C" size_t qp_rotate_linear_static_max_bytes(void) { return QP_STATIC_SCRATCH_BYTES; }
+
+extern "C" qp_status qp_rotate_linear_static(const qp_weight *w, const void *x, const int8_t *signs, int32_t block,
+                                             int32_t B, int64_t ldx, void *y, int64_t ldy, void *hip_stream) {
+    qp_status s = qp_validate(w);
+    if (s != QP_OK) return s;
+    if (B < 1 || B > QP_MAX_BATCH) return QP_ERR_SHAPE;
+    const size_t need = qp_rotate_linear_workspace_bytes(w, B);
+    if (need == 0 || need > QP_STATIC_SCRATCH_BYTES) return QP_ERR_WORKSPACE;   // layer too wide for the fixed array
+    void *ws = scratch_address();
+    if (!ws) return QP_ERR_DEVICE;
+    // Nothing has to be cleared between calls: the rotation writes the B batch rows that the layer's
+    // results depend on; what the layer reads of the padding rows (B rounded up to a power of two) is
+    // whatever an earlier call left and only reaches accumulator columns that are never stored.
+    return qp_rotate_linear(w, x, signs, block, B, ldx, y, ldy, ws, QP_STATIC_SCRATCH_BYTES, hip_stream);
+}
+
 extern "C" qp_status qp_dequant(const qp_weight *w, void *W_out, void *hip_stream) {
     qp_status s = qp_validate(w);
     if (s != QP_OK) return s;
