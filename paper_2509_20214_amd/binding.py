@@ -180,7 +180,9 @@ class Weight:
     @property
     def code_bytes(self) -> int:
         d = self.desc
-        return d.M * (d.N // d.vec * d.code_bits // 8)
+        if d.scheme == QP_TCQHH:   # code_bits per step on the first half of the columns, one more on the second
+            return d.M * (d.N // 4 * (2 * d.code_bits + 1) // 8)
+        return d.M * ((d.N // d.vec * d.code_bits + 7) // 8)
 
 
 def qp_validate(w: Weight) -> int:

@@ -78,7 +78,7 @@ static qp_status scheme_supported(const qp_weight *w) {
 
 static inline int64_t row_bytes(const qp_weight *w) {
     if (w->scheme == QP_TCQHH) return (int64_t)w->N / 4 * (2 * w->code_bits + 1) / 8;
-    return (int64_t)w->N / w->vec * w->code_bits / 8;
+    return ((int64_t)w->N / w->vec * w->code_bits + 7) / 8;   // a row of 5- or 7-bit codes may end inside a byte
 }
 static inline int span_bytes(const qp_weight *w) { return 32 * w->code_bits / w->vec; }
 

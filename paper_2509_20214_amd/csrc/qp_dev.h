@@ -91,8 +91,11 @@ __device__ __forceinline__ uint64_t qp_group_bits(const QpW &w, int row, int grp
         int off = grp * T::BITS8;
         r = off & 31;
         d0 = off >> 5;
-        d1 = d0 + 1;
-        if (d1 * 4 >= (w.N / 8) * T::BITS8 / 8) d1 = d0;   // last dword of the row: nothing beyond is needed
+        // The next dword is read only when the group's BITS8 bits reach into it.  It then holds at
+        // least one bit of the row, so it lies inside the row's bytes rounded up to a dword, which
+        // the row stride (a multiple of 16, at least the row's bytes rounded up) covers - also when a
+        // row of 5- or 7-bit codes ends in the middle of a byte.
+        d1 = (r + T::BITS8 > 32) ? d0 + 1 : d0;
     }
     uint32_t lo = *qp_dword_ptr<T::SPAN>(w, row, d0 * 4);
     uint32_t hi = *qp_dword_ptr<T::SPAN>(w, row, d1 * 4);

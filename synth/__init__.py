@@ -15,8 +15,9 @@ Why uniform random bytes stand in for real packed codes: after the rotation
 and per-output-channel scaling the weights are close to N(0,1) per column
 (Section 3.3 "Reducing rotation overhead"), the codebooks are fitted to
 N(0,1), so the codes of a well-designed quantizer are close to uniform; the
-row length in bytes is a whole number for every supported shape, so uniform
-bytes ARE uniform codes.  Byte traffic and lookup pattern are those of a real
+row length in bytes is a whole number for every benchmark shape, so uniform
+bytes ARE uniform codes (a vector-quantized row whose 5- or 7-bit codes end inside
+a byte gets that byte whole; its spare bits belong to no code).  Byte traffic and lookup pattern are those of a real
 layer.
 """
 from __future__ import annotations
@@ -141,9 +142,9 @@ def row_bytes_for(scheme: int, N: int, code_bits: int, vec: int) -> int:
             raise ValueError("each half must be whole 256-weight tiles")
         return row_bytes_for(TCQH, N // 2, code_bits, vec) + row_bytes_for(TCQH, N // 2, code_bits + 1, vec)
     bits = N // vec * code_bits
-    if bits % 8:
+    if bits % 8 and scheme != VQ:
         raise ValueError("row is not a whole number of bytes")
-    return bits // 8
+    return (bits + 7) // 8   # a row of 5- or 7-bit codes may end inside its last byte (the spare bits are never read)
 
 
 def make_layer(cfg: int, layer: int, scheme: int, M: int, N: int, code_bits: int,

@@ -45,6 +45,11 @@ def desc(**kw):
     (dict(scheme=qp.QP_VQ, vec=2, code_bits=6), 3),
     (dict(scheme=qp.QP_VQ, vec=2, code_bits=5, row_stride=320), 0),
     (dict(scheme=qp.QP_TCQ, code_bits=2, window_bits=16, tile=256, row_stride=256), 0),
+    # a row of 52 codes of 5 bits = 260 bits ends inside its 33rd byte: 32 bytes are one too few
+    (dict(scheme=qp.QP_VQ, vec=2, code_bits=5, N=104, row_stride=32), 2),
+    (dict(scheme=qp.QP_VQ, vec=2, code_bits=5, N=104, row_stride=48), 0),
+    (dict(scheme=qp.QP_VQ, vec=2, code_bits=7, N=120, row_stride=48), 2),   # 420 bits = 52.5 bytes
+    (dict(scheme=qp.QP_VQ, vec=2, code_bits=7, N=120, row_stride=64), 0),
     (dict(scheme=qp.QP_TCQ, code_bits=2, window_bits=12, tile=256, row_stride=256), 3),
     (dict(scheme=qp.QP_TCQ, code_bits=3, window_bits=16, tile=256, N=1000, row_stride=384), 2),
     (dict(scheme=qp.QP_TCQH, vec=2, code_bits=5, window_bits=16, tile=256, tlut_bits=9, row_stride=320), 0),

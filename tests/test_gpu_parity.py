@@ -53,6 +53,32 @@ def test_dequant_bit_exact(qp, scheme, cb, layout, M, N):
     assert np.array_equal(got, want)
 
 
+@pytest.mark.parametrize("cb,N", [(5, 40), (5, 104), (7, 56), (7, 120), (5, 1288), (7, 2104)])
+def test_vq_rows_that_end_inside_a_byte(qp, cb, N):
+    """5- and 7-bit codes: N / 2 codes need not fill whole bytes (N = 40: 100 bits).  The last code
+    pair of a row then sits in a dword whose upper bytes lie beyond the row's last whole byte."""
+    M = 37
+    lay = synth.make_layer(69, cb * 1000 + N, synth.VQ, M, N, cb)
+    # canonical stride: a multiple of 16 that holds the row's bytes, the padding filled with other
+    # values so that a read beyond the row would show
+    rb = lay.codes.shape[1]
+    stride = (rb + 15) // 16 * 16
+    padded = np.full((M, stride), 0xA5, dtype=np.uint8)
+    padded[:, :rb] = lay.codes
+    w = qp.Weight(lay.scheme, M, N, cb, 2, 0, 0, dev(padded), dev(lay.lut), dev(lay.scales), row_stride=stride)
+    assert qp.qp_validate(w) == 0
+    assert np.array_equal(host16(qp.qp_dequant(w)), oracle.decode(lay))
+    for B in (1, 3, 16):
+        x = synth.make_x(69, B, B, N)
+        assert rel_err(host16(qp.qp_linear(w, dev(x))), oracle.linear(lay, x)) <= TOL
+        # one-hot on the last column: the product is the row's last weight, exact to one rounding
+    e = np.zeros((1, N), dtype=np.float16)
+    e[0, N - 1] = 1.0
+    want = oracle.linear(lay, e)
+    y = host16(qp.qp_linear(w, dev(e))).view(np.float16).astype(np.float64)
+    assert np.all(np.abs(y - want) <= np.abs(want) * 2.0 ** -11 + 1e-7)
+
+
 def test_repack_layout_is_as_documented(qp):
     """Piece p of lane l = 16 g + i of block (R, C) holds canonical bytes
     [(4C+g)*span + 16p, +16) of row 16R+i."""

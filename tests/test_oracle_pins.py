@@ -85,9 +85,10 @@ def test_sq_decode_is_table_take(bits):
     assert np.array_equal(oracle.decode(lay), want)
 
 
+@pytest.mark.parametrize("N", [512, 40, 104, 56, 120])   # the last four: rows that end inside a byte
 @pytest.mark.parametrize("cbits", [3, 5, 7])
-def test_vq_decode_is_table_take(cbits):
-    M, N = 6, 512
+def test_vq_decode_is_table_take(cbits, N):
+    M = 6
     lay = synth.make_layer(91, cbits, synth.VQ, M, N, cbits)
     idx = unpack_indices_numpy(lay.codes, cbits, N // 2)
     want = np.take(lay.lut.view(np.uint16).reshape(-1, 2), idx, axis=0).reshape(M, N)
