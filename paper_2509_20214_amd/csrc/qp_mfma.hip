@@ -74,7 +74,8 @@ constexpr int qp_umax(int BP) { return BP == 1 ? QP_UMAX_SMALL_BATCH : (BP <= 4 
 // disturb what it measures) and written out by each wavefront when it ends.
 __device__ uint64_t *qp_trace_buf;
 extern "C" void qp_debug_set_trace(void *p) { (void)hipMemcpyToSymbol(HIP_SYMBOL(qp_trace_buf), &p, sizeof(p)); }
-__shared__ uint64_t qp_trace_lds[16 * 16];
+#define QP_TS 20   // slots per wavefront; 16 / 17: the 100 MHz clock that all XCDs share, at start / end
+__shared__ uint64_t qp_trace_lds[16 * QP_TS];
 // ticks of s_memtime against the 100 MHz constant clock: out[0..1] ticks, out[2..3] 10 ns units
 __global__ void k_debug_calibrate(uint64_t *out) {
     const uint64_t t0 = __builtin_amdgcn_s_memtime(), r0 = __builtin_amdgcn_s_memrealtime();
@@ -85,17 +86,18 @@ __global__ void k_debug_calibrate(uint64_t *out) {
 extern "C" void qp_debug_calibrate(void *out) { hipLaunchKernelGGL(k_debug_calibrate, dim3(1), dim3(64), 0, 0, (uint64_t *)out); }
 #define QP_T(slot)                                                                                   \
     do {                                                                                             \
-        if ((threadIdx.x & 63) == 0) qp_trace_lds[(threadIdx.x >> 6) * 16 + (slot)] = __builtin_amdgcn_s_memtime(); \
+        if ((threadIdx.x & 63) == 0) qp_trace_lds[(threadIdx.x >> 6) * QP_TS + (slot)] =                \
+            ((slot) == 16 || (slot) == 17 ? __builtin_amdgcn_s_memrealtime() : __builtin_amdgcn_s_memtime()); \
     } while (0)
 #define QP_T_INIT()                                                                                  \
     do {                                                                                             \
-        if ((threadIdx.x & 63) < 16) qp_trace_lds[(threadIdx.x >> 6) * 16 + (threadIdx.x & 15)] = 0;    \
+        if ((threadIdx.x & 63) < QP_TS) qp_trace_lds[(threadIdx.x >> 6) * QP_TS + (threadIdx.x & 63)] = 0; \
     } while (0)
 #define QP_T_FLUSH()                                                                                 \
     do {                                                                                             \
-        if ((threadIdx.x & 63) < 16)                                                                 \
-            qp_trace_buf[((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 16 + (threadIdx.x & 15)] =    \
-                qp_trace_lds[(threadIdx.x >> 6) * 16 + (threadIdx.x & 15)];                          \
+        if ((threadIdx.x & 63) < QP_TS)                                                              \
+            qp_trace_buf[((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * QP_TS + (threadIdx.x & 63)] = \
+                qp_trace_lds[(threadIdx.x >> 6) * QP_TS + (threadIdx.x & 63)];                       \
     } while (0)
 #else
 #define QP_T(slot)
@@ -584,7 +586,12 @@ struct QpXPtr {
     uint32_t lo;       // unused (0)
     int xfs;           // halves between fragments
     __device__ __forceinline__ half8_t frag(int n, uint32_t) const { return frag(n); }
-    __device__ __forceinline__ half8_t frag(int n) const { return *reinterpret_cast<const half8_t *>(p + xfs * n); }
+    __device__ __forceinline__ half8_t frag(int n) const {
+#ifdef QP_NOX  // development builds only: no activation loads, to time what they cost
+        return __builtin_bit_cast(half8_t, u32x4_t{(uint32_t)(uintptr_t)p, (uint32_t)n, 0x3c003c00u, 0x3c003c00u});
+#endif
+        return *reinterpret_cast<const half8_t *>(p + xfs * n);
+    }
 };
 
 template <int P, int PF, bool OPTIONAL_LAST, class XS>
@@ -629,6 +636,14 @@ __device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8
 #ifdef QP_NODECODE  // development builds only: loads without decode, to time the memory side alone
     {
         uint32_t z = 0;
+#ifdef QP_TRACE   // arrival of the first, the middle and the last piece (one load, the scale, was issued after them)
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(P) : "memory");
+        QP_T(18);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(P - P / 2) : "memory");
+        QP_T(19);
+        asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
+        QP_T(10);
+#endif
 #pragma unroll
         for (int p = 0; p < P; ++p) z ^= q[p][0] ^ q[p][1] ^ q[p][2] ^ q[p][3];
 #pragma unroll
@@ -780,6 +795,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     constexpr int PF = SPLIT ? NXF / 2 : ((NXF < PFMAX) ? NXF : PFMAX);   // fragments kept in flight
     constexpr int BLK16 = T::BLOCK_BYTES / 16;
     QP_T_INIT();
+    QP_T(16);
     QP_T(0);
 
     // ---- first pass, straight-line up to the first loads ------------------------------
@@ -1055,9 +1071,10 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
         }
     }
     QP_T(6);
+    QP_T(17);
 #ifdef QP_TRACE
-    if ((threadIdx.x & 63) == 0) {
-        uint64_t *tb = &qp_trace_lds[(threadIdx.x >> 6) * 16];
+    if ((threadIdx.x & 63) == 0 && tr_units) {
+        uint64_t *tb = &qp_trace_lds[(threadIdx.x >> 6) * QP_TS];
         tb[10] = tr_wait; tb[11] = tr_dec; tb[12] = tr_units;
     }
     QP_T_FLUSH();
