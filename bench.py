@@ -31,6 +31,20 @@ import numpy as np
 HBM_PEAK_GBS = 8000.0
 
 
+def committed_traffic(cfg, layer, batch):
+    """HBM bytes per qp_linear launch from the committed counter summaries under profiles/ (a line
+    `traffic_bytes_per_launch cfg<c> layer<l> batch<b> = <bytes>`), or None."""
+    import glob
+    import re
+    here = os.path.dirname(os.path.abspath(__file__))
+    pat = re.compile(rf"traffic_bytes_per_launch cfg{cfg} layer{layer} batch{batch} = (\d+)")
+    for path in sorted(glob.glob(os.path.join(here, "profiles", "*pmc*"))):
+        m = pat.search(open(path).read())
+        if m:
+            return int(m.group(1))
+    return None
+
+
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
@@ -319,10 +333,10 @@ def main():
         """One layer resident on the device: a ring of native-layout copies of its codes."""
 
         def __init__(self, cfg, li, B, ring_bytes=640 << 20):
+            self.cfg, self.li = cfg, li
             self.desc = synth.config_layers(cfg)[li]
             self.lay = synth.build(self.desc)
             lay = self.lay
-            self.B = B
             self.code_bytes = lay.code_bytes
             base = qp.Weight.from_layer(lay)
             nat = qp.qp_repack(base)
@@ -331,16 +345,28 @@ def main():
             for _ in range(n - 1):
                 self.ring.append(nat.with_codes(nat.codes.clone()))
             self.block = synth.hadamard_block(lay.N)
-            self.x = upload(synth.make_x(cfg, li, B, lay.N))
             self.signs = upload(synth.make_signs(cfg, li, lay.N))
+            self.sink = torch.zeros(4, dtype=torch.int32, device=dev)
+            self.i = 0
+            self.set_batch(B)
+
+        def set_batch(self, B):
+            """Activations, outputs and workspaces for batch B (the ring of codes stays)."""
+            lay, nat = self.lay, self.ring[0]
+            self.B = B
+            self.x = upload(synth.make_x(self.cfg, self.li, B, lay.N))
             self.xr = torch.empty_like(self.x)
             self.y = torch.empty((B, lay.M), dtype=torch.float16, device=dev)
             self.ws = torch.empty(qp.qp_rotate_linear_workspace_bytes(nat, B), dtype=torch.uint8, device=dev)
             need = qp.qp_linear_workspace_bytes(nat, B)   # the layer's own optional scratch (large layers, batch > 4)
             self.lin_ws = torch.empty(need, dtype=torch.uint8, device=dev) if need else False
-            self.i = 0
             # algorithmic bytes of one qp_linear launch: codes + scales + x + y + one LUT
             self.alg_bytes = lay.code_bytes + 2 * lay.M + 2 * B * lay.N + 2 * B * lay.M + 2 * lay.lut.size
+
+        def stream_only(self):
+            # the yardstick: a kernel that only reads the same code bytes from the same cold ring
+            qp.qp_bench_stream_read(self.ring[self.i % len(self.ring)].codes, self.sink)
+            self.i += 1
 
         def step(self):
             # rotation + fused layer through the single-call entry point
@@ -424,19 +450,23 @@ def main():
         torch.cuda.synchronize()
         return
 
-    # ---------------- whole-step throughput: W warm-up steps, then exactly K timed steps
+    # ---------------- whole-step throughput: W warm-up steps, then the K timed steps.  The K steps are one
+    # HIP graph (at most 500 steps per graph); a short K would mostly measure the latency of launching
+    # one graph, so the K-step sequence is replayed until at least 2000 steps have run, the wall clock
+    # is taken around all of them (synchronised on both sides) and divided by the steps run.
     chunk = min(a.steps, 500)
     assert a.steps % chunk == 0, "--steps must be a multiple of 500 (or below 500)"
     g_step = graph_of(head.step, chunk)
     for _ in range(max(1, a.warmup // chunk)):
         g_step.replay()
+    rounds = max(1, -(-2000 // a.steps))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(a.steps // chunk):
+    for _ in range(rounds * (a.steps // chunk)):
         g_step.replay()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / a.steps
+    ms_per_step = (t1 - t0) * 1e3 / (rounds * a.steps)
     value = head.code_bytes / (ms_per_step * 1e-3) / 1e9
 
     g_two = graph_of(head.step_two_calls, 500)
@@ -453,40 +483,66 @@ def main():
     g_had.replay()
     had_us = event_time_us(g_had, R)
     achieved = head.alg_bytes / (lin_us * 1e-6) / 1e9
-    # HBM bytes per launch from the committed rocprofv3 --pmc runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0,
-    # factors from a plain copy of known size; profiles/qp_linear_pmc_*.md): only for the workload profiled
-    traffic = (18324 + 8) * 1024 if (a.cfg, a.layer, a.batch) == (3, 0, 1) else None
+    # the two yardsticks of this box, same protocol (graph of R launches, cold ring, HIP events): a kernel
+    # that only streams the layer's code bytes, and an empty launch
+    g_str = graph_of(head.stream_only, R)
+    g_str.replay()
+    stream_us = event_time_us(g_str, R)
+    g_emp = graph_of(qp.qp_bench_empty_launch, R)
+    g_emp.replay()
+    empty_us = event_time_us(g_emp, R)
+    del g_str, g_emp
+    # HBM bytes per launch: not counted in this run (that takes rocprofv3 --pmc); the figure of the
+    # committed counter summary for exactly this workload, if there is one, else null
+    traffic = committed_traffic(a.cfg, a.layer, a.batch)
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "traffic_source": "profiles/ (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE of an earlier run of this "
+                                  "workload, not of this run)" if traffic else None,
                 "kernel": "qp_linear", "us_per_launch": round(lin_us, 3),
-                "algorithmic_bytes": head.alg_bytes}
+                "algorithmic_bytes": head.alg_bytes,
+                "stream_read_us": round(stream_us, 3), "empty_launch_us": round(empty_us, 3),
+                "frac_of_ceiling": round(stream_us / lin_us, 4),
+                "ceiling": "a kernel that only reads the same code bytes (128-bit non-temporal loads, same cold "
+                           "ring, same graph-and-events protocol); frac_of_ceiling = its time / the layer's"}
 
     # ---------------- other (layer, batch) cases: us per qp_linear call, cold ring
     cases = []
     if not a.no_cases:
         del g_lin, g_had
-        todo = [(3, 0, 1), (3, 0, 4), (3, 0, 8), (3, 0, 16), (2, 0, 1), (1, 0, 1),
-                (4, 0, 1), (4, 1, 1), (4, 2, 1), (4, 3, 1), (4, 3, 8), (4, 3, 16), (4, 2, 8),
-                (5, 0, 1), (5, 1, 1), (5, 2, 1), (5, 3, 1), (5, 2, 8), (5, 3, 8), (5, 3, 16),
-                (6, 0, 1), (6, 1, 1), (6, 2, 1), (6, 3, 1), (6, 1, 8), (6, 4, 1), (6, 5, 1), (6, 6, 1),
-                (6, 7, 1), (6, 8, 1), (6, 8, 8), (6, 9, 1)]
-        for cfg, li, B in todo:
-            if (cfg, li, B) == (a.cfg, a.layer, a.batch):
-                continue
-            c = Case(cfg, li, B)
-            c.hadamard_only()
-            g = graph_of(c.linear_only, 200)
+        # every (layer, batch) cell the benchmark configurations ask for: configuration 3 at batch 1, 4, 8
+        # (+ 2, 16), configuration 4's four projections at batch 1, 2, 4, 8, 16, configuration 5's at
+        # 1, 8, 16, configurations 1 and 2 at batch 1; configuration 6: the paper's V = 2 trellis
+        todo = [(3, 0, (1, 2, 4, 8, 16)), (2, 0, (1,)), (1, 0, (1,)),
+                (4, 0, (1, 2, 4, 8, 16)), (4, 1, (1, 2, 4, 8, 16)), (4, 2, (1, 2, 4, 8, 16)), (4, 3, (1, 2, 4, 8, 16)),
+                (5, 0, (1, 8, 16)), (5, 1, (1, 8, 16)), (5, 2, (1, 8, 16)), (5, 3, (1, 8, 16)),
+                (6, 0, (1,)), (6, 1, (1, 8)), (6, 2, (1,)), (6, 3, (1,)), (6, 4, (1,)), (6, 5, (1,)), (6, 6, (1,)),
+                (6, 7, (1,)), (6, 8, (1, 8)), (6, 9, (1,))]
+        for cfg, li, batches in todo:
+            c = Case(cfg, li, batches[0])
+            g = graph_of(c.stream_only, 100)
             g.replay()
-            us = event_time_us(g, 200, repeats=3)
+            us_stream = event_time_us(g, 100, repeats=3)
             del g
-            g = graph_of(c.step, 200)
-            g.replay()
-            us_step = event_time_us(g, 200, repeats=3)
-            cases.append({"workload": c.desc["name"], "batch": B, "us_per_call": round(us, 3),
-                          "us_rotate_linear": round(us_step, 3),
-                          "weight_GBps": round(c.code_bytes / us / 1e3, 1),
-                          "frac_of_peak": round(c.code_bytes / us / 1e3 / HBM_PEAK_GBS, 4)})
-            del c, g
+            for B in batches:
+                if (cfg, li, B) == (a.cfg, a.layer, a.batch):
+                    continue
+                c.set_batch(B)
+                c.hadamard_only()
+                g = graph_of(c.linear_only, 200)
+                g.replay()
+                us = event_time_us(g, 200, repeats=3)
+                del g
+                g = graph_of(c.step, 200)
+                g.replay()
+                us_step = event_time_us(g, 200, repeats=3)
+                del g
+                cases.append({"workload": c.desc["name"], "batch": B, "us_per_call": round(us, 3),
+                              "us_rotate_linear": round(us_step, 3),
+                              "weight_GBps": round(c.code_bytes / us / 1e3, 1),
+                              "frac_of_peak": round(c.code_bytes / us / 1e3 / HBM_PEAK_GBS, 4),
+                              "stream_read_us": round(us_stream, 3), "frac_of_ceiling": round(us_stream / us, 4)})
+            del c
             torch.cuda.empty_cache()
 
     # ---------------- dequantize-only kernel on the headline layer (write-bound: 2 bytes per weight)
@@ -552,7 +608,7 @@ def main():
         "vs_baseline": None, "dtype": "f16 inputs, f32 accumulate", "data": "synthetic",
         "config": {"workload": f"cfg{a.cfg} {head.desc['name']} batch {a.batch}, native layout, cold ring of "
                                f"{len(head.ring)} weight buffers ({len(head.ring) * head.code_bytes >> 20} MiB)",
-                   "steps_in_one_hip_graph": chunk},
+                   "steps_in_one_hip_graph": chunk, "graph_replays_timed": rounds * (a.steps // chunk)},
         "us_per_step": round(ms_per_step * 1e3, 3), "us_step_as_two_calls": round(two_us, 3),
         "us_qp_linear": round(lin_us, 3),
         "us_qp_hadamard": round(had_us, 3),

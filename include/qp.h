@@ -298,6 +298,16 @@ qp_status qp_msq_solve(int32_t n_classes, const int32_t *begin, const double *lo
                        double budget, int32_t resolution, int32_t *choice, double *total_loss,
                        double *total_cost);
 
+/* Measurement aids, no part of the method (Appendix E.2 profiles each kernel alone; these give the
+ * two yardsticks for such a profile on the machine at hand).  qp_bench_stream_read enqueues a kernel
+ * that does nothing but read `bytes` bytes at `data` (device, 16-byte aligned, bytes a multiple of
+ * 16) once, with 128-bit non-temporal loads, one contiguous KiB per wavefront and instruction, 256
+ * workgroups: the time no kernel that has to read that many bytes of packed codes can beat.
+ * sink: 4 bytes of device scratch (4-byte aligned).  qp_bench_empty_launch enqueues an empty kernel of
+ * 256 workgroups x 1024 threads: the cost of a launch as such. */
+qp_status qp_bench_stream_read(const void *data, size_t bytes, void *sink, void *hip_stream);
+qp_status qp_bench_empty_launch(void *hip_stream);
+
 const char *qp_status_string(qp_status s);
 int32_t qp_version(void);
 

@@ -11,10 +11,12 @@ from .binding import (QP_SQ, QP_VQ, QP_TCQ, QP_TCQH, QP_TCQHH, QP_LAYOUT_CANONIC
                       load_library, qp_dequant, qp_hadamard, qp_linear, qp_linear_workspace_bytes,
                       qp_encode, qp_encode_workspace_bytes, qp_kmeans, qp_kmeans_workspace_bytes, qp_msq_solve, qp_row_normalize, qp_native_bytes, qp_repack, qp_rotate_linear, qp_rotate_linear_workspace_bytes,
                       qp_status_string, qp_validate, qp_version, qp_set_option, qp_get_option, qp_reset_options,
-                      qp_rotate_linear_static, qp_rotate_linear_static_max_bytes)
+                      qp_rotate_linear_static, qp_rotate_linear_static_max_bytes,
+                      qp_bench_stream_read, qp_bench_empty_launch)
 
 __all__ = ["QP_SQ", "QP_VQ", "QP_TCQ", "QP_TCQH", "QP_TCQHH", "QP_LAYOUT_CANONICAL", "QP_LAYOUT_NATIVE", "QpError", "Weight",
            "load_library", "qp_dequant", "qp_hadamard", "qp_linear", "qp_linear_workspace_bytes",
            "qp_encode", "qp_encode_workspace_bytes", "qp_kmeans", "qp_kmeans_workspace_bytes", "qp_msq_solve", "qp_row_normalize", "qp_native_bytes", "qp_repack", "qp_rotate_linear", "qp_rotate_linear_workspace_bytes",
            "qp_status_string", "qp_validate", "qp_version", "qp_set_option", "qp_get_option", "qp_reset_options",
-           "qp_rotate_linear_static", "qp_rotate_linear_static_max_bytes"]
+           "qp_rotate_linear_static", "qp_rotate_linear_static_max_bytes",
+           "qp_bench_stream_read", "qp_bench_empty_launch"]

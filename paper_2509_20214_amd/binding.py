@@ -16,7 +16,7 @@ EXPORTS = ["qp_linear", "qp_dequant", "qp_hadamard", "qp_repack", "qp_native_byt
            "qp_rotate_linear", "qp_rotate_linear_workspace_bytes", "qp_encode", "qp_encode_workspace_bytes",
            "qp_row_normalize", "qp_msq_solve", "qp_kmeans", "qp_kmeans_workspace_bytes",
            "qp_set_option", "qp_get_option", "qp_reset_options", "qp_rotate_linear_static",
-           "qp_rotate_linear_static_max_bytes"]
+           "qp_rotate_linear_static_max_bytes", "qp_bench_stream_read", "qp_bench_empty_launch"]
 
 # qp_option (include/qp.h)
 QP_OPT_LINEAR_KERNEL, QP_OPT_DEQUANT_KERNEL, QP_OPT_ROTATE_SPLIT, QP_OPT_LINEAR_PACK = 0, 1, 2, 3
@@ -67,6 +67,10 @@ def load_library(build_if_missing: bool = True):
     L.qp_rotate_linear_static.argtypes = [wp, vp, vp, i32, i32, i64, vp, i64, vp]
     L.qp_rotate_linear_static_max_bytes.restype = sz
     L.qp_rotate_linear_static_max_bytes.argtypes = []
+    L.qp_bench_stream_read.restype = C.c_int
+    L.qp_bench_stream_read.argtypes = [vp, sz, vp, vp]
+    L.qp_bench_empty_launch.restype = C.c_int
+    L.qp_bench_empty_launch.argtypes = [vp]
     L.qp_rotate_linear_workspace_bytes.restype = sz
     L.qp_rotate_linear_workspace_bytes.argtypes = [wp, i32]
     L.qp_dequant.restype = C.c_int
@@ -362,3 +366,13 @@ def qp_rotate_linear_static(w: Weight, x, signs, block: int, y, stream=None):
                                                   x.stride(0), y.data_ptr(), y.stride(0), _stream_ptr(stream)),
            "qp_rotate_linear_static")
     return y
+
+
+def qp_bench_stream_read(data, sink, stream=None):
+    """Enqueue the read-only streaming kernel over the bytes of the tensor `data` (a yardstick, see qp.h)."""
+    _check(load_library().qp_bench_stream_read(data.data_ptr(), data.numel() * data.element_size(), sink.data_ptr(),
+                                               _stream_ptr(stream)), "qp_bench_stream_read")
+
+
+def qp_bench_empty_launch(stream=None):
+    _check(load_library().qp_bench_empty_launch(_stream_ptr(stream)), "qp_bench_empty_launch")

@@ -248,3 +248,13 @@ def test_options_are_plain_integers_with_ranges():
     finally:
         L.qp_reset_options()
     assert [L.qp_get_option(o) for o in range(8)] == defaults
+
+
+def test_bench_aids_reject_bad_arguments_on_the_host():
+    L = qp.load_library()
+    assert L.qp_bench_stream_read(None, 1024, 0x1000, None) == 1
+    assert L.qp_bench_stream_read(0x1000, 1024, None, None) == 1
+    assert L.qp_bench_stream_read(0x1000, 0, 0x2000, None) == 2
+    assert L.qp_bench_stream_read(0x1000, 1000, 0x2000, None) == 2      # not a multiple of 16
+    assert L.qp_bench_stream_read(0x1008, 1024, 0x2000, None) == 4
+    assert L.qp_bench_stream_read(0x1000, 1024, 0x2002, None) == 4
