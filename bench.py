@@ -170,8 +170,7 @@ def msq_demo(torch, synth, qp, dev, upload, graph_of, event_time_us):
     rows = {"q": 4096, "k": 1024, "v": 1024, "o": 4096, "u": 14336, "g": 14336, "d": 4096}
     cols = {"q": 4096, "k": 4096, "v": 4096, "o": 4096, "u": 4096, "g": 4096, "d": 14336}
     palette = [3, 4, 5, 6, 7, 8]                       # TCQH, bits per step; bits per weight = s / 2
-    groups = [g for cl in msq.CLUSTERS for part in msq.set_partitions(cl) for g in part]
-    groups = sorted(set(groups), key=lambda g: (len(g), g))
+    groups = sorted(msq.GROUPS, key=lambda g: (len(g), g))   # the twelve fusible groups of a block
     gen = torch.Generator(device=dev)
     gen.manual_seed(8)
     # distortion of each quantizer on N(0,1) targets (256 x 4096)

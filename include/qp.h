@@ -74,7 +74,8 @@ typedef enum {
     QP_ERR_ALIGN = 4,       /* pointer or stride not aligned as documented                 */
     QP_ERR_LAYOUT = 5,      /* layout value unknown, or shape not representable in it      */
     QP_ERR_DEVICE = 6,      /* HIP reported a launch error                                 */
-    QP_ERR_WORKSPACE = 7    /* workspace smaller than qp_linear_workspace_bytes()          */
+    QP_ERR_WORKSPACE = 7,   /* workspace smaller than qp_linear_workspace_bytes()          */
+    QP_ERR_MEMORY = 8       /* host memory exhausted (qp_msq_solve*: tables too large)     */
 } qp_status;
 
 typedef enum { QP_SQ = 0, QP_VQ = 1, QP_TCQ = 2, QP_TCQH = 3, QP_TCQHH = 4 } qp_scheme;
@@ -288,15 +289,34 @@ qp_status qp_validate(const qp_weight *w);
  * into fused groups with a quantizer per group (its loss: the sum over its layers; its cost: the
  * sum over its groups), which makes (C1) hold by construction.
  * Method: dynamic programming over the cost axis cut into `resolution` cells of budget/resolution;
- * costs are rounded up to whole cells, so the result always satisfies the true budget and is
- * optimal among the selections whose rounded costs fit - in particular exactly optimal when all
- * costs are multiples of the cell, and otherwise no worse than the optimum for the budget reduced
- * by n_classes cells.  Ties go to the lower option index.  All pointers are host pointers;
- * total_loss / total_cost (optional) receive the sums of the true values.
- * QP_ERR_UNSUPPORTED: no selection fits.  1 <= resolution <= 2^22. */
+ * costs are rounded up to whole cells (a cost that is a whole number of cells up to the rounding
+ * of one floating-point multiplication counts as that number), so the result satisfies the true
+ * budget up to that rounding - summed cost <= budget (1 + n_classes 2^-52) - and is optimal among
+ * the selections whose rounded costs fit: exactly optimal when all costs are multiples of the
+ * cell, otherwise no worse than the optimum for the budget reduced by n_classes cells.  Ties go to
+ * the lower option index.  All pointers are host pointers; total_loss / total_cost (optional)
+ * receive the sums of the true values.  QP_ERR_UNSUPPORTED: no selection fits; QP_ERR_MEMORY: the
+ * tables (n_classes x (resolution + 1) cells) do not fit the host's memory.  1 <= resolution <= 2^22. */
 qp_status qp_msq_solve(int32_t n_classes, const int32_t *begin, const double *loss, const double *cost,
                        double budget, int32_t resolution, int32_t *choice, double *total_loss,
                        double *total_cost);
+
+/* The fusion-aware problem of Section 4.2, eq. (4), stated directly: n_blocks Transformer blocks of
+ * seven linear layers each, in the order q, k, v, o, u (up), g (gate), d (down); the twelve fusible
+ * groups of a block in the order {q} {k} {v} {q,k} {q,v} {k,v} {q,k,v} {o} {u} {g} {u,g} {d};
+ * n_quant quantizers.  loss: host double [n_blocks][7][n_quant], the loss term of a layer under a
+ * quantizer; cost: host double [n_blocks][12][n_quant], the profiled cost of a (fused) group under
+ * a quantizer, >= 0.  Finds binary P[g, q] with every layer in exactly one active group (C1) and
+ * the summed cost of the active groups within budget (C2) that minimises the summed loss terms of
+ * the layers of the active groups: assign (host int32 [n_blocks][12]) receives the quantizer of
+ * every active group and -1 for the others.  fusion == 0 restricts the groups to single layers
+ * (the per-layer problem of Section 4.1, eq. (3)).  Method: every cluster of layers with a common
+ * input ({q,k,v}, {o}, {u,g}, {d}) becomes a class of qp_msq_solve whose options are its splits into
+ * groups with one quantizer per group, options that another one beats in both loss and cost
+ * dropped; same guarantees, same error codes.  1 <= n_blocks <= 4096, 1 <= n_quant <= 16. */
+qp_status qp_msq_solve_fused(int32_t n_blocks, int32_t n_quant, const double *loss, const double *cost,
+                             double budget, int32_t resolution, int32_t fusion, int32_t *assign,
+                             double *total_loss, double *total_cost);
 
 /* Measurement aids, no part of the method (Appendix E.2 profiles each kernel alone; these give the
  * two yardsticks for such a profile on the machine at hand).  qp_bench_stream_read enqueues a kernel

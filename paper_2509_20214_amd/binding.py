@@ -16,7 +16,7 @@ EXPORTS = ["qp_linear", "qp_dequant", "qp_hadamard", "qp_repack", "qp_native_byt
            "qp_rotate_linear", "qp_rotate_linear_workspace_bytes", "qp_encode", "qp_encode_workspace_bytes",
            "qp_row_normalize", "qp_msq_solve", "qp_kmeans", "qp_kmeans_workspace_bytes",
            "qp_set_option", "qp_get_option", "qp_reset_options", "qp_rotate_linear_static",
-           "qp_rotate_linear_static_max_bytes", "qp_bench_stream_read", "qp_bench_empty_launch"]
+           "qp_rotate_linear_static_max_bytes", "qp_bench_stream_read", "qp_bench_empty_launch", "qp_msq_solve_fused"]
 
 # qp_option (include/qp.h)
 QP_OPT_LINEAR_KERNEL, QP_OPT_DEQUANT_KERNEL, QP_OPT_ROTATE_SPLIT, QP_OPT_LINEAR_PACK = 0, 1, 2, 3
@@ -82,6 +82,9 @@ def load_library(build_if_missing: bool = True):
     L.qp_msq_solve.restype = C.c_int
     L.qp_msq_solve.argtypes = [i32, C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_double,
                                i32, C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    L.qp_msq_solve_fused.restype = C.c_int
+    L.qp_msq_solve_fused.argtypes = [i32, i32, C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_double, i32, i32,
+                                     C.POINTER(C.c_int32), C.POINTER(C.c_double), C.POINTER(C.c_double)]
     L.qp_encode_workspace_bytes.restype = sz
     L.qp_encode_workspace_bytes.argtypes = [wp]
     L.qp_kmeans.restype = C.c_int

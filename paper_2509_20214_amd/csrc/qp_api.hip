@@ -412,6 +412,7 @@ extern "C" const char *qp_status_string(qp_status s) {
         case QP_ERR_LAYOUT: return "bad layout";
         case QP_ERR_DEVICE: return "device launch error";
         case QP_ERR_WORKSPACE: return "workspace too small";
+        case QP_ERR_MEMORY: return "host memory exhausted";
         default: return "unknown status";
     }
 }

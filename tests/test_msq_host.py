@@ -86,12 +86,28 @@ def test_mckp_argument_errors():
     assert call(2, beg, loss, cost, 2.0, 100, ch) == 3                             # nothing fits
 
 
-def test_set_partitions_counts():
-    assert len(list(msq.set_partitions(("q", "k", "v")))) == 5      # Bell numbers
-    assert len(list(msq.set_partitions(("u", "g")))) == 2
-    groups = {g for p in msq.set_partitions(("q", "k", "v")) for g in p} | \
-             {g for p in msq.set_partitions(("u", "g")) for g in p} | {("o",), ("d",)}
-    assert groups == set(omsq.GROUPS)          # exactly the paper's twelve fusible groups per block
+def test_group_order_is_the_headers():
+    """The binding's layer / group order is the one qp.h documents (and the paper's twelve groups)."""
+    assert msq.LAYERS == omsq.LAYERS and set(msq.GROUPS) == set(omsq.GROUPS) and len(msq.GROUPS) == 12
+    assert msq.GROUPS == (("q",), ("k",), ("v",), ("q", "k"), ("q", "v"), ("k", "v"), ("q", "k", "v"),
+                          ("o",), ("u",), ("g",), ("u", "g"), ("d",))
+
+
+def test_fused_solver_argument_errors():
+    L = qp.load_library()
+    loss = (C.c_double * 14)(*([1.0] * 14))
+    cost = (C.c_double * 24)(*([1.0] * 24))
+    out = (C.c_int32 * 12)()
+    call = lambda nb, nq, l, c, bud, r, o: L.qp_msq_solve_fused(nb, nq, l, c, bud, r, 1, o, None, None)
+    assert call(1, 2, loss, cost, 10.0, 100, out) == 0
+    assert sorted(i for i in range(12) if out[i] >= 0) == [6, 7, 10, 11]      # equal costs: the fewest groups
+    assert call(1, 2, None, cost, 10.0, 100, out) == 1
+    assert call(1, 2, loss, cost, 10.0, 100, None) == 1
+    assert call(0, 2, loss, cost, 10.0, 100, out) == 2
+    assert call(1, 17, loss, cost, 10.0, 100, out) == 2
+    assert call(1, 2, loss, cost, 3.0, 100, out) == 3                         # four clusters cost at least 4
+    bad = (C.c_double * 24)(*([1.0] * 23 + [-1.0]))
+    assert call(1, 2, loss, bad, 10.0, 100, out) == 2
 
 
 @pytest.mark.parametrize("seed,n_blocks,n_quant", [(0, 1, 2), (1, 1, 3), (2, 2, 2), (3, 1, 2), (4, 2, 2)])
