@@ -1,6 +1,7 @@
-"""Parity at the benchmark's full sizes and launch configuration: the GPU output of a
-whole layer is checked on sampled output rows that the oracle computes one by one, and
-the dequantized matrix on sampled rows bit for bit."""
+"""Parity at the benchmark's full sizes and launch configuration: the dequantized matrix of a whole
+layer is compared with the oracle's bit for bit (every element; configuration 5's largest layers on
+sampled rows), the layer's output on every element, within the stated 1e-2 and within the sharper
+bound that one fp16 rounding plus fp32 accumulation allow."""
 import numpy as np
 import pytest
 
@@ -35,23 +36,31 @@ def sample_rows(M, k=24, seed=0):
     return sorted(rows)
 
 
+TOL = 1e-2          # the stated bound: max |y - y_ref| / max |y_ref|
+TOL_SHARP = 1e-3    # one rounding to fp16 (2^-11 of |y|) plus fp32 accumulation (orders below): twice 2^-11
+
+
 @pytest.mark.parametrize("cfg,li,batches", CASES)
-def test_full_size_layer_on_sampled_rows(qp, cfg, li, batches):
+def test_full_size_layer(qp, cfg, li, batches):
     desc = synth.config_layers(cfg)[li]
     lay = synth.build(desc)
     w_can = qp.Weight.from_layer(lay)
     w = qp.qp_repack(w_can)
-    rows = sample_rows(lay.M, seed=cfg * 10 + li)
-    # decode, sampled rows, both layouts
-    Wd = qp.qp_dequant(w)
-    Wc = qp.qp_dequant(w_can)
-    sub = synth.Layer(**{**lay.__dict__, "codes": lay.codes[rows], "scales": lay.scales[rows], "M": len(rows)})
+    # decode: the whole matrix, both layouts, bit for bit (the 70B-shaped layers of configuration 5,
+    # up to 470 M weights, on sampled rows: the oracle would take a minute per layer)
+    whole = lay.M * lay.N <= (1 << 27)
+    rows = list(range(lay.M)) if whole else sample_rows(lay.M, seed=cfg * 10 + li)
+    sub = lay if whole else synth.Layer(**{**lay.__dict__, "codes": lay.codes[rows], "scales": lay.scales[rows],
+                                            "M": len(rows)})
     want_W = oracle.decode(sub)
     idx = torch.tensor(rows, device="cuda")
-    for Wg in (Wd, Wc):
-        got = Wg[idx].cpu().view(torch.int16).numpy().view(np.uint16)
+    for wv in (w, w_can):
+        Wg = qp.qp_dequant(wv)
+        got = (Wg if whole else Wg[idx]).cpu().view(torch.int16).numpy().view(np.uint16)
+        del Wg
         assert np.array_equal(got, want_W)
-    del Wd, Wc
+        del got
+    del want_W
     block = synth.hadamard_block(lay.N)
     sg = synth.make_signs(cfg, li, lay.N)
     for B in batches:
@@ -65,12 +74,14 @@ def test_full_size_layer_on_sampled_rows(qp, cfg, li, batches):
         torch.cuda.synchronize()
         assert torch.equal(y_step, y)
         xr_host = xr.cpu().view(torch.int16).numpy().view(np.uint16)
-        # isolated check: the oracle multiplies the very fp16 xr the kernel received
-        want = oracle.linear(sub, xr_host)
-        got = y[:, idx].cpu().numpy().astype(np.float64)
-        scale = np.max(np.abs(want))
-        assert np.max(np.abs(got - want)) / scale <= 1e-2
-        # chained check against fp64 rotation
-        want2 = oracle.linear(sub, oracle.hadamard(x, sg, block, fast=True))
-        assert np.max(np.abs(got - want2)) / np.max(np.abs(want2)) <= 1e-2
+        # isolated check, every output: the oracle multiplies the very fp16 xr the kernel received
+        want = oracle.linear(lay, xr_host, threads=True)
+        got = y.cpu().numpy().astype(np.float64)
+        err = np.max(np.abs(got - want)) / np.max(np.abs(want))
+        assert err <= TOL
+        assert err <= TOL_SHARP, err
+        # chained check against the fp64 rotation (the rotated activations are rounded to fp16 on the
+        # GPU and not in the oracle: only the stated bound applies)
+        want2 = oracle.linear(lay, oracle.hadamard(x, sg, block, fast=True), threads=True)
+        assert np.max(np.abs(got - want2)) / np.max(np.abs(want2)) <= TOL
         assert torch.isfinite(y.float()).all()

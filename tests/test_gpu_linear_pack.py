@@ -47,7 +47,9 @@ def test_workspace_or_not(qp, scheme, cb, M, N, B):
     sub = synth.Layer(**{**lay.__dict__, "codes": lay.codes[rows], "scales": lay.scales[rows], "M": len(rows)})
     want = oracle.linear(sub, x.view(np.uint16))
     got = y_ws[:, torch.tensor(rows, device="cuda")].cpu().numpy().astype(np.float64)
-    assert np.max(np.abs(got - want)) / np.max(np.abs(want)) <= 1e-2
+    err = np.max(np.abs(got - want)) / np.max(np.abs(want))
+    assert err <= 1e-2      # the stated bound
+    assert err <= 1e-3, err  # one fp16 rounding (2^-11) plus fp32 accumulation: twice 2^-11
 
 
 def test_strided_activations(qp):

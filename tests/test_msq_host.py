@@ -110,8 +110,19 @@ def test_fused_solver_argument_errors():
     assert call(1, 2, loss, bad, 10.0, 100, out) == 2
 
 
+@pytest.mark.gpu
+def test_fusion_aware_selection_runs_in_the_gpu_suite_too():
+    """The selection is host code; this one instance is also collected by `-m gpu`, so that the run on
+    the GPU machine exercises the same library build."""
+    check_fusion_aware(5, 1, 2)
+
+
 @pytest.mark.parametrize("seed,n_blocks,n_quant", [(0, 1, 2), (1, 1, 3), (2, 2, 2), (3, 1, 2), (4, 2, 2)])
 def test_fusion_aware_selection_against_brute_force(seed, n_blocks, n_quant):
+    check_fusion_aware(seed, n_blocks, n_quant)
+
+
+def check_fusion_aware(seed, n_blocks, n_quant):
     """Integer costs in which a fused group is cheaper than its members one by one (as profiled
     latencies are): the class construction + knapsack equals brute force over all P[g, q] that
     satisfy (C1) and (C2); without fusion the optimum can only be worse."""
