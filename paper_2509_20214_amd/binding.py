@@ -142,6 +142,17 @@ def _stream_ptr(stream):
     return C.c_void_p(stream.cuda_stream)
 
 
+def _scratch(nbytes: int, device, stream):
+    """A temporary workspace that this module allocates itself.  It comes from torch's caching
+    allocator, which would hand the block out again as soon as the tensor is dropped as far as the
+    CURRENT stream is concerned; the kernels run on `stream`, so the block is tied to that one too."""
+    import torch
+    t = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    if stream is not None:
+        t.record_stream(stream)
+    return t
+
+
 def _check(code: int, what: str):
     if code != QP_OK:
         raise QpError(code, what)
@@ -229,7 +240,7 @@ def qp_encode(w: Weight, W, tile_err: bool = False, workspace=None, stream=None)
     d = w.desc
     need = int(load_library().qp_encode_workspace_bytes(C.byref(d)))
     if workspace is None and need:
-        workspace = torch.empty(need, dtype=torch.uint8, device=W.device)
+        workspace = _scratch(need, W.device, stream)
     err = torch.zeros((d.M, d.N // 256), dtype=torch.float32, device=W.device) if tile_err else None
     _check(load_library().qp_encode(C.byref(d), W.data_ptr(), W.stride(0), w.codes.data_ptr(),
                                     err.data_ptr() if err is not None else None,
@@ -271,7 +282,7 @@ def qp_kmeans(samples, centres, max_iter: int = 300, tol: float = 1e-6, assign=N
         raise ValueError("samples and centres must be float32")
     nbytes = qp_kmeans_workspace_bytes(k, d)
     if workspace is None:
-        workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=samples.device)
+        workspace = _scratch(max(nbytes, 16), samples.device, stream)
     _check(load_library().qp_kmeans(samples.data_ptr(), n, d, centres.data_ptr(), k, int(max_iter), float(tol),
                                     workspace.data_ptr(), workspace.numel(),
                                     assign.data_ptr() if assign is not None else None,
@@ -311,7 +322,7 @@ def qp_linear(w: Weight, x, y=None, workspace=None, stream=None):
         y = torch.empty((B, w.M), dtype=torch.float16, device=x.device)
     if workspace is None:   # allocate what the layer asks for (usually nothing); workspace=False: none
         need = qp_linear_workspace_bytes(w, B)
-        workspace = torch.empty(need, dtype=torch.uint8, device=x.device) if need else False
+        workspace = _scratch(need, x.device, stream) if need else False
     ws_ptr, ws_bytes = (None, 0) if workspace is False else (workspace.data_ptr(), workspace.numel() * workspace.element_size())
     _check(load_library().qp_linear(C.byref(w.desc), x.data_ptr(), B, x.stride(0), y.data_ptr(), y.stride(0),
                                     ws_ptr, ws_bytes, _stream_ptr(stream)), "qp_linear")
@@ -350,7 +361,7 @@ def qp_rotate_linear(w: Weight, x, signs, block: int, y=None, workspace=None, st
     if y is None:
         y = torch.empty((B, w.M), dtype=torch.float16, device=x.device)
     if workspace is None:
-        workspace = torch.empty(qp_rotate_linear_workspace_bytes(w, B), dtype=torch.uint8, device=x.device)
+        workspace = _scratch(qp_rotate_linear_workspace_bytes(w, B), x.device, stream)
     _check(load_library().qp_rotate_linear(C.byref(w.desc), x.data_ptr(), signs.data_ptr(), block, B, x.stride(0),
                                            y.data_ptr(), y.stride(0), workspace.data_ptr(),
                                            workspace.numel(), _stream_ptr(stream)), "qp_rotate_linear")
