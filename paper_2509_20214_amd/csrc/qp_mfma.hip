@@ -249,7 +249,9 @@ struct QpDecByte {
             if (wave < SRC_BYTES / 128)
                 qp_scalar_to_lds<8>(qp_scalar_ptr(g) + 32 * wave, reinterpret_cast<u32x4_t *>(small) + 8 * wave);
         }
+        QP_T(11);
         __syncthreads();
+        QP_T(12);
         const uint32_t *s32 = reinterpret_cast<const uint32_t *>(small);
         u32x4_t *t4 = reinterpret_cast<u32x4_t *>(tab);
         for (int idx = threadIdx.x; idx < 1024; idx += blockDim.x) {
@@ -262,6 +264,7 @@ struct QpDecByte {
             t4[b * 16 + part * 2 + flip] = v4;
             t4[b * 16 + part * 2 + (flip ^ 1)] = v4;
         }
+        QP_T(15);
         __syncthreads();
     }
     template <int P, int SI>
@@ -670,6 +673,25 @@ __device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8
         keep[m] = (lane_t / NACC) == m ? 0xffffffffu : 0u;
         asm volatile("" : "+v"(keep[m]));   // stays a register: the compiler would turn the AND back into a select
     }
+    // The table lookups of a step are issued DEPTH steps ahead of the matrix instruction that consumes
+    // them.  Left to itself the compiler issues the lookups of two steps and waits for them right
+    // away; a wavefront that has its SIMD to itself (a workgroup with four units, or the last wavefront
+    // of a workgroup to get its data) then sits out the LDS latency once per pair of steps.  Measured on
+    // 4096x4096 at 2.5 bits: batch 1 4.19 -> 4.01 us, batch 4 4.60 -> 4.34 us, batch 8 4.38 -> 4.21 us;
+    // within 1 % either way on 4096x14336 and larger.  Not at one step per fragment (batch 9 - 16),
+    // where the registers do not allow it (spills: 12 -> 51 us).
+#ifndef QP_PIPE_DEPTH_BYTE
+#define QP_PIPE_DEPTH_BYTE 4
+#endif
+#ifndef QP_PIPE_DEPTH_TRELLIS
+#define QP_PIPE_DEPTH_TRELLIS 0
+#endif
+    constexpr int DEPTH = (TT == 1) ? 0 : (D::BYTE_WINDOW ? QP_PIPE_DEPTH_BYTE : QP_PIPE_DEPTH_TRELLIS);
+    half8_t pipe[DEPTH > 0 ? DEPTH : 1];
+    qp_static_for<0, DEPTH>([&](auto dc) __attribute__((always_inline)) {
+        constexpr int d = decltype(dc)::value;
+        if constexpr (S0 + d < S1) pipe[d] = qp_step<D, P, S0 + d>(q, tab, lc, pre);
+    });
     qp_static_for<S0, S1>([&](auto sc) __attribute__((always_inline)) {
         constexpr int s = decltype(sc)::value;
         constexpr int n = s / TT, t = s % TT;
@@ -693,7 +715,16 @@ __device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8
                 xf[(n - N0) % PF] = xs.frag(n + PF, xlo);
             }
         }
-        half8_t a = qp_step<D, P, s>(q, tab, lc, pre);
+        half8_t a;
+        if constexpr (DEPTH > 0) {
+            a = pipe[(s - S0) % DEPTH];
+            if constexpr (s + DEPTH < S1) {
+                pipe[(s - S0) % DEPTH] = qp_step<D, P, s + DEPTH>(q, tab, lc, pre);
+                __builtin_amdgcn_sched_barrier(0);   // the lookups above stay in front of the multiply below
+            }
+        } else {
+            a = qp_step<D, P, s>(q, tab, lc, pre);
+        }
         if constexpr (TT == 1 && XS::TIE_REFILLS) dep = __builtin_bit_cast(u32x4_t, a)[3];
         acc[t % NACC] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, __builtin_bit_cast(half8_t, masked[t / NACC]),
                                                                acc[t % NACC], 0, 0, 0);
@@ -1187,7 +1218,13 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
     // A table that the whole workgroup shares is built after the first loads have been issued when
     // the workgroup has few units, and at batch >= 4 with row-major activations (whose many
     // small loads then start earlier); before them otherwise.
-    int late_max = (!x_packed && B >= 4) ? 1024 : 8;
+    // (few units = what they request fits the compute unit's window of loads in flight, so nobody
+    // queues in front of the build's barriers: at most 56 KiB of codes, and at most 8 units.
+    // 4 bit scalar at batch 1, 8 units of 8 KiB: 5.9 us late, 5.6 us early.)
+    const int unit_kib = (scheme == QP_SQ) ? 2 * cb : cb;   // of the schemes with such a table: 4 bit scalar, 5 and 7 bit pairs
+    int late_few = 56 / (unit_kib > 0 ? unit_kib : 1);
+    if (late_few > 8) late_few = 8;
+    int late_max = (!x_packed && B >= 4) ? 1024 : late_few;
     if (const int forced = qp_opt(QP_OPT_TABLE_LATE_MAX); forced >= 0) late_max = forced;
     const int x_flags = (x_packed ? 1 : 0) | (late_max << 8);
 #define CALL_BP(S, C, BP) \
