@@ -219,6 +219,10 @@ extern "C" qp_status qp_rotate_linear(const qp_weight *w, const void *x, const i
     // the small transform, and the second launch is saved.  QP_OPT_ROTATE_SPLIT forces two launches.
     if (B == 1 && block == w->N && block >= 1024 && block <= 8192 && !qp_opt(QP_OPT_ROTATE_SPLIT))
         return qp_launch_linear_mfma(d, w->scheme, w->code_bits, x, 1, ldx, y, ldy, 0, signs, block, st);
+    // Batch 1, several blocks of 1024 and a layer of at most 4096 x 16384 (N = 14336 ...): every
+    // wavefront of a workgroup transforms the block of its own unit; again one launch.
+    if (B == 1 && qp_linear_rotates_blocks(w->scheme, w->M, w->N, block) && !qp_opt(QP_OPT_ROTATE_SPLIT))
+        return qp_launch_linear_mfma(d, w->scheme, w->code_bits, x, 1, ldx, y, ldy, 0, signs, block, st);
     s = qp_launch_hadamard(x, signs, B, w->N, block, ldx, workspace, w->N, pow2_at_least(B), st);
     if (s != QP_OK) return s;
     return qp_launch_linear_mfma(d, w->scheme, w->code_bits, workspace, B, w->N, y, ldy, 1, nullptr, 0, st);

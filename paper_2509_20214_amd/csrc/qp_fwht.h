@@ -165,3 +165,133 @@ __device__ __forceinline__ void qp_fwht_tile(bool active, int t, const half_t *s
     qp_fwht_fetch<V>(active, t, src, sg, v);
     qp_fwht_finish<V, W>(active, t, v, norm, buf, store);
 }
+
+
+// ------------------------------------------------------------------ a block of 1024 on the matrix cores
+// One wavefront transforms one block of 1024 as a 32 x 32 matrix X[a][b] = x[32 a + b]:
+// Y = H32 X H32 (the Sylvester matrix of order 1024 is H32 (x) H32), two passes of
+// v_mfma_f32_16x16x32_f16 instead of ten butterfly stages - the six stages that cross lanes cost
+// three vector operations per value each, about 350 per wavefront and block; this takes 12 matrix
+// instructions and about 80 vector operations.
+//   pass 1  T[a][b'] = sum_b X[a][b] H[b][b'] / 32    X: fp16 times its sign, exact; fp32 sums
+//   pass 2  Y[b'][a'] = sum_a T[a][b'] H[a][a']       T = hi + lo, two fp16 numbers that carry 22 bits
+//                                                      of its mantissa; hi first, then lo, fp32 sums
+// The 1 / 32 = 1 / sqrt(1024) rides in pass 1's constant matrix, so T fits fp16 whenever x does.
+// Pass 1's results already sit where pass 2's A operand wants them (a lane's accumulator rows become
+// its k slots; the constant matrix of pass 2 is labelled to match), so nothing moves between lanes.
+// Lane (g, j) = 16 g + j ends up with out[tb][ta][r] = element 32 (16 ta + j) + 16 tb + 4 g + r of the
+// transformed block, r = 0 .. 3: four consecutive elements per register quadruple.
+// Dword d (k slots 2 d, 2 d + 1) of lane (g, j)'s piece q of the two constant matrices: q = 0, 1 pass 1,
+// column tile q; q = 2, 3 pass 2, column tile q - 2.
+__device__ __forceinline__ uint32_t qp_had1024_word(int q, int lane, int d) {
+    const int g = lane >> 4, c = 16 * (q & 1) + (lane & 15);
+    uint32_t w = 0;
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+        const int e = 2 * d + hh;
+        const int k = (q < 2) ? 8 * g + e                                       // pass 1: k slot e of lane group g is b = 8 g + e
+                              : ((e < 4) ? 4 * g + e : 16 + 4 * g + (e - 4));   // pass 2: it is a = pi(g, e)
+        const uint32_t one = (q < 2) ? 0x2800u : 0x3c00u;                        // 2^-5 and 1 in fp16
+        w |= (one | ((uint32_t)(__builtin_popcount(k & c) & 1) << 15)) << (16 * hh);
+    }
+    return w;
+}
+
+struct QpHad1024 {
+    u32x4_t h1[2];   // pass 1, B operand for columns b' = 16 tb + j: H[8 g + e][b'] / 32, e = 0 .. 7
+    u32x4_t h2[2];   // pass 2, B operand for columns a' = 16 ta + j: H[pi(g, e)][a'], pi(g, e) = 4 g + e, 16 + 4 g + e - 4
+    // Every lane works out its own 16 dwords (about 200 vector operations: fine for a kernel that does
+    // nothing else, too much for one that has a layer to compute).
+    __device__ __forceinline__ void init(int lane) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                h1[t][d] = qp_had1024_word(t, lane, d);
+                h2[t][d] = qp_had1024_word(2 + t, lane, d);
+            }
+    }
+    // The workgroup works them out once, one dword per thread, into 4 KiB of LDS (1024 dwords, [q][lane][d]);
+    // after a barrier every wavefront reads its copy.
+    static __device__ __forceinline__ void fill(uint32_t *lds) {
+        for (int idx = threadIdx.x; idx < 1024; idx += blockDim.x) lds[idx] = qp_had1024_word(idx >> 8, (idx >> 2) & 63, idx & 3);
+    }
+    __device__ __forceinline__ void read(const uint32_t *lds, int lane) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            h1[t] = *reinterpret_cast<const u32x4_t *>(lds + (t * 64 + lane) * 4);
+            h2[t] = *reinterpret_cast<const u32x4_t *>(lds + ((2 + t) * 64 + lane) * 4);
+        }
+    }
+};
+
+// The loads of one block: lane (g, i) takes x[32 (16 ta + i) + 8 g .. + 7] and the signs of the same
+// elements, ta = 0, 1 (src and sg 16- and 8-byte aligned).
+struct QpHad1024In {
+    u32x4_t xv[2];
+    uint64_t sv[2];
+};
+__device__ __forceinline__ QpHad1024In qp_fwht1024_fetch(const half_t *src, const int8_t *sg, int lane) {
+    QpHad1024In in;
+    const int g = lane >> 4, i = lane & 15;
+#pragma unroll
+    for (int ta = 0; ta < 2; ++ta) {
+        const int off = 32 * (16 * ta + i) + 8 * g;
+        in.xv[ta] = *reinterpret_cast<const u32x4_t *>(src + off);
+        in.sv[ta] = *reinterpret_cast<const uint64_t *>(sg + off);
+    }
+    return in;
+}
+
+__device__ __forceinline__ void qp_fwht1024_run(const QpHad1024 &H, const QpHad1024In &in, float4_t (&out)[2][2]) {
+    const float4_t zero = float4_t{0.f, 0.f, 0.f, 0.f};
+    float4_t t1[2][2];
+#pragma unroll
+    for (int ta = 0; ta < 2; ++ta) {
+        // sign byte 0x01 / 0xff -> bit 7; byte 2 d of the eight goes to bit 15 of dword d, byte 2 d + 1 to bit 31
+        const uint32_t s_lo = (uint32_t)in.sv[ta] & 0x80808080u, s_hi = (uint32_t)(in.sv[ta] >> 32) & 0x80808080u;
+        u32x4_t xa = in.xv[ta];
+        xa[0] ^= __builtin_amdgcn_perm(0u, s_lo, 0x010c000cu);
+        xa[1] ^= __builtin_amdgcn_perm(0u, s_lo, 0x030c020cu);
+        xa[2] ^= __builtin_amdgcn_perm(0u, s_hi, 0x010c000cu);
+        xa[3] ^= __builtin_amdgcn_perm(0u, s_hi, 0x030c020cu);
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb)
+            t1[ta][tb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, xa),
+                                                                __builtin_bit_cast(half8_t, H.h1[tb]), zero, 0, 0, 0);
+    }
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+        half8_t hi, lo;
+#pragma unroll
+        for (int ta = 0; ta < 2; ++ta) {
+#pragma unroll
+            for (int r = 0; r < 4; r += 2) {   // two at a time: packed conversions, mixed-precision subtractions
+                const float t0 = t1[ta][tb][r], t1v = t1[ta][tb][r + 1];
+                const half2_t h = half2_t{(half_t)t0, (half_t)t1v};
+                const half2_t l = half2_t{(half_t)__builtin_fmaf((float)h[0], -1.0f, t0),    // t - hi is exact in fp32
+                                          (half_t)__builtin_fmaf((float)h[1], -1.0f, t1v)};
+                hi[4 * ta + r] = h[0];
+                hi[4 * ta + r + 1] = h[1];
+                lo[4 * ta + r] = l[0];
+                lo[4 * ta + r + 1] = l[1];
+            }
+        }
+#pragma unroll
+        for (int ta = 0; ta < 2; ++ta) {
+            float4_t acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(hi, __builtin_bit_cast(half8_t, H.h2[ta]), zero, 0, 0, 0);
+            out[tb][ta] = __builtin_amdgcn_mfma_f32_16x16x32_f16(lo, __builtin_bit_cast(half8_t, H.h2[ta]), acc, 0, 0, 0);
+        }
+    }
+}
+
+// Element index inside the block of out[tb][ta][0] of lane `lane` (the other three follow it).
+__device__ __forceinline__ int qp_fwht1024_elem(int lane, int tb, int ta) {
+    return 32 * (16 * ta + (lane & 15)) + 16 * tb + 4 * (lane >> 4);
+}
+
+// Four transformed values rounded to fp16 (the scale is already in), as two dwords.
+__device__ __forceinline__ uint2 qp_fwht1024_pack(const float4_t &v) {
+    const half2_t a = half2_t{(half_t)v[0], (half_t)v[1]}, b = half2_t{(half_t)v[2], (half_t)v[3]};
+    return uint2{__builtin_bit_cast(uint32_t, a), __builtin_bit_cast(uint32_t, b)};
+}

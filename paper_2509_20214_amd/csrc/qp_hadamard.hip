@@ -42,6 +42,27 @@ __global__ __launch_bounds__(64 * W) void k_hadamard_reg(const half_t *x, const 
                        [&](int idx, half_t val) { xr[qp_xr_index(b, col0 + idx, ldxr, pack_bp)] = val; });
 }
 
+// Blocks of 1024 on the matrix cores: one wavefront per (batch row, block), four per workgroup.
+__global__ __launch_bounds__(256) void k_hadamard_1024(const half_t *x, const int8_t *signs, int n, int64_t ldx,
+                                                       half_t *xr, int64_t ldxr, int pack_bp, int items) {
+    const int lane = threadIdx.x & 63;
+    const int it = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (it >= items) return;
+    const int nblk = n >> 10;
+    const int b = it / nblk, c = it - b * nblk;
+    QpHad1024 H;
+    H.init(lane);
+    const QpHad1024In in = qp_fwht1024_fetch(x + (int64_t)b * ldx + 1024 * c, signs + 1024 * c, lane);
+    float4_t o[2][2];
+    qp_fwht1024_run(H, in, o);
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int ta = 0; ta < 2; ++ta)
+            *reinterpret_cast<uint2 *>(xr + qp_xr_index(b, 1024 * c + qp_fwht1024_elem(lane, tb, ta), ldxr, pack_bp)) =
+                qp_fwht1024_pack(o[tb][ta]);
+}
+
 static inline bool qp_aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 qp_status qp_launch_hadamard(const void *x, const int8_t *signs, int B, int n, int block, int64_t ldx,
@@ -53,6 +74,12 @@ qp_status qp_launch_hadamard(const void *x, const int8_t *signs, int B, int n, i
 #define QP_HAD(V, W)                                                                                     \
     hipLaunchKernelGGL((k_hadamard_reg<V, W>), dim3(grid), dim3(64 * W), 0, st, (const half_t *)x, signs, n, \
                        ldx, (half_t *)xr, ldxr, norm, pack_bp)
+    if (vec_ok && block == 1024 && (reinterpret_cast<uintptr_t>(xr) & 7) == 0 && ldxr % 4 == 0) {
+        const int items = grid;
+        hipLaunchKernelGGL(k_hadamard_1024, dim3((items + 3) / 4), dim3(256), 0, st, (const half_t *)x, signs, n, ldx,
+                           (half_t *)xr, ldxr, pack_bp, items);
+        return qp_check_launch();
+    }
     if (vec_ok && block >= 256 && block <= 16384) {
         switch (block) {
             case 256: QP_HAD(4, 1); break;

@@ -229,25 +229,35 @@ struct QpDecByte {
     static constexpr int TAB_BYTES = 65536;
     static constexpr int SRC_BYTES = (S == QP_SQ) ? 32 : (4 << CB);   // the table's source in global memory
     typedef QpLane8 Lane;
-    struct Pre { const uint16_t *g; };
-    static __device__ __forceinline__ Pre pre(const uint16_t *g) { return Pre{g}; }
+    // The table's source: at most 128 bytes per wavefront (the first SRC_BYTES / 128 wavefronts
+    // take 128 bytes each), requested into scalar registers as the very first thing a kernel does -
+    // the fetch takes about as long as the first weights need to arrive, and the scalar path does
+    // not queue behind the vector loads of the weight stream.
+    static constexpr int NQ = (SRC_BYTES <= 128 ? SRC_BYTES : 128) / 16;
+    static constexpr int NSRCW = SRC_BYTES <= 128 ? 1 : SRC_BYTES / 128;   // wavefronts that carry a part
+    struct Pre { u32x4_t src[NQ]; };
+    static __device__ __forceinline__ Pre pre(const uint16_t *g) {
+        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        qp_cu32 *s = qp_scalar_ptr(g) + 32 * (wave < NSRCW ? wave : NSRCW - 1);
+        Pre p;
+#pragma unroll
+        for (int k = 0; k < NQ; ++k) p.src[k] = u32x4_t{s[4 * k], s[4 * k + 1], s[4 * k + 2], s[4 * k + 3]};
+        return p;
+    }
     static __device__ __forceinline__ Lane lane_const() {
         Lane l;
 #pragma unroll
         for (int k = 0; k < 8; ++k) l.a[k] = (threadIdx.x & 31u) << 2;
         return l;
     }
-    static __device__ __forceinline__ void early(uint8_t *tab, uint16_t *small, const uint16_t *g) { table(tab, small, g); }
-    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *small, const Pre &p) { table(tab, small, p.g); }
-    // The source comes through scalar registers (the scalar path does not queue behind the
-    // vector loads of the weight stream) into `small`; then every thread writes 32 bytes of a row.
-    static __device__ __forceinline__ void table(uint8_t *tab, uint16_t *small, const uint16_t *g) {
+    static __device__ __forceinline__ void early(uint8_t *tab, uint16_t *small, const uint16_t *g) { build(tab, small, pre(g)); }
+    // Lane 0 of the wavefronts that carry a part of the source writes it to `small`; then every
+    // thread writes 32 bytes of a row.
+    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *small, const Pre &p) {
         const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        if constexpr (SRC_BYTES <= 128) {
-            if (wave == 0) qp_scalar_to_lds<SRC_BYTES / 16>(qp_scalar_ptr(g), reinterpret_cast<u32x4_t *>(small));
-        } else {
-            if (wave < SRC_BYTES / 128)
-                qp_scalar_to_lds<8>(qp_scalar_ptr(g) + 32 * wave, reinterpret_cast<u32x4_t *>(small) + 8 * wave);
+        if (wave < NSRCW && (threadIdx.x & 63) == 0) {
+#pragma unroll
+            for (int k = 0; k < NQ; ++k) reinterpret_cast<u32x4_t *>(small)[8 * wave + k] = p.src[k];
         }
         QP_T(11);
         __syncthreads();
@@ -791,15 +801,27 @@ struct QpLinLds {
     // (only the 128 KiB table leaves no room for a scratch of its own; a table that may be built
     // before the rotation runs cannot lend its room)
     static constexpr bool SCRATCH_IN_TAB = !QpTableMovable<D>::value && D::TAB_BYTES > 65536;
+    // per-wavefront rotation of N / 1024 <= 16 blocks (batch 1): the rotated activations of the whole
+    // row; the 128 KiB table leaves no room for that
+    static constexpr int ROTM_MAX = 16384;
+    static constexpr bool ROTM = (BP == 1) && D::TAB_BYTES <= 65536;
+    // every table build of these kernels has a workgroup barrier behind the point where the transform's
+    // constants are written - except the per-wavefront table
+    static constexpr bool TABLE_HAS_BARRIER = D::TAB_BYTES > 16 * 128;
 };
 
 // XL: the activations are rotated here (Section 3.3), by the workgroup itself, into LDS, and
 // the B-operand fragments are read from there; otherwise they come from global memory.
-template <int S, int CB, int BP, bool XL, bool ALT>
+// XL == 1: one Hadamard block of up to 8192, transformed by up to eight wavefronts together.
+// XL == 2: N / 1024 <= 16 blocks of 1024 and one row block per workgroup; every wavefront transforms
+// the block of its own unit on the matrix cores (qp_fwht1024_run, shared with the stand-alone kernel,
+// so the same bits).
+template <int S, int CB, int BP, int XL, bool ALT>
 __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, int B, int64_t ldx, half_t *y,
                                                int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic,
                                                int x_flags, const int8_t *signs, int rot_block, float rot_norm, uint8_t *tab,
                                                float *red, half_t *xr_lds, float *rot_buf) {
+    uint32_t *had_lds = reinterpret_cast<uint32_t *>(rot_buf);   // XL == 2: 4 KiB for the transform's constant matrices
     const int x_packed = x_flags & 0xff;   // activations in fragment order
     const int late_max = x_flags >> 8;     // a movable table is built after the first loads up to this many units
     using T = QpTraits<S, CB>;
@@ -905,7 +927,14 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     const int xn0 = half1 ? PF : 0;   // first fragment of this item
     // XL: the unrotated activations and their signs are requested first, ahead of the weights
     float rv[16];
-    if constexpr (XL) {
+    QpHad1024In rin0;
+    QpHad1024 had;
+    if constexpr (XL == 2) {
+        // block `wave` (a wavefront without one fetches the last block instead - no branch around the
+        // loads - and drops it)
+        const int c0 = wave < nbc ? wave : nbc - 1;
+        rin0 = qp_fwht1024_fetch(x + 1024 * c0, signs + 1024 * c0, lane);
+    } else if constexpr (XL == 1) {
         const int t = threadIdx.x;
         if (rot_block == 1024) qp_fwht_fetch<4>(t < 256, t, x, signs, reinterpret_cast<float(&)[4]>(rv));
         else if (rot_block == 2048) qp_fwht_fetch<8>(t < 256, t, x, signs, reinterpret_cast<float(&)[8]>(rv));
@@ -942,6 +971,12 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
             return codes16 + ((int64_t)rb0 * nbc + un) * BLK16 + lane;
         }
     };
+    // XL == 2: the constant matrices of the transform are worked out by the workgroup once, one dword
+    // per thread, in front of a table build (whose barriers publish them) and behind the first loads:
+    // vector work in front of loads delays them, four wavefronts share a SIMD.
+    auto rotate_consts = [&]() __attribute__((always_inline)) {
+        if constexpr (XL == 2) QpHad1024::fill(had_lds);
+    };
     u32x4_t q[P];
     bool full;
     QP_T(14);
@@ -958,6 +993,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
             } else {
                 q[0] = qp_stream_load(blk);
             }
+            rotate_consts();
             D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
             if constexpr (SPLIT) {
                 if (half1) qp_half_pieces_load<S, CB, P, 1, 2>(blk, ps, q);
@@ -976,6 +1012,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
         } else if constexpr (SPLIT) {
             if (half1) qp_half_pieces_load<S, CB, P, 1>(blk, ps, q);
             else qp_half_pieces_load<S, CB, P, 0>(blk, ps, q);
+            rotate_consts();
         } else {
             if constexpr (MOVABLE && !HH) {
                 // A table shared by the workgroup that is built "before the loads" is built with the
@@ -985,11 +1022,13 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
                 // order - step 0 can start as soon as the table stands.
                 // (measured with one, two and three pieces ahead of the build: one is best)
                 q[0] = qp_stream_load(blk);
-                if (!table_late) D::early(tab, reinterpret_cast<uint16_t *>(red), w.lut);
+                rotate_consts();
+                if (!table_late) D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
 #pragma unroll
                 for (int p = 1; p < P; ++p) q[p] = qp_stream_load(blk + p * ps);
             } else {
                 qp_pieces_load<P, HH>(blk, ps, full, q);
+                rotate_consts();
             }
         }
     }
@@ -1002,7 +1041,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     }
     typename D::Lane lc = D::lane_const();
     QP_T(7);
-    if constexpr (XL) {
+    if constexpr (XL == 1) {
         // The weight loads of the first unit are in flight; meanwhile the first 64 W threads
         // of the workgroup rotate the one block of activations (same arithmetic as the
         // stand-alone kernel, so the same bits), everybody meets at the barriers.
@@ -1019,6 +1058,32 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     }
     if constexpr (!MID_BUILD) {
         if (!MOVABLE || table_late) D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
+    }
+    if constexpr (XL == 2) {
+        // Every wavefront transforms the block of its own unit on the matrix cores while its weights are
+        // on their way, and writes it to LDS in fragment order (four consecutive elements = 8 bytes).
+        // The workgroup has one row block and a wavefront per column block (the host checks), so a
+        // wavefront only ever reads what it wrote itself - LDS operations of a wavefront complete in
+        // order - and nobody waits for anybody.
+        if constexpr (!QpLinLds<D, S, CB, BP>::TABLE_HAS_BARRIER) __syncthreads();   // the constant matrices
+        had.read(had_lds, lane);
+        QP_T(18);
+        if (wave < nbc) {
+            float4_t o[2][2];
+            qp_fwht1024_run(had, rin0, o);
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int ta = 0; ta < 2; ++ta)
+                    *reinterpret_cast<uint2 *>(xr_lds + qp_xr_index(0, 1024 * wave + qp_fwht1024_elem(lane, tb, ta), 0, 1)) =
+                        qp_fwht1024_pack(o[tb][ta]);
+        }
+        QP_T(19);
+        // (two wavefronts per unit: a wavefront's half units belong to other column blocks than the one
+        // it transformed, so here everybody does wait for everybody)
+        if constexpr (SPLIT) __syncthreads();
+#pragma unroll
+        for (int n = 0; n < PF; ++n) xf[n] = xu.frag(xn0 + n);
     }
     QP_T(1);
     if (k < units) {
@@ -1115,25 +1180,31 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
 
 // XL (batch 1 only): the workgroup rotates the activations itself; a kernel of its own, so that the
 // plain kernel does not carry the transform's LDS arrays and more workgroups fit a compute unit.
-template <int S, int CB, int BP, bool SPLIT, bool XL>
+template <int S, int CB, int BP, bool SPLIT, int XL>
 __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, int B, int64_t ldx, half_t *y,
                                                       int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic,
                                                       int x_packed, const int8_t *signs, int rot_block, float rot_norm) {
     using D = typename QpDecSel<S, CB, SPLIT>::type;
     using L = QpLinLds<D, S, CB, BP>;
-    static_assert(!XL || L::ROT, "in-kernel rotation: batch 1");
+    static_assert(XL == 0 || L::ROT, "in-kernel rotation: batch 1");
+    static_assert(XL != 2 || L::ROTM, "per-wavefront rotation: tables of at most 64 KiB");
     __shared__ __attribute__((aligned(16))) uint8_t tab[D::TAB_BYTES];
     // [unit][b][row]; before the first pass the same room stages a table's source
     __shared__ __attribute__((aligned(16))) float red[L::RED];
-    if constexpr (XL) {
+    if constexpr (XL == 2) {
+        __shared__ __attribute__((aligned(16))) half_t xr_all[L::ROTM_MAX];
+        __shared__ __attribute__((aligned(16))) float had_consts[1024];
+        qp_linear_body<S, CB, BP, 2, SPLIT>(w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
+                                            rot_block, rot_norm, tab, red, xr_all, had_consts);
+    } else if constexpr (XL == 1) {
         __shared__ __attribute__((aligned(16))) half_t xr_lds[L::ROT_MAX];
         __shared__ __attribute__((aligned(16))) float rot_own[L::SCRATCH_IN_TAB ? 1 : L::ROT_SCRATCH_FLOATS];
         float *rot_buf = L::SCRATCH_IN_TAB ? reinterpret_cast<float *>(tab) : rot_own;
-        qp_linear_body<S, CB, BP, true, SPLIT>(w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
-                                               rot_block, rot_norm, tab, red, xr_lds, rot_buf);
+        qp_linear_body<S, CB, BP, 1, SPLIT>(w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
+                                            rot_block, rot_norm, tab, red, xr_lds, rot_buf);
     } else {
-        qp_linear_body<S, CB, BP, false, SPLIT>(w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
-                                                rot_block, rot_norm, tab, red, nullptr, nullptr);
+        qp_linear_body<S, CB, BP, 0, SPLIT>(w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
+                                            rot_block, rot_norm, tab, red, nullptr, nullptr);
     }
 }
 
@@ -1144,14 +1215,23 @@ static void qp_launch_xl(int grid, int nw, hipStream_t st, const QpW &w, const v
                          int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic, int x_packed, const int8_t *signs,
                          int rot_block, float rot_norm) {
     if constexpr (BP == 1) {
+        using D = typename QpDecSel<S, CB, SPLIT>::type;
+        if constexpr (QpLinLds<D, S, CB, BP>::ROTM) {
+            if (rot_block > 0 && rot_block != w.N) {
+                hipLaunchKernelGGL((k_linear_mfma<S, CB, BP, SPLIT, 2>), dim3(grid), dim3(64 * nw), 0, st, w,
+                                   (const half_t *)x, B, ldx, (half_t *)y, ldy, G, rb_q, rb_r, nbc_magic, x_packed,
+                                   signs, rot_block, rot_norm);
+                return;
+            }
+        }
         if (rot_block > 0) {
-            hipLaunchKernelGGL((k_linear_mfma<S, CB, BP, SPLIT, true>), dim3(grid), dim3(64 * nw), 0, st, w,
+            hipLaunchKernelGGL((k_linear_mfma<S, CB, BP, SPLIT, 1>), dim3(grid), dim3(64 * nw), 0, st, w,
                                (const half_t *)x, B, ldx, (half_t *)y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
                                rot_block, rot_norm);
             return;
         }
     }
-    hipLaunchKernelGGL((k_linear_mfma<S, CB, BP, SPLIT, false>), dim3(grid), dim3(64 * nw), 0, st, w,
+    hipLaunchKernelGGL((k_linear_mfma<S, CB, BP, SPLIT, 0>), dim3(grid), dim3(64 * nw), 0, st, w,
                        (const half_t *)x, B, ldx, (half_t *)y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
                        rot_block, rot_norm);
 }
@@ -1172,6 +1252,15 @@ static void qp_launch_one(bool split, int grid, int nw, hipStream_t st, const Qp
                                    rot_block, rot_norm);
 }
 
+// Whether the block kernel can rotate N / 1024 blocks of 1024 itself at batch 1: every workgroup has
+// one row block (M <= 4096) and a wavefront per column block (N <= 16384), and the rotated row fits
+// into LDS beside the table (not beside the 128 KiB one of the V = 1 trellis).  Larger layers take
+// the two launches: with several units per wavefront the transform would need a workgroup barrier
+// behind it, and measured no faster (8192 x 28672: 22.6 against 22.3 us).
+bool qp_linear_rotates_blocks(int scheme, int M, int N, int rot_block) {
+    return rot_block == 1024 && N > 1024 && N % 1024 == 0 && N <= 16384 && M <= 4096 && scheme != QP_TCQ;
+}
+
 qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x, int B, int64_t ldx, void *y,
                                 int64_t ldy, int x_packed, const int8_t *signs, int rot_block, hipStream_t st) {
     const int nbc = w.nbc, rbk = w.M / 16;
@@ -1188,14 +1277,15 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
     int units = G * nbc;
     int rb_q = rbk / grid, rb_r = rbk % grid;
     int nbc_magic = (65536 + nbc - 1) / nbc;  // u / nbc == (u * magic) >> 16 for u < 1024
-    // Two wavefronts per unit where a pass has no more units than the workgroup has
-    // wavefronts: the decode work of the trellis schemes then spreads over all SIMDs.  Measured:
-    // 3 .. 5 % faster from 6 units per workgroup on (4096x14336: 14 units, 6144x4096: 6), a few
-    // per cent slower at 4 units (4096x4096), where the second copy of the shared pieces costs
-    // more than the idle SIMDs.  QP_OPT_LINEAR_SPLIT = 0 / 1 switches it off / on wherever it is legal.
+    // Two wavefronts per unit (trellis schemes, batch <= 2, a pass with no more units than the workgroup
+    // has wavefronts) spread the decode work over all SIMDs, but the pieces both halves need are read
+    // twice and twice as many wavefronts queue for the load path.  Measured per call, one / two wavefronts
+    // per unit: 4096x14336 at 3 bits V = 1 15.8 / 16.2 us, hybrid at 2, 4 and 5 bits 8.1 / 8.3, 9.4 / 10.2
+    // and 11.1 / 12.0 us, 4096x8192 at 3 bits hybrid 6.7 / 6.9 us; only 4096x4096 at 3 bits hybrid
+    // gains (5.4 / 5.2 us).  So: off unless QP_OPT_LINEAR_SPLIT = 1 asks for it where it is legal.
     const int split_opt = qp_opt(QP_OPT_LINEAR_SPLIT);
     const bool can_split = (scheme == QP_TCQ || scheme == QP_TCQH) && B <= 2 && units <= 16;
-    bool split = can_split && units >= 6;
+    bool split = false;
     if (split_opt == 0) split = false;
     if (split_opt == 1) split = can_split;
     // VQ 5 bit: the per-wavefront table while a workgroup has at most one unit per wavefront, at the
@@ -1211,9 +1301,16 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
     if (nw < 4) nw = 4;
     const float rot_norm = rot_block > 0 ? 1.0f / sqrtf((float)rot_block) : 0.f;
     if (rot_block > 0) {
-        // in-kernel rotation: batch 1, one block; up to 8 wavefronts transform it
-        if (B != 1 || rot_block != w.N || rot_block > 8192 || rot_block < 1024) return QP_ERR_UNSUPPORTED;
-        if (nw < 8) nw = 8;
+        if (B != 1) return QP_ERR_UNSUPPORTED;
+        if (rot_block == w.N) {
+            // in-kernel rotation of one block; up to 8 wavefronts transform it
+            if (rot_block > 8192 || rot_block < 1024) return QP_ERR_UNSUPPORTED;
+            if (nw < 8) nw = 8;
+        } else {
+            // N / 1024 blocks of 1024, one per wavefront
+            if (!qp_linear_rotates_blocks(scheme, w.M, w.N, rot_block) || rb_per_wg != 1) return QP_ERR_UNSUPPORTED;
+            nw = 16;
+        }
     }
     // A table that the whole workgroup shares is built after the first loads have been issued when
     // the workgroup has few units, and at batch >= 4 with row-major activations (whose many

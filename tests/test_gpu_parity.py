@@ -405,6 +405,68 @@ def test_rotate_linear_in_kernel_rotation_block_1024(qp):
     assert torch.equal(y, qp.qp_linear(w, qp.qp_hadamard(dev(x), dev(sg), 1024)))
 
 
+@pytest.mark.parametrize("scheme,cb,M,N", [(synth.VQ, 5, 4096, 14336), (synth.SQ, 4, 48, 16384), (synth.VQ, 7, 1040, 2048),
+                                           (synth.TCQH, 4, 512, 14336), (synth.TCQH, 9, 64, 3072), (synth.TCQH, 10, 4096, 2048),
+                                           (synth.TCQHH, 4, 256, 4096 + 2048), (synth.TCQ, 3, 64, 3072),
+                                           (synth.VQ, 5, 4112, 3072), (synth.SQ, 4, 32, 17408)],
+                         ids=["vq5-4096x14336", "sq4-48x16384", "vq7-1040x2048", "tcqh2-512x14336", "tcqh4.5-64x3072",
+                              "tcqh5-4096x2048", "tcqhh2.25-256x6144", "tcq3-two-launches", "vq5-4112-rows-two-launches",
+                              "sq4-17-blocks-two-launches"])
+def test_rotate_linear_rotates_blocks_of_1024_in_kernel(qp, scheme, cb, M, N):
+    """Batch 1, blocks of 1024, a layer of at most 4096 x 16384 (not the V = 1 trellis): one launch, every
+    wavefront transforms the block of its own unit on the matrix cores.  Same bits as rotation kernel +
+    layer kernel - which the larger layers and the V = 1 trellis still take - and the fp64 chain within
+    tolerance."""
+    lay = synth.make_layer(86, scheme * 10 + cb, scheme, M, N, cb)
+    x = synth.make_x(86, N % 89, 1, N)
+    sg = synth.make_signs(86, N % 89, N)
+    want = oracle.linear(lay, oracle.hadamard(x, sg, 1024, fast=True), threads=True)
+    w = qp.qp_repack(qp.Weight.from_layer(lay))
+    qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_BLOCK)
+    xd, sd = dev(x), dev(sg)
+    y_two = qp.qp_linear(w, qp.qp_hadamard(xd, sd, 1024))
+    y_one = qp.qp_rotate_linear(w, xd, sd, 1024)
+    y_again = qp.qp_rotate_linear(w, xd, sd, 1024)
+    qp.qp_set_option(qp.QP_OPT_ROTATE_SPLIT, 1)
+    y_split = qp.qp_rotate_linear(w, xd, sd, 1024)
+    torch.cuda.synchronize()
+    assert rel_err(host16(y_one), want) <= TOL_SHARP
+    assert torch.equal(y_one, y_two)
+    assert torch.equal(y_again, y_two)
+    assert torch.equal(y_split, y_two)
+    if scheme == synth.TCQH:
+        # two wavefronts per unit: a wavefront's half units lie in other column blocks than the one it transformed
+        qp.qp_reset_options()
+        qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_BLOCK)
+        qp.qp_set_option(qp.QP_OPT_LINEAR_SPLIT, 1)
+        y_two = qp.qp_linear(w, qp.qp_hadamard(xd, sd, 1024))
+        y_one = qp.qp_rotate_linear(w, xd, sd, 1024)
+        torch.cuda.synchronize()
+        assert rel_err(host16(y_one), want) <= TOL_SHARP
+        assert torch.equal(y_one, y_two)
+
+
+def test_hadamard_blocks_of_1024_both_kernels(qp):
+    """Blocks of 1024 run on the matrix cores when the output is 8-byte aligned, as ten butterfly stages
+    otherwise; both against the oracle, and against each other to an fp16 ulp."""
+    B, n = 3, 5120
+    x = synth.make_x(87, 0, B, n)
+    sg = synth.make_signs(87, 0, n)
+    want = oracle.hadamard(x, sg, 1024)
+    tol = np.abs(want) * 2.0 ** -11 + np.max(np.abs(want)) * 2.0 ** -20 + 2.0 ** -24
+    xd, sd = dev(x), dev(sg)
+    a = qp.qp_hadamard(xd, sd, 1024)
+    buf = torch.zeros(B * n + 8, dtype=torch.float16, device="cuda")
+    out = buf[1:1 + B * n].view(B, n)          # 2 bytes off an 8-byte boundary
+    qp.qp_hadamard(xd, sd, 1024, out=out)
+    torch.cuda.synchronize()
+    for got in (a, out):
+        assert np.all(np.abs(host16(got).view(np.float16).astype(np.float64) - want) <= tol)
+    assert float(buf[0]) == 0 and torch.all(buf[1 + B * n:] == 0)
+    ga, gb = host16(a).view(np.float16).astype(np.float64), host16(out).view(np.float16).astype(np.float64)
+    assert np.all(np.abs(ga - gb) <= np.spacing(np.abs(want).astype(np.float16)).astype(np.float64))
+
+
 @pytest.mark.parametrize("scheme,cb", [(synth.TCQ, 2), (synth.TCQ, 3), (synth.TCQ, 4)] +
                          [(synth.TCQH, s) for s in range(3, 11)],
                          ids=["tcq2", "tcq3", "tcq4"] + [f"tcqh{s / 2}" for s in range(3, 11)])
