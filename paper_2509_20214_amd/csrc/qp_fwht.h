@@ -295,3 +295,47 @@ __device__ __forceinline__ uint2 qp_fwht1024_pack(const float4_t &v) {
     const half2_t a = half2_t{(half_t)v[0], (half_t)v[1]}, b = half2_t{(half_t)v[2], (half_t)v[3]};
     return uint2{__builtin_bit_cast(uint32_t, a), __builtin_bit_cast(uint32_t, b)};
 }
+
+// ------------------------------------------------------------------ blocks of 2048 .. 8192 on the matrix cores
+// A block of 1024 W is W chunks of 1024 (H_{1024 W} = H_W (x) H_1024): W wavefronts transform a chunk each
+// (qp_fwht1024_run), park the fp32 results in LDS, and after a barrier 256 threads run the log2 W butterfly
+// stages across the chunks, scale by 1 / sqrt(W), round to fp16 and hand out 8 bytes at a time.
+// The parking room: QP_FWHT_EX_FLOATS(W) floats, a chunk's element e at e + (e >> 5) * 4 of its 1152 (one
+// 16-byte piece of padding per 32 floats keeps the 16-byte writes of a wavefront - rows of 32 floats apart -
+// off each other's banks).
+#define QP_FWHT_EX_CHUNK 1152
+#define QP_FWHT_EX_FLOATS(W) ((W) * QP_FWHT_EX_CHUNK)
+__device__ __forceinline__ int qp_fwht_ex_index(int chunk, int e) { return chunk * QP_FWHT_EX_CHUNK + e + ((e >> 5) << 2); }
+
+__device__ __forceinline__ void qp_fwht_park(float *ex, int chunk, int lane, const float4_t (&o)[2][2]) {
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+        for (int ta = 0; ta < 2; ++ta)
+            *reinterpret_cast<float4_t *>(ex + qp_fwht_ex_index(chunk, qp_fwht1024_elem(lane, tb, ta))) = o[tb][ta];
+}
+
+// Thread t (0 .. 255) finishes elements 4 t .. 4 t + 3 of every chunk; store(index in the block, 8 bytes).
+// scale = 32 / sqrt(1024 W), the part of the normalisation that the chunks do not carry yet; the product is
+// rounded to fp32 and then to fp16, two roundings, always (see qp_scale_round).
+template <int W, class Store>
+__device__ __forceinline__ void qp_fwht_cross(int t, const float *ex, float scale, Store store) {
+    float4_t v[W];
+#pragma unroll
+    for (int c = 0; c < W; ++c) v[c] = *reinterpret_cast<const float4_t *>(ex + qp_fwht_ex_index(c, 4 * t));
+#pragma unroll
+    for (int h = 1; h < W; h <<= 1)
+#pragma unroll
+        for (int c = 0; c < W; ++c)
+            if ((c & h) == 0) {
+                const float4_t a = v[c], b = v[c + h];
+                v[c] = a + b;
+                v[c + h] = a - b;
+            }
+#pragma unroll
+    for (int c = 0; c < W; ++c) {
+        const half2_t lo = half2_t{qp_scale_round(v[c][0], scale), qp_scale_round(v[c][1], scale)};
+        const half2_t hi = half2_t{qp_scale_round(v[c][2], scale), qp_scale_round(v[c][3], scale)};
+        store(1024 * c + 4 * t, uint2{__builtin_bit_cast(uint32_t, lo), __builtin_bit_cast(uint32_t, hi)});
+    }
+}

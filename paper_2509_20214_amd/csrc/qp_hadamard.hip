@@ -63,6 +63,32 @@ __global__ __launch_bounds__(256) void k_hadamard_1024(const half_t *x, const in
                 qp_fwht1024_pack(o[tb][ta]);
 }
 
+// Blocks of 1024 W, W = 2, 4, 8: one workgroup of W wavefronts per (batch row, block).
+template <int W>
+__global__ __launch_bounds__(64 * W < 256 ? 256 : 64 * W) void k_hadamard_chunks(const half_t *x, const int8_t *signs, int n,
+                                                                                 int64_t ldx, half_t *xr, int64_t ldxr,
+                                                                                 float norm, int pack_bp) {
+    constexpr int block = 1024 * W;
+    __shared__ __attribute__((aligned(16))) float ex[QP_FWHT_EX_FLOATS(W)];
+    const int nblk = n / block;
+    const int b = blockIdx.x / nblk, q = blockIdx.x - b * nblk;
+    const int col0 = q * block;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (wave < W) {
+        QpHad1024 H;
+        H.init(lane);
+        const QpHad1024In in = qp_fwht1024_fetch(x + (int64_t)b * ldx + col0 + 1024 * wave, signs + col0 + 1024 * wave, lane);
+        float4_t o[2][2];
+        qp_fwht1024_run(H, in, o);
+        qp_fwht_park(ex, wave, lane, o);
+    }
+    __syncthreads();
+    if (threadIdx.x < 256)
+        qp_fwht_cross<W>(threadIdx.x, ex, norm * 32.0f, [&](int idx, uint2 v) {
+            *reinterpret_cast<uint2 *>(xr + qp_xr_index(b, col0 + idx, ldxr, pack_bp)) = v;
+        });
+}
+
 static inline bool qp_aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 qp_status qp_launch_hadamard(const void *x, const int8_t *signs, int B, int n, int block, int64_t ldx,
@@ -78,6 +104,17 @@ qp_status qp_launch_hadamard(const void *x, const int8_t *signs, int B, int n, i
         const int items = grid;
         hipLaunchKernelGGL(k_hadamard_1024, dim3((items + 3) / 4), dim3(256), 0, st, (const half_t *)x, signs, n, ldx,
                            (half_t *)xr, ldxr, pack_bp, items);
+        return qp_check_launch();
+    }
+    if (vec_ok && (block == 2048 || block == 4096 || block == 8192) && (reinterpret_cast<uintptr_t>(xr) & 7) == 0 &&
+        ldxr % 4 == 0) {
+#define QP_HADC(W)                                                                                              \
+    hipLaunchKernelGGL((k_hadamard_chunks<W>), dim3(grid), dim3(64 * W < 256 ? 256 : 64 * W), 0, st, (const half_t *)x, \
+                       signs, n, ldx, (half_t *)xr, ldxr, norm, pack_bp)
+        if (block == 2048) QP_HADC(2);
+        else if (block == 4096) QP_HADC(4);
+        else QP_HADC(8);
+#undef QP_HADC
         return qp_check_launch();
     }
     if (vec_ok && block >= 256 && block <= 16384) {

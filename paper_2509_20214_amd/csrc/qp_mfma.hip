@@ -792,10 +792,10 @@ struct QpLinLds {
     static constexpr int SMALL_FLOATS = T::HYBRID ? (1 << T::TLUT_BITS) : 0;
     static constexpr int RED = RED_FLOATS > SMALL_FLOATS ? RED_FLOATS : SMALL_FLOATS;
     // in-kernel rotation (batch 1, one Hadamard block of at most 8192): the rotated
-    // activations (fp16) and the transform's transposition scratch (8192 + 256 floats),
-    // which borrows the table's room where that is large enough and still unused
+    // activations (fp16), and the transform's constant matrices and parked chunks (fp32),
+    // which borrow the table's room where that is large enough and still unused
     static constexpr int ROT_MAX = 8192;
-    static constexpr int ROT_SCRATCH_FLOATS = ROT_MAX + ROT_MAX / 32;
+    static constexpr int ROT_SCRATCH_FLOATS = 1024 + QP_FWHT_EX_FLOATS(ROT_MAX / 1024);   // constant matrices, parked chunks
     static constexpr bool ROT = (BP == 1);
     // (not a table that may be built before the rotation runs)
     // (only the 128 KiB table leaves no room for a scratch of its own; a table that may be built
@@ -812,7 +812,8 @@ struct QpLinLds {
 
 // XL: the activations are rotated here (Section 3.3), by the workgroup itself, into LDS, and
 // the B-operand fragments are read from there; otherwise they come from global memory.
-// XL == 1: one Hadamard block of up to 8192, transformed by up to eight wavefronts together.
+// XL == 1: one Hadamard block of 1024 W <= 8192, a chunk of 1024 per wavefront on the matrix cores and
+// log2 W butterfly stages across the chunks (qp_fwht_cross).
 // XL == 2: N / 1024 <= 16 blocks of 1024 and one row block per workgroup; every wavefront transforms
 // the block of its own unit on the matrix cores (qp_fwht1024_run, shared with the stand-alone kernel,
 // so the same bits).
@@ -821,7 +822,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
                                                int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic,
                                                int x_flags, const int8_t *signs, int rot_block, float rot_norm, uint8_t *tab,
                                                float *red, half_t *xr_lds, float *rot_buf) {
-    uint32_t *had_lds = reinterpret_cast<uint32_t *>(rot_buf);   // XL == 2: 4 KiB for the transform's constant matrices
+    uint32_t *had_lds = reinterpret_cast<uint32_t *>(rot_buf);   // in-kernel rotation: 4 KiB for the transform's constant matrices
     const int x_packed = x_flags & 0xff;   // activations in fragment order
     const int late_max = x_flags >> 8;     // a movable table is built after the first loads up to this many units
     using T = QpTraits<S, CB>;
@@ -926,7 +927,6 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     const auto xu = x_at(uu - ((uu * nbc_magic) >> 16) * nbc);   // column block = uu % nbc
     const int xn0 = half1 ? PF : 0;   // first fragment of this item
     // XL: the unrotated activations and their signs are requested first, ahead of the weights
-    float rv[16];
     QpHad1024In rin0;
     QpHad1024 had;
     if constexpr (XL == 2) {
@@ -935,11 +935,10 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
         const int c0 = wave < nbc ? wave : nbc - 1;
         rin0 = qp_fwht1024_fetch(x + 1024 * c0, signs + 1024 * c0, lane);
     } else if constexpr (XL == 1) {
-        const int t = threadIdx.x;
-        if (rot_block == 1024) qp_fwht_fetch<4>(t < 256, t, x, signs, reinterpret_cast<float(&)[4]>(rv));
-        else if (rot_block == 2048) qp_fwht_fetch<8>(t < 256, t, x, signs, reinterpret_cast<float(&)[8]>(rv));
-        else if (rot_block == 4096) qp_fwht_fetch<8>(t < 512, t, x, signs, reinterpret_cast<float(&)[8]>(rv));
-        else qp_fwht_fetch<16>(t < 512, t, x, signs, rv);
+        // chunk `wave` of the one block (a wavefront beyond the last chunk fetches the last one again - no
+        // branch around the loads - and drops it)
+        const int nch = rot_block >> 10;
+        rin0 = qp_fwht1024_fetch(x + 1024 * (wave < nch ? wave : nch - 1), signs + 1024 * (wave < nch ? wave : nch - 1), lane);
     } else {
 #pragma unroll
         for (int n = 0; n < PF; ++n) xf[n] = xu.frag(xn0 + n);
@@ -975,7 +974,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     // per thread, in front of a table build (whose barriers publish them) and behind the first loads:
     // vector work in front of loads delays them, four wavefronts share a SIMD.
     auto rotate_consts = [&]() __attribute__((always_inline)) {
-        if constexpr (XL == 2) QpHad1024::fill(had_lds);
+        if constexpr (XL != 0) QpHad1024::fill(had_lds);
     };
     u32x4_t q[P];
     bool full;
@@ -1041,23 +1040,53 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     }
     typename D::Lane lc = D::lane_const();
     QP_T(7);
-    if constexpr (XL == 1) {
-        // The weight loads of the first unit are in flight; meanwhile the first 64 W threads
-        // of the workgroup rotate the one block of activations (same arithmetic as the
-        // stand-alone kernel, so the same bits), everybody meets at the barriers.
-        const float norm = rot_norm;   // computed on the host, like the stand-alone kernel's
-        auto put = [&](int idx, half_t val) { xr_lds[qp_xr_index(0, idx, 0, 1)] = val; };
-        const int t = threadIdx.x;
-        if (rot_block == 1024) qp_fwht_finish<4, 4>(t < 256, t, reinterpret_cast<float(&)[4]>(rv), norm, rot_buf, put);
-        else if (rot_block == 2048) qp_fwht_finish<8, 4>(t < 256, t, reinterpret_cast<float(&)[8]>(rv), norm, rot_buf, put);
-        else if (rot_block == 4096) qp_fwht_finish<8, 8>(t < 512, t, reinterpret_cast<float(&)[8]>(rv), norm, rot_buf, put);
-        else qp_fwht_finish<16, 8>(t < 512, t, rv, norm, rot_buf, put);
-        __syncthreads();
+    // XL == 1: the first W = rot_block / 1024 wavefronts transform a chunk of 1024 each on the matrix cores
+    // and park it in LDS; 256 threads then run the stages across the chunks and write the rotated block in
+    // fragment order (same code as the stand-alone kernel, so the same bits).  Where the parking room borrows
+    // the table's, the table is built afterwards; otherwise before, while the activations are on their way.
+    auto rotate_chunks = [&]() __attribute__((always_inline)) {
+        if constexpr (XL == 1) {
+            __syncthreads();              // the constant matrices stand
+            QP_T(18);
+            if (wave < (rot_block >> 10)) {
+                had.read(had_lds, lane);
+                float4_t o[2][2];
+                qp_fwht1024_run(had, rin0, o);
+                qp_fwht_park(rot_buf + 1024, wave, lane, o);   // behind the constant matrices
+            }
+        }
+    };
+    auto rotate_across = [&]() __attribute__((always_inline)) {
+        if constexpr (XL == 1) {
+            const float *ex = rot_buf + 1024;
+            const int nch = rot_block >> 10;
+            __syncthreads();
+            if (threadIdx.x < 256) {
+                auto put = [&](int idx, uint2 v) { *reinterpret_cast<uint2 *>(xr_lds + qp_xr_index(0, idx, 0, 1)) = v; };
+                const float scale = rot_norm * 32.0f;
+                if (nch == 1) qp_fwht_cross<1>(threadIdx.x, ex, scale, put);
+                else if (nch == 2) qp_fwht_cross<2>(threadIdx.x, ex, scale, put);
+                else if (nch == 4) qp_fwht_cross<4>(threadIdx.x, ex, scale, put);
+                else qp_fwht_cross<8>(threadIdx.x, ex, scale, put);
+            }
+            QP_T(19);
+            __syncthreads();
 #pragma unroll
-        for (int n = 0; n < PF; ++n) xf[n] = xu.frag(xn0 + n);
+            for (int n = 0; n < PF; ++n) xf[n] = xu.frag(xn0 + n);
+        }
+    };
+    // (Measured slower with the late table build between the two halves: 4096x4096 at 2.5 bits 4.9 -> 5.3 us.)
+    constexpr bool ROT_FIRST = (XL == 1) && QpLinLds<D, S, CB, BP>::SCRATCH_IN_TAB;
+    if constexpr (ROT_FIRST) {
+        rotate_chunks();
+        rotate_across();
     }
     if constexpr (!MID_BUILD) {
         if (!MOVABLE || table_late) D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
+    }
+    if constexpr (!ROT_FIRST) {
+        rotate_chunks();
+        rotate_across();
     }
     if constexpr (XL == 2) {
         // Every wavefront transforms the block of its own unit on the matrix cores while its weights are

@@ -446,25 +446,27 @@ def test_rotate_linear_rotates_blocks_of_1024_in_kernel(qp, scheme, cb, M, N):
         assert torch.equal(y_one, y_two)
 
 
-def test_hadamard_blocks_of_1024_both_kernels(qp):
-    """Blocks of 1024 run on the matrix cores when the output is 8-byte aligned, as ten butterfly stages
-    otherwise; both against the oracle, and against each other to an fp16 ulp."""
-    B, n = 3, 5120
+@pytest.mark.parametrize("block", [1024, 2048, 4096, 8192])
+def test_hadamard_matrix_core_and_butterfly_kernels(qp, block):
+    """Blocks of 1024 .. 8192 run on the matrix cores when the output is 8-byte aligned, as butterfly stages
+    otherwise; both against the oracle, and against each other to neighbouring fp16 numbers."""
+    B, n = 3, (5 * 1024 if block == 1024 else 2 * block)
     x = synth.make_x(87, 0, B, n)
     sg = synth.make_signs(87, 0, n)
-    want = oracle.hadamard(x, sg, 1024)
+    want = oracle.hadamard(x, sg, block, fast=True)
     tol = np.abs(want) * 2.0 ** -11 + np.max(np.abs(want)) * 2.0 ** -20 + 2.0 ** -24
     xd, sd = dev(x), dev(sg)
-    a = qp.qp_hadamard(xd, sd, 1024)
+    a = qp.qp_hadamard(xd, sd, block)
     buf = torch.zeros(B * n + 8, dtype=torch.float16, device="cuda")
     out = buf[1:1 + B * n].view(B, n)          # 2 bytes off an 8-byte boundary
-    qp.qp_hadamard(xd, sd, 1024, out=out)
+    qp.qp_hadamard(xd, sd, block, out=out)
     torch.cuda.synchronize()
     for got in (a, out):
         assert np.all(np.abs(host16(got).view(np.float16).astype(np.float64) - want) <= tol)
     assert float(buf[0]) == 0 and torch.all(buf[1 + B * n:] == 0)
     ga, gb = host16(a).view(np.float16).astype(np.float64), host16(out).view(np.float16).astype(np.float64)
-    assert np.all(np.abs(ga - gb) <= np.spacing(np.abs(want).astype(np.float16)).astype(np.float64))
+    # (neighbouring fp16 numbers; across a power of two the larger of the two spacings applies)
+    assert np.all(np.abs(ga - gb) <= 2.0 * np.spacing(np.abs(want).astype(np.float16)).astype(np.float64) + 2.0 ** -24)
 
 
 @pytest.mark.parametrize("scheme,cb", [(synth.TCQ, 2), (synth.TCQ, 3), (synth.TCQ, 4)] +
