@@ -217,7 +217,8 @@ extern "C" qp_status qp_rotate_linear(const qp_weight *w, const void *x, const i
     // Batch 1 and one rotation block (N a power of two up to 8192): the layer's kernel rotates
     // the activations itself while its first weights are on their way - every workgroup repeats
     // the small transform, and the second launch is saved.  QP_OPT_ROTATE_SPLIT forces two launches.
-    if (B == 1 && block == w->N && block >= 1024 && block <= 8192 && !qp_opt(QP_OPT_ROTATE_SPLIT))
+    // (Not the V = 1 trellis: beside its 128 KiB table the transform has no room of its own in LDS.)
+    if (B == 1 && block == w->N && block >= 1024 && block <= 8192 && w->scheme != QP_TCQ && !qp_opt(QP_OPT_ROTATE_SPLIT))
         return qp_launch_linear_mfma(d, w->scheme, w->code_bits, x, 1, ldx, y, ldy, 0, signs, block, st);
     // Batch 1, several blocks of 1024 and a layer of at most 4096 x 16384 (N = 14336 ...): every
     // wavefront of a workgroup transforms the block of its own unit; again one launch.

@@ -796,11 +796,9 @@ struct QpLinLds {
     // which borrow the table's room where that is large enough and still unused
     static constexpr int ROT_MAX = 8192;
     static constexpr int ROT_SCRATCH_FLOATS = 1024 + QP_FWHT_EX_FLOATS(ROT_MAX / 1024);   // constant matrices, parked chunks
-    static constexpr bool ROT = (BP == 1);
-    // (not a table that may be built before the rotation runs)
-    // (only the 128 KiB table leaves no room for a scratch of its own; a table that may be built
-    // before the rotation runs cannot lend its room)
-    static constexpr bool SCRATCH_IN_TAB = !QpTableMovable<D>::value && D::TAB_BYTES > 65536;
+    // (not beside the 128 KiB table of the V = 1 trellis: the transform would have to borrow the table's room
+    // and run before the table is built - measured no faster than two launches, 8192x8192 23.6 against 20.7 us)
+    static constexpr bool ROT = (BP == 1) && D::TAB_BYTES <= 65536;
     // per-wavefront rotation of N / 1024 <= 16 blocks (batch 1): the rotated activations of the whole
     // row; the 128 KiB table leaves no room for that
     static constexpr int ROTM_MAX = 16384;
@@ -860,7 +858,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     // (a table that can be built at either point: late when the workgroup has few units)
     constexpr bool MOVABLE = QpTableMovable<D>::value;
     // (not where the in-kernel rotation's scratch borrows the table's room first)
-    constexpr bool MID_BUILD = !MOVABLE && !(XL && QpLinLds<D, S, CB, BP>::SCRATCH_IN_TAB) &&
+    constexpr bool MID_BUILD = !MOVABLE &&
                                (S == QP_TCQ || S == QP_TCQH || S == QP_TCQHH);
     const bool table_late = MOVABLE && (rb_q + (rb_r ? 1 : 0)) * w.nbc <= late_max;
     QP_T(13);
@@ -1076,18 +1074,11 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
         }
     };
     // (Measured slower with the late table build between the two halves: 4096x4096 at 2.5 bits 4.9 -> 5.3 us.)
-    constexpr bool ROT_FIRST = (XL == 1) && QpLinLds<D, S, CB, BP>::SCRATCH_IN_TAB;
-    if constexpr (ROT_FIRST) {
-        rotate_chunks();
-        rotate_across();
-    }
     if constexpr (!MID_BUILD) {
         if (!MOVABLE || table_late) D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
     }
-    if constexpr (!ROT_FIRST) {
-        rotate_chunks();
-        rotate_across();
-    }
+    rotate_chunks();
+    rotate_across();
     if constexpr (XL == 2) {
         // Every wavefront transforms the block of its own unit on the matrix cores while its weights are
         // on their way, and writes it to LDS in fragment order (four consecutive elements = 8 bytes).
@@ -1227,8 +1218,7 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
                                             rot_block, rot_norm, tab, red, xr_all, had_consts);
     } else if constexpr (XL == 1) {
         __shared__ __attribute__((aligned(16))) half_t xr_lds[L::ROT_MAX];
-        __shared__ __attribute__((aligned(16))) float rot_own[L::SCRATCH_IN_TAB ? 1 : L::ROT_SCRATCH_FLOATS];
-        float *rot_buf = L::SCRATCH_IN_TAB ? reinterpret_cast<float *>(tab) : rot_own;
+        __shared__ __attribute__((aligned(16))) float rot_buf[L::ROT_SCRATCH_FLOATS];
         qp_linear_body<S, CB, BP, 1, SPLIT>(w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
                                             rot_block, rot_norm, tab, red, xr_lds, rot_buf);
     } else {
@@ -1253,11 +1243,13 @@ static void qp_launch_xl(int grid, int nw, hipStream_t st, const QpW &w, const v
                 return;
             }
         }
-        if (rot_block > 0) {
-            hipLaunchKernelGGL((k_linear_mfma<S, CB, BP, SPLIT, 1>), dim3(grid), dim3(64 * nw), 0, st, w,
-                               (const half_t *)x, B, ldx, (half_t *)y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
-                               rot_block, rot_norm);
-            return;
+        if constexpr (QpLinLds<D, S, CB, BP>::ROT) {
+            if (rot_block > 0) {
+                hipLaunchKernelGGL((k_linear_mfma<S, CB, BP, SPLIT, 1>), dim3(grid), dim3(64 * nw), 0, st, w,
+                                   (const half_t *)x, B, ldx, (half_t *)y, ldy, G, rb_q, rb_r, nbc_magic, x_packed,
+                                   signs, rot_block, rot_norm);
+                return;
+            }
         }
     }
     hipLaunchKernelGGL((k_linear_mfma<S, CB, BP, SPLIT, 0>), dim3(grid), dim3(64 * nw), 0, st, w,
@@ -1333,7 +1325,7 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
         if (B != 1) return QP_ERR_UNSUPPORTED;
         if (rot_block == w.N) {
             // in-kernel rotation of one block; up to 8 wavefronts transform it
-            if (rot_block > 8192 || rot_block < 1024) return QP_ERR_UNSUPPORTED;
+            if (rot_block > 8192 || rot_block < 1024 || scheme == QP_TCQ) return QP_ERR_UNSUPPORTED;
             if (nw < 8) nw = 8;
         } else {
             // N / 1024 blocks of 1024, one per wavefront
