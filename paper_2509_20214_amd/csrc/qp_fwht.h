@@ -269,8 +269,12 @@ __device__ __forceinline__ void qp_fwht1024_run(const QpHad1024 &H, const QpHad1
             for (int r = 0; r < 4; r += 2) {   // two at a time: packed conversions, mixed-precision subtractions
                 const float t0 = t1[ta][tb][r], t1v = t1[ta][tb][r + 1];
                 const half2_t h = half2_t{(half_t)t0, (half_t)t1v};
-                const half2_t l = half2_t{(half_t)__builtin_fmaf((float)h[0], -1.0f, t0),    // t - hi is exact in fp32
-                                          (half_t)__builtin_fmaf((float)h[1], -1.0f, t1v)};
+                // t - hi (exact in fp32) as one mixed-precision operation per value, reading hi from its half of
+                // the packed register (the compiler converts back and subtracts: two operations)
+                float l0, l1;
+                asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(l0) : "v"(h), "v"(t0));
+                asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(l1) : "v"(h), "v"(t1v));
+                const half2_t l = half2_t{(half_t)l0, (half_t)l1};
                 hi[4 * ta + r] = h[0];
                 hi[4 * ta + r + 1] = h[1];
                 lo[4 * ta + r] = l[0];
