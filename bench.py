@@ -136,24 +136,49 @@ def sweep_model(model, label, torch, synth, qp, dev, upload, graph_of, event_tim
     Ms = sorted({d["M"] for row in model for d in row})
     n_proj = sum(len(row) for row in model)
     for B in (1, 8):
-        xs = {N: upload(synth.make_x(5, N, B, N)) for N in Ns}
+        # every projection of a decoder layer has an input of its own (position in the layer), shared by all layers
+        width = max(len(ws) for ws in layers)
+        xs = {(N, i): upload(synth.make_x(5, N + i, B, N)) for N in Ns for i in range(width)}
         sg = {N: upload(synth.make_signs(5, N, N)) for N in Ns}
-        wsp = {N: torch.empty(2 * 16 * N, dtype=torch.uint8, device=dev) for N in xs}
+        wsp = {N: torch.empty(2 * 16 * N, dtype=torch.uint8, device=dev) for N in Ns}
         ys = {M: torch.empty((B, M), dtype=torch.float16, device=dev) for M in Ms}
 
         def step():
             for ws in layers:
-                for d, nat in ws:
+                for i, (d, nat) in enumerate(ws):
                     N = d["N"]
-                    qp.qp_rotate_linear(nat, xs[N], sg[N], synth.hadamard_block(N), y=ys[d["M"]], workspace=wsp[N])
+                    qp.qp_rotate_linear(nat, xs[(N, i)], sg[N], synth.hadamard_block(N), y=ys[d["M"]], workspace=wsp[N])
 
         g = graph_of(step, 1)
         g.replay()
         us = event_time_us(g, 1, repeats=5)
+        # the same step as one unit of the library (qp_block_*): one call enqueues it, one graph launch replays it
+        blk = qp.Block([(nat, xs[(d["N"], i)], sg[d["N"]], synth.hadamard_block(d["N"]), ys[d["M"]])
+                        for ws in layers for i, (d, nat) in enumerate(ws)])
+        blk.graph()
+
+        def wall_us(f, reps=5):
+            out = []
+            for _ in range(reps):
+                torch.cuda.synchronize()
+                t = time.perf_counter()
+                f()
+                torch.cuda.synchronize()
+                out.append((time.perf_counter() - t) * 1e6)
+            return statistics.median(out)
+
+        blk.run()
+        us_block_graph = wall_us(blk.run)
+        us_calls = wall_us(step)
+        us_enqueue = wall_us(blk.enqueue)
+        blk.close()
         out_cases.append({"batch": B, "ms_per_model_step": round(us / 1e3, 4),
                           "weight_GBps": round(total_bytes / us / 1e3, 1),
                           "frac_of_peak": round(total_bytes / us / 1e3 / HBM_PEAK_GBS, 4),
-                          "steps_per_s": round(1e6 / us, 1)})
+                          "steps_per_s": round(1e6 / us, 1),
+                          "wall_ms_host_included": {"one_python_call_per_projection": round(us_calls / 1e3, 4),
+                                                    "qp_block_enqueue": round(us_enqueue / 1e3, 4),
+                                                    "qp_block_run": round(us_block_graph / 1e3, 4)}})
     print(json.dumps({"metric": f"{label}: one decode step through all {n_proj} quantized projections "
                                 f"({len(model)} decoder layers resident), rotation + fused layer each",
                       "resident_weight_GiB": round(total_bytes / 2**30, 2), "setup_s": round(setup_s, 1),

@@ -158,6 +158,43 @@ qp_status qp_rotate_linear(const qp_weight *w, const void *x, const int8_t *sign
                            void *hip_stream);
 size_t qp_rotate_linear_workspace_bytes(const qp_weight *w, int32_t B);
 
+/* A decoder block's rotations and fused layers as one unit (Section 4.2: layers that share an input
+ * are what fusion groups; Appendix E.2 measures a block end to end): n items, each one qp_rotate_linear
+ * call's arguments, run in order on one stream with no host work between them.  Consecutive items
+ * with the same (x, signs, block, B, ldx) and the same N share one rotation where that is cheaper
+ * than rotating inside each layer's kernel: q, k, v read one rotated copy, gate and up another.
+ * Every y is the same, bit for bit, as the qp_rotate_linear call of its item.
+ *   qp_block_enqueue   validates every item, then launches everything (two workspaces' worth of
+ *                      room: qp_block_workspace_bytes; device, 256-byte aligned).
+ *   qp_block_create    the same sequence captured once into a HIP graph that the library owns;
+ *                      qp_block_run replays it with one graph launch, qp_block_destroy frees it.
+ *                      The graph holds the pointers of the items and of the workspace as they were
+ *                      at creation (the buffers' contents may change between runs, their addresses
+ *                      and shapes may not) and the tuning options in force then.  Creation allocates
+ *                      host and driver objects (not device memory through this library) and must not
+ *                      itself run under stream capture; runs that overlap in time share the workspace
+ *                      and race.
+ * Errors: those of qp_rotate_linear for the first offending item (nothing is launched then);
+ * QP_ERR_SHAPE for n < 1 or n > 4096; QP_ERR_DEVICE when capture or instantiation fails. */
+typedef struct qp_block_item {
+    const qp_weight *w;
+    const void *x;          /* device fp16 [B, ldx], unrotated */
+    const int8_t *signs;    /* device int8 [N] */
+    int32_t block;
+    int32_t B;
+    int64_t ldx;
+    void *y;                /* device fp16 [B, ldy] */
+    int64_t ldy;
+} qp_block_item;
+typedef struct qp_block qp_block;
+size_t qp_block_workspace_bytes(const qp_block_item *items, int32_t n);
+qp_status qp_block_enqueue(const qp_block_item *items, int32_t n, void *workspace, size_t workspace_bytes,
+                           void *hip_stream);
+qp_status qp_block_create(const qp_block_item *items, int32_t n, void *workspace, size_t workspace_bytes,
+                          qp_block **out);
+qp_status qp_block_run(const qp_block *blk, void *hip_stream);
+qp_status qp_block_destroy(qp_block *blk);
+
 /* qp_rotate_linear for callers that cannot allocate device memory or hand in a workspace: code
  * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
  * without the workspace, same kernels, same result bit for bit; the rotated activations pass

@@ -16,7 +16,8 @@ EXPORTS = ["qp_linear", "qp_dequant", "qp_hadamard", "qp_repack", "qp_native_byt
            "qp_rotate_linear", "qp_rotate_linear_workspace_bytes", "qp_encode", "qp_encode_workspace_bytes",
            "qp_row_normalize", "qp_msq_solve", "qp_kmeans", "qp_kmeans_workspace_bytes",
            "qp_set_option", "qp_get_option", "qp_reset_options", "qp_rotate_linear_static",
-           "qp_rotate_linear_static_max_bytes", "qp_bench_stream_read", "qp_bench_empty_launch", "qp_msq_solve_fused"]
+           "qp_rotate_linear_static_max_bytes", "qp_bench_stream_read", "qp_bench_empty_launch", "qp_msq_solve_fused",
+           "qp_block_workspace_bytes", "qp_block_enqueue", "qp_block_create", "qp_block_run", "qp_block_destroy"]
 
 # qp_option (include/qp.h)
 QP_OPT_LINEAR_KERNEL, QP_OPT_DEQUANT_KERNEL, QP_OPT_ROTATE_SPLIT, QP_OPT_LINEAR_PACK = 0, 1, 2, 3
@@ -30,6 +31,11 @@ class qp_weight(C.Structure):
                 ("vec", C.c_int32), ("window_bits", C.c_int32), ("tile", C.c_int32), ("layout", C.c_int32),
                 ("row_stride", C.c_int64), ("codes", C.c_void_p), ("lut", C.c_void_p), ("scales", C.c_void_p),
                 ("tlut_bits", C.c_int32), ("reserved", C.c_int32)]
+
+
+class qp_block_item(C.Structure):
+    _fields_ = [("w", C.POINTER(qp_weight)), ("x", C.c_void_p), ("signs", C.c_void_p), ("block", C.c_int32),
+                ("B", C.c_int32), ("ldx", C.c_int64), ("y", C.c_void_p), ("ldy", C.c_int64)]
 
 
 class QpError(RuntimeError):
@@ -67,6 +73,17 @@ def load_library(build_if_missing: bool = True):
     L.qp_rotate_linear_static.argtypes = [wp, vp, vp, i32, i32, i64, vp, i64, vp]
     L.qp_rotate_linear_static_max_bytes.restype = sz
     L.qp_rotate_linear_static_max_bytes.argtypes = []
+    bp = C.POINTER(qp_block_item)
+    L.qp_block_workspace_bytes.restype = sz
+    L.qp_block_workspace_bytes.argtypes = [bp, i32]
+    L.qp_block_enqueue.restype = C.c_int
+    L.qp_block_enqueue.argtypes = [bp, i32, vp, sz, vp]
+    L.qp_block_create.restype = C.c_int
+    L.qp_block_create.argtypes = [bp, i32, vp, sz, C.POINTER(vp)]
+    L.qp_block_run.restype = C.c_int
+    L.qp_block_run.argtypes = [vp, vp]
+    L.qp_block_destroy.restype = C.c_int
+    L.qp_block_destroy.argtypes = [vp]
     L.qp_bench_stream_read.restype = C.c_int
     L.qp_bench_stream_read.argtypes = [vp, sz, vp, vp]
     L.qp_bench_empty_launch.restype = C.c_int
@@ -380,6 +397,70 @@ def qp_rotate_linear_static(w: Weight, x, signs, block: int, y, stream=None):
                                                   x.stride(0), y.data_ptr(), y.stride(0), _stream_ptr(stream)),
            "qp_rotate_linear_static")
     return y
+
+
+class Block:
+    """A decoder block's rotations and layers as one unit: `items` is a list of (Weight, x, signs, block, y)
+    with x fp16 [B, N] unrotated and y fp16 [B, M]; the tensors (and the workspace made here) are kept alive
+    by this object.  enqueue() launches the sequence, graph() captures it once into a graph that the
+    library owns and run() replays it."""
+
+    def __init__(self, items):
+        import torch
+        self.items = list(items)
+        self._arr = (qp_block_item * len(self.items))()
+        for a, (w, x, signs, block, y) in zip(self._arr, self.items):
+            a.w, a.x, a.signs, a.block = C.pointer(w.desc), x.data_ptr(), signs.data_ptr(), block
+            a.B, a.ldx, a.y, a.ldy = x.shape[0], x.stride(0), y.data_ptr(), y.stride(0)
+        need = qp_block_workspace_bytes(self)
+        self.workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=self.items[0][1].device)
+        self._handle = None
+
+    def enqueue(self, stream=None):
+        qp_block_enqueue(self, stream)
+
+    def graph(self):
+        if self._handle is None:
+            self._handle = qp_block_create(self)
+        return self
+
+    def run(self, stream=None):
+        qp_block_run(self.graph()._handle, stream)
+
+    def close(self):
+        if self._handle is not None:
+            qp_block_destroy(self._handle)
+            self._handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def qp_block_workspace_bytes(blk: "Block") -> int:
+    return int(load_library().qp_block_workspace_bytes(blk._arr, len(blk._arr)))
+
+
+def qp_block_enqueue(blk: "Block", stream=None):
+    _check(load_library().qp_block_enqueue(blk._arr, len(blk._arr), blk.workspace.data_ptr(), blk.workspace.numel(),
+                                           _stream_ptr(stream)), "qp_block_enqueue")
+
+
+def qp_block_create(blk: "Block"):
+    h = C.c_void_p()
+    _check(load_library().qp_block_create(blk._arr, len(blk._arr), blk.workspace.data_ptr(), blk.workspace.numel(),
+                                          C.byref(h)), "qp_block_create")
+    return h
+
+
+def qp_block_run(handle, stream=None):
+    _check(load_library().qp_block_run(handle, _stream_ptr(stream)), "qp_block_run")
+
+
+def qp_block_destroy(handle):
+    _check(load_library().qp_block_destroy(handle), "qp_block_destroy")
 
 
 def qp_bench_stream_read(data, sink, stream=None):

@@ -3,10 +3,11 @@
 #include <atomic>
 #include <climits>
 #include <cstring>
+#include <new>
 
 #include "qp_internal.h"
 
-#define QP_VERSION 200
+#define QP_VERSION 210
 
 // ------------------------------------------------------------------ tuning options
 // Plain process-wide integers (relaxed atomics: a read is an ordinary load); nothing here or
@@ -227,6 +228,145 @@ extern "C" qp_status qp_rotate_linear(const qp_weight *w, const void *x, const i
     s = qp_launch_hadamard(x, signs, B, w->N, block, ldx, workspace, w->N, pow2_at_least(B), st);
     if (s != QP_OK) return s;
     return qp_launch_linear_mfma(d, w->scheme, w->code_bits, workspace, B, w->N, y, ldy, 1, nullptr, 0, st);
+}
+
+// ------------------------------------------------------------------ a decoder block as one unit
+static qp_status block_item_check(const qp_block_item &it) {
+    if (!it.w) return QP_ERR_NULL;
+    qp_status s = qp_validate(it.w);
+    if (s != QP_OK) return s;
+    if (!it.x || !it.signs || !it.y) return QP_ERR_NULL;
+    if (it.B < 1 || it.B > QP_MAX_BATCH) return QP_ERR_SHAPE;
+    if (it.ldx < it.w->N || it.ldx > QP_MAX_LDX || it.ldy < it.w->M || it.ldx % 8 != 0) return QP_ERR_SHAPE;
+    if (it.block < 2 || it.block > 16384 || (it.block & (it.block - 1)) != 0 || it.w->N % it.block != 0) return QP_ERR_SHAPE;
+    if (!aligned(it.x, 16) || !aligned(it.y, 2) || !aligned(it.signs, 16)) return QP_ERR_ALIGN;
+    return QP_OK;
+}
+
+static bool block_same_input(const qp_block_item &a, const qp_block_item &b) {
+    return a.x == b.x && a.signs == b.signs && a.block == b.block && a.B == b.B && a.ldx == b.ldx && a.w->N == b.w->N;
+}
+
+// Whether qp_rotate_linear would rotate inside the layer's kernel (one launch).
+static bool rotates_in_kernel(const qp_weight *w, int B, int block) {
+    if (B != 1 || use_rowwave(w) || qp_opt(QP_OPT_ROTATE_SPLIT)) return false;
+    if (block == w->N) return block >= 1024 && block <= 8192 && w->scheme != QP_TCQ;
+    return qp_linear_rotates_blocks(w->scheme, w->M, w->N, block);
+}
+
+extern "C" size_t qp_block_workspace_bytes(const qp_block_item *items, int32_t n) {
+    if (!items || n < 1) return 0;
+    size_t need = 0;
+    for (int i = 0; i < n; ++i) {
+        if (!items[i].w) return 0;
+        const size_t one = qp_rotate_linear_workspace_bytes(items[i].w, items[i].B);
+        if (one > need) need = one;
+    }
+    return 2 * need;   // a shared rotation may be needed in fragment order and row-major at once
+}
+
+extern "C" qp_status qp_block_enqueue(const qp_block_item *items, int32_t n, void *workspace, size_t workspace_bytes,
+                                      void *hip_stream) {
+    if (!items || !workspace) return QP_ERR_NULL;
+    if (n < 1 || n > 4096) return QP_ERR_SHAPE;
+    for (int i = 0; i < n; ++i) {
+        const qp_status s = block_item_check(items[i]);
+        if (s != QP_OK) return s;
+    }
+    if (!aligned(workspace, 256)) return QP_ERR_ALIGN;
+    const size_t need = qp_block_workspace_bytes(items, n);
+    if (workspace_bytes < need) return QP_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    void *ws_packed = workspace, *ws_rows = static_cast<char *>(workspace) + need / 2;
+    for (int i = 0; i < n;) {
+        int j = i + 1;
+        while (j < n && block_same_input(items[i], items[j])) ++j;
+        const qp_block_item &a = items[i];
+        // One rotation for the whole group costs a launch of its own (about 2 us); rotating inside every
+        // layer's kernel costs each of them about 1 us where that form exists (batch 1), and a launch
+        // each where it does not.
+        bool all_in_kernel = true;
+        for (int k = i; k < j; ++k) all_in_kernel = all_in_kernel && rotates_in_kernel(items[k].w, a.B, a.block);
+        const bool share = (j - i >= 2) && (!all_in_kernel || j - i >= 3);
+        if (!share) {
+            for (int k = i; k < j; ++k) {
+                const qp_block_item &it = items[k];
+                const qp_status s = qp_rotate_linear(it.w, it.x, it.signs, it.block, it.B, it.ldx, it.y, it.ldy, workspace,
+                                                     workspace_bytes, hip_stream);
+                if (s != QP_OK) return s;
+            }
+        } else {
+            bool any_rows = false, any_blocks = false;
+            for (int k = i; k < j; ++k) (use_rowwave(items[k].w) ? any_rows : any_blocks) = true;
+            const int N = a.w->N;
+            qp_status s = QP_OK;
+            if (any_blocks) s = qp_launch_hadamard(a.x, a.signs, a.B, N, a.block, a.ldx, ws_packed, N, pow2_at_least(a.B), st);
+            if (s == QP_OK && any_rows) s = qp_launch_hadamard(a.x, a.signs, a.B, N, a.block, a.ldx, ws_rows, N, 0, st);
+            for (int k = i; k < j && s == QP_OK; ++k) {
+                const qp_block_item &it = items[k];
+                const QpW d = make_dev(it.w);
+                if (use_rowwave(it.w)) s = qp_launch_linear_rowwave(d, it.w->scheme, it.w->code_bits, ws_rows, it.B, N, it.y, it.ldy, st);
+                else s = qp_launch_linear_mfma(d, it.w->scheme, it.w->code_bits, ws_packed, it.B, N, it.y, it.ldy, 1, nullptr, 0, st);
+            }
+            if (s != QP_OK) return s;
+        }
+        i = j;
+    }
+    return QP_OK;
+}
+
+struct qp_block {
+    hipGraphExec_t exec;
+};
+
+extern "C" qp_status qp_block_create(const qp_block_item *items, int32_t n, void *workspace, size_t workspace_bytes,
+                                     qp_block **out) {
+    if (!out) return QP_ERR_NULL;
+    *out = nullptr;
+    if (!items || !workspace) return QP_ERR_NULL;
+    if (n < 1 || n > 4096) return QP_ERR_SHAPE;
+    for (int i = 0; i < n; ++i) {   // refuse before anything is created
+        const qp_status s = block_item_check(items[i]);
+        if (s != QP_OK) return s;
+    }
+    if (!aligned(workspace, 256)) return QP_ERR_ALIGN;
+    if (workspace_bytes < qp_block_workspace_bytes(items, n)) return QP_ERR_WORKSPACE;
+    hipStream_t cs = nullptr;
+    if (hipStreamCreateWithFlags(&cs, hipStreamNonBlocking) != hipSuccess) return QP_ERR_DEVICE;
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    qp_status s = QP_ERR_DEVICE;
+    if (hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal) == hipSuccess) {
+        s = qp_block_enqueue(items, n, workspace, workspace_bytes, cs);
+        const hipError_t e = hipStreamEndCapture(cs, &graph);   // always ends the capture, also after an error
+        if (s == QP_OK && (e != hipSuccess || !graph)) s = QP_ERR_DEVICE;
+        if (s == QP_OK && hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0) != hipSuccess) s = QP_ERR_DEVICE;
+    }
+    if (graph) (void)hipGraphDestroy(graph);
+    (void)hipStreamDestroy(cs);
+    if (s != QP_OK) {
+        (void)hipGetLastError();
+        return s;
+    }
+    qp_block *b = new (std::nothrow) qp_block{exec};
+    if (!b) {
+        (void)hipGraphExecDestroy(exec);
+        return QP_ERR_MEMORY;
+    }
+    *out = b;
+    return QP_OK;
+}
+
+extern "C" qp_status qp_block_run(const qp_block *blk, void *hip_stream) {
+    if (!blk) return QP_ERR_NULL;
+    return hipGraphLaunch(blk->exec, static_cast<hipStream_t>(hip_stream)) == hipSuccess ? QP_OK : QP_ERR_DEVICE;
+}
+
+extern "C" qp_status qp_block_destroy(qp_block *blk) {
+    if (!blk) return QP_ERR_NULL;
+    const hipError_t e = hipGraphExecDestroy(blk->exec);
+    delete blk;
+    return e == hipSuccess ? QP_OK : QP_ERR_DEVICE;
 }
 
 // ------------------------------------------------------------------ the entry point that allocates nothing

@@ -258,3 +258,20 @@ def test_bench_aids_reject_bad_arguments_on_the_host():
     assert L.qp_bench_stream_read(0x1000, 1000, 0x2000, None) == 2      # not a multiple of 16
     assert L.qp_bench_stream_read(0x1008, 1024, 0x2000, None) == 4
     assert L.qp_bench_stream_read(0x1000, 1024, 0x2002, None) == 4
+
+
+def test_block_argument_errors_do_not_launch():
+    """qp_block_*: every refusal comes before any device call (this test runs without a GPU)."""
+    L = qp.load_library()
+    from paper_2509_20214_amd.binding import qp_block_item
+    items = (qp_block_item * 2)()
+    h = C.c_void_p()
+    assert L.qp_block_enqueue(None, 1, C.c_void_p(256), 1024, None) == 1
+    assert L.qp_block_enqueue(items, 0, C.c_void_p(256), 1024, None) == 2
+    assert L.qp_block_enqueue(items, 5000, C.c_void_p(256), 1024, None) == 2
+    assert L.qp_block_enqueue(items, 2, C.c_void_p(256), 1024, None) == 1        # items[0].w is NULL
+    assert L.qp_block_create(items, 2, C.c_void_p(256), 1024, None) == 1
+    assert L.qp_block_create(items, 2, C.c_void_p(256), 1024, C.byref(h)) == 1 and not h.value
+    assert L.qp_block_workspace_bytes(items, 2) == 0
+    assert L.qp_block_run(None, None) == 1
+    assert L.qp_block_destroy(None) == 1
