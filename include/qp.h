@@ -157,6 +157,9 @@ qp_status qp_rotate_linear(const qp_weight *w, const void *x, const int8_t *sign
                            int64_t ldx, void *y, int64_t ldy, void *workspace, size_t workspace_bytes,
                            void *hip_stream);
 size_t qp_rotate_linear_workspace_bytes(const qp_weight *w, int32_t B);
+/* How many kernels qp_rotate_linear launches for this layer, batch and block with the options in
+ * force: 1 when the layer's kernel rotates the activations itself, else 2 (0 for a NULL descriptor). */
+int32_t qp_rotate_linear_launches(const qp_weight *w, int32_t B, int32_t block);
 
 /* A decoder block's rotations and fused layers as one unit (Section 4.2: layers that share an input
  * are what fusion groups; Appendix E.2 measures a block end to end): n items, each one qp_rotate_linear

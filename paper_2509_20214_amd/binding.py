@@ -13,7 +13,7 @@ QP_OK = 0
 
 EXPORTS = ["qp_linear", "qp_dequant", "qp_hadamard", "qp_repack", "qp_native_bytes",
            "qp_linear_workspace_bytes", "qp_validate", "qp_status_string", "qp_version",
-           "qp_rotate_linear", "qp_rotate_linear_workspace_bytes", "qp_encode", "qp_encode_workspace_bytes",
+           "qp_rotate_linear", "qp_rotate_linear_workspace_bytes", "qp_rotate_linear_launches", "qp_encode", "qp_encode_workspace_bytes",
            "qp_row_normalize", "qp_msq_solve", "qp_kmeans", "qp_kmeans_workspace_bytes",
            "qp_set_option", "qp_get_option", "qp_reset_options", "qp_rotate_linear_static",
            "qp_rotate_linear_static_max_bytes", "qp_bench_stream_read", "qp_bench_empty_launch", "qp_msq_solve_fused",
@@ -90,6 +90,8 @@ def load_library(build_if_missing: bool = True):
     L.qp_bench_empty_launch.argtypes = [vp]
     L.qp_rotate_linear_workspace_bytes.restype = sz
     L.qp_rotate_linear_workspace_bytes.argtypes = [wp, i32]
+    L.qp_rotate_linear_launches.restype = i32
+    L.qp_rotate_linear_launches.argtypes = [wp, i32, i32]
     L.qp_dequant.restype = C.c_int
     L.qp_dequant.argtypes = [wp, vp, vp]
     L.qp_encode.restype = C.c_int
@@ -367,6 +369,10 @@ def qp_hadamard(x, signs, block: int, out=None, stream=None):
 
 def qp_rotate_linear_workspace_bytes(w: Weight, B: int) -> int:
     return int(load_library().qp_rotate_linear_workspace_bytes(C.byref(w.desc), B))
+
+
+def qp_rotate_linear_launches(w: Weight, B: int, block: int) -> int:
+    return int(load_library().qp_rotate_linear_launches(C.byref(w.desc), B, block))
 
 
 def qp_rotate_linear(w: Weight, x, signs, block: int, y=None, workspace=None, stream=None):

@@ -193,6 +193,18 @@ extern "C" size_t qp_rotate_linear_workspace_bytes(const qp_weight *w, int32_t B
     return round256((size_t)pow2_at_least(B) * (size_t)w->N * 2);
 }
 
+// Whether qp_rotate_linear would rotate inside the layer's kernel (one launch).
+static bool rotates_in_kernel(const qp_weight *w, int B, int block) {
+    if (B != 1 || use_rowwave(w) || qp_opt(QP_OPT_ROTATE_SPLIT)) return false;
+    if (block == w->N) return block >= 1024 && block <= 8192 && w->scheme != QP_TCQ;
+    return qp_linear_rotates_blocks(w->scheme, w->M, w->N, block);
+}
+
+extern "C" int32_t qp_rotate_linear_launches(const qp_weight *w, int32_t B, int32_t block) {
+    if (!w) return 0;
+    return rotates_in_kernel(w, B, block) ? 1 : 2;
+}
+
 extern "C" qp_status qp_rotate_linear(const qp_weight *w, const void *x, const int8_t *signs, int32_t block,
                                       int32_t B, int64_t ldx, void *y, int64_t ldy, void *workspace,
                                       size_t workspace_bytes, void *hip_stream) {
@@ -215,15 +227,12 @@ extern "C" qp_status qp_rotate_linear(const qp_weight *w, const void *x, const i
         if (s != QP_OK) return s;
         return qp_launch_linear_rowwave(d, w->scheme, w->code_bits, workspace, B, w->N, y, ldy, st);
     }
-    // Batch 1 and one rotation block (N a power of two up to 8192): the layer's kernel rotates
-    // the activations itself while its first weights are on their way - every workgroup repeats
-    // the small transform, and the second launch is saved.  QP_OPT_ROTATE_SPLIT forces two launches.
-    // (Not the V = 1 trellis: beside its 128 KiB table the transform has no room of its own in LDS.)
-    if (B == 1 && block == w->N && block >= 1024 && block <= 8192 && w->scheme != QP_TCQ && !qp_opt(QP_OPT_ROTATE_SPLIT))
-        return qp_launch_linear_mfma(d, w->scheme, w->code_bits, x, 1, ldx, y, ldy, 0, signs, block, st);
-    // Batch 1, several blocks of 1024 and a layer of at most 4096 x 16384 (N = 14336 ...): every
-    // wavefront of a workgroup transforms the block of its own unit; again one launch.
-    if (B == 1 && qp_linear_rotates_blocks(w->scheme, w->M, w->N, block) && !qp_opt(QP_OPT_ROTATE_SPLIT))
+    // Batch 1 and either one rotation block (N a power of two up to 8192) or several blocks of 1024 in a
+    // layer of at most 4096 x 16384 (N = 14336 ...): the layer's kernel rotates the activations itself
+    // while its first weights are on their way - every workgroup repeats the small transform, and the
+    // second launch is saved.  Not the V = 1 trellis (beside its 128 KiB table the transform has no room
+    // of its own in LDS).  QP_OPT_ROTATE_SPLIT forces two launches.
+    if (rotates_in_kernel(w, B, block))
         return qp_launch_linear_mfma(d, w->scheme, w->code_bits, x, 1, ldx, y, ldy, 0, signs, block, st);
     s = qp_launch_hadamard(x, signs, B, w->N, block, ldx, workspace, w->N, pow2_at_least(B), st);
     if (s != QP_OK) return s;
@@ -245,13 +254,6 @@ static qp_status block_item_check(const qp_block_item &it) {
 
 static bool block_same_input(const qp_block_item &a, const qp_block_item &b) {
     return a.x == b.x && a.signs == b.signs && a.block == b.block && a.B == b.B && a.ldx == b.ldx && a.w->N == b.w->N;
-}
-
-// Whether qp_rotate_linear would rotate inside the layer's kernel (one launch).
-static bool rotates_in_kernel(const qp_weight *w, int B, int block) {
-    if (B != 1 || use_rowwave(w) || qp_opt(QP_OPT_ROTATE_SPLIT)) return false;
-    if (block == w->N) return block >= 1024 && block <= 8192 && w->scheme != QP_TCQ;
-    return qp_linear_rotates_blocks(w->scheme, w->M, w->N, block);
 }
 
 extern "C" size_t qp_block_workspace_bytes(const qp_block_item *items, int32_t n) {

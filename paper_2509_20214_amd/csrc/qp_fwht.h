@@ -17,6 +17,17 @@ __device__ __forceinline__ int64_t qp_xr_index(int b, int col, int64_t ldxr, int
     return ((((int64_t)((C << (5 - lt)) + n) << 6) + 16 * g + (b << lt) + t) << 3) + e;
 }
 
+// The copy of the rotated activations that a layer's kernel keeps in LDS for itself (batch 1, fragment
+// order) is swizzled: the 16-byte piece of lane l of a fragment sits in slot l ^ ((l >> 3) & 7).  Readers -
+// one piece per lane - still cover every 128-byte row with each group of eight lanes; the writers of the
+// matrix-core transform, whose sixteen lanes of a row would otherwise hit two bank pairs (eight-way conflict,
+// 400 k conflict cycles per launch of 4096x14336), spread over all of them.
+__device__ __forceinline__ int qp_xr_swizzle_lane(int lane) { return lane ^ ((lane >> 3) & 7); }
+__device__ __forceinline__ int qp_xr_swizzled(int64_t half_index) {
+    const int h = (int)half_index, slot = (h >> 3) & 63;
+    return (h & ~(63 << 3)) | (qp_xr_swizzle_lane(slot) << 3);
+}
+
 // Fast path for blocks of 256..16384: thread t holds V consecutive values.  The
 // butterfly stages factor over the bits of the element index e = [wave | lane | k]:
 // the k bits are done in registers, the lane bits with wavefront shuffles, the wave

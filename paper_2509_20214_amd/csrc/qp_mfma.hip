@@ -907,7 +907,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     constexpr bool XBUF = !XL && BP >= 8 && S != QP_TCQ;
     // the lane's part of the address: a 32-bit byte offset (the host checks that it fits) or its pointer
     const uint32_t xlo = x_packed ? 16u * lane : 2u * ((uint32_t)(xlive ? bj : 0) * (uint32_t)ldx + 256u * g + 8u * tj);
-    const half_t *xlane = XL ? xr_lds + 8 * lane
+    const half_t *xlane = XL ? xr_lds + 8 * qp_xr_swizzle_lane(lane)
                              : (x_packed ? x + 8 * lane : x + (int64_t)(xlive ? bj : 0) * ldx + 256 * g + 8 * tj);
     const int xcs = (XL || x_packed) ? 1024 * BP : 1024;   // halves between column blocks
     const int xfs = (XL || x_packed) ? 512 : 8 * TT;       // halves between fragments
@@ -1060,7 +1060,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
             const int nch = rot_block >> 10;
             __syncthreads();
             if (threadIdx.x < 256) {
-                auto put = [&](int idx, uint2 v) { *reinterpret_cast<uint2 *>(xr_lds + qp_xr_index(0, idx, 0, 1)) = v; };
+                auto put = [&](int idx, uint2 v) { *reinterpret_cast<uint2 *>(xr_lds + qp_xr_swizzled(qp_xr_index(0, idx, 0, 1))) = v; };
                 const float scale = rot_norm * 32.0f;
                 if (nch == 1) qp_fwht_cross<1>(threadIdx.x, ex, scale, put);
                 else if (nch == 2) qp_fwht_cross<2>(threadIdx.x, ex, scale, put);
@@ -1088,6 +1088,8 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
         if constexpr (!QpLinLds<D, S, CB, BP>::TABLE_HAS_BARRIER) __syncthreads();   // the constant matrices
         had.read(had_lds, lane);
         QP_T(18);
+        // (Transforming in front of an early table build instead - the SIMDs are idle there - delays the
+        // remaining loads by as much as it saves: 8.3 against 8.1 us on 4096x14336 at 2.5 bits.)
         if (wave < nbc) {
             float4_t o[2][2];
             qp_fwht1024_run(had, rin0, o);
@@ -1095,7 +1097,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
             for (int tb = 0; tb < 2; ++tb)
 #pragma unroll
                 for (int ta = 0; ta < 2; ++ta)
-                    *reinterpret_cast<uint2 *>(xr_lds + qp_xr_index(0, 1024 * wave + qp_fwht1024_elem(lane, tb, ta), 0, 1)) =
+                    *reinterpret_cast<uint2 *>(xr_lds + qp_xr_swizzled(qp_xr_index(0, 1024 * wave + qp_fwht1024_elem(lane, tb, ta), 0, 1))) =
                         qp_fwht1024_pack(o[tb][ta]);
         }
         QP_T(19);

@@ -158,6 +158,8 @@ def test_rotate_linear_argument_errors_do_not_launch():
     assert call(0x4000, 0x5000, 1024, 0, 1024, 0x6000, 16, 0x10000, need) == 2
     assert call(0x4000, 0x5000, 1024, 1, 1024, 0x6000, 16, 0x10010, need) == 4
     assert L.qp_rotate_linear_workspace_bytes(None, 1) == 0
+    assert L.qp_rotate_linear_launches(None, 1, 1024) == 0
+    assert L.qp_rotate_linear_launches(C.byref(d), 2, 1024) == 2
 
 
 def test_repack_argument_errors_do_not_launch():

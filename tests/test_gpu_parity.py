@@ -423,6 +423,9 @@ def test_rotate_linear_rotates_blocks_of_1024_in_kernel(qp, scheme, cb, M, N):
     want = oracle.linear(lay, oracle.hadamard(x, sg, 1024, fast=True), threads=True)
     w = qp.qp_repack(qp.Weight.from_layer(lay))
     qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_BLOCK)
+    one_launch = scheme != synth.TCQ and M <= 4096 and N <= 16384
+    assert qp.qp_rotate_linear_launches(w, 1, 1024) == (1 if one_launch else 2)
+    assert qp.qp_rotate_linear_launches(w, 2, 1024) == 2
     xd, sd = dev(x), dev(sg)
     y_two = qp.qp_linear(w, qp.qp_hadamard(xd, sd, 1024))
     y_one = qp.qp_rotate_linear(w, xd, sd, 1024)
