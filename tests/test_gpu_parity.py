@@ -449,6 +449,26 @@ def test_rotate_linear_rotates_blocks_of_1024_in_kernel(qp, scheme, cb, M, N):
         assert torch.equal(y_one, y_two)
 
 
+@pytest.mark.parametrize("scheme,cb,M,N,block", [(synth.VQ, 5, 256, 3072, 1024), (synth.TCQH, 6, 512, 5120, 1024),
+                                                 (synth.SQ, 4, 4096, 2048, 2048), (synth.TCQHH, 4, 256, 4096, 4096)],
+                         ids=["vq5-3-blocks", "tcqh3-5-blocks", "sq4-one-block-2048", "tcqhh2.25-one-block-4096"])
+def test_rotate_linear_in_kernel_rotation_canonical_layout(qp, scheme, cb, M, N, block):
+    """The one-launch forms on weights that were not repacked (the block kernel reads the canonical layout too)."""
+    lay = synth.make_layer(88, scheme * 10 + cb, scheme, M, N, cb)
+    x = synth.make_x(88, N % 89, 1, N)
+    sg = synth.make_signs(88, N % 89, N)
+    want = oracle.linear(lay, oracle.hadamard(x, sg, block, fast=True), threads=True)
+    w = qp.Weight.from_layer(lay)
+    qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_BLOCK)
+    assert qp.qp_rotate_linear_launches(w, 1, block) == 1
+    xd, sd = dev(x), dev(sg)
+    y_two = qp.qp_linear(w, qp.qp_hadamard(xd, sd, block))
+    y_one = qp.qp_rotate_linear(w, xd, sd, block)
+    torch.cuda.synchronize()
+    assert rel_err(host16(y_one), want) <= TOL_SHARP
+    assert torch.equal(y_one, y_two)
+
+
 @pytest.mark.parametrize("block", [1024, 2048, 4096, 8192])
 def test_hadamard_matrix_core_and_butterfly_kernels(qp, block):
     """Blocks of 1024 .. 8192 run on the matrix cores when the output is 8-byte aligned, as butterfly stages
