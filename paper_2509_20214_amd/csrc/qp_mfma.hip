@@ -37,10 +37,11 @@
 //
 // Variants of the same kernel: the activations come row-major from global memory, in
 // fragment order from global memory (written that way by the rotation kernel), or - batch 1,
-// one Hadamard block - are rotated by the workgroup itself into LDS while its first weights
-// are in flight (qp_fwht.h; a kernel instance of its own, so that the plain one does not carry
-// the transform's LDS arrays); for the trellis schemes at batch <= 2 a unit can be shared by two
-// wavefronts that decode half of its steps each.  The file ends with the dequantize-only
+// one Hadamard block of up to 8192 or up to 16 blocks of 1024 - are rotated by the workgroup
+// itself into LDS while its first weights are in flight (qp_fwht.h: on the matrix cores; kernel
+// instances of their own, so that the plain one does not carry the transform's LDS arrays); for
+// the trellis schemes at batch <= 2 a unit can be shared by two wavefronts that decode half of
+// its steps each (on request).  The file ends with the dequantize-only
 // kernel for the native layout, which reuses the units, loads and decoders.
 //
 // A workgroup owns a contiguous range of 16-row blocks and walks it in passes of G
@@ -589,6 +590,9 @@ struct QpXBuf {
     uint32_t lo;   // the lane's bytes
     int xfs;       // bytes between fragments
     __device__ __forceinline__ half8_t frag(int n, uint32_t lane_off) const {
+#ifdef QP_NOX  // development builds only: no activation loads, to time what they cost
+        return __builtin_bit_cast(half8_t, u32x4_t{lane_off, (uint32_t)(soff + xfs * n), 0x3c003c00u, 0x3c003c00u});
+#endif
         return __builtin_bit_cast(half8_t, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)lane_off, soff + xfs * n, 0));
     }
     __device__ __forceinline__ half8_t frag(int n) const { return frag(n, lo); }
