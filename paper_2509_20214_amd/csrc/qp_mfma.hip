@@ -1319,7 +1319,11 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
     // batch sizes where it measured faster than the workgroup's byte-window table (4096x14336,
     // us per call, per-wavefront / shared: batch 1 7.3 / 6.7, 2 7.35 / 7.07, 3 7.7 / 7.9, 4 7.8 / 8.7,
     // 8 10.85 / 10.1, 16 with fragment-order activations 14.05 / 15.4).
-    if (scheme == QP_VQ && cb == 5 && rb_per_wg * nbc <= 16 && ((B > 2 && B <= 4) || (B > 8 && x_packed))) {
+    // (Batch 3 - 4 only from 9 units per workgroup on: with the shared table's lookups issued ahead,
+    // 4096x4096 runs 4.55 -> 3.97 us and 4096x8192 5.70 -> 5.46 us on the shared table, 4096x12288 and
+    // 4096x14336 stay faster with the private one, 7.15 / 7.9 against 7.4 / 8.5 us.)
+    const int units_wg = rb_per_wg * nbc;
+    if (scheme == QP_VQ && cb == 5 && units_wg <= 16 && ((B > 2 && B <= 4 && units_wg > 8) || (B > 8 && x_packed))) {
         split = split_opt != 0;
     }
     int nw = units < 16 ? units : 16;
