@@ -55,6 +55,9 @@ def parse():
     p.add_argument("--layer", type=int, default=0)
     p.add_argument("--batch", type=int, default=1)
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--micro", action="store_true",
+                   help="build and run the stand-alone micro-benchmarks under paper_2509_20214_amd/csrc/microbench "
+                        "(lookup paths, multiply of a decode step) and print what they print")
     p.add_argument("--no-cases", action="store_true", help="skip the table of other (layer, batch) cases")
     p.add_argument("--sweep70b", action="store_true",
                    help="configuration 5: all 80 layers of the 70B-shaped mixed-scheme model resident, "
@@ -438,6 +441,19 @@ def main():
             out.append(e0.elapsed_time(e1) * 1e3 / count)
         return statistics.median(out)
 
+    if a.micro:
+        import subprocess
+        import tempfile
+        src_dir = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2509_20214_amd", "csrc", "microbench")
+        with tempfile.TemporaryDirectory() as tmp:
+            for name in sorted(f for f in os.listdir(src_dir) if f.endswith(".hip")):
+                exe = os.path.join(tmp, name[:-4])
+                subprocess.check_call(["/opt/rocm/bin/hipcc", "-O3", "--offload-arch=gfx950", "-Xclang", "-target-feature",
+                                       "-Xclang", "-packed-fp32-ops", "-o", exe, os.path.join(src_dir, name)],
+                                      stderr=subprocess.DEVNULL)
+                print(f"== {name}", flush=True)
+                subprocess.check_call([exe])
+        return
     if a.sweep70b:
         sweep_model(synth.config5_model(80), "configuration 5, 70B-shaped mixed-scheme model", torch, synth, qp, dev,
                     upload, graph_of, event_time_us)
