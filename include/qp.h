@@ -147,9 +147,12 @@ qp_status qp_hadamard(const void *x, const int8_t *signs, int32_t B, int32_t n, 
  * Two kernels are enqueued, with the rotated activations (fp16) passing through the workspace
  * in whatever order the layer's kernel reads them best (for the native layout: the order of
  * its matrix-core operand fragments, so that its activation loads stay contiguous at every
- * batch size) - or one kernel, at batch 1 on the native layout when block == N is a power of
- * two between 1024 and 8192: its workgroups then rotate the activations themselves while
- * their first weights are on the way, and the workspace is not touched.
+ * batch size) - or one kernel, at batch 1, where the layer's kernel can rotate the activations
+ * itself while its first weights are on the way (the workspace is then not touched): block == N
+ * a power of two between 1024 and 8192, or blocks of 1024 in a layer of at most 4096 x 16384 -
+ * not the V = 1 trellis; tiny and ragged layers (those the row kernel takes) with N a multiple
+ * of 1024 up to 8192 likewise, the V = 1 trellis with blocks of 1024 only.
+ * qp_rotate_linear_launches tells which.
  * x: device fp16 [B, ldx], unrotated, 16-byte aligned, ldx % 8 == 0, N <= ldx <= QP_MAX_LDX;
  * signs: device int8 [N], 16-byte aligned.  workspace: device, 256-byte aligned, at least
  * qp_rotate_linear_workspace_bytes(w, B) bytes; contents on entry and exit are unspecified. */

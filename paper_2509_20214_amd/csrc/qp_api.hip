@@ -195,7 +195,8 @@ extern "C" size_t qp_rotate_linear_workspace_bytes(const qp_weight *w, int32_t B
 
 // Whether qp_rotate_linear would rotate inside the layer's kernel (one launch).
 static bool rotates_in_kernel(const qp_weight *w, int B, int block) {
-    if (B != 1 || use_rowwave(w) || qp_opt(QP_OPT_ROTATE_SPLIT)) return false;
+    if (B != 1 || qp_opt(QP_OPT_ROTATE_SPLIT)) return false;
+    if (use_rowwave(w)) return qp_rowwave_rotates(w->scheme, w->code_bits, w->N, block);
     if (block == w->N) return block >= 1024 && block <= 8192 && w->scheme != QP_TCQ;
     return qp_linear_rotates_blocks(w->scheme, w->M, w->N, block);
 }
@@ -223,6 +224,9 @@ extern "C" qp_status qp_rotate_linear(const qp_weight *w, const void *x, const i
     // every one of its activation loads is a contiguous KiB whatever the batch; the results
     // are the same bit for bit (same values, same order of operations, other addresses).
     if (use_rowwave(w)) {
+        // a tiny layer at batch 1: the row kernel rotates the activations itself where it can
+        if (rotates_in_kernel(w, B, block))
+            return qp_launch_linear_rowwave_rot(d, w->scheme, w->code_bits, x, signs, block, y, st);
         s = qp_launch_hadamard(x, signs, B, w->N, block, ldx, workspace, w->N, 0, st);
         if (s != QP_OK) return s;
         return qp_launch_linear_rowwave(d, w->scheme, w->code_bits, workspace, B, w->N, y, ldy, st);

@@ -10,6 +10,10 @@ qp_status qp_launch_dequant(const QpW &w, int scheme, int cb, void *out, hipStre
 qp_status qp_launch_dequant_blocks(const QpW &w, int scheme, int cb, void *out, hipStream_t st);
 qp_status qp_launch_linear_rowwave(const QpW &w, int scheme, int cb, const void *x, int B, int64_t ldx,
                                    void *y, int64_t ldy, hipStream_t st);
+// the row kernel with the rotation inside (batch 1, x and y contiguous rows); the predicate says where it exists
+bool qp_rowwave_rotates(int scheme, int cb, int N, int rot_block);
+qp_status qp_launch_linear_rowwave_rot(const QpW &w, int scheme, int cb, const void *x, const int8_t *signs,
+                                       int rot_block, void *y, hipStream_t st);
 bool qp_linear_rotates_blocks(int scheme, int M, int N, int rot_block);
 qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x, int B, int64_t ldx, void *y,
                                 int64_t ldy, int x_packed, const int8_t *signs, int rot_block, hipStream_t st);

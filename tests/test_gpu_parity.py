@@ -449,6 +449,41 @@ def test_rotate_linear_rotates_blocks_of_1024_in_kernel(qp, scheme, cb, M, N):
         assert torch.equal(y_one, y_two)
 
 
+@pytest.mark.parametrize("scheme,cb,M,N,block,one", [
+    (synth.SQ, 4, 1024, 1024, 1024, True), (synth.VQ, 5, 37, 3072, 1024, True), (synth.VQ, 7, 1000, 2048, 2048, True),
+    (synth.TCQ, 3, 48, 2048, 1024, True), (synth.TCQ, 2, 64, 2048, 2048, False), (synth.TCQH, 6, 5, 8192, 8192, True),
+    (synth.TCQH, 10, 130, 7168, 1024, True), (synth.TCQHH, 4, 256, 4096, 4096, True), (synth.SQ, 4, 16, 9216, 1024, False),
+    (synth.VQ, 5, 64, 2048, 512, False)],
+    ids=["sq4-1024x1024", "vq5-37x3072", "vq7-1000x2048-one-block", "tcq3-48x2048", "tcq2-one-block-two-launches",
+         "tcqh3-5x8192-one-block", "tcqh5-130x7168", "tcqhh2.25-256x4096-one-block", "sq4-9-blocks-two-launches",
+         "vq5-blocks-of-512-two-launches"])
+def test_rotate_linear_row_kernel_rotates_in_kernel(qp, scheme, cb, M, N, block, one):
+    """Tiny and ragged layers (the row kernel) at batch 1, N <= 8192, blocks of 1024 or one block of up to 8192:
+    one launch, the workgroup rotates the row into LDS itself.  Same bits as rotation kernel + layer kernel;
+    the fp64 chain within tolerance.  Beside the V = 1 trellis' table only blocks of 1024."""
+    lay = synth.make_layer(89, scheme * 10 + cb, scheme, M, N, cb)
+    x = synth.make_x(89, N % 89, 1, N)
+    sg = synth.make_signs(89, N % 89, N)
+    want = oracle.linear(lay, oracle.hadamard(x, sg, block, fast=True), threads=True)
+    w = qp.Weight.from_layer(lay)
+    if M % 16 == 0 and scheme != synth.VQ: w = qp.qp_repack(w)
+    qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_ROW)
+    assert qp.qp_rotate_linear_launches(w, 1, block) == (1 if one else 2)
+    assert qp.qp_rotate_linear_launches(w, 2, block) == 2
+    xd, sd = dev(x), dev(sg)
+    y_two = qp.qp_linear(w, qp.qp_hadamard(xd, sd, block))
+    y_one = qp.qp_rotate_linear(w, xd, sd, block)
+    y_again = qp.qp_rotate_linear(w, xd, sd, block)
+    qp.qp_set_option(qp.QP_OPT_ROTATE_SPLIT, 1)
+    assert qp.qp_rotate_linear_launches(w, 1, block) == 2
+    y_split = qp.qp_rotate_linear(w, xd, sd, block)
+    torch.cuda.synchronize()
+    assert rel_err(host16(y_one), want) <= TOL_SHARP
+    assert torch.equal(y_one, y_two)
+    assert torch.equal(y_again, y_two)
+    assert torch.equal(y_split, y_two)
+
+
 @pytest.mark.parametrize("scheme,cb,M,N,block", [(synth.VQ, 5, 256, 3072, 1024), (synth.TCQH, 6, 512, 5120, 1024),
                                                  (synth.SQ, 4, 4096, 2048, 2048), (synth.TCQHH, 4, 256, 4096, 4096)],
                          ids=["vq5-3-blocks", "tcqh3-5-blocks", "sq4-one-block-2048", "tcqhh2.25-one-block-4096"])
