@@ -121,21 +121,27 @@ static QpW make_dev(const qp_weight *w) {
 }
 
 // Which kernel runs a layer.  QP_OPT_LINEAR_KERNEL = 1 / 2 forces the row / the block kernel (used
-// by the tests to cover both on weights of any size); 0 lets the shape decide.
-// The matrix-core kernel pays a fixed table-build and reduction cost per workgroup; below
-// one 16x1024 block per CU (measured: 1024x1024 runs 3.2 us on the row kernel, 6.4 us on
-// the block kernel) the row kernel is the faster one.
-static bool use_rowwave(const qp_weight *w) {
+// by the tests to cover both on weights of any size); 0 lets shape, scheme and batch decide.
+// The block kernel needs whole 16 x 1024 blocks; everything else goes to the row kernel.  Below one
+// block per compute unit the row kernel still wins where a row is short and the batch is small
+// (us per call, row / block kernel): 4 bit scalar 1024x1024 batch 1 3.15 / 3.45, batch 2 3.9 / 3.5,
+// batch 8 7.5 / 3.6; pairs at 2.5 bits 256x1024 3.3 / 3.6 but 1024x2048 5.0 / 3.7 and 256x4096
+// 7.5 / 3.7; the V = 1 trellis, whose block kernel first stages a 128 KiB table, 1024x1024 at 3 bits
+// batch 1 / 2 / 4 4.7 / 5.5 / 6.5 against 6.2 / 6.25 / 6.6 and 1024x2048 batch 1 5.9 / 6.6, batch 2
+// 7.55 / 6.6; the V = 2 trellis never (1024x1024 at 3 bits 6.3 / 4.4, 1024x3072 14.1 / 4.7).
+static bool use_rowwave(const qp_weight *w, int B) {
     const int nbc = w->N / 1024;
     const int force = qp_opt(QP_OPT_LINEAR_KERNEL);
     const int64_t blocks = (int64_t)(w->M / 16) * nbc;
-    // the block kernel needs whole 16 x 1024 blocks; it reads them from either layout (in the
-    // canonical one a lane's pieces are consecutive in its row instead of one KiB per piece)
+    // the block kernel reads whole blocks from either layout (in the canonical one a lane's pieces
+    // are consecutive in its row instead of one KiB per piece)
     const bool fits = w->M % 16 == 0 && w->N % 1024 == 0 && nbc <= 32 &&
                       !(w->scheme == QP_TCQHH && w->N % 2048 != 0);
-    bool rowwave = !fits || blocks < 256 || force == 1;
-    if (force == 2 && fits) rowwave = false;
-    return rowwave;
+    if (!fits || force == 1) return true;
+    if (force == 2 || blocks >= 256) return false;
+    if (w->scheme == QP_SQ || w->scheme == QP_VQ) return nbc == 1 && B == 1;
+    if (w->scheme == QP_TCQ) return (nbc == 1 && B <= 4) || (nbc == 2 && B == 1);
+    return false;
 }
 
 static inline int pow2_at_least(int B) { return B <= 1 ? 1 : B <= 2 ? 2 : B <= 4 ? 4 : B <= 8 ? 8 : 16; }
@@ -153,7 +159,7 @@ static inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 // gains the same: launches of large kernels back to back cost more than the same launches with
 // any small kernel between them - an effect of the launch sequence, not of the layout.
 static bool pack_pays(const qp_weight *w, int B) {
-    if (use_rowwave(w)) return false;
+    if (use_rowwave(w, B)) return false;
     if (const int force = qp_opt(QP_OPT_LINEAR_PACK); force >= 0) return force == 1;   // always / never
     const int64_t weights = (int64_t)w->M * w->N;
     if (B > 8) return weights >= ((int64_t)1 << 25);
@@ -176,7 +182,7 @@ extern "C" qp_status qp_linear(const qp_weight *w, const void *x, int32_t B, int
     if (!aligned(x, 16) || !aligned(y, 2)) return QP_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     QpW d = make_dev(w);
-    if (use_rowwave(w)) return qp_launch_linear_rowwave(d, w->scheme, w->code_bits, x, B, ldx, y, ldy, st);
+    if (use_rowwave(w, B)) return qp_launch_linear_rowwave(d, w->scheme, w->code_bits, x, B, ldx, y, ldy, st);
     // The workspace is optional: without one (or with one that is too small or not 256-byte
     // aligned) the layer reads the activations where they are - same result, bit for bit.
     const size_t need = qp_linear_workspace_bytes(w, B);
@@ -196,7 +202,7 @@ extern "C" size_t qp_rotate_linear_workspace_bytes(const qp_weight *w, int32_t B
 // Whether qp_rotate_linear would rotate inside the layer's kernel (one launch).
 static bool rotates_in_kernel(const qp_weight *w, int B, int block) {
     if (B != 1 || qp_opt(QP_OPT_ROTATE_SPLIT)) return false;
-    if (use_rowwave(w)) return qp_rowwave_rotates(w->scheme, w->code_bits, w->N, block);
+    if (use_rowwave(w, B)) return qp_rowwave_rotates(w->scheme, w->code_bits, w->N, block);
     if (block == w->N) return block >= 1024 && block <= 8192 && w->scheme != QP_TCQ;
     return qp_linear_rotates_blocks(w->scheme, w->M, w->N, block);
 }
@@ -223,7 +229,7 @@ extern "C" qp_status qp_rotate_linear(const qp_weight *w, const void *x, const i
     // the rotation writes them in the order that kernel loads its B-operand fragments, so that
     // every one of its activation loads is a contiguous KiB whatever the batch; the results
     // are the same bit for bit (same values, same order of operations, other addresses).
-    if (use_rowwave(w)) {
+    if (use_rowwave(w, B)) {
         // a tiny layer at batch 1: the row kernel rotates the activations itself where it can
         if (rotates_in_kernel(w, B, block))
             return qp_launch_linear_rowwave_rot(d, w->scheme, w->code_bits, x, signs, block, y, st);
@@ -303,7 +309,7 @@ extern "C" qp_status qp_block_enqueue(const qp_block_item *items, int32_t n, voi
             }
         } else {
             bool any_rows = false, any_blocks = false;
-            for (int k = i; k < j; ++k) (use_rowwave(items[k].w) ? any_rows : any_blocks) = true;
+            for (int k = i; k < j; ++k) (use_rowwave(items[k].w, a.B) ? any_rows : any_blocks) = true;
             const int N = a.w->N;
             qp_status s = QP_OK;
             if (any_blocks) s = qp_launch_hadamard(a.x, a.signs, a.B, N, a.block, a.ldx, ws_packed, N, pow2_at_least(a.B), st);
@@ -311,7 +317,7 @@ extern "C" qp_status qp_block_enqueue(const qp_block_item *items, int32_t n, voi
             for (int k = i; k < j && s == QP_OK; ++k) {
                 const qp_block_item &it = items[k];
                 const QpW d = make_dev(it.w);
-                if (use_rowwave(it.w)) s = qp_launch_linear_rowwave(d, it.w->scheme, it.w->code_bits, ws_rows, it.B, N, it.y, it.ldy, st);
+                if (use_rowwave(it.w, it.B)) s = qp_launch_linear_rowwave(d, it.w->scheme, it.w->code_bits, ws_rows, it.B, N, it.y, it.ldy, st);
                 else s = qp_launch_linear_mfma(d, it.w->scheme, it.w->code_bits, ws_packed, it.B, N, it.y, it.ldy, 1, nullptr, 0, st);
             }
             if (s != QP_OK) return s;
