@@ -33,7 +33,9 @@
  * tiles of the second half (16 (s + 1) bytes each).
  *
  * NATIVE LAYOUT (QP_LAYOUT_NATIVE), produced by qp_repack; needs M % 16 == 0 and
- * N % 1024 == 0.  The matrix is cut into blocks of 16 rows x 1024 columns, stored
+ * N % 256 == 0.  The matrix is cut into blocks of 16 rows x 1024 columns (ceil(N / 1024) per
+ * block row; where N is not a multiple of 1024 - 11008, 13824 - the spans of the last column
+ * block that lie beyond N hold zero bytes and the kernels multiply them with zeros), stored
  * block-row-major (all column blocks of rows 0..15, then rows 16..31, ...).  Within
  * a block, "lane" l = 16*g + i (g = 0..3, i = 0..15) owns row i, columns
  * 256*g .. 256*g+255 of the block: the same 32*bpw bytes that the canonical stream
@@ -41,7 +43,7 @@
  * pieces of 16 bytes; piece p of lane l sits at byte (p*64 + l)*16 of the block, so
  * one 128-bit load per lane of a 64-wide wavefront reads 1 KiB contiguously.
  * row_stride is ignored for this layout.  It is the layout the kernels are fastest on; layers
- * made of whole blocks run the same matrix-core kernel from the canonical layout too, some
+ * of these shapes run the same matrix-core kernel from the canonical layout too, some
  * 25 % slower, anything else a layout-agnostic kernel.  QP_TCQHH (needs N % 2048 == 0): the column blocks of the
  * second half have one piece more than those of the first; a block row is the N/2048 blocks of the
  * first half followed by the N/2048 blocks of the second.

@@ -97,7 +97,8 @@ extern "C" qp_status qp_validate(const qp_weight *w) {
         if (w->row_stride < row_bytes(w)) return QP_ERR_SHAPE;
         if ((int64_t)w->row_stride * w->M > ((int64_t)1 << 40)) return QP_ERR_SHAPE;
     } else if (w->layout == QP_LAYOUT_NATIVE) {
-        if (w->M % 16 != 0 || w->N % 1024 != 0) return QP_ERR_LAYOUT;
+        // whole 16 x 256 spans; a last column block of fewer than 1024 columns is padded with zero bytes
+        if (w->M % 16 != 0 || w->N % 256 != 0) return QP_ERR_LAYOUT;
         if (w->scheme == QP_TCQHH && w->N % 2048 != 0) return QP_ERR_LAYOUT;
     } else {
         return QP_ERR_LAYOUT;
@@ -115,7 +116,7 @@ static QpW make_dev(const qp_weight *w) {
     d.N = w->N;
     d.row_stride = w->row_stride;
     d.layout = w->layout;
-    d.nbc = w->N / 1024;
+    d.nbc = (w->N + 1023) / 1024;
     d.tlut_bits = w->tlut_bits;
     return d;
 }
@@ -130,12 +131,13 @@ static QpW make_dev(const qp_weight *w) {
 // batch 1 / 2 / 4 4.7 / 5.5 / 6.5 against 6.2 / 6.25 / 6.6 and 1024x2048 batch 1 5.9 / 6.6, batch 2
 // 7.55 / 6.6; the V = 2 trellis never (1024x1024 at 3 bits 6.3 / 4.4, 1024x3072 14.1 / 4.7).
 static bool use_rowwave(const qp_weight *w, int B) {
-    const int nbc = w->N / 1024;
+    const int nbc = (w->N + 1023) / 1024;
     const int force = qp_opt(QP_OPT_LINEAR_KERNEL);
     const int64_t blocks = (int64_t)(w->M / 16) * nbc;
     // the block kernel reads whole blocks from either layout (in the canonical one a lane's pieces
-    // are consecutive in its row instead of one KiB per piece)
-    const bool fits = w->M % 16 == 0 && w->N % 1024 == 0 && nbc <= 32 &&
+    // are consecutive in its row instead of one KiB per piece); the last column block may stop
+    // after one, two or three of its four spans of 256 columns (N = 11008, 13824 ...)
+    const bool fits = w->M % 16 == 0 && w->N % 256 == 0 && nbc <= 32 &&
                       !(w->scheme == QP_TCQHH && w->N % 2048 != 0);
     if (!fits || force == 1) return true;
     if (force == 2 || blocks >= 256) return false;
@@ -147,6 +149,8 @@ static bool use_rowwave(const qp_weight *w, int B) {
 static inline int pow2_at_least(int B) { return B <= 1 ? 1 : B <= 2 ? 2 : B <= 4 ? 4 : B <= 8 ? 8 : 16; }
 
 static inline size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+// columns of the activations in fragment order: whole blocks of 1024
+static inline size_t padded_cols(const qp_weight *w) { return ((size_t)w->N + 1023) / 1024 * 1024; }
 
 // Whether qp_linear first copies the activations into the fragment order of the matrix-core
 // kernel (one more small launch; every activation load of the layer is then a contiguous KiB
@@ -169,7 +173,7 @@ static bool pack_pays(const qp_weight *w, int B) {
 
 extern "C" size_t qp_linear_workspace_bytes(const qp_weight *w, int32_t B) {
     if (!w || B < 1 || B > QP_MAX_BATCH || w->N <= 0 || w->M <= 0) return 0;
-    return pack_pays(w, B) ? round256((size_t)pow2_at_least(B) * (size_t)w->N * 2) : 0;
+    return pack_pays(w, B) ? round256((size_t)pow2_at_least(B) * padded_cols(w) * 2) : 0;
 }
 
 extern "C" qp_status qp_linear(const qp_weight *w, const void *x, int32_t B, int64_t ldx, void *y, int64_t ldy,
@@ -196,7 +200,7 @@ extern "C" qp_status qp_linear(const qp_weight *w, const void *x, int32_t B, int
 
 extern "C" size_t qp_rotate_linear_workspace_bytes(const qp_weight *w, int32_t B) {
     if (!w || B < 1 || B > QP_MAX_BATCH || w->N <= 0) return 0;
-    return round256((size_t)pow2_at_least(B) * (size_t)w->N * 2);
+    return round256((size_t)pow2_at_least(B) * padded_cols(w) * 2);
 }
 
 // Whether qp_rotate_linear would rotate inside the layer's kernel (one launch).
@@ -431,7 +435,7 @@ extern "C" qp_status qp_dequant(const qp_weight *w, void *W_out, void *hip_strea
     // takes 6.5 us there, 2.9 us on the layout-agnostic kernel).  QP_OPT_DEQUANT_KERNEL = 1 / 2
     // forces the layout-agnostic / the block kernel (the tests cover both on weights of any size).
     const int force = qp_opt(QP_OPT_DEQUANT_KERNEL);
-    const bool small = (int64_t)(w->M / 16) * (w->N / 1024) < 256 && force != 2;
+    const bool small = (int64_t)(w->M / 16) * ((w->N + 1023) / 1024) < 256 && force != 2;
     if (w->layout == QP_LAYOUT_NATIVE && !small && force != 1)
         return qp_launch_dequant_blocks(make_dev(w), w->scheme, w->code_bits, W_out,
                                         static_cast<hipStream_t>(hip_stream));
@@ -457,9 +461,10 @@ extern "C" qp_status qp_hadamard(const void *x, const int8_t *signs, int32_t B, 
 
 extern "C" size_t qp_native_bytes(const qp_weight *c) {
     if (!c || scheme_supported(c) != QP_OK) return 0;
-    if (c->M <= 0 || c->N <= 0 || c->M % 16 != 0 || c->N % 1024 != 0) return 0;
-    if (c->scheme == QP_TCQHH && c->N % 2048 != 0) return 0;
-    return (size_t)c->M * (size_t)row_bytes(c);
+    if (c->M <= 0 || c->N <= 0 || c->M % 16 != 0 || c->N % 256 != 0) return 0;
+    if (c->scheme == QP_TCQHH) return c->N % 2048 != 0 ? 0 : (size_t)c->M * (size_t)row_bytes(c);
+    // whole blocks of 16 x 1024: a last column block of fewer columns is padded
+    return (size_t)c->M * (padded_cols(c) / 256) * (size_t)span_bytes(c);
 }
 
 extern "C" qp_status qp_repack(const qp_weight *c, qp_weight *native_out, void *native_codes, size_t bytes,

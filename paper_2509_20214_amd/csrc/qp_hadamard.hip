@@ -144,25 +144,27 @@ qp_status qp_launch_hadamard(const void *x, const int8_t *signs, int B, int n, i
 // 64 pieces of 16 bytes whose cache lines its neighbours read next (x is small and stays in L2;
 // the other way round - coalesced reads, scattered 16-byte writes - took twice as long).
 // The batch columns B .. pack_bp - 1 are written as zeros.
-__global__ __launch_bounds__(256) void k_pack_x(const half_t *x, int B, int nbc, int64_t ldx, half_t *xp, int lt) {
+__global__ __launch_bounds__(256) void k_pack_x(const half_t *x, int B, int ncols, int64_t ldx, half_t *xp, int lt) {
     // destination piece d = (C * NXF + n) * 64 + 16 g + (b << lt) + t, TT = 1 << lt steps per fragment
     const int d = blockIdx.x * blockDim.x + threadIdx.x;
     const int nxf_log = 5 - lt;
+    const int nbc = (ncols + 1023) >> 10;   // a last block of fewer than 1024 columns is filled up with zeros
     if (d >= (nbc << (nxf_log + 6))) return;
     const int lane = d & 63, frag = d >> 6;
     const int n = frag & ((1 << nxf_log) - 1), C = frag >> nxf_log;
     const int g = lane >> 4, j = lane & 15;
     const int b = j >> lt, t = j & ((1 << lt) - 1);
     u32x4_t v = u32x4_t{0u, 0u, 0u, 0u};
-    if (b < B) v = *reinterpret_cast<const u32x4_t *>(x + (int64_t)b * ldx + 1024 * C + 256 * g + 8 * ((n << lt) + t));
+    const int col = 1024 * C + 256 * g + 8 * ((n << lt) + t);
+    if (b < B && col < ncols) v = *reinterpret_cast<const u32x4_t *>(x + (int64_t)b * ldx + col);
     reinterpret_cast<u32x4_t *>(xp)[d] = v;
 }
 
 qp_status qp_launch_pack_x(const void *x, int B, int n, int64_t ldx, void *xp, int pack_bp, hipStream_t st) {
     const int lt = 4 - __builtin_ctz(pack_bp);   // log2 of the steps per fragment, 16 / pack_bp
-    const int nbc = n / 1024;
+    const int nbc = (n + 1023) / 1024;
     const int total = nbc << (5 - lt + 6);
-    hipLaunchKernelGGL(k_pack_x, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const half_t *)x, B, nbc, ldx,
+    hipLaunchKernelGGL(k_pack_x, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, (const half_t *)x, B, n, ldx,
                        (half_t *)xp, lt);
     return qp_check_launch();
 }

@@ -18,7 +18,7 @@ bool qp_linear_rotates_blocks(int scheme, int M, int N, int rot_block);
 qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x, int B, int64_t ldx, void *y,
                                 int64_t ldy, int x_packed, const int8_t *signs, int rot_block, hipStream_t st);
 // pack_bp: 0 writes xr row-major; a power of two >= B writes the fragment order that
-// qp_launch_linear_mfma reads with x_packed (needs n % 1024 == 0, pack_bp * n halves of room)
+// qp_launch_linear_mfma reads with x_packed (pack_bp * n halves of room, n rounded up to a multiple of 1024)
 qp_status qp_launch_hadamard(const void *x, const int8_t *signs, int B, int n, int block, int64_t ldx,
                              void *xr, int64_t ldxr, int pack_bp, hipStream_t st);
 qp_status qp_launch_pack_x(const void *x, int B, int n, int64_t ldx, void *xp, int pack_bp, hipStream_t st);

@@ -589,6 +589,8 @@ struct QpXBuf {
     int soff;      // bytes to the unit's column block
     uint32_t lo;   // the lane's bytes
     int xfs;       // bytes between fragments
+    bool tail;     // (wave-uniform) the unit's column block is cut short by N: `keep` applies
+    uint32_t keep; // all ones, or zero where the lane's 256 columns lie beyond N
     __device__ __forceinline__ half8_t frag(int n, uint32_t lane_off) const {
 #ifdef QP_NOX  // development builds only: no activation loads, to time what they cost
         return __builtin_bit_cast(half8_t, u32x4_t{lane_off, (uint32_t)(soff + xfs * n), 0x3c003c00u, 0x3c003c00u});
@@ -602,6 +604,8 @@ struct QpXPtr {
     const half_t *p;   // the lane's first fragment of the unit
     uint32_t lo;       // unused (0)
     int xfs;           // halves between fragments
+    bool tail;         // (wave-uniform) the unit's column block is cut short by N: `keep` applies
+    uint32_t keep;     // all ones, or zero where the lane's 256 columns lie beyond N
     __device__ __forceinline__ half8_t frag(int n, uint32_t) const { return frag(n); }
     __device__ __forceinline__ half8_t frag(int n) const {
 #ifdef QP_NOX  // development builds only: no activation loads, to time what they cost
@@ -710,7 +714,11 @@ __device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8
         constexpr int s = decltype(sc)::value;
         constexpr int n = s / TT, t = s % TT;
         if constexpr (t == 0) {
-            const u32x4_t raw = __builtin_bit_cast(u32x4_t, xf[(n - N0) % PF]);
+            u32x4_t raw = __builtin_bit_cast(u32x4_t, xf[(n - N0) % PF]);
+            if (xs.tail) {   // lane groups beyond N: whatever was fetched for them becomes zero
+#pragma unroll
+                for (int r = 0; r < 4; ++r) raw[r] &= xs.keep;
+            }
             if constexpr (NM == 1) {
                 masked[0] = raw;
             } else {
@@ -819,7 +827,8 @@ struct QpLinLds {
 // XL == 2: N / 1024 <= 16 blocks of 1024 and one row block per workgroup; every wavefront transforms
 // the block of its own unit on the matrix cores (qp_fwht1024_run, shared with the stand-alone kernel,
 // so the same bits).
-template <int S, int CB, int BP, int XL, bool ALT>
+// TN: N is not a multiple of 1024 (a kernel of its own: the masks cost the others 2 - 6 %).
+template <int S, int CB, int BP, int XL, bool ALT, bool TN = false>
 __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, int B, int64_t ldx, half_t *y,
                                                int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic,
                                                int x_flags, const int8_t *signs, int rot_block, float rot_norm, uint8_t *tab,
@@ -916,13 +925,23 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     const int xcs = (XL || x_packed) ? 1024 * BP : 1024;   // halves between column blocks
     const int xfs = (XL || x_packed) ? 512 : 8 * TT;       // halves between fragments
     // extent of the activations in bytes: a load beyond it would return zeros instead of faulting
-    const uint32_t xbytes = x_packed ? (uint32_t)nbc * (2048u * BP) : 2u * ((uint32_t)(B - 1) * (uint32_t)ldx + 1024u * (uint32_t)nbc);
+    const uint32_t xbytes = x_packed ? (uint32_t)nbc * (2048u * BP) : 2u * ((uint32_t)(B - 1) * (uint32_t)ldx + (uint32_t)w.N);
+    // N % 1024 != 0 (N % 256 == 0: 11008, 13824 ...): the last column block has only tail_cols / 256 of its
+    // four lane groups.  The codes of the others are padding (zero bytes in the native layout; in the
+    // canonical one the lane re-reads group 0), their activations are fetched from group 0's address -
+    // which exists - and masked to zero.
+    const int tail_cols = TN ? (w.N & 1023) : 0;
+    const bool g_beyond = TN && tail_cols != 0 && 256 * g >= tail_cols;
+    const uint32_t x_keep = g_beyond ? 0u : 0xffffffffu;
+    const int x_back = (XL || x_packed) ? 0 : 256 * g;   // halves back to group 0 (row-major activations)
     auto x_at = [&](int C) __attribute__((always_inline)) {
+        const bool tail = TN && tail_cols != 0 && C == nbc - 1;
+        const int back = (tail && g_beyond) ? x_back : 0;
         if constexpr (XBUF)
             return QpXBuf{__builtin_amdgcn_make_buffer_rsrc(const_cast<half_t *>(x), 0, (int)xbytes, 0x00020000),
-                          2 * C * xcs, xlo, 2 * xfs};
+                          2 * C * xcs, xlo - 2u * (uint32_t)back, 2 * xfs, tail, x_keep};
         else
-            return QpXPtr{xlane + C * xcs, 0u, xfs};
+            return QpXPtr{xlane + C * xcs - back, 0u, xfs, tail, x_keep};
     };
     const bool owner = (tj == 0) && xlive;  // lane (g, b*TT) ends up with rows 4g..4g+3 of batch row b
     half8_t xf[PF];
@@ -962,7 +981,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
                 off = full ? (int64_t)hcb * (64 * CB) + (int64_t)((C - hcb) * 4 + (lane >> 4)) * (16 * (CB + 1))
                            : (int64_t)(C * 4 + (lane >> 4)) * (16 * CB);
             else
-                off = (int64_t)(C * 4 + (lane >> 4)) * T::SPAN;
+                off = (int64_t)(C * 4 + ((g_beyond && C == nbc - 1) ? 0 : (lane >> 4))) * T::SPAN;
             return reinterpret_cast<const u32x4_t *>(w.codes + ((int64_t)(rb0 + slot) * 16 + (lane & 15)) * w.row_stride + off);
         }
         if constexpr (HH) {
@@ -1206,7 +1225,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
 
 // XL (batch 1 only): the workgroup rotates the activations itself; a kernel of its own, so that the
 // plain kernel does not carry the transform's LDS arrays and more workgroups fit a compute unit.
-template <int S, int CB, int BP, bool SPLIT, int XL>
+template <int S, int CB, int BP, bool SPLIT, int XL, bool TN = false>
 __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, int B, int64_t ldx, half_t *y,
                                                       int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic,
                                                       int x_packed, const int8_t *signs, int rot_block, float rot_norm) {
@@ -1228,8 +1247,8 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
         qp_linear_body<S, CB, BP, 1, SPLIT>(w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
                                             rot_block, rot_norm, tab, red, xr_lds, rot_buf);
     } else {
-        qp_linear_body<S, CB, BP, 0, SPLIT>(w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
-                                            rot_block, rot_norm, tab, red, nullptr, nullptr);
+        qp_linear_body<S, CB, BP, 0, SPLIT, TN>(w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
+                                                rot_block, rot_norm, tab, red, nullptr, nullptr);
     }
 }
 
@@ -1256,6 +1275,14 @@ static void qp_launch_xl(int grid, int nw, hipStream_t st, const QpW &w, const v
                                    signs, rot_block, rot_norm);
                 return;
             }
+        }
+    }
+    if constexpr (!SPLIT) {
+        if (w.N % 1024 != 0) {   // the last column block is cut short
+            hipLaunchKernelGGL((k_linear_mfma<S, CB, BP, false, 0, true>), dim3(grid), dim3(64 * nw), 0, st, w,
+                               (const half_t *)x, B, ldx, (half_t *)y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
+                               rot_block, rot_norm);
+            return;
         }
     }
     hipLaunchKernelGGL((k_linear_mfma<S, CB, BP, SPLIT, 0>), dim3(grid), dim3(64 * nw), 0, st, w,
@@ -1311,7 +1338,7 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
     // and 11.1 / 12.0 us, 4096x8192 at 3 bits hybrid 6.7 / 6.9 us; only 4096x4096 at 3 bits hybrid
     // gains (5.4 / 5.2 us).  So: off unless QP_OPT_LINEAR_SPLIT = 1 asks for it where it is legal.
     const int split_opt = qp_opt(QP_OPT_LINEAR_SPLIT);
-    const bool can_split = (scheme == QP_TCQ || scheme == QP_TCQH) && B <= 2 && units <= 16;
+    const bool can_split = (scheme == QP_TCQ || scheme == QP_TCQH) && B <= 2 && units <= 16 && w.N % 1024 == 0;
     bool split = false;
     if (split_opt == 0) split = false;
     if (split_opt == 1) split = can_split;
@@ -1326,6 +1353,7 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
     if (scheme == QP_VQ && cb == 5 && units_wg <= 16 && ((B > 2 && B <= 4 && units_wg > 8) || (B > 8 && x_packed))) {
         split = split_opt != 0;
     }
+    if (w.N % 1024 != 0) split = false;   // a last column block cut short: the plain form only
     int nw = units < 16 ? units : 16;
     if (scheme == QP_TCQ || scheme == QP_TCQH || scheme == QP_TCQHH) nw = 16;  // the table staging is written for 1024 threads
     if (nw_forced >= 4 && nw_forced <= 16 && nw_forced < nw) nw = nw_forced;
@@ -1450,7 +1478,8 @@ __global__ __launch_bounds__(1024) void k_dequant_blocks(QpW w, uint16_t *out, i
             for (int k = 0; k < 4; ++k) {
                 const int slot = 16 * k + rd_slot0;
                 const u32x4_t v = tl[slot * 4 + ((rd_c + (slot >> 1)) & 3)];
-                *reinterpret_cast<u32x4_t *>(dst + k * 256 + s4 * 32) = v;
+                // (column group k of a last block that N cuts short is padding)
+                if (C * 1024 + k * 256 < w.N) *reinterpret_cast<u32x4_t *>(dst + k * 256 + s4 * 32) = v;
             }
             __builtin_amdgcn_wave_barrier();
         });

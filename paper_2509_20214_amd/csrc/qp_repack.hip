@@ -14,7 +14,10 @@ __global__ void k_repack(QpW src, int span_bytes, u32x4_t *dst) {
         int R = (int)(blk / src.nbc), C = (int)(blk - (int64_t)R * src.nbc);
         int row = R * 16 + i;
         int64_t byte_off = (int64_t)(C * 4 + g) * span_bytes + p * 16;
-        dst[t] = *reinterpret_cast<const u32x4_t *>(src.codes + (int64_t)row * src.row_stride + byte_off);
+        // spans of the last column block beyond N (N % 1024 != 0) are padding: zero bytes
+        u32x4_t v = u32x4_t{0u, 0u, 0u, 0u};
+        if ((C * 4 + g) * 256 < src.N) v = *reinterpret_cast<const u32x4_t *>(src.codes + (int64_t)row * src.row_stride + byte_off);
+        dst[t] = v;
     }
 }
 

@@ -189,8 +189,11 @@ def make_signs(cfg: int, layer: int, n: int) -> np.ndarray:
 
 def hadamard_block(N: int) -> int:
     """Block length of the block-diagonal rotation: N itself when it is a power
-    of two, else 1024 (14336 = 14 x 1024, 28672 = 28 x 1024)."""
-    return N if N & (N - 1) == 0 else 1024
+    of two, else 1024 (14336 = 14 x 1024, 28672 = 28 x 1024) where that divides N,
+    else the largest power of two that does (11008 = 43 x 256, 13824 = 27 x 512)."""
+    if N & (N - 1) == 0:
+        return N
+    return 1024 if N % 1024 == 0 else N & -N
 
 
 # --------------------------------------------------------------------------

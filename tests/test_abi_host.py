@@ -81,7 +81,8 @@ def desc(**kw):
     (dict(codes=0x1004), 4),
     (dict(layout=5), 5),
     (dict(layout=qp.QP_LAYOUT_NATIVE, M=24), 5),
-    (dict(layout=qp.QP_LAYOUT_NATIVE, N=1024 + 256, row_stride=640), 5),
+    (dict(layout=qp.QP_LAYOUT_NATIVE, N=1024 + 256, row_stride=640), 0),   # a last column block cut short: whole spans of 256
+    (dict(layout=qp.QP_LAYOUT_NATIVE, N=1024 + 128, row_stride=640), 5),
 ])
 def test_descriptor_validation(kw, code):
     d = desc(**kw)
@@ -168,6 +169,10 @@ def test_repack_argument_errors_do_not_launch():
     d = desc()
     assert L.qp_native_bytes(C.byref(d)) == 16 * 512
     assert L.qp_native_bytes(C.byref(desc(M=24))) == 0
+    # N = 1280: two column blocks, the second padded from 256 to 1024 columns; N = 1152: no native form
+    assert L.qp_native_bytes(C.byref(desc(N=1280, row_stride=640))) == 16 * 1024
+    assert L.qp_native_bytes(C.byref(desc(N=1152, row_stride=640))) == 0
+    assert L.qp_repack(C.byref(desc(N=1280, row_stride=640)), C.byref(out), 0x100000, 16 * 640, None) == 2   # room for the padding too
     assert L.qp_repack(C.byref(d), C.byref(out), None, 16 * 512, None) == 1
     assert L.qp_repack(C.byref(d), C.byref(out), 0x100000, 100, None) == 2
     assert L.qp_repack(C.byref(desc(M=24)), C.byref(out), 0x100000, 1 << 20, None) == 5

@@ -449,6 +449,72 @@ def test_rotate_linear_rotates_blocks_of_1024_in_kernel(qp, scheme, cb, M, N):
         assert torch.equal(y_one, y_two)
 
 
+RAGGED_SCHEMES = [(synth.SQ, 4), (synth.VQ, 5), (synth.VQ, 7), (synth.TCQ, 2), (synth.TCQ, 3), (synth.TCQ, 4),
+                  (synth.TCQH, 3), (synth.TCQH, 6), (synth.TCQH, 9), (synth.TCQH, 10)]
+RAGGED_IDS = ["sq4", "vq5", "vq7", "tcq2", "tcq3", "tcq4", "tcqh1.5", "tcqh3", "tcqh4.5", "tcqh5"]
+
+
+@pytest.mark.parametrize("scheme,cb", RAGGED_SCHEMES, ids=RAGGED_IDS)
+@pytest.mark.parametrize("M,N", [(48, 768), (272, 1280), (32, 2816), (16, 256)])
+def test_last_column_block_cut_short(qp, scheme, cb, M, N):
+    """N a multiple of 256 but not of 1024 (the 11008 and 13824 input channels of the 7B- and 13B-shaped
+    models): the native layout pads the last column block with zero bytes and the block kernel multiplies
+    the padding with zeros.  Decode bit-exact through both dequantization kernels; the layer against the
+    oracle from either layout, with row-major and fragment-order activations, at every batch size class;
+    rotation + layer the same bits as the two calls; one-hot activations on the last real columns exact."""
+    lay = synth.make_layer(90, scheme * 10 + cb + N, scheme, M, N, cb)
+    wc = qp.Weight.from_layer(lay)
+    wn = qp.qp_repack(wc)
+    assert wn.codes.numel() == M * ((N + 1023) // 1024 * 1024 // 256) * (32 * cb // (1 if scheme in (synth.SQ, synth.TCQ) else 2))
+    want_w = oracle.decode(lay)
+    for kern in (qp.QP_DEQUANT_GENERIC, qp.QP_DEQUANT_BLOCKS):
+        qp.qp_set_option(qp.QP_OPT_DEQUANT_KERNEL, kern)
+        assert np.array_equal(host16(qp.qp_dequant(wn)), want_w)
+    block = synth.hadamard_block(N)
+    sg = synth.make_signs(90, N, N)
+    for B in (1, 2, 3, 8, 13):
+        x = synth.make_x(90, B, B, N)
+        xd = dev(x)
+        want = oracle.linear(lay, x, threads=True)
+        for w in (wn, wc):
+            for pack in (0, 1):
+                qp.qp_reset_options()
+                qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_BLOCK)
+                qp.qp_set_option(qp.QP_OPT_LINEAR_PACK, pack)
+                assert rel_err(host16(qp.qp_linear(w, xd)), want) <= TOL_SHARP, (B, w.layout, pack)
+        qp.qp_reset_options()
+        qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_ROW)
+        assert rel_err(host16(qp.qp_linear(wn, xd)), want) <= TOL_SHARP   # the row kernel on the padded native layout
+        qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_BLOCK)
+        y = qp.qp_rotate_linear(wn, xd, dev(sg), block)
+        assert torch.equal(y, qp.qp_linear(wn, qp.qp_hadamard(xd, dev(sg), block), workspace=False))
+        assert rel_err(host16(y), oracle.linear(lay, oracle.hadamard(x, sg, block, fast=True), threads=True)) <= TOL_SHARP
+    qp.qp_reset_options()
+    qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_BLOCK)
+    cols = sorted({N - 1, N - 8, N - 256, max(N - 257, 0), 0})
+    e = np.zeros((len(cols), N), dtype=np.float16)
+    for r, c in enumerate(cols):
+        e[r, c] = 1.0
+    want = oracle.linear(lay, e)
+    y = host16(qp.qp_linear(wn, dev(e))).view(np.float16).astype(np.float64)
+    assert np.all(np.abs(y - want) <= np.abs(want) * 2.0 ** -11 + 1e-7)
+
+
+def test_last_column_block_cut_short_at_full_size(qp):
+    """4096 x 11008 at 2.5 bits: taken by the block kernel by default (not the row kernel), batch 1 and 8."""
+    lay = synth.make_layer(91, 0, synth.VQ, 4096, 11008, 5)
+    wn = qp.qp_repack(qp.Weight.from_layer(lay))
+    sg = synth.make_signs(91, 0, 11008)
+    for B in (1, 8):
+        x = synth.make_x(91, B, B, 11008)
+        want = oracle.linear(lay, oracle.hadamard(x, sg, 256, fast=True), threads=True)
+        y = qp.qp_rotate_linear(wn, dev(x), dev(sg), 256)
+        assert rel_err(host16(y), want) <= TOL_SHARP
+        qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_BLOCK)
+        assert torch.equal(y, qp.qp_rotate_linear(wn, dev(x), dev(sg), 256))   # the default was the block kernel
+        qp.qp_reset_options()
+
+
 @pytest.mark.parametrize("scheme,cb,M,N,block,one", [
     (synth.SQ, 4, 1024, 1024, 1024, True), (synth.VQ, 5, 37, 3072, 1024, True), (synth.VQ, 7, 1000, 2048, 2048, True),
     (synth.TCQ, 3, 48, 2048, 1024, True), (synth.TCQ, 2, 64, 2048, 2048, False), (synth.TCQH, 6, 5, 8192, 8192, True),
