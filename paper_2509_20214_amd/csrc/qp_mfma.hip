@@ -64,10 +64,22 @@
 #ifndef QP_UMAX_SMALL_BATCH
 #define QP_UMAX_SMALL_BATCH 128
 #endif
+// big: beside the 128 KiB table of the V = 1 trellis (32 KiB are left for the partial sums).
+#ifndef QP_UMAX_B4
+#define QP_UMAX_B4 64
+#endif
+#ifndef QP_UMAX_B8
+#define QP_UMAX_B8 64
+#endif
+#ifndef QP_UMAX_B16
+#define QP_UMAX_B16 32   // (64 would gain the same 5 % on 28 column blocks, but the 64 KiB array alone costs every other layer 2 %)
+#endif
 #ifdef QP_TRACE   // (the timestamps take 2 KiB of LDS; the 128 KiB trellis table leaves room for 28 units at batch 16 then)
-constexpr int qp_umax(int BP) { return BP == 1 ? QP_UMAX_SMALL_BATCH : (BP <= 4 ? 64 : BP <= 8 ? 32 : 28); }
+constexpr int qp_umax(int BP, bool big) { return BP == 1 ? QP_UMAX_SMALL_BATCH : (BP <= 4 ? 64 : BP <= 8 ? 32 : 28); }
 #else
-constexpr int qp_umax(int BP) { return BP == 1 ? QP_UMAX_SMALL_BATCH : (BP <= 4 ? 64 : 32); }
+constexpr int qp_umax(int BP, bool big) {
+    return BP == 1 ? QP_UMAX_SMALL_BATCH : BP <= 4 ? (big ? 64 : QP_UMAX_B4) : BP <= 8 ? (big ? 32 : QP_UMAX_B8) : (big ? 32 : QP_UMAX_B16);
+}
 #endif
 
 #ifdef QP_TRACE  // development builds only: per-wavefront timestamps of the kernel's phases
@@ -800,7 +812,7 @@ __device__ __forceinline__ void qp_pass_store(const QpW &w, const float *red, ha
 template <class D, int S, int CB, int BP>
 struct QpLinLds {
     using T = QpTraits<S, CB>;
-    static constexpr int RED_FLOATS = qp_umax(BP) * 16 * BP;
+    static constexpr int RED_FLOATS = qp_umax(BP, D::TAB_BYTES > 65536) * 16 * BP;
     static constexpr int SMALL_FLOATS = T::HYBRID ? (1 << T::TLUT_BITS) : 0;
     static constexpr int RED = RED_FLOATS > SMALL_FLOATS ? RED_FLOATS : SMALL_FLOATS;
     // in-kernel rotation (batch 1, one Hadamard block of at most 8192): the rotated
@@ -1319,7 +1331,12 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
                                 int64_t ldy, int x_packed, const int8_t *signs, int rot_block, hipStream_t st) {
     const int nbc = w.nbc, rbk = w.M / 16;
     if (nbc < 1 || nbc > QP_NBC_MAX) return QP_ERR_UNSUPPORTED;
-    const int umax = qp_umax(B <= 1 ? 1 : B <= 2 ? 2 : B <= 4 ? 4 : B <= 8 ? 8 : 16);
+    int umax = qp_umax(B <= 1 ? 1 : B <= 2 ? 2 : B <= 4 ? 4 : B <= 8 ? 8 : 16, scheme == QP_TCQ);
+    // Batch 5 - 8: passes of 64 units only where 32 would hold a single row block (more than 16 column
+    // blocks): two row blocks per pass let pairs of wavefronts share a column block's activation fragments
+    // in the L1 (8192x28672 at 3.5 bits, batch 8: 31.2 -> 29.1 us per step); with four row blocks in 32
+    // units already, 64 measured the same or slower.
+    if (B > 4 && nbc <= 16 && umax > 32) umax = 32;
     // Tuning options: workgroups per compute unit and wavefronts per workgroup.
     int wg_per_cu = qp_opt(QP_OPT_WG_PER_CU), nw_forced = qp_opt(QP_OPT_NW);
     const bool big_table = (scheme == QP_TCQ || scheme == QP_TCQH || scheme == QP_TCQHH);
