@@ -71,6 +71,40 @@ def test_block_equals_one_call_per_layer(qp, B):
     blk.close()
 
 
+@pytest.mark.parametrize("B", [1, 8])
+def test_block_with_a_down_projection_whose_last_column_block_is_cut_short(qp, B):
+    """A 7B-shaped block in miniature: the down projection reads 2816 = 11 x 256 input channels (rotation in
+    blocks of 256), two of them share that input; default kernel choice."""
+    shapes = [("gate", synth.VQ, 5, 2816, 2048), ("up", synth.TCQH, 6, 2816, 2048), ("down", synth.SQ, 4, 2048, 2816),
+              ("down2", synth.TCQ, 3, 512, 2816)]
+    inp = {"gate": 0, "up": 0, "down": 1, "down2": 1}
+    width = {0: 2048, 1: 2816}
+    rot = {0: 2048, 1: 256}
+    lays = {name: synth.make_layer(93, i, scheme, M, N, cb) for i, (name, scheme, cb, M, N) in enumerate(shapes)}
+    ws = {name: qp.qp_repack(qp.Weight.from_layer(lays[name])) for name in lays}
+    xs_host = {k: synth.make_x(93, k, B, width[k]) for k in width}
+    sg_host = {k: synth.make_signs(93, k, width[k]) for k in width}
+    xs = {k: dev(v) for k, v in xs_host.items()}
+    sg = {k: dev(v) for k, v in sg_host.items()}
+    ys = {name: torch.zeros((B, M), dtype=torch.float16, device="cuda") for name, _, _, M, _ in shapes}
+    blk = qp.Block([(ws[name], xs[inp[name]], sg[inp[name]], rot[inp[name]], ys[name]) for name, *_ in shapes])
+    ref = {name: qp.qp_rotate_linear(ws[name], xs[inp[name]], sg[inp[name]], rot[inp[name]]) for name, *_ in shapes}
+    torch.cuda.synchronize()
+    for name, *_ in shapes:
+        k = inp[name]
+        want = oracle.linear(lays[name], oracle.hadamard(xs_host[k], sg_host[k], rot[k], fast=True), threads=True)
+        got = ref[name].cpu().numpy().astype(np.float64)
+        assert np.max(np.abs(got - want)) / np.max(np.abs(want)) <= 1e-3, name
+    for rep in range(2):
+        for y in ys.values():
+            y.zero_()
+        (blk.enqueue if rep == 0 else blk.run)()
+        torch.cuda.synchronize()
+        for name, *_ in shapes:
+            assert torch.equal(ys[name], ref[name]), (rep, name)
+    blk.close()
+
+
 def test_block_rejects_a_bad_item_before_launching(qp):
     lay = synth.make_layer(92, 0, synth.VQ, 64, 2048, 5)
     w = qp.qp_repack(qp.Weight.from_layer(lay))
