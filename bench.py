@@ -15,7 +15,7 @@ Prints ONE JSON line: metric / value / unit (code bytes per second through the w
 the per-kernel times, `roofline` for the dominant kernel (qp_linear: algorithmic bytes over its
 HIP-event time against the 8 TB/s peak), `cpu_baseline` (the oracle on the host cores), the
 dequantize-only kernel, the encoder, and `cases`: the other configurations.  --sweep70b and
---sweep8b run whole models resident in HBM; --profile-only is the short run that profilers wrap.
+--sweep8b / --sweep7b run whole models resident in HBM; --profile-only is the short run that profilers wrap.
 """
 from __future__ import annotations
 
@@ -65,6 +65,9 @@ def parse():
     p.add_argument("--sweep8b", default="", metavar="SCHEME:BITS",
                    help="Llama-3-8B-shaped model (configuration 4's projections, 32 layers) with one quantizer, "
                         "e.g. tcq:3, tcqh:6, vq:5, tcqhh:6; prints its own JSON line")
+    p.add_argument("--sweep7b", default="", metavar="SCHEME:BITS",
+                   help="Llama-2-7B-shaped model (11008 intermediate channels: a down projection whose last column "
+                        "block is cut short, rotation in blocks of 256) with one quantizer; prints its own JSON line")
     p.add_argument("--msq", action="store_true",
                    help="profile every (fusible group, quantizer) of an 8B-shaped block and run the fusion-aware "
                         "mixed-scheme selection on the measured latencies; prints its own JSON line")
@@ -144,7 +147,8 @@ def sweep_model(model, label, torch, synth, qp, dev, upload, graph_of, event_tim
         width = max(len(ws) for ws in layers)
         xs = {(N, i): upload(synth.make_x(5, N + i, B, N)) for N in Ns for i in range(width)}
         sg = {N: upload(synth.make_signs(5, N, N)) for N in Ns}
-        wsp = {N: torch.empty(2 * 16 * N, dtype=torch.uint8, device=dev) for N in Ns}
+        wsp = {N: torch.empty(max(qp.qp_rotate_linear_workspace_bytes(nat, B) for ws in layers for d, nat in ws if d["N"] == N),
+                              dtype=torch.uint8, device=dev) for N in Ns}
         ys = {M: torch.empty((B, M), dtype=torch.float16, device=dev) for M in Ms}
 
         def step():
@@ -468,6 +472,13 @@ def main():
         name, bits = a.sweep8b.split(":")
         scheme = {v: k for k, v in synth.SCHEME_NAMES.items()}[name]
         sweep_model(synth.model_8b(scheme, int(bits)), f"8B-shaped model, every projection {name} code_bits {bits}",
+                    torch, synth, qp, dev, upload, graph_of, event_time_us)
+        return
+    if a.sweep7b:
+        name, bits = a.sweep7b.split(":")
+        scheme = {v: k for k, v in synth.SCHEME_NAMES.items()}[name]
+        sweep_model(synth.model_7b(scheme, int(bits)),
+                    f"7B-shaped model (11008 intermediate channels), every projection {name} code_bits {bits}",
                     torch, synth, qp, dev, upload, graph_of, event_time_us)
         return
 

@@ -270,6 +270,15 @@ def model_8b(scheme: int, code_bits: int, n_layers: int = 32):
                   M=M, N=N, code_bits=code_bits) for i, (nm, M, N) in enumerate(shapes)] for L in range(n_layers)]
 
 
+def model_7b(scheme: int, code_bits: int, n_layers: int = 32):
+    """Llama-2-7B-shaped model with one quantizer for every projection: 4096 hidden and 11008
+    intermediate channels - the down projection's 11008 = 43 x 256 input channels are not a multiple of
+    1024 (its rotation runs in blocks of 256).  Returns descriptions only (list of lists)."""
+    shapes = [("qkv", 12288, 4096), ("o", 4096, 4096), ("gateup", 22016, 4096), ("down", 4096, 11008)]
+    return [[dict(cfg=7, layer=3000 + 4 * L + i, name=f"L{L}.{SCHEME_NAMES[scheme]}{code_bits}_{nm}", scheme=scheme,
+                  M=M, N=N, code_bits=code_bits) for i, (nm, M, N) in enumerate(shapes)] for L in range(n_layers)]
+
+
 def build(desc: dict) -> Layer:
     return make_layer(desc["cfg"], desc["layer"], desc["scheme"], desc["M"], desc["N"],
                       desc["code_bits"], name=desc["name"])
