@@ -588,7 +588,7 @@ def main():
                 (4, 0, (1, 2, 4, 8, 16)), (4, 1, (1, 2, 4, 8, 16)), (4, 2, (1, 2, 4, 8, 16)), (4, 3, (1, 2, 4, 8, 16)),
                 (5, 0, (1, 8, 16)), (5, 1, (1, 8, 16)), (5, 2, (1, 8, 16)), (5, 3, (1, 8, 16)),
                 (6, 0, (1,)), (6, 1, (1, 8)), (6, 2, (1,)), (6, 3, (1,)), (6, 4, (1,)), (6, 5, (1,)), (6, 6, (1,)),
-                (6, 7, (1,)), (6, 8, (1, 8)), (6, 9, (1,))]
+                (6, 7, (1,)), (6, 8, (1, 8)), (6, 9, (1,)), (6, 10, (1, 8)), (6, 11, (1, 8))]
         for cfg, li, batches in todo:
             c = Case(cfg, li, batches[0])
             g = graph_of(c.stream_only, 100)

@@ -35,7 +35,8 @@
  * NATIVE LAYOUT (QP_LAYOUT_NATIVE), produced by qp_repack; needs M % 16 == 0 and
  * N % 256 == 0.  The matrix is cut into blocks of 16 rows x 1024 columns (ceil(N / 1024) per
  * block row; where N is not a multiple of 1024 - 11008, 13824 - the spans of the last column
- * block that lie beyond N hold zero bytes and the kernels multiply them with zeros), stored
+ * block that lie beyond N hold zero bytes and the kernels multiply what those decode to - finite
+ * table entries, which is all a table may hold - with zeros), stored
  * block-row-major (all column blocks of rows 0..15, then rows 16..31, ...).  Within
  * a block, "lane" l = 16*g + i (g = 0..3, i = 0..15) owns row i, columns
  * 256*g .. 256*g+255 of the block: the same 32*bpw bytes that the canonical stream

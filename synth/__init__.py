@@ -240,7 +240,11 @@ def config_layers(cfg: int, *, small: bool = False):
                 # half-TCQ: 2 / 2.5 bits and 3 / 3.5 bits on the two halves of the input channels
                 d(7, "tcqhh2.25_down_4096x14336", TCQHH, 4096, 14336, 4),
                 d(8, "tcqhh3.25_down_4096x14336", TCQHH, 4096, 14336, 6),
-                d(9, "tcqhh3.25_gateup_28672x4096", TCQHH, 28672, 4096, 6)]
+                d(9, "tcqhh3.25_gateup_28672x4096", TCQHH, 28672, 4096, 6),
+                # down projections of the 7B- and 13B-shaped models: 11008 = 43 x 256 and 13824 = 54 x 256
+                # input channels, not multiples of 1024
+                d(10, "vq2.5_down_4096x11008", VQ, 4096, 11008, 5),
+                d(11, "tcqh3_down_5120x13824", TCQH, 5120, 13824, 6)]
     raise ValueError(cfg)
 
 

@@ -26,6 +26,8 @@ CASES = [  # (cfg, layer index, batches)
     (6, 1, [1, 8]),
     (6, 6, [1]),
     (6, 8, [1, 8]),
+    (6, 10, [1, 8]),
+    (6, 11, [1, 16]),
 ]
 
 
