@@ -72,7 +72,7 @@
 #define QP_UMAX_B8 64
 #endif
 #ifndef QP_UMAX_B16
-#define QP_UMAX_B16 32   // (64 would gain the same 5 % on 28 column blocks, but the 64 KiB array alone costs every other layer 2 %)
+#define QP_UMAX_B16 64
 #endif
 #ifdef QP_TRACE   // (the timestamps take 2 KiB of LDS; the 128 KiB trellis table leaves room for 28 units at batch 16 then)
 constexpr int qp_umax(int BP, bool big) { return BP == 1 ? QP_UMAX_SMALL_BATCH : (BP <= 4 ? 64 : BP <= 8 ? 32 : 28); }
@@ -1245,22 +1245,26 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
     using L = QpLinLds<D, S, CB, BP>;
     static_assert(XL == 0 || L::ROT, "in-kernel rotation: batch 1");
     static_assert(XL != 2 || L::ROTM, "per-wavefront rotation: tables of at most 64 KiB");
-    __shared__ __attribute__((aligned(16))) uint8_t tab[D::TAB_BYTES];
-    // [unit][b][row]; before the first pass the same room stages a table's source
-    __shared__ __attribute__((aligned(16))) float red[L::RED];
+    // One object, the table first: at LDS address 0 a lookup's address register is the whole address;
+    // anywhere above 64 KiB (where the compiler would put it once another array grows larger than it)
+    // every lookup costs a vector add for the base.
+    struct Lds {
+        __attribute__((aligned(16))) uint8_t tab[D::TAB_BYTES];
+        // [unit][b][row]; before the first pass the same room stages a table's source
+        __attribute__((aligned(16))) float red[L::RED];
+        __attribute__((aligned(16))) half_t xr[XL == 2 ? L::ROTM_MAX : XL == 1 ? L::ROT_MAX : 0];   // (empty without in-kernel rotation)
+        __attribute__((aligned(16))) float rot[XL == 2 ? 1024 : XL == 1 ? L::ROT_SCRATCH_FLOATS : 0];
+    };
+    __shared__ Lds lds;
     if constexpr (XL == 2) {
-        __shared__ __attribute__((aligned(16))) half_t xr_all[L::ROTM_MAX];
-        __shared__ __attribute__((aligned(16))) float had_consts[1024];
         qp_linear_body<S, CB, BP, 2, SPLIT>(w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
-                                            rot_block, rot_norm, tab, red, xr_all, had_consts);
+                                            rot_block, rot_norm, lds.tab, lds.red, lds.xr, lds.rot);
     } else if constexpr (XL == 1) {
-        __shared__ __attribute__((aligned(16))) half_t xr_lds[L::ROT_MAX];
-        __shared__ __attribute__((aligned(16))) float rot_buf[L::ROT_SCRATCH_FLOATS];
         qp_linear_body<S, CB, BP, 1, SPLIT>(w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
-                                            rot_block, rot_norm, tab, red, xr_lds, rot_buf);
+                                            rot_block, rot_norm, lds.tab, lds.red, lds.xr, lds.rot);
     } else {
         qp_linear_body<S, CB, BP, 0, SPLIT, TN>(w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed, signs,
-                                                rot_block, rot_norm, tab, red, nullptr, nullptr);
+                                                rot_block, rot_norm, lds.tab, lds.red, nullptr, nullptr);
     }
 }
 
@@ -1332,7 +1336,7 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
     const int nbc = w.nbc, rbk = w.M / 16;
     if (nbc < 1 || nbc > QP_NBC_MAX) return QP_ERR_UNSUPPORTED;
     int umax = qp_umax(B <= 1 ? 1 : B <= 2 ? 2 : B <= 4 ? 4 : B <= 8 ? 8 : 16, scheme == QP_TCQ);
-    // Batch 5 - 8: passes of 64 units only where 32 would hold a single row block (more than 16 column
+    // Batch 5 - 16: passes of 64 units only where 32 would hold a single row block (more than 16 column
     // blocks): two row blocks per pass let pairs of wavefronts share a column block's activation fragments
     // in the L1 (8192x28672 at 3.5 bits, batch 8: 31.2 -> 29.1 us per step); with four row blocks in 32
     // units already, 64 measured the same or slower.
