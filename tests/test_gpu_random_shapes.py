@@ -1,4 +1,5 @@
-"""Seeded random shapes for the fused layer on the native layout: column-block counts from 1 to 32,
+"""Seeded random shapes for the fused layer on the native layout: column-block counts from 1 to 32
+(and a few that end inside a column block),
 row-block counts on both sides of the workgroup count (one row block per workgroup, several with a
 ragged last pass, fewer than 256 in all), every batch size, every scheme; checked on sampled output
 rows against the oracle, through qp_linear and through the single-call step."""
@@ -35,6 +36,12 @@ def cases():
              (synth.TCQ, 3, 3000, 16, 2), (synth.TCQHH, 5, 1000, 14, 1), (synth.SQ, 4, 900, 28, 4)]
     for j, (scheme, cb, rbk, nbc, B) in enumerate(extra):
         out.append((100 + j, scheme, cb, rbk * 16, nbc * 1024, B))
+    # Input channels that are a multiple of 256 but not of 1024: the last column block is cut short.
+    ragged = [(synth.VQ, 5, 256, 11008, 1), (synth.SQ, 4, 100, 13824, 8), (synth.TCQ, 3, 300, 2816, 2),
+              (synth.TCQH, 7, 257, 6912, 16), (synth.VQ, 7, 700, 29440, 5), (synth.TCQH, 10, 17, 1280, 3),
+              (synth.TCQ, 2, 1500, 768, 13), (synth.SQ, 4, 511, 256, 1)]
+    for j, (scheme, cb, rbk, N, B) in enumerate(ragged):
+        out.append((200 + j, scheme, cb, rbk * 16, N, B))
     return out
 
 
