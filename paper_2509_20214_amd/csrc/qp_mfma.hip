@@ -304,8 +304,81 @@ struct QpDecByte {
     }
 };
 template <> struct QpDec<QP_SQ, 4> : QpDecByte<QP_SQ, 4> {};
+#ifdef QP_VQ5_BYTE_WINDOW   // (development builds: the one-code-per-lookup form, for comparison)
 template <> struct QpDec<QP_VQ, 5> : QpDecByte<QP_VQ, 5> {};
+#endif
 template <> struct QpDec<QP_VQ, 7> : QpDecByte<QP_VQ, 7> {};
+
+// VQ 5 bit, two codes per lookup: the 10 stream bits of two neighbouring codes index a table of 1024
+// entries of 8 bytes (the four weights of the two codes), one ds_read_b64 per four weights instead of two
+// ds_read_b32 - a decode step is two shifts, two and-ors and two lookups where the byte-window form has
+// four SDWA operations and four lookups.  64 KiB hold eight copies of the table, copy lane % 8 at
+// (index << 6) | (lane % 8) << 3: lanes of different copies never share a bank, the four lanes of a
+// 32-lane pass that share a copy collide when their indices have the same parity.
+struct QpDecVq5Pair {
+    static constexpr bool BYTE_WINDOW = false;
+    static constexpr bool AHEAD = true;          // lookups issued ahead of the multiply, like the byte-window decoders
+    static constexpr int TAB_BYTES = 65536;
+    typedef uint32_t Lane;
+    struct Pre { u32x4_t src[8]; };              // the 32 x 4 bytes of the code book, in scalar registers
+    static __device__ __forceinline__ Pre pre(const uint16_t *g) {
+        qp_cu32 *s = qp_scalar_ptr(g);
+        Pre p;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) p.src[k] = u32x4_t{s[4 * k], s[4 * k + 1], s[4 * k + 2], s[4 * k + 3]};
+        return p;
+    }
+    static __device__ __forceinline__ uint32_t lane_const() { return (threadIdx.x & 7u) << 3; }
+    static __device__ __forceinline__ void early(uint8_t *tab, uint16_t *small, const uint16_t *g) { build(tab, small, pre(g)); }
+    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *small, const Pre &p) {
+        if (threadIdx.x < 64) {   // (the source sits in scalar registers of every wavefront: the first one writes it out)
+            if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) reinterpret_cast<u32x4_t *>(small)[k] = p.src[k];
+            }
+        }
+        QP_T(11);
+        __syncthreads();
+        QP_T(12);
+        const uint32_t *s32 = reinterpret_cast<const uint32_t *>(small);
+        u32x4_t *t4 = reinterpret_cast<u32x4_t *>(tab);
+        for (int idx = threadIdx.x; idx < 1024; idx += blockDim.x) {
+            const uint32_t lo = s32[idx & 31], hi = s32[idx >> 5];   // first code in the low five bits
+            const u32x4_t v4 = u32x4_t{lo, hi, lo, hi};
+            const int rot = (idx >> 1) & 3;   // neighbouring threads start on different banks
+#pragma unroll
+            for (int k = 0; k < 4; ++k) t4[idx * 4 + ((k + rot) & 3)] = v4;
+        }
+        QP_T(15);
+        __syncthreads();
+    }
+    template <int P>
+    static __device__ __forceinline__ half8_t step(const u32x4_t (&q)[P], int s, const uint8_t *tab, uint32_t lc,
+                                                   const Pre &) {
+        uint32_t r[4];
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            // 32 stream bits that start six bits below the pair: its index then sits at bits 6 .. 15
+            const int from = 20 * s + 10 * c - 6;
+            uint32_t t;
+            if (from < 0) {
+                t = qp_dw<P>(q, 0) << 6;
+            } else {
+                const int i0 = from >> 5, r0 = from & 31;
+                if (r0 <= 16) t = qp_dw<P>(q, i0) >> r0;
+                else t = __builtin_amdgcn_alignbit(qp_dw<P>(q, i0 + 1), qp_dw<P>(q, i0), r0);
+            }
+            const uint32_t a = (t & 0xffc0u) | lc;
+            const uint2 v = *reinterpret_cast<const uint2 *>(tab + a);
+            r[2 * c] = v.x;
+            r[2 * c + 1] = v.y;
+        }
+        return __builtin_bit_cast(half8_t, u32x4_t{r[0], r[1], r[2], r[3]});
+    }
+};
+#ifndef QP_VQ5_BYTE_WINDOW
+template <> struct QpDec<QP_VQ, 5> : QpDecVq5Pair {};
+#endif
 
 // VQ 5 bit, small layers at some batch sizes: 32 entries of half2 = one dword per LDS bank, conflict-free
 // as it is (two lanes either read the same entry or different banks), so every wavefront keeps
@@ -524,6 +597,11 @@ __device__ __forceinline__ half8_t qp_step(const u32x4_t (&q)[P], const uint8_t 
     else return D::template step<P>(q, SI, tab, lc, pre);
 }
 
+// Decoders whose lookups are issued ahead of the multiply: the byte-window ones, and those that say so.
+template <class D, class = void> struct QpAhead { static constexpr bool value = D::BYTE_WINDOW; };
+template <class D> struct QpAhead<D, decltype((void)D::AHEAD)> { static constexpr bool value = D::AHEAD; };
+template <class D> constexpr bool qp_looks_ahead() { return QpAhead<D>::value; }
+
 template <int B, int E, class F>
 __device__ __forceinline__ void qp_static_for(F &&f) {
     if constexpr (B < E) {
@@ -601,6 +679,9 @@ struct QpXBuf {
     int soff;      // bytes to the unit's column block
     uint32_t lo;   // the lane's bytes
     int xfs;       // bytes between fragments
+    // (Kernels of whole blocks carry these two as constants.  They stay members all the same: without them the
+    // register allocator gives the batch-16 kernels 128 registers and spills where it now takes 99 and none -
+    // 4-bit scalar 4096x14336 at batch 16 14.9 against 13.9 us.)
     bool tail;     // (wave-uniform) the unit's column block is cut short by N: `keep` applies
     uint32_t keep; // all ones, or zero where the lane's 256 columns lie beyond N
     __device__ __forceinline__ half8_t frag(int n, uint32_t lane_off) const {
@@ -716,7 +797,7 @@ __device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8
 #ifndef QP_PIPE_DEPTH_TRELLIS
 #define QP_PIPE_DEPTH_TRELLIS 0
 #endif
-    constexpr int DEPTH = (TT == 1) ? 0 : (D::BYTE_WINDOW ? QP_PIPE_DEPTH_BYTE : QP_PIPE_DEPTH_TRELLIS);
+    constexpr int DEPTH = (TT == 1) ? 0 : (qp_looks_ahead<D>() ? QP_PIPE_DEPTH_BYTE : QP_PIPE_DEPTH_TRELLIS);
     half8_t pipe[DEPTH > 0 ? DEPTH : 1];
     qp_static_for<0, DEPTH>([&](auto dc) __attribute__((always_inline)) {
         constexpr int d = decltype(dc)::value;
@@ -1310,7 +1391,7 @@ template <int S, int CB, int BP>
 static void qp_launch_one(bool split, int grid, int nw, hipStream_t st, const QpW &w, const void *x, int B,
                           int64_t ldx, void *y, int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic, int x_packed,
                           const int8_t *signs, int rot_block, float rot_norm) {
-    constexpr bool CAN_SPLIT = (qp_alt_splits(S) && BP <= 2) || (S == QP_VQ && CB == 5 && (BP == 4 || BP == 16));
+    constexpr bool CAN_SPLIT = (qp_alt_splits(S) && BP <= 2) || (S == QP_VQ && CB == 5 && BP == 4);
     if constexpr (CAN_SPLIT) {
         if (split) {
             qp_launch_xl<S, CB, BP, true>(grid, nw, st, w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed,
@@ -1363,15 +1444,13 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
     bool split = false;
     if (split_opt == 0) split = false;
     if (split_opt == 1) split = can_split;
-    // VQ 5 bit: the per-wavefront table while a workgroup has at most one unit per wavefront, at the
-    // batch sizes where it measured faster than the workgroup's byte-window table (4096x14336,
-    // us per call, per-wavefront / shared: batch 1 7.3 / 6.7, 2 7.35 / 7.07, 3 7.7 / 7.9, 4 7.8 / 8.7,
-    // 8 10.85 / 10.1, 16 with fragment-order activations 14.05 / 15.4).
-    // (Batch 3 - 4 only from 9 units per workgroup on: with the shared table's lookups issued ahead,
-    // 4096x4096 runs 4.55 -> 3.97 us and 4096x8192 5.70 -> 5.46 us on the shared table, 4096x12288 and
-    // 4096x14336 stay faster with the private one, 7.15 / 7.9 against 7.4 / 8.5 us.)
+    // VQ 5 bit: the per-wavefront table (32 entries, one code per lookup, no workgroup barrier in front of the
+    // decode) where it measured faster than the workgroup's table of code pairs: batch 3 - 4 with 9 to 16
+    // units per workgroup (us per call, per-wavefront / shared: 4096x14336 batch 4 7.9 / 8.6, 4096x12288
+    // 6.9 / 7.5; the same at batch 3 and from 8 units down; at batch 9 - 16 with fragment-order activations
+    // the shared table wins since it holds pairs, 4096x14336 12.75 / 12.6, 4096x8192 8.8 / 8.6).
     const int units_wg = rb_per_wg * nbc;
-    if (scheme == QP_VQ && cb == 5 && units_wg <= 16 && ((B > 2 && B <= 4 && units_wg > 8) || (B > 8 && x_packed))) {
+    if (scheme == QP_VQ && cb == 5 && units_wg <= 16 && B > 2 && B <= 4 && units_wg > 8) {
         split = split_opt != 0;
     }
     if (w.N % 1024 != 0) split = false;   // a last column block cut short: the plain form only
