@@ -368,6 +368,8 @@ struct QpDecVq5Pair {
                 if (r0 <= 16) t = qp_dw<P>(q, i0) >> r0;
                 else t = __builtin_amdgcn_alignbit(qp_dw<P>(q, i0 + 1), qp_dw<P>(q, i0), r0);
             }
+            // (the lane's own copy: taking whichever copy the stream bits below the index name - one plain AND -
+            // measured 6 % slower, 6.70 -> 7.09 us: collisions are cheap only up to a point)
             const uint32_t a = (t & 0xffc0u) | lc;
             const uint2 v = *reinterpret_cast<const uint2 *>(tab + a);
             r[2 * c] = v.x;
@@ -535,6 +537,7 @@ struct QpDecTcqh {
 #else
             // the index field of h already sits where the row number of the address does
             static_assert(LSH == 15 - TB, "row stride = 2^(15 - TB) bytes");
+            // (the lane's own copy; any copy, i.e. h & 0xfffc as one two-operand AND: 8.8 -> 10.4 us on 4096x14336 at 3 bits)
             asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(a) : "v"(h), "s"((ENTRIES - 1) << LSH), "v"(lc));
 #endif
             r[c] = *reinterpret_cast<const uint32_t *>(tab + a);
