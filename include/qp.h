@@ -301,7 +301,8 @@ size_t qp_linear_workspace_bytes(const qp_weight *w, int32_t B);
  *   QP_OPT_LINEAR_PACK     -1 by shape, 0 qp_linear never asks for a workspace, 1 always (block kernel)
  *   QP_OPT_LINEAR_SPLIT    -1 by shape, 0 / 1 the alternative form of the block kernel off / on where
  *                          it exists (two wavefronts per unit for the trellis schemes at batch <= 2:
- *                          only on request; per-wavefront table for 5-bit VQ: by batch)
+ *                          only on request; for 5-bit VQ the sixteen-copy table of code pairs at
+ *                          batch <= 2 and the per-wavefront table at batch 3 - 4: by shape)
  *   QP_OPT_WG_PER_CU       workgroups per compute unit of the block kernel (SQ / VQ; default 1)
  *   QP_OPT_NW              0 by shape, 4..16 wavefronts per workgroup of the block kernel (SQ / VQ)
  *   QP_OPT_TABLE_LATE_MAX  -1 by shape; units per workgroup up to which a shared table is built

@@ -313,12 +313,22 @@ template <> struct QpDec<QP_VQ, 7> : QpDecByte<QP_VQ, 7> {};
 // entries of 8 bytes (the four weights of the two codes), one ds_read_b64 per four weights instead of two
 // ds_read_b32 - a decode step is two shifts, two and-ors and two lookups where the byte-window form has
 // four SDWA operations and four lookups.  64 KiB hold eight copies of the table, copy lane % 8 at
-// (index << 6) | (lane % 8) << 3: lanes of different copies never share a bank, the four lanes of a
-// 32-lane pass that share a copy collide when their indices have the same parity.
-struct QpDecVq5Pair {
+// (index << 6) | (lane % 8) << 3: lanes of different copies never share a bank; an 8-byte lookup is served
+// 16 lanes at a time, and the two lanes of such a group that share a copy collide when their indices have
+// the same parity - nearly every group takes two cycles instead of one (measured: 3.9 conflict cycles per
+// 64-lane lookup).  LSH = 7: sixteen copies in 128 KiB, copy lane % 16 at (index << 7) | (lane % 16) << 3 -
+// one per lane of a group, no collisions.  Writing 128 KiB costs a small layer more than the collisions
+// do (4096x14336 6.77 -> 6.99 us, 4096x4096 3.80 -> 4.17 us, and the in-kernel rotation has no room beside
+// it); layers with many units per workgroup, whose decode runs against the LDS pipe in steady state, gain
+// at batch 1 - 2 (57344x8192 37.1 -> 32.8 us, batch 2 39.5 -> 37.5; 8192x28672 20.7 -> 19.9, batch 2
+// 22.0 -> 20.4) and are unchanged at batch 8 - 16.
+template <int LSH_>
+struct QpDecVq5PairT {
     static constexpr bool BYTE_WINDOW = false;
     static constexpr bool AHEAD = true;          // lookups issued ahead of the multiply, like the byte-window decoders
-    static constexpr int TAB_BYTES = 65536;
+    static constexpr int LSH = LSH_;             // the index sits at bits LSH .. LSH + 9 of a lookup's address
+    static constexpr int COPIES = 1 << (LSH - 3);
+    static constexpr int TAB_BYTES = 1024 << LSH;
     typedef uint32_t Lane;
     struct Pre { u32x4_t src[8]; };              // the 32 x 4 bytes of the code book, in scalar registers
     static __device__ __forceinline__ Pre pre(const uint16_t *g) {
@@ -328,7 +338,7 @@ struct QpDecVq5Pair {
         for (int k = 0; k < 8; ++k) p.src[k] = u32x4_t{s[4 * k], s[4 * k + 1], s[4 * k + 2], s[4 * k + 3]};
         return p;
     }
-    static __device__ __forceinline__ uint32_t lane_const() { return (threadIdx.x & 7u) << 3; }
+    static __device__ __forceinline__ uint32_t lane_const() { return (threadIdx.x & (uint32_t)(COPIES - 1)) << 3; }
     static __device__ __forceinline__ void early(uint8_t *tab, uint16_t *small, const uint16_t *g) { build(tab, small, pre(g)); }
     static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *small, const Pre &p) {
         if (threadIdx.x < 64) {   // (the source sits in scalar registers of every wavefront: the first one writes it out)
@@ -345,9 +355,10 @@ struct QpDecVq5Pair {
         for (int idx = threadIdx.x; idx < 1024; idx += blockDim.x) {
             const uint32_t lo = s32[idx & 31], hi = s32[idx >> 5];   // first code in the low five bits
             const u32x4_t v4 = u32x4_t{lo, hi, lo, hi};
-            const int rot = (idx >> 1) & 3;   // neighbouring threads start on different banks
+            constexpr int NP = COPIES / 2;    // 16-byte pieces per entry
+            const int rot = (idx >> (NP == 4 ? 1 : 0)) & (NP - 1);   // neighbouring threads start on different banks
 #pragma unroll
-            for (int k = 0; k < 4; ++k) t4[idx * 4 + ((k + rot) & 3)] = v4;
+            for (int k = 0; k < NP; ++k) t4[idx * NP + ((k + rot) & (NP - 1))] = v4;
         }
         QP_T(15);
         __syncthreads();
@@ -358,19 +369,19 @@ struct QpDecVq5Pair {
         uint32_t r[4];
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
-            // 32 stream bits that start six bits below the pair: its index then sits at bits 6 .. 15
-            const int from = 20 * s + 10 * c - 6;
+            // 32 stream bits that start LSH bits below the pair: its index then sits at bits LSH .. LSH + 9
+            const int from = 20 * s + 10 * c - LSH;
             uint32_t t;
             if (from < 0) {
-                t = qp_dw<P>(q, 0) << 6;
+                t = qp_dw<P>(q, 0) << LSH;
             } else {
                 const int i0 = from >> 5, r0 = from & 31;
-                if (r0 <= 16) t = qp_dw<P>(q, i0) >> r0;
+                if (r0 <= 22 - LSH) t = qp_dw<P>(q, i0) >> r0;
                 else t = __builtin_amdgcn_alignbit(qp_dw<P>(q, i0 + 1), qp_dw<P>(q, i0), r0);
             }
             // (the lane's own copy: taking whichever copy the stream bits below the index name - one plain AND -
             // measured 6 % slower, 6.70 -> 7.09 us: collisions are cheap only up to a point)
-            const uint32_t a = (t & 0xffc0u) | lc;
+            const uint32_t a = (t & (1023u << LSH)) | lc;
             const uint2 v = *reinterpret_cast<const uint2 *>(tab + a);
             r[2 * c] = v.x;
             r[2 * c + 1] = v.y;
@@ -378,6 +389,8 @@ struct QpDecVq5Pair {
         return __builtin_bit_cast(half8_t, u32x4_t{r[0], r[1], r[2], r[3]});
     }
 };
+typedef QpDecVq5PairT<6> QpDecVq5Pair;
+typedef QpDecVq5PairT<7> QpDecVq5Pair16;
 #ifndef QP_VQ5_BYTE_WINDOW
 template <> struct QpDec<QP_VQ, 5> : QpDecVq5Pair {};
 #endif
@@ -584,11 +597,15 @@ template <class D> struct QpTableMovable { static constexpr bool value = false; 
 template <> struct QpTableMovable<QpDec<QP_SQ, 4>> { static constexpr bool value = true; };
 template <> struct QpTableMovable<QpDec<QP_VQ, 7>> { static constexpr bool value = true; };
 template <> struct QpTableMovable<QpDec<QP_VQ, 5>> { static constexpr bool value = true; };
+template <> struct QpTableMovable<QpDecVq5Pair16> { static constexpr bool value = true; };
 
 // ALT selects the second form of a kernel where there is one: two wavefronts per unit for the
-// V = 1 and V = 2 trellis, the per-wavefront table for VQ 5 bit.
-template <int S, int CB, bool ALT> struct QpDecSel { typedef QpDec<S, CB> type; };
-template <> struct QpDecSel<QP_VQ, 5, true> { typedef QpDecVq5Private type; };
+// V = 1 and V = 2 trellis; for VQ 5 bit the sixteen-copy table of code pairs at batch 1 - 2 and the
+// per-wavefront table at batch 3 - 4.
+template <int S, int CB, bool ALT, int BP> struct QpDecSel { typedef QpDec<S, CB> type; };
+template <int BP> struct QpDecSel<QP_VQ, 5, true, BP> {
+    typedef std::conditional_t<(BP <= 2), QpDecVq5Pair16, QpDecVq5Private> type;
+};
 constexpr bool qp_alt_splits(int S) { return S == QP_TCQ || S == QP_TCQH; }
 
 // Step SI of a unit with the step index as a compile-time constant (the byte-window decoders
@@ -933,7 +950,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     const int x_packed = x_flags & 0xff;   // activations in fragment order
     const int late_max = x_flags >> 8;     // a movable table is built after the first loads up to this many units
     using T = QpTraits<S, CB>;
-    using D = typename QpDecSel<S, CB, ALT>::type;
+    using D = typename QpDecSel<S, CB, ALT, BP>::type;
     constexpr bool SPLIT = ALT && qp_alt_splits(S);
     // Half-TCQ: the units of the second half of the column blocks have P pieces and decode
     // with D, those of the first half have P - 1 and decode with D::Lo; both kinds share the
@@ -1325,7 +1342,7 @@ template <int S, int CB, int BP, bool SPLIT, int XL, bool TN = false>
 __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, int B, int64_t ldx, half_t *y,
                                                       int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic,
                                                       int x_packed, const int8_t *signs, int rot_block, float rot_norm) {
-    using D = typename QpDecSel<S, CB, SPLIT>::type;
+    using D = typename QpDecSel<S, CB, SPLIT, BP>::type;
     using L = QpLinLds<D, S, CB, BP>;
     static_assert(XL == 0 || L::ROT, "in-kernel rotation: batch 1");
     static_assert(XL != 2 || L::ROTM, "per-wavefront rotation: tables of at most 64 KiB");
@@ -1359,7 +1376,7 @@ static void qp_launch_xl(int grid, int nw, hipStream_t st, const QpW &w, const v
                          int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic, int x_packed, const int8_t *signs,
                          int rot_block, float rot_norm) {
     if constexpr (BP == 1) {
-        using D = typename QpDecSel<S, CB, SPLIT>::type;
+        using D = typename QpDecSel<S, CB, SPLIT, BP>::type;
         if constexpr (QpLinLds<D, S, CB, BP>::ROTM) {
             if (rot_block > 0 && rot_block != w.N) {
                 hipLaunchKernelGGL((k_linear_mfma<S, CB, BP, SPLIT, 2>), dim3(grid), dim3(64 * nw), 0, st, w,
@@ -1394,7 +1411,7 @@ template <int S, int CB, int BP>
 static void qp_launch_one(bool split, int grid, int nw, hipStream_t st, const QpW &w, const void *x, int B,
                           int64_t ldx, void *y, int64_t ldy, int G, int rb_q, int rb_r, int nbc_magic, int x_packed,
                           const int8_t *signs, int rot_block, float rot_norm) {
-    constexpr bool CAN_SPLIT = (qp_alt_splits(S) && BP <= 2) || (S == QP_VQ && CB == 5 && BP == 4);
+    constexpr bool CAN_SPLIT = (qp_alt_splits(S) && BP <= 2) || (S == QP_VQ && CB == 5 && BP <= 4);
     if constexpr (CAN_SPLIT) {
         if (split) {
             qp_launch_xl<S, CB, BP, true>(grid, nw, st, w, x, B, ldx, y, ldy, G, rb_q, rb_r, nbc_magic, x_packed,
@@ -1455,6 +1472,12 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
     const int units_wg = rb_per_wg * nbc;
     if (scheme == QP_VQ && cb == 5 && units_wg <= 16 && B > 2 && B <= 4 && units_wg > 8) {
         split = split_opt != 0;
+    }
+    // VQ 5 bit at batch 1 - 2: the sixteen-copy table of code pairs (128 KiB, no lookup collisions) from 48 units
+    // per workgroup on (measured from 56: 8192x28672; 28 and fewer lose or draw); never with the rotation
+    // inside the kernel, which has no room beside it.
+    if (scheme == QP_VQ && cb == 5 && B <= 2) {
+        split = (split_opt < 0 ? units_wg >= 48 : split_opt == 1) && rot_block <= 0;
     }
     if (w.N % 1024 != 0) split = false;   // a last column block cut short: the plain form only
     int nw = units < 16 ? units : 16;

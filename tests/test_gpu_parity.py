@@ -175,6 +175,19 @@ def test_block_kernel_one_hot_sweep_is_exact(qp, scheme, cb, layout):
         c0 = 1024 - B // 2 - 1 if B > 1 else 1999                                   # straddles the two column blocks
         y = qp.qp_linear(w, eye[c0:c0 + B]).cpu().numpy()
         assert np.array_equal(y.astype(np.float32), want.T[c0:c0 + B].astype(np.float32)), B
+    if (scheme, cb) == (synth.VQ, 5):
+        # the forms of this kernel that large layers (batch 1 - 2: sixteen-copy table of code pairs) and some
+        # small ones (batch 3 - 4: per-wavefront table) take by shape, forced here: every column, then
+        # ragged offsets at the other batch sizes
+        qp.qp_set_option(qp.QP_OPT_LINEAR_SPLIT, 1)
+        alt = torch.empty((N, M), dtype=torch.float16, device="cuda")
+        for c0 in range(0, N, 2):
+            qp.qp_linear(w, eye[c0:c0 + 2], y=alt[c0:c0 + 2])
+        torch.cuda.synchronize()
+        assert np.array_equal(alt.cpu().numpy().T.astype(np.float32), want.astype(np.float32))
+        for B, c0 in ((1, 0), (1, 1023), (1, 2047), (2, 1023), (3, 1022), (4, 1021)):
+            y = qp.qp_linear(w, eye[c0:c0 + B]).cpu().numpy()
+            assert np.array_equal(y.astype(np.float32), want.T[c0:c0 + B].astype(np.float32)), (B, c0)
 
 
 def test_linear_one_hot_picks_single_weights(qp):
@@ -611,6 +624,27 @@ def test_linear_two_wavefronts_per_unit(qp, scheme, cb, M, N, B, split):
     y = qp.qp_linear(w, dev(x))
     torch.cuda.synchronize()
     assert rel_err(host16(y), want) <= TOL_SHARP    # (and so within the stated TOL)
+
+
+@pytest.mark.parametrize("M,N,B", [(48, 4096, 1), (1040, 2048, 2), (16, 14336, 1), (4112, 3072, 2), (272, 3072, 1)])
+@pytest.mark.parametrize("split", [0, 1])
+def test_vq5_tables_of_code_pairs(qp, M, N, B, split):
+    """The 2.5-bit vector quantizer at batch <= 2 decodes two codes per lookup from a table of pairs held
+    eight times (64 KiB) or sixteen times (128 KiB, taken by shape from 48 units per workgroup on); both
+    forms on layers of one and of several passes, same bits from both (the decoded weights are the same
+    and so is the order of the sums)."""
+    lay = synth.make_layer(85, M + B, synth.VQ, M, N, 5)
+    x = synth.make_x(85, B, B, N)
+    want = oracle.linear(lay, x, threads=True)
+    w = qp.qp_repack(qp.Weight.from_layer(lay))
+    qp.qp_set_option(qp.QP_OPT_LINEAR_KERNEL, qp.QP_KERNEL_BLOCK)
+    qp.qp_set_option(qp.QP_OPT_LINEAR_SPLIT, split)
+    y = qp.qp_linear(w, dev(x))
+    qp.qp_set_option(qp.QP_OPT_LINEAR_SPLIT, 1 - split)
+    y_other = qp.qp_linear(w, dev(x))
+    torch.cuda.synchronize()
+    assert rel_err(host16(y), want) <= TOL_SHARP
+    assert torch.equal(y, y_other)
 
 
 def test_calls_captured_in_a_hip_graph_replay_identically(qp):
