@@ -74,6 +74,8 @@ def parse():
     p.add_argument("--codebooks", action="store_true",
                    help="fit code books on the GPU (qp_kmeans) and measure the distortion of Gaussian weights "
                         "quantized with them (fit -> qp_encode -> qp_dequant); prints its own JSON line")
+    p.add_argument("--option", action="append", default=[], metavar="QP_OPT_NAME=VALUE",
+                   help="set a tuning option of the library before anything runs (qp_set_option; repeatable)")
     p.add_argument("--profile-only", action="store_true",
                    help="run a short sequence of the dominant kernel only (for rocprofv3)")
     return p.parse_args()
@@ -350,6 +352,9 @@ def main():
     import synth
     import paper_2509_20214_amd as qp
     qp.load_library()
+    for kv in a.option:
+        name, value = kv.split("=")
+        qp.qp_set_option(getattr(qp, name), int(value))
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
@@ -588,7 +593,7 @@ def main():
                 (4, 0, (1, 2, 4, 8, 16)), (4, 1, (1, 2, 4, 8, 16)), (4, 2, (1, 2, 4, 8, 16)), (4, 3, (1, 2, 4, 8, 16)),
                 (5, 0, (1, 8, 16)), (5, 1, (1, 8, 16)), (5, 2, (1, 8, 16)), (5, 3, (1, 8, 16)),
                 (6, 0, (1,)), (6, 1, (1, 8)), (6, 2, (1,)), (6, 3, (1,)), (6, 4, (1,)), (6, 5, (1,)), (6, 6, (1,)),
-                (6, 7, (1,)), (6, 8, (1, 8)), (6, 9, (1,)), (6, 10, (1, 8)), (6, 11, (1, 8))]
+                (6, 7, (1,)), (6, 8, (1, 8)), (6, 9, (1,)), (6, 10, (1, 8)), (6, 11, (1, 8)), (6, 12, (1, 2))]
         for cfg, li, batches in todo:
             c = Case(cfg, li, batches[0])
             g = graph_of(c.stream_only, 100)

@@ -313,11 +313,13 @@ template <> struct QpDec<QP_VQ, 7> : QpDecByte<QP_VQ, 7> {};
 // entries of 8 bytes (the four weights of the two codes), one ds_read_b64 per four weights instead of two
 // ds_read_b32 - a decode step is two shifts, two and-ors and two lookups where the byte-window form has
 // four SDWA operations and four lookups.  64 KiB hold eight copies of the table, copy lane % 8 at
-// (index << 6) | (lane % 8) << 3: lanes of different copies never share a bank; an 8-byte lookup is served
-// 16 lanes at a time, and the two lanes of such a group that share a copy collide when their indices have
-// the same parity - nearly every group takes two cycles instead of one (measured: 3.9 conflict cycles per
-// 64-lane lookup).  LSH = 7: sixteen copies in 128 KiB, copy lane % 16 at (index << 7) | (lane % 16) << 3 -
-// one per lane of a group, no collisions.  Writing 128 KiB costs a small layer more than the collisions
+// (index << 6) | (lane % 8) << 3: lanes of different copies never share a bank.  An 8-byte lookup is served
+// 32 lanes at a time, 64 dwords through 32 banks: two cycles when every pair of banks serves exactly two
+// lanes.  Here the four lanes of such a half that share a copy fall on one of the copy's two bank pairs by
+// the parity of their index, and the half takes as long as the fullest pair - 3.1 cycles on average
+// (measured: 6.2 LDS cycles per 64-lane lookup where 4 is the least).  LSH = 7: sixteen copies in 128 KiB, copy
+// lane % 16 at (index << 7) | (lane % 16) << 3 - two lanes per copy and half, one bank pair per copy: always
+// the two cycles (measured 4.5 per lookup).  Writing 128 KiB costs a small layer more than the collisions
 // do (4096x14336 6.77 -> 6.99 us, 4096x4096 3.80 -> 4.17 us, and the in-kernel rotation has no room beside
 // it); layers with many units per workgroup, whose decode runs against the LDS pipe in steady state, gain
 // at batch 1 - 2 (57344x8192 37.1 -> 32.8 us, batch 2 39.5 -> 37.5; 8192x28672 20.7 -> 19.9, batch 2

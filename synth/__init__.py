@@ -244,7 +244,9 @@ def config_layers(cfg: int, *, small: bool = False):
                 # down projections of the 7B- and 13B-shaped models: 11008 = 43 x 256 and 13824 = 54 x 256
                 # input channels, not multiples of 1024
                 d(10, "vq2.5_down_4096x11008", VQ, 4096, 11008, 5),
-                d(11, "tcqh3_down_5120x13824", TCQH, 5120, 13824, 6)]
+                d(11, "tcqh3_down_5120x13824", TCQH, 5120, 13824, 6),
+                # the 70B-shaped down projection at 2.5 bits: 56 units of 16 x 1024 per workgroup
+                d(12, "vq2.5_down_8192x28672", VQ, 8192, 28672, 5)]
     raise ValueError(cfg)
 
 

@@ -28,6 +28,7 @@ CASES = [  # (cfg, layer index, batches)
     (6, 8, [1, 8]),
     (6, 10, [1, 8]),
     (6, 11, [1, 16]),
+    (6, 12, [1, 2]),
 ]
 
 
