@@ -194,12 +194,14 @@ __device__ __forceinline__ float qp_half_bits_to_float(uint16_t h) {
 }
 
 // Dispatch a (scheme, code_bits) pair known at run time to a template.
-#ifdef QP_DEV_SUBSET  // development builds only: the scalar and vector quantizers, for short compile times
+#ifdef QP_DEV_SUBSET  // development builds only: a few schemes, for short compile times
 #define QP_DISPATCH_SCHEME(scheme, cb, CALL)                                          \
     do {                                                                              \
         if ((scheme) == QP_SQ && (cb) == 4) { CALL(QP_SQ, 4); }                       \
         else if ((scheme) == QP_VQ && (cb) == 5) { CALL(QP_VQ, 5); }                  \
         else if ((scheme) == QP_VQ && (cb) == 7) { CALL(QP_VQ, 7); }                  \
+        else if ((scheme) == QP_TCQH && (cb) == 4) { CALL(QP_TCQH, 4); }              \
+        else if ((scheme) == QP_TCQH && (cb) == 8) { CALL(QP_TCQH, 8); }              \
         else return QP_ERR_UNSUPPORTED;                                               \
     } while (0)
 #else

@@ -560,12 +560,67 @@ struct QpDecTcqh {
         return __builtin_bit_cast(half8_t, u32x4_t{r[0], r[1], r[2], r[3]});
     }
 };
-template <> struct QpDec<QP_TCQH, 3> : QpDecTcqh<3> {};
+// 4 and 8 bits per step (2 and 4 bits per weight): states 16 / K steps apart start 16 bits apart, so one 32-bit
+// window of the stream holds TWO states in its two halves, and one packed 16-bit multiply-add hashes both -
+// h = x (x + 1) is only needed modulo 2^16.  Per pair of states: one funnel shift (none where the window is a
+// dword of the stream), one v_pk_mad_u16, one and-or for the low half's address, a shift and an and-or for the
+// high half's: five vector operations where the plain form has six.  At 4 bits per step the two states of a
+// window belong to two consecutive decode steps (the even step hashes for both and parks the odd step's four
+// addresses in the lane's state), at 8 bits to the same step.
+template <int K, int TB = QpTraits<QP_TCQH, K>::TLUT_BITS>
+struct QpDecTcqhPacked : QpDecTcqh<K, TB> {
+    static_assert(K == 4 || K == 8, "two states per 32-bit window");
+    typedef QpDecTcqh<K, TB> Base;
+    typedef typename Base::Pre Pre;
+    struct Lane { uint32_t lc; uint32_t hi[4]; };
+    static __device__ __forceinline__ Lane lane_const() { return Lane{Base::lane_const(), {0u, 0u, 0u, 0u}}; }
+    // addresses of the two states in the halves of `win`
+    static __device__ __forceinline__ void pair(uint32_t win, uint32_t lc, uint32_t &a_lo, uint32_t &a_hi) {
+        static_assert(Base::LSH == 15 - TB, "the index field of the hash is the row number of the address");
+        uint32_t h, t;
+        asm("v_pk_mad_u16 %0, %1, %1, %1" : "=v"(h) : "v"(win));   // x (x + 1) modulo 2^16 in both halves
+        asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(a_lo) : "v"(h), "s"((Base::ENTRIES - 1) << Base::LSH), "v"(lc));
+        t = h >> 16;
+        asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(a_hi) : "v"(t), "s"((Base::ENTRIES - 1) << Base::LSH), "v"(lc));
+    }
+    template <int P>
+    static __device__ __forceinline__ half8_t step(const u32x4_t (&q)[P], int s, const uint8_t *tab, Lane &l, const Pre &) {
+        uint32_t r[4];
+        if constexpr (K == 4) {
+            if ((s & 1) == 0) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    uint32_t a;
+                    pair(qp_bits32<P, true, K>(q, 16 * s + 4 * c), l.lc, a, l.hi[c]);   // states 4 s + c and 4 (s + 1) + c
+                    r[c] = *reinterpret_cast<const uint32_t *>(tab + a);
+                }
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) r[c] = *reinterpret_cast<const uint32_t *>(tab + l.hi[c]);
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                uint32_t a, b;
+                pair(qp_bits32<P, true, K>(q, 32 * s + 8 * c), l.lc, a, b);   // states 4 s + c and 4 s + c + 2
+                r[c] = *reinterpret_cast<const uint32_t *>(tab + a);
+                r[c + 2] = *reinterpret_cast<const uint32_t *>(tab + b);
+            }
+        }
+        return __builtin_bit_cast(half8_t, u32x4_t{r[0], r[1], r[2], r[3]});
+    }
+};
+#ifdef QP_TCQH_TABLE_128K
 template <> struct QpDec<QP_TCQH, 4> : QpDecTcqh<4> {};
+template <> struct QpDec<QP_TCQH, 8> : QpDecTcqh<8> {};
+#else
+template <> struct QpDec<QP_TCQH, 4> : QpDecTcqhPacked<4> {};
+template <> struct QpDec<QP_TCQH, 8> : QpDecTcqhPacked<8> {};
+#endif
+template <> struct QpDec<QP_TCQH, 3> : QpDecTcqh<3> {};
 template <> struct QpDec<QP_TCQH, 5> : QpDecTcqh<5> {};
 template <> struct QpDec<QP_TCQH, 6> : QpDecTcqh<6> {};
 template <> struct QpDec<QP_TCQH, 7> : QpDecTcqh<7> {};
-template <> struct QpDec<QP_TCQH, 8> : QpDecTcqh<8> {};
 template <> struct QpDec<QP_TCQH, 9> : QpDecTcqh<9> {};
 template <> struct QpDec<QP_TCQH, 10> : QpDecTcqh<10> {};
 
