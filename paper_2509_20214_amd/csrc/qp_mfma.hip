@@ -474,6 +474,11 @@ struct QpDecTcq {
 // per *two* weights - never collide; 16 and 8 copies for TB = 10 and 11, where only lanes
 // with equal l % COPIES can still meet in a bank.  The per-state work is a 24-bit
 // multiply-add, a bit-field extract and a shift-or.
+// A lane's state for the V = 2 decoders: the offset of its copy of the table, and (the packed form at 4 bits
+// per step) the four addresses that an even decode step worked out for the odd one behind it.  One type for
+// every step width, so that the two halves of a half-TCQ layer can share it.
+struct QpTcqhLane { uint32_t lc; uint32_t hi[4]; };
+
 template <int TB>
 struct QpTcqhPre { uint32_t raw[(1 << TB) / 1024 ? (1 << TB) / 1024 : 1]; };
 
@@ -492,8 +497,8 @@ struct QpDecTcqh {
     static constexpr int SMALL_BYTES = 4 << TB;             // staging room for the source
     static constexpr int NSRC = (1 << TB) / 1024 ? (1 << TB) / 1024 : 1;   // source dwords per thread
     typedef QpTcqhPre<TB> Pre;
-    typedef uint32_t Lane;
-    static __device__ __forceinline__ uint32_t lane_const() { return (threadIdx.x & (COPIES - 1)) << 2; }
+    typedef QpTcqhLane Lane;
+    static __device__ __forceinline__ Lane lane_const() { return Lane{(threadIdx.x & (uint32_t)(COPIES - 1)) << 2, {0u, 0u, 0u, 0u}}; }
     static __device__ __forceinline__ void early(uint8_t *, uint16_t *, const uint16_t *) {}
     static __device__ __forceinline__ Pre pre(const uint16_t *g) {  // needs blockDim.x == 1024
         Pre p;
@@ -530,8 +535,9 @@ struct QpDecTcqh {
         __syncthreads();
     }
     template <int P>
-    static __device__ __forceinline__ half8_t step(const u32x4_t (&q)[P], int s, const uint8_t *tab, uint32_t lc,
+    static __device__ __forceinline__ half8_t step(const u32x4_t (&q)[P], int s, const uint8_t *tab, const Lane &l,
                                                    const Pre &) {
+        const uint32_t lc = l.lc;
         uint32_t r[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
@@ -572,8 +578,7 @@ struct QpDecTcqhPacked : QpDecTcqh<K, TB> {
     static_assert(K == 4 || K == 8, "two states per 32-bit window");
     typedef QpDecTcqh<K, TB> Base;
     typedef typename Base::Pre Pre;
-    struct Lane { uint32_t lc; uint32_t hi[4]; };
-    static __device__ __forceinline__ Lane lane_const() { return Lane{Base::lane_const(), {0u, 0u, 0u, 0u}}; }
+    typedef QpTcqhLane Lane;
     // addresses of the two states in the halves of `win`
     static __device__ __forceinline__ void pair(uint32_t win, uint32_t lc, uint32_t &a_lo, uint32_t &a_hi) {
         static_assert(Base::LSH == 15 - TB, "the index field of the hash is the row number of the address");
@@ -628,9 +633,14 @@ template <> struct QpDec<QP_TCQH, 10> : QpDecTcqh<10> {};
 // carry K bits per step, those of the second half K + 1; one table, that of K + 1.
 // QpDec<QP_TCQHH, K> is the decoder of the second half (it also builds the table); Lo
 // decodes the first half from the same table.
+template <int K, int TB> struct QpTcqhPick { typedef QpDecTcqh<K, TB> type; };
+#ifndef QP_TCQH_TABLE_128K
+template <int TB> struct QpTcqhPick<4, TB> { typedef QpDecTcqhPacked<4, TB> type; };
+template <int TB> struct QpTcqhPick<8, TB> { typedef QpDecTcqhPacked<8, TB> type; };
+#endif
 template <int K>
-struct QpDecHalf : QpDecTcqh<K + 1, QpTraits<QP_TCQHH, K>::TLUT_BITS> {
-    typedef QpDecTcqh<K, QpTraits<QP_TCQHH, K>::TLUT_BITS> Lo;
+struct QpDecHalf : QpTcqhPick<K + 1, QpTraits<QP_TCQHH, K>::TLUT_BITS>::type {
+    typedef typename QpTcqhPick<K, QpTraits<QP_TCQHH, K>::TLUT_BITS>::type Lo;
 };
 template <> struct QpDec<QP_TCQHH, 3> : QpDecHalf<3> {};
 template <> struct QpDec<QP_TCQHH, 4> : QpDecHalf<4> {};
