@@ -76,9 +76,37 @@ def parse():
                         "quantized with them (fit -> qp_encode -> qp_dequant); prints its own JSON line")
     p.add_argument("--option", action="append", default=[], metavar="QP_OPT_NAME=VALUE",
                    help="set a tuning option of the library before anything runs (qp_set_option; repeatable)")
+    p.add_argument("--encode-only", action="store_true",
+                   help="run the encoder case alone (two calls; for rocprofv3) and print its JSON line")
     p.add_argument("--profile-only", action="store_true",
                    help="run a short sequence of the dominant kernel only (for rocprofv3)")
     return p.parse_args()
+
+
+def encode_case(torch, synth, qp, dev, upload):
+    """The trellis encoder (two-pass tail-biting Viterbi) on 1024 x 4096 Gaussian targets at 2 bits; two calls, the
+    second is the timed one."""
+    M_e, N_e, s_e = 1024, 4096, 4
+    lay_e = synth.make_layer(6, 900, synth.TCQH, 16, N_e, s_e)
+    Wt = torch.randn((M_e, N_e), device=dev, generator=torch.Generator(device=dev).manual_seed(6)).half()
+    codes_e = torch.zeros((M_e, lay_e.codes.shape[1]), dtype=torch.uint8, device=dev)
+    we = qp.Weight(synth.TCQH, M_e, N_e, s_e, 2, 16, 256, codes_e, upload(lay_e.lut).view(torch.int16),
+                   torch.full((M_e,), 0x3C00, dtype=torch.int16, device=dev), tlut_bits=lay_e.tlut_bits)
+    ws_e = torch.empty(qp.qp_encode_workspace_bytes(we), dtype=torch.uint8, device=dev)
+    dt = None
+    for _ in range(2):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        qp.qp_encode(we, Wt, workspace=ws_e)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+    Wd = qp.qp_dequant(we).float()
+    mse = float(((Wd - Wt.float()) ** 2).mean() / (Wt.float() ** 2).mean())
+    out = {"workload": "tcqh 2 bit, 1024x4096 N(0,1) targets", "ms": round(dt * 1e3, 1),
+           "Mweights_per_s": round(M_e * N_e / dt / 1e6, 1), "normalised_mse": round(mse, 5)}
+    del Wt, Wd, ws_e, we, codes_e
+    torch.cuda.empty_cache()
+    return out
 
 
 def sweep_model(model, label, torch, synth, qp, dev, upload, graph_of, event_time_us):
@@ -450,6 +478,9 @@ def main():
             out.append(e0.elapsed_time(e1) * 1e3 / count)
         return statistics.median(out)
 
+    if a.encode_only:
+        print(json.dumps({"encode": encode_case(torch, synth, qp, dev, upload)}))
+        return
     if a.micro:
         import subprocess
         import tempfile
@@ -639,26 +670,7 @@ def main():
     # ---------------- encoder (offline path): 1024 x 4096 Gaussian targets at 2 bits, V = 2 trellis
     encode = None
     if not a.no_cases:
-        M_e, N_e, s_e = 1024, 4096, 4
-        lay_e = synth.make_layer(6, 900, synth.TCQH, 16, N_e, s_e)
-        Wt = torch.randn((M_e, N_e), device=dev, generator=torch.Generator(device=dev).manual_seed(6)).half()
-        codes_e = torch.zeros((M_e, lay_e.codes.shape[1]), dtype=torch.uint8, device=dev)
-        we = qp.Weight(synth.TCQH, M_e, N_e, s_e, 2, 16, 256, codes_e, upload(lay_e.lut).view(torch.int16),
-                       torch.full((M_e,), 0x3C00, dtype=torch.int16, device=dev), tlut_bits=lay_e.tlut_bits)
-        ws_e = torch.empty(qp.qp_encode_workspace_bytes(we), dtype=torch.uint8, device=dev)
-        dt = None
-        for _ in range(2):     # the second call is the timed one
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            qp.qp_encode(we, Wt, workspace=ws_e)
-            torch.cuda.synchronize()
-            dt = time.perf_counter() - t0
-        Wd = qp.qp_dequant(we).float()
-        mse = float(((Wd - Wt.float()) ** 2).mean() / (Wt.float() ** 2).mean())
-        encode = {"workload": "tcqh 2 bit, 1024x4096 N(0,1) targets", "ms": round(dt * 1e3, 1),
-                  "Mweights_per_s": round(M_e * N_e / dt / 1e6, 1), "normalised_mse": round(mse, 5)}
-        del Wt, Wd, ws_e, we, codes_e
-        torch.cuda.empty_cache()
+        encode = encode_case(torch, synth, qp, dev, upload)
 
     # ---------------- the oracle on this machine's host cores (a reported baseline, not a target)
     cpu = None
