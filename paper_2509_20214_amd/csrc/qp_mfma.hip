@@ -242,19 +242,31 @@ struct QpDecByte {
     static constexpr int TAB_BYTES = 65536;
     static constexpr int SRC_BYTES = (S == QP_SQ) ? 32 : (4 << CB);   // the table's source in global memory
     typedef QpLane8 Lane;
-    // The table's source: at most 128 bytes per wavefront (the first SRC_BYTES / 128 wavefronts
-    // take 128 bytes each), requested into scalar registers as the very first thing a kernel does -
-    // the fetch takes about as long as the first weights need to arrive, and the scalar path does
-    // not queue behind the vector loads of the weight stream.
-    static constexpr int NQ = (SRC_BYTES <= 128 ? SRC_BYTES : 128) / 16;
-    static constexpr int NSRCW = SRC_BYTES <= 128 ? 1 : SRC_BYTES / 128;   // wavefronts that carry a part
-    struct Pre { u32x4_t src[NQ]; };
+    static constexpr bool DIRECT = (S != QP_SQ);
+    // Vector codes: every thread fetches the code book entries that its table rows are made of itself, ahead of
+    // everything else (the code book - 128 or 512 bytes - is hot in L2 after the first workgroup): no staging in
+    // LDS, no barrier in front of the build (3.5 bit 1024x4096 3.91 -> 3.55 us, 4096x4096 4.23 -> 4.17 us, the step
+    // of 4096x14336 8.38 -> 8.31 us).  Scalar codes (a row = two entries of a 32-byte table) keep the staged
+    // form: 32 bytes into scalar registers as the very first thing a kernel does - the scalar path does not queue
+    // behind the vector loads of the weight stream -, lane 0 writes them to LDS, a barrier, then the build (with
+    // two 2-byte fetches per row instead: 4096x4096 3.95 -> 4.30 us).
+    static constexpr int NQ = 2;
+    struct PreStaged { u32x4_t src[NQ]; };
+    struct PreDirect { uint32_t v[4]; };   // the row's entry for idx = thread + k * workgroup size, row idx >> 2
+    typedef std::conditional_t<DIRECT, PreDirect, PreStaged> Pre;
     static __device__ __forceinline__ Pre pre(const uint16_t *g) {
-        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        qp_cu32 *s = qp_scalar_ptr(g) + 32 * (wave < NSRCW ? wave : NSRCW - 1);
         Pre p;
+        if constexpr (DIRECT) {
 #pragma unroll
-        for (int k = 0; k < NQ; ++k) p.src[k] = u32x4_t{s[4 * k], s[4 * k + 1], s[4 * k + 2], s[4 * k + 3]};
+            for (int k = 0; k < 4; ++k) {
+                const int idx = threadIdx.x + k * blockDim.x, b = idx >> 2;
+                p.v[k] = idx < 1024 ? reinterpret_cast<const uint32_t *>(g)[b & ((1 << CB) - 1)] : 0u;
+            }
+        } else {
+            qp_cu32 *s = qp_scalar_ptr(g);
+#pragma unroll
+            for (int k = 0; k < NQ; ++k) p.src[k] = u32x4_t{s[4 * k], s[4 * k + 1], s[4 * k + 2], s[4 * k + 3]};
+        }
         return p;
     }
     static __device__ __forceinline__ Lane lane_const() {
@@ -264,28 +276,31 @@ struct QpDecByte {
         return l;
     }
     static __device__ __forceinline__ void early(uint8_t *tab, uint16_t *small, const uint16_t *g) { build(tab, small, pre(g)); }
-    // Lane 0 of the wavefronts that carry a part of the source writes it to `small`; then every
-    // thread writes 32 bytes of a row.
+    // every thread writes 32 bytes of a row
     static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *small, const Pre &p) {
-        const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        if (wave < NSRCW && (threadIdx.x & 63) == 0) {
+        if constexpr (!DIRECT) {
+            if (threadIdx.x == 0) {
 #pragma unroll
-            for (int k = 0; k < NQ; ++k) reinterpret_cast<u32x4_t *>(small)[8 * wave + k] = p.src[k];
+                for (int k = 0; k < NQ; ++k) reinterpret_cast<u32x4_t *>(small)[k] = p.src[k];
+            }
+            QP_T(11);
+            __syncthreads();
         }
-        QP_T(11);
-        __syncthreads();
         QP_T(12);
-        const uint32_t *s32 = reinterpret_cast<const uint32_t *>(small);
         u32x4_t *t4 = reinterpret_cast<u32x4_t *>(tab);
-        for (int idx = threadIdx.x; idx < 1024; idx += blockDim.x) {
-            const int b = idx >> 2, part = idx & 3;
-            uint32_t v;
-            if constexpr (S == QP_SQ) v = (uint32_t)small[b & 15] | ((uint32_t)small[b >> 4] << 16);   // two weights per code byte
-            else v = s32[b & ((1 << CB) - 1)];
-            const u32x4_t v4 = u32x4_t{v, v, v, v};
-            const int flip = (idx >> 3) & 1;   // neighbouring rows start on different banks
-            t4[b * 16 + part * 2 + flip] = v4;
-            t4[b * 16 + part * 2 + (flip ^ 1)] = v4;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {          // (a workgroup has at least 256 threads)
+            const int idx = threadIdx.x + k * blockDim.x;
+            if (idx < 1024) {
+                const int b = idx >> 2, part = idx & 3;
+                uint32_t v;
+                if constexpr (DIRECT) v = p.v[k];
+                else v = (uint32_t)small[b & 15] | ((uint32_t)small[b >> 4] << 16);   // two weights per code byte
+                const u32x4_t v4 = u32x4_t{v, v, v, v};
+                const int flip = (idx >> 3) & 1;   // neighbouring rows start on different banks
+                t4[b * 16 + part * 2 + flip] = v4;
+                t4[b * 16 + part * 2 + (flip ^ 1)] = v4;
+            }
         }
         QP_T(15);
         __syncthreads();
@@ -332,35 +347,37 @@ struct QpDecVq5PairT {
     static constexpr int COPIES = 1 << (LSH - 3);
     static constexpr int TAB_BYTES = 1024 << LSH;
     typedef uint32_t Lane;
-    struct Pre { u32x4_t src[8]; };              // the 32 x 4 bytes of the code book, in scalar registers
+    // Every thread fetches the two code book entries that its table entries are made of itself (32 x 4 bytes, hot
+    // in L2 after the first workgroup), ahead of everything else: staging the code book in LDS first cost a barrier
+    // and an LDS round trip in front of the build (one-launch step of 4096x14336 8.03 -> 7.79 us, 1024x4096
+    // 3.71 -> 3.40 us, 4096x4096 3.85 -> 3.80 us, nothing slower).
+    struct Pre { uint32_t lo; uint32_t hi[4]; };   // entry idx = thread + k * workgroup size: codes idx & 31 and idx >> 5
     static __device__ __forceinline__ Pre pre(const uint16_t *g) {
-        qp_cu32 *s = qp_scalar_ptr(g);
+        const uint32_t *s = reinterpret_cast<const uint32_t *>(g);
         Pre p;
+        p.lo = s[threadIdx.x & 31];                // (the workgroup size is a multiple of 32)
 #pragma unroll
-        for (int k = 0; k < 8; ++k) p.src[k] = u32x4_t{s[4 * k], s[4 * k + 1], s[4 * k + 2], s[4 * k + 3]};
+        for (int k = 0; k < 4; ++k) {
+            const int idx = threadIdx.x + k * blockDim.x;
+            p.hi[k] = idx < 1024 ? s[idx >> 5] : 0u;
+        }
         return p;
     }
     static __device__ __forceinline__ uint32_t lane_const() { return (threadIdx.x & (uint32_t)(COPIES - 1)) << 3; }
     static __device__ __forceinline__ void early(uint8_t *tab, uint16_t *small, const uint16_t *g) { build(tab, small, pre(g)); }
-    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *small, const Pre &p) {
-        if (threadIdx.x < 64) {   // (the source sits in scalar registers of every wavefront: the first one writes it out)
-            if ((threadIdx.x & 63) == 0) {
-#pragma unroll
-                for (int k = 0; k < 8; ++k) reinterpret_cast<u32x4_t *>(small)[k] = p.src[k];
-            }
-        }
-        QP_T(11);
-        __syncthreads();
-        QP_T(12);
-        const uint32_t *s32 = reinterpret_cast<const uint32_t *>(small);
+    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *, const Pre &p) {
         u32x4_t *t4 = reinterpret_cast<u32x4_t *>(tab);
-        for (int idx = threadIdx.x; idx < 1024; idx += blockDim.x) {
-            const uint32_t lo = s32[idx & 31], hi = s32[idx >> 5];   // first code in the low five bits
-            const u32x4_t v4 = u32x4_t{lo, hi, lo, hi};
-            constexpr int NP = COPIES / 2;    // 16-byte pieces per entry
-            const int rot = (idx >> (NP == 4 ? 1 : 0)) & (NP - 1);   // neighbouring threads start on different banks
+        QP_T(12);
 #pragma unroll
-            for (int k = 0; k < NP; ++k) t4[idx * NP + ((k + rot) & (NP - 1))] = v4;
+        for (int k = 0; k < 4; ++k) {              // (a workgroup has at least 256 threads)
+            const int idx = threadIdx.x + k * blockDim.x;
+            if (idx < 1024) {
+                const u32x4_t v4 = u32x4_t{p.lo, p.hi[k], p.lo, p.hi[k]};   // first code in the low five bits
+                constexpr int NP = COPIES / 2;     // 16-byte pieces per entry
+                const int rot = (idx >> (NP == 4 ? 1 : 0)) & (NP - 1);   // neighbouring threads start on different banks
+#pragma unroll
+                for (int m = 0; m < NP; ++m) t4[idx * NP + ((m + rot) & (NP - 1))] = v4;
+            }
         }
         QP_T(15);
         __syncthreads();
@@ -503,21 +520,16 @@ struct QpDecTcqh {
     static __device__ __forceinline__ Pre pre(const uint16_t *g) {  // needs blockDim.x == 1024
         Pre p;
 #pragma unroll
+        // (thread t builds entries t, t + 1024, ... of the table, whose sources are entries (t + 1024 k) mod 2^TB of
+        // the small table: it fetches exactly those itself - no staging in LDS, no barrier in front of the build)
         for (int k = 0; k < NSRC; ++k) {
-            const int i = k * 1024 + threadIdx.x;
-            p.raw[k] = (i < (1 << TB)) ? reinterpret_cast<const uint32_t *>(g)[i] : 0u;
+            const int i = (k * 1024 + (int)threadIdx.x) & ((1 << TB) - 1);
+            p.raw[k] = reinterpret_cast<const uint32_t *>(g)[i];
         }
         __builtin_amdgcn_s_barrier();   // every wavefront's table request is queued before any weight load
         return p;
     }
-    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *small, const Pre &p) {
-        uint32_t *s32 = reinterpret_cast<uint32_t *>(small);
-#pragma unroll
-        for (int k = 0; k < NSRC; ++k) {
-            const int i = k * 1024 + threadIdx.x;
-            if (i < (1 << TB)) s32[i] = p.raw[k];
-        }
-        __syncthreads();
+    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *, const Pre &p) {
         // Thread t writes all copies of entries t, t + 1024, ...: COPIES / 4 pieces of 16 bytes
         // each, in an order rotated by the lane so that eight neighbouring lanes always cover
         // all 32 banks (a few dozen instructions per thread instead of one per dword).
@@ -527,7 +539,7 @@ struct QpDecTcqh {
 #pragma unroll
         for (int m = 0; m < ENTRIES / 1024; ++m) {
             const int e = m * 1024 + (int)threadIdx.x;
-            const uint32_t v = s32[e & ((1 << TB) - 1)] ^ ((uint32_t)(e >> TB) << 15);
+            const uint32_t v = p.raw[m & (NSRC - 1)] ^ ((uint32_t)(e >> TB) << 15);
             const u32x4_t v4 = u32x4_t{v, v, v, v};
 #pragma unroll
             for (int k = 0; k < NP; ++k) t4[e * NP + ((k + rot) & (NP - 1))] = v4;
