@@ -668,8 +668,8 @@ template <> struct QpDec<QP_TCQ, 4> : QpDecTcq<4> {};
 
 // Decoders whose workgroup-wide table can be built either before the first loads are issued
 // (early) or after (build) define both to do the same thing; the kernel calls exactly one.
-// Early delays the first loads by the scalar fetch and two barriers; late makes every
-// wavefront wait at a barrier until the slowest one has issued its loads.  Measured (SQ 4 bit):
+// Early delays most loads by the fetch of the table's source, the LDS writes and a barrier; late makes
+// every wavefront wait at a barrier until the slowest one has issued its loads.  Measured (SQ 4 bit):
 // late wins for workgroups with few units (4096x4096: 5.8 -> 4.4 us), early for many
 // (4096x14336: 8.2 vs 9.3 us).
 template <class D> struct QpTableMovable { static constexpr bool value = false; };
@@ -1056,10 +1056,10 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     QP_T(0);
 
     // ---- first pass, straight-line up to the first loads ------------------------------
-    // Tables shared by the whole workgroup are built right away from scalar loads (one
-    // early barrier, before any vector load is queued); a per-wavefront table only fetches
-    // its source here and is written once the weight loads are in flight; the trellis
-    // table's source is requested first so that it can be waited for alone.
+    // The source of a table that the whole workgroup shares is requested here, ahead of every other load
+    // (every thread the code book entries of its own table entries; scalar codes through scalar registers);
+    // a per-wavefront table only fetches its source here and is written once the weight loads are in
+    // flight; the trellis table's source is requested first so that it can be waited for alone.
     // (a table that can be built at either point: late when the workgroup has few units)
     constexpr bool MOVABLE = QpTableMovable<D>::value;
     // (not where the in-kernel rotation's scratch borrows the table's room first)
@@ -1228,10 +1228,10 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
         } else {
             if constexpr (MOVABLE && !HH) {
                 // A table shared by the workgroup that is built "before the loads" is built with the
-                // activation fragments and the first piece(s) already on their way: the scalar fetch
-                // of its source, two barriers and 32 KiB of LDS writes take over a microsecond, the
-                // few early requests are accepted without back-pressure, and - loads returning in
-                // order - step 0 can start as soon as the table stands.
+                // activation fragments and the first piece(s) already on their way: the fetch of its
+                // source, 32 - 64 KiB of LDS writes and a barrier take most of a microsecond, the few
+                // early requests are accepted without back-pressure, and - loads returning in order -
+                // step 0 can start as soon as the table stands.
                 // (measured with one, two and three pieces ahead of the build: one is best)
                 q[0] = qp_stream_load(blk);
                 rotate_consts();
