@@ -1136,26 +1136,6 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
             return QpXPtr{xlane + C * xcs - back, 0u, xfs, tail, x_keep};
     };
     const bool owner = (tj == 0) && xlive;  // lane (g, b*TT) ends up with rows 4g..4g+3 of batch row b
-    half8_t xf[PF];
-    const auto xu = x_at(uu - ((uu * nbc_magic) >> 16) * nbc);   // column block = uu % nbc
-    const int xn0 = half1 ? PF : 0;   // first fragment of this item
-    // XL: the unrotated activations and their signs are requested first, ahead of the weights
-    QpHad1024In rin0;
-    QpHad1024 had;
-    if constexpr (XL == 2) {
-        // block `wave` (a wavefront without one fetches the last block instead - no branch around the
-        // loads - and drops it)
-        const int c0 = wave < nbc ? wave : nbc - 1;
-        rin0 = qp_fwht1024_fetch(x + 1024 * c0, signs + 1024 * c0, lane);
-    } else if constexpr (XL == 1) {
-        // chunk `wave` of the one block (a wavefront beyond the last chunk fetches the last one again - no
-        // branch around the loads - and drops it)
-        const int nch = rot_block >> 10;
-        rin0 = qp_fwht1024_fetch(x + 1024 * (wave < nch ? wave : nch - 1), signs + 1024 * (wave < nch ? wave : nch - 1), lane);
-    } else {
-#pragma unroll
-        for (int n = 0; n < PF; ++n) xf[n] = xu.frag(xn0 + n);
-    }
     // block (row block rb0 + slot, column block C) of unit u = slot * nbc + C, and whether
     // it has all P pieces
     const int hcb = nbc >> 1;   // half-TCQ: column blocks per half
@@ -1183,159 +1163,203 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
             return codes16 + ((int64_t)rb0 * nbc + un) * BLK16 + lane;
         }
     };
-    // XL == 2: the constant matrices of the transform are worked out by the workgroup once, one dword
-    // per thread, in front of a table build (whose barriers publish them) and behind the first loads:
-    // vector work in front of loads delays them, four wavefronts share a SIMD.
-    auto rotate_consts = [&]() __attribute__((always_inline)) {
-        if constexpr (XL != 0) QpHad1024::fill(had_lds);
-    };
-    u32x4_t q[P];
-    bool full;
-    QP_T(14);
-    {
-        const u32x4_t *blk = unit_block(rb_begin, uu, uu - ((uu * nbc_magic) >> 16) * nbc, full);
-        if constexpr (MID_BUILD) {
-            // The trellis tables (64 / 128 KiB of LDS writes, two barriers) are built with the activation
-            // fragments and the first piece already requested and the other pieces still to be asked
-            // for: every wavefront reaches the barriers without waiting in the load queue, and the
-            // first data arrives while the table is written (5 - 7 % on 4096x4096 and 28672x4096).
-            if constexpr (SPLIT) {
-                if (half1) qp_half_pieces_load<S, CB, P, 1, 1>(blk, ps, q);
-                else qp_half_pieces_load<S, CB, P, 0, 1>(blk, ps, q);
-            } else {
-                q[0] = qp_stream_load(blk);
-            }
-            rotate_consts();
-            D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
-            if constexpr (SPLIT) {
-                if (half1) qp_half_pieces_load<S, CB, P, 1, 2>(blk, ps, q);
-                else qp_half_pieces_load<S, CB, P, 0, 2>(blk, ps, q);
-            } else {
-#pragma unroll
-                for (int p = 1; p < P; ++p) {
-                    if (HH && p == P - 1) {   // half-TCQ: the last piece only exists in the second half
-                        q[p] = u32x4_t{0u, 0u, 0u, 0u};
-                        if (full) q[p] = qp_stream_load(blk + p * ps);
-                    } else {
-                        q[p] = qp_stream_load(blk + p * ps);
-                    }
-                }
-            }
-        } else if constexpr (SPLIT) {
-            if (half1) qp_half_pieces_load<S, CB, P, 1>(blk, ps, q);
-            else qp_half_pieces_load<S, CB, P, 0>(blk, ps, q);
-            rotate_consts();
-        } else {
-            if constexpr (MOVABLE && !HH) {
-                // A table shared by the workgroup that is built "before the loads" is built with the
-                // activation fragments and the first piece(s) already on their way: the fetch of its
-                // source, 32 - 64 KiB of LDS writes and a barrier take most of a microsecond, the few
-                // early requests are accepted without back-pressure, and - loads returning in order -
-                // step 0 can start as soon as the table stands.
-                // (measured with one, two and three pieces ahead of the build: one is best)
-                q[0] = qp_stream_load(blk);
-                rotate_consts();
-                if (!table_late) D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
-#pragma unroll
-                for (int p = 1; p < P; ++p) q[p] = qp_stream_load(blk + p * ps);
-            } else {
-                qp_pieces_load<P, HH>(blk, ps, full, q);
-                rotate_consts();
-            }
-        }
-    }
-    // the first output this thread stores after the pass: its per-row scale is fetched now
-    uint16_t scale_first;
-    {
-        const int o = threadIdx.x;
-        const int i = o & 15, slot = o >> (4 + LB);
-        scale_first = w.scales[(slot < gcount) ? (rb_begin + slot) * 16 + i : 0];
-    }
+    uint16_t scale_first = 0;
     typename D::Lane lc = D::lane_const();
-    QP_T(7);
-    // XL == 1: the first W = rot_block / 1024 wavefronts transform a chunk of 1024 each on the matrix cores
-    // and park it in LDS; 256 threads then run the stages across the chunks and write the rotated block in
-    // fragment order (same code as the stand-alone kernel, so the same bits).  Where the parking room borrows
-    // the table's, the table is built afterwards; otherwise before, while the activations are on their way.
-    auto rotate_chunks = [&]() __attribute__((always_inline)) {
-        if constexpr (XL == 1) {
-            __syncthreads();              // the constant matrices stand
-            QP_T(18);
-            if (wave < (rot_block >> 10)) {
-                had.read(had_lds, lane);
-                float4_t o[2][2];
-                qp_fwht1024_run(had, rin0, o);
-                qp_fwht_park(rot_buf + 1024, wave, lane, o);   // behind the constant matrices
-            }
-        }
-    };
-    auto rotate_across = [&]() __attribute__((always_inline)) {
-        if constexpr (XL == 1) {
-            const float *ex = rot_buf + 1024;
+    // The first pass in two instances: for a wavefront that has a work item - the straight-line code below, no
+    // branch around any load, so that every wait can name exactly the loads it needs - and for one that has none
+    // (the trellis kernels always run 16 wavefronts, the kernels that rotate the activations themselves 8 or 16),
+    // which takes part in the table build, the transform's constants and every barrier but requests nothing.
+    // (Such a wavefront used to load item 0 as well, to keep this code free of branches: on a layer of four units
+    // per workgroup twelve wavefronts' worth of requests queued in front of the four that mattered.)
+    auto first_pass = [&](auto act_c) __attribute__((always_inline)) {
+        constexpr bool ACT = decltype(act_c)::value;
+        half8_t xf[PF];
+        const auto xu = x_at(uu - ((uu * nbc_magic) >> 16) * nbc);   // column block = uu % nbc
+        const int xn0 = half1 ? PF : 0;   // first fragment of this item
+        // XL: the unrotated activations and their signs are requested first, ahead of the weights
+        QpHad1024In rin0;
+        QpHad1024 had;
+        if constexpr (XL == 2) {
+            // block `wave` (a wavefront without one fetches the last block instead - no branch around the
+            // loads - and drops it)
+            const int c0 = wave < nbc ? wave : nbc - 1;
+            if constexpr (ACT) rin0 = qp_fwht1024_fetch(x + 1024 * c0, signs + 1024 * c0, lane);
+        } else if constexpr (XL == 1) {
+            // chunk `wave` of the one block (a wavefront beyond the last chunk fetches the last one again - no
+            // branch around the loads - and drops it)
             const int nch = rot_block >> 10;
-            __syncthreads();
-            if (threadIdx.x < 256) {
-                auto put = [&](int idx, uint2 v) { *reinterpret_cast<uint2 *>(xr_lds + qp_xr_swizzled(qp_xr_index(0, idx, 0, 1))) = v; };
-                const float scale = rot_norm * 32.0f;
-                if (nch == 1) qp_fwht_cross<1>(threadIdx.x, ex, scale, put);
-                else if (nch == 2) qp_fwht_cross<2>(threadIdx.x, ex, scale, put);
-                else if (nch == 4) qp_fwht_cross<4>(threadIdx.x, ex, scale, put);
-                else qp_fwht_cross<8>(threadIdx.x, ex, scale, put);
-            }
-            QP_T(19);
-            __syncthreads();
-#pragma unroll
+            if constexpr (ACT) rin0 = qp_fwht1024_fetch(x + 1024 * (wave < nch ? wave : nch - 1), signs + 1024 * (wave < nch ? wave : nch - 1), lane);
+        } else if constexpr (ACT) {
+    #pragma unroll
             for (int n = 0; n < PF; ++n) xf[n] = xu.frag(xn0 + n);
         }
+        // XL == 2: the constant matrices of the transform are worked out by the workgroup once, one dword
+        // per thread, in front of a table build (whose barriers publish them) and behind the first loads:
+        // vector work in front of loads delays them, four wavefronts share a SIMD.
+        auto rotate_consts = [&]() __attribute__((always_inline)) {
+            if constexpr (XL != 0) QpHad1024::fill(had_lds);
+        };
+        u32x4_t q[P];
+        bool full;
+        QP_T(14);
+        {
+            const u32x4_t *blk = unit_block(rb_begin, uu, uu - ((uu * nbc_magic) >> 16) * nbc, full);
+            if constexpr (MID_BUILD) {
+                // The trellis tables (64 / 128 KiB of LDS writes, two barriers) are built with the activation
+                // fragments and the first piece already requested and the other pieces still to be asked
+                // for: every wavefront reaches the barriers without waiting in the load queue, and the
+                // first data arrives while the table is written (5 - 7 % on 4096x4096 and 28672x4096).
+                if constexpr (!ACT) {
+                } else if constexpr (SPLIT) {
+                    if (half1) qp_half_pieces_load<S, CB, P, 1, 1>(blk, ps, q);
+                    else qp_half_pieces_load<S, CB, P, 0, 1>(blk, ps, q);
+                } else {
+                    q[0] = qp_stream_load(blk);
+                }
+                rotate_consts();
+                D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
+                if constexpr (!ACT) {
+                } else if constexpr (SPLIT) {
+                    if (half1) qp_half_pieces_load<S, CB, P, 1, 2>(blk, ps, q);
+                    else qp_half_pieces_load<S, CB, P, 0, 2>(blk, ps, q);
+                } else {
+    #pragma unroll
+                    for (int p = 1; p < P; ++p) {
+                        if (HH && p == P - 1) {   // half-TCQ: the last piece only exists in the second half
+                            q[p] = u32x4_t{0u, 0u, 0u, 0u};
+                            if (full) q[p] = qp_stream_load(blk + p * ps);
+                        } else {
+                            q[p] = qp_stream_load(blk + p * ps);
+                        }
+                    }
+                }
+            } else if constexpr (SPLIT) {
+                if constexpr (ACT) {
+                    if (half1) qp_half_pieces_load<S, CB, P, 1>(blk, ps, q);
+                    else qp_half_pieces_load<S, CB, P, 0>(blk, ps, q);
+                }
+                rotate_consts();
+            } else {
+                if constexpr (MOVABLE && !HH) {
+                    // A table shared by the workgroup that is built "before the loads" is built with the
+                    // activation fragments and the first piece(s) already on their way: the fetch of its
+                    // source, 32 - 64 KiB of LDS writes and a barrier take most of a microsecond, the few
+                    // early requests are accepted without back-pressure, and - loads returning in order -
+                    // step 0 can start as soon as the table stands.
+                    // (measured with one, two and three pieces ahead of the build: one is best)
+                    if constexpr (ACT) q[0] = qp_stream_load(blk);
+                    rotate_consts();
+                    if (!table_late) D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
+                    if constexpr (ACT) {
+    #pragma unroll
+                        for (int p = 1; p < P; ++p) q[p] = qp_stream_load(blk + p * ps);
+                    }
+                } else {
+                    if constexpr (ACT) qp_pieces_load<P, HH>(blk, ps, full, q);
+                    rotate_consts();
+                }
+            }
+        }
+        // the first output this thread stores after the pass: its per-row scale is fetched now
+        {
+            const int o = threadIdx.x;
+            const int i = o & 15, slot = o >> (4 + LB);
+            scale_first = w.scales[(slot < gcount) ? (rb_begin + slot) * 16 + i : 0];
+        }
+        QP_T(7);
+        // XL == 1: the first W = rot_block / 1024 wavefronts transform a chunk of 1024 each on the matrix cores
+        // and park it in LDS; 256 threads then run the stages across the chunks and write the rotated block in
+        // fragment order (same code as the stand-alone kernel, so the same bits).  Where the parking room borrows
+        // the table's, the table is built afterwards; otherwise before, while the activations are on their way.
+        auto rotate_chunks = [&]() __attribute__((always_inline)) {
+            if constexpr (XL == 1) {
+                __syncthreads();              // the constant matrices stand
+                QP_T(18);
+                if (wave < (rot_block >> 10)) {
+                    had.read(had_lds, lane);
+                    float4_t o[2][2];
+                    qp_fwht1024_run(had, rin0, o);
+                    qp_fwht_park(rot_buf + 1024, wave, lane, o);   // behind the constant matrices
+                }
+            }
+        };
+        auto rotate_across = [&]() __attribute__((always_inline)) {
+            if constexpr (XL == 1) {
+                const float *ex = rot_buf + 1024;
+                const int nch = rot_block >> 10;
+                __syncthreads();
+                if (threadIdx.x < 256) {
+                    auto put = [&](int idx, uint2 v) { *reinterpret_cast<uint2 *>(xr_lds + qp_xr_swizzled(qp_xr_index(0, idx, 0, 1))) = v; };
+                    const float scale = rot_norm * 32.0f;
+                    if (nch == 1) qp_fwht_cross<1>(threadIdx.x, ex, scale, put);
+                    else if (nch == 2) qp_fwht_cross<2>(threadIdx.x, ex, scale, put);
+                    else if (nch == 4) qp_fwht_cross<4>(threadIdx.x, ex, scale, put);
+                    else qp_fwht_cross<8>(threadIdx.x, ex, scale, put);
+                }
+                QP_T(19);
+                __syncthreads();
+                if constexpr (ACT) {
+    #pragma unroll
+                    for (int n = 0; n < PF; ++n) xf[n] = xu.frag(xn0 + n);
+                }
+            }
+        };
+        // (Measured slower with the late table build between the two halves: 4096x4096 at 2.5 bits 4.9 -> 5.3 us.)
+        if constexpr (!MID_BUILD) {
+            if (!MOVABLE || table_late) D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
+        }
+        rotate_chunks();
+        rotate_across();
+        if constexpr (XL == 2) {
+            // Every wavefront transforms the block of its own unit on the matrix cores while its weights are
+            // on their way, and writes it to LDS in fragment order (four consecutive elements = 8 bytes).
+            // The workgroup has one row block and a wavefront per column block (the host checks), so a
+            // wavefront only ever reads what it wrote itself - LDS operations of a wavefront complete in
+            // order - and nobody waits for anybody.
+            if constexpr (!QpLinLds<D, S, CB, BP>::TABLE_HAS_BARRIER) __syncthreads();   // the constant matrices
+            had.read(had_lds, lane);
+            QP_T(18);
+            // (Transforming in front of an early table build instead - the SIMDs are idle there - delays the
+            // remaining loads by as much as it saves: 8.3 against 8.1 us on 4096x14336 at 2.5 bits.)
+            if (wave < nbc) {
+                float4_t o[2][2];
+                qp_fwht1024_run(had, rin0, o);
+    #pragma unroll
+                for (int tb = 0; tb < 2; ++tb)
+    #pragma unroll
+                    for (int ta = 0; ta < 2; ++ta)
+                        *reinterpret_cast<uint2 *>(xr_lds + qp_xr_swizzled(qp_xr_index(0, 1024 * wave + qp_fwht1024_elem(lane, tb, ta), 0, 1))) =
+                            qp_fwht1024_pack(o[tb][ta]);
+            }
+            QP_T(19);
+            // (two wavefronts per unit: a wavefront's half units belong to other column blocks than the one
+            // it transformed, so here everybody does wait for everybody)
+            if constexpr (SPLIT) __syncthreads();
+            if constexpr (ACT) {
+    #pragma unroll
+                for (int n = 0; n < PF; ++n) xf[n] = xu.frag(xn0 + n);
+            }
+        }
+        QP_T(1);
+        if (ACT && k < units) {
+            float4_t v;
+            if constexpr (SPLIT) {
+                if (half1) v = qp_unit_compute<D, P, PF, TT, 16, 32>(q, xf, xu, tab, lc, pre);
+                else v = qp_unit_compute<D, P, PF, TT, 0, 16>(q, xf, xu, tab, lc, pre);
+            } else if constexpr (HH) {
+                if (full) v = qp_unit_compute<D, P, PF, TT>(q, xf, xu, tab, lc, pre);
+                else v = qp_unit_compute<typename D::Lo, P, PF, TT>(q, xf, xu, tab, lc, pre);
+            } else {
+                v = qp_unit_compute<D, P, PF, TT>(q, xf, xu, tab, lc, pre);
+            }
+            if (owner) *reinterpret_cast<float4_t *>(&red[(u * BP + bj) * 16 + 4 * g]) = v;
+        }
     };
-    // (Measured slower with the late table build between the two halves: 4096x4096 at 2.5 bits 4.9 -> 5.3 us.)
-    if constexpr (!MID_BUILD) {
-        if (!MOVABLE || table_late) D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
-    }
-    rotate_chunks();
-    rotate_across();
-    if constexpr (XL == 2) {
-        // Every wavefront transforms the block of its own unit on the matrix cores while its weights are
-        // on their way, and writes it to LDS in fragment order (four consecutive elements = 8 bytes).
-        // The workgroup has one row block and a wavefront per column block (the host checks), so a
-        // wavefront only ever reads what it wrote itself - LDS operations of a wavefront complete in
-        // order - and nobody waits for anybody.
-        if constexpr (!QpLinLds<D, S, CB, BP>::TABLE_HAS_BARRIER) __syncthreads();   // the constant matrices
-        had.read(had_lds, lane);
-        QP_T(18);
-        // (Transforming in front of an early table build instead - the SIMDs are idle there - delays the
-        // remaining loads by as much as it saves: 8.3 against 8.1 us on 4096x14336 at 2.5 bits.)
-        if (wave < nbc) {
-            float4_t o[2][2];
-            qp_fwht1024_run(had, rin0, o);
-#pragma unroll
-            for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-                for (int ta = 0; ta < 2; ++ta)
-                    *reinterpret_cast<uint2 *>(xr_lds + qp_xr_swizzled(qp_xr_index(0, 1024 * wave + qp_fwht1024_elem(lane, tb, ta), 0, 1))) =
-                        qp_fwht1024_pack(o[tb][ta]);
-        }
-        QP_T(19);
-        // (two wavefronts per unit: a wavefront's half units belong to other column blocks than the one
-        // it transformed, so here everybody does wait for everybody)
-        if constexpr (SPLIT) __syncthreads();
-#pragma unroll
-        for (int n = 0; n < PF; ++n) xf[n] = xu.frag(xn0 + n);
-    }
-    QP_T(1);
-    if (k < units) {
-        float4_t v;
-        if constexpr (SPLIT) {
-            if (half1) v = qp_unit_compute<D, P, PF, TT, 16, 32>(q, xf, xu, tab, lc, pre);
-            else v = qp_unit_compute<D, P, PF, TT, 0, 16>(q, xf, xu, tab, lc, pre);
-        } else if constexpr (HH) {
-            if (full) v = qp_unit_compute<D, P, PF, TT>(q, xf, xu, tab, lc, pre);
-            else v = qp_unit_compute<typename D::Lo, P, PF, TT>(q, xf, xu, tab, lc, pre);
-        } else {
-            v = qp_unit_compute<D, P, PF, TT>(q, xf, xu, tab, lc, pre);
-        }
-        if (owner) *reinterpret_cast<float4_t *>(&red[(u * BP + bj) * 16 + 4 * g]) = v;
-    }
+    // (the scalar and vector quantizers without a rotation of their own run as many wavefronts as a pass has units,
+    // at least four: the few that can be left over there keep the old way)
+    constexpr bool IDLE_INSTANCE = XL != 0 || S == QP_TCQ || S == QP_TCQH || S == QP_TCQHH;
+    if (!IDLE_INSTANCE || k < units) first_pass(std::true_type{});
+    else first_pass(std::false_type{});
     QP_T(2);
     int rb0 = rb_begin;
     k += nw;
