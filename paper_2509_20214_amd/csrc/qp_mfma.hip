@@ -1172,7 +1172,8 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     // (Such a wavefront used to load item 0 as well, to keep this code free of branches: on a layer of four units
     // per workgroup twelve wavefronts' worth of requests queued in front of the four that mattered.)
     auto first_pass = [&](auto act_c) __attribute__((always_inline)) {
-        constexpr bool ACT = decltype(act_c)::value;
+        constexpr bool ACT = decltype(act_c)::value != 0;      // 0: no work item
+        constexpr bool FETCH = decltype(act_c)::value == 1;    // 2: an item, but no chunk of the block to rotate (XL == 1)
         half8_t xf[PF];
         const auto xu = x_at(uu - ((uu * nbc_magic) >> 16) * nbc);   // column block = uu % nbc
         const int xn0 = half1 ? PF : 0;   // first fragment of this item
@@ -1188,7 +1189,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
             // chunk `wave` of the one block (a wavefront beyond the last chunk fetches the last one again - no
             // branch around the loads - and drops it)
             const int nch = rot_block >> 10;
-            if constexpr (ACT) rin0 = qp_fwht1024_fetch(x + 1024 * (wave < nch ? wave : nch - 1), signs + 1024 * (wave < nch ? wave : nch - 1), lane);
+            if constexpr (FETCH) rin0 = qp_fwht1024_fetch(x + 1024 * (wave < nch ? wave : nch - 1), signs + 1024 * (wave < nch ? wave : nch - 1), lane);
         } else if constexpr (ACT) {
     #pragma unroll
             for (int n = 0; n < PF; ++n) xf[n] = xu.frag(xn0 + n);
@@ -1358,8 +1359,12 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     // (the scalar and vector quantizers without a rotation of their own run as many wavefronts as a pass has units,
     // at least four: the few that can be left over there keep the old way)
     constexpr bool IDLE_INSTANCE = XL != 0 || S == QP_TCQ || S == QP_TCQH || S == QP_TCQHH;
-    if (!IDLE_INSTANCE || k < units) first_pass(std::true_type{});
-    else first_pass(std::false_type{});
+    if (!IDLE_INSTANCE || k < units) {
+        if (XL == 1 && wave >= (rot_block >> 10)) first_pass(std::integral_constant<int, 2>{});   // (see FETCH)
+        else first_pass(std::integral_constant<int, 1>{});
+    } else {
+        first_pass(std::integral_constant<int, 0>{});
+    }
     QP_T(2);
     int rb0 = rb_begin;
     k += nw;
