@@ -486,11 +486,15 @@ struct QpDecTcq {
 // half2 entries; the sign flag is bit 15 of h and the index bits sit right below it, so
 // bits [15 : 15-TB] of h = x (x + 1) are one (TB+1)-bit index into a table of 2^(TB+1)
 // entries in which the upper half is the lower half with component 0 negated.  That table
-// fills 128 KiB of LDS with as many copies as fit (entry e, copy c at dword COPIES e + c;
-// a lane reads copy l % COPIES): 32 copies for TB = 9, one per bank, so the lookups - one
-// per *two* weights - never collide; 16 and 8 copies for TB = 10 and 11, where only lanes
-// with equal l % COPIES can still meet in a bank.  The per-state work is a 24-bit
-// multiply-add, a bit-field extract and a shift-or.
+// fills 64 KiB of LDS with as many copies as fit (entry e, copy c at dword COPIES e + c;
+// a lane reads copy l % COPIES): 16, 8 and 4 copies for TB = 9, 10 and 11.  A row of the
+// table is then 2^(15 - TB) bytes, which puts the index field of h exactly where the row
+// number of the address is: the per-state work is a shift, a 24-bit multiply-add and one
+// and-or.  Lanes l and l + 16 of a 32-lane pass share a copy and meet in a bank when their
+// rows have the same parity, so a lookup - one per *two* weights - mostly takes two LDS
+// cycles per pass instead of one.  (QP_TCQH_TABLE_128K, development builds: 32 copies in
+// 128 KiB at TB = 9, one per bank and no collisions, for a bit-field extract and a shift-or
+// in place of the and-or; measured slower, the vector pipe being the scarcer one.)
 // A lane's state for the V = 2 decoders: the offset of its copy of the table, and (the packed form at 4 bits
 // per step) the four addresses that an even decode step worked out for the odd one behind it.  One type for
 // every step width, so that the two halves of a half-TCQ layer can share it.
