@@ -334,11 +334,11 @@ template <> struct QpDec<QP_VQ, 7> : QpDecByte<QP_VQ, 7> {};
 // the parity of their index, and the half takes as long as the fullest pair - 3.1 cycles on average
 // (measured: 6.2 LDS cycles per 64-lane lookup where 4 is the least).  LSH = 7: sixteen copies in 128 KiB, copy
 // lane % 16 at (index << 7) | (lane % 16) << 3 - two lanes per copy and half, one bank pair per copy: always
-// the two cycles (measured 4.5 per lookup).  Writing 128 KiB costs a small layer more than the collisions
-// do (4096x14336 6.77 -> 6.99 us, 4096x4096 3.80 -> 4.17 us, and the in-kernel rotation has no room beside
-// it); layers with many units per workgroup, whose decode runs against the LDS pipe in steady state, gain
-// at batch 1 - 2 (57344x8192 37.1 -> 32.8 us, batch 2 39.5 -> 37.5; 8192x28672 20.7 -> 19.9, batch 2
-// 22.0 -> 20.4) and are unchanged at batch 8 - 16.
+// the two cycles (measured 4.5 per lookup).  Writing 128 KiB costs the smallest layers more than the
+// collisions do (4096x4096 3.77 -> 3.88 us, and the in-kernel rotation has no room beside it); with the tables
+// built from registers the others gain at batch 1 - 2 (4096x14336 6.66 -> 6.50 us, 8192x8192 6.85 -> 6.63,
+// 57344x8192 37.1 -> 32.8 us, batch 2 39.5 -> 37.5; 8192x28672 20.7 -> 19.9, batch 2 22.0 -> 20.4) and are
+// unchanged at batch 8 - 16.  The host's rule by units per workgroup is in qp_launch_linear_mfma.
 template <int LSH_>
 struct QpDecVq5PairT {
     static constexpr bool BYTE_WINDOW = false;
@@ -1585,11 +1585,18 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
     if (scheme == QP_VQ && cb == 5 && units_wg <= 16 && B > 2 && B <= 4 && units_wg > 8) {
         split = split_opt != 0;
     }
-    // VQ 5 bit at batch 1 - 2: the sixteen-copy table of code pairs (128 KiB, no lookup collisions) from 48 units
-    // per workgroup on (measured from 56: 8192x28672; 28 and fewer lose or draw); never with the rotation
-    // inside the kernel, which has no room beside it.
+    // VQ 5 bit at batch 1 - 2: the sixteen-copy table of code pairs (128 KiB, no lookup collisions) where its
+    // longer build is paid back - from 13 units per workgroup on (12 at batch 2), and at 7 - 8 units, where the
+    // table is built behind the loads anyway; never with the rotation inside the kernel, which has no room
+    // beside it.  us per call at batch 1, eight / sixteen copies, by units per workgroup: 4 (4096x4096)
+    // 3.77 / 3.88, 5 4.33 / 4.42, 6 4.48 / 4.48, 7 4.64 / 4.61, 8 (4096x8192, 8192x4096, 2048x8192) 4.87 / 4.78,
+    // 4.87 / 4.79, 4.62 / 4.45, 9 5.55 / 5.84, 10 5.69 / 5.90, 12 (4096x12288, 12288x4096) 6.07 / 6.04,
+    // 5.75 / 5.90, 13 6.58 / 6.50, 14 (4096x14336) 6.66 / 6.50, 16 (4096x16384, 8192x8192) 7.03 / 6.78,
+    // 6.85 / 6.63, 28 (8192x14336) 11.09 / 10.82, 49 (14336x14336) 16.73 / 16.20; at batch 2: 4 3.79 / 3.87,
+    // 8 5.15 / 5.01, 9 5.69 / 5.80, 12 6.25 / 6.02 and 6.05 / 5.92, 14 7.03 / 6.67, 28 11.45 / 10.74.
     if (scheme == QP_VQ && cb == 5 && B <= 2) {
-        split = (split_opt < 0 ? units_wg >= 48 : split_opt == 1) && rot_block <= 0;
+        const bool pays = units_wg >= (B == 2 ? 12 : 13) || units_wg == 7 || units_wg == 8;
+        split = (split_opt < 0 ? pays : split_opt == 1) && rot_block <= 0;
     }
     if (w.N % 1024 != 0) split = false;   // a last column block cut short: the plain form only
     int nw = units < 16 ? units : 16;
