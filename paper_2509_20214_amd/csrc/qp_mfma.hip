@@ -335,8 +335,9 @@ template <> struct QpDec<QP_VQ, 7> : QpDecByte<QP_VQ, 7> {};
 // (measured: 6.2 LDS cycles per 64-lane lookup where 4 is the least).  LSH = 7: sixteen copies in 128 KiB, copy
 // lane % 16 at (index << 7) | (lane % 16) << 3 - two lanes per copy and half, one bank pair per copy: always
 // the two cycles (measured 4.5 per lookup).  Writing 128 KiB costs the smallest layers more than the
-// collisions do (4096x4096 3.77 -> 3.88 us, and the in-kernel rotation has no room beside it); with the tables
-// built from registers the others gain at batch 1 - 2 (4096x14336 6.66 -> 6.50 us, 8192x8192 6.85 -> 6.63,
+// collisions do (4096x4096 3.77 -> 3.88 us, and the in-kernel rotation has no room beside it); layers of 13 to
+// 16 units per workgroup gain on some machines and lose on others (4096x14336 6.66 -> 6.50 us and
+// 6.77 -> 6.89 us), larger ones gain everywhere at batch 1 - 2 (10240x8192 8.34 -> 8.01 and 9.11 -> 8.78 us,
 // 57344x8192 37.1 -> 32.8 us, batch 2 39.5 -> 37.5; 8192x28672 20.7 -> 19.9, batch 2 22.0 -> 20.4) and are
 // unchanged at batch 8 - 16.  The host's rule by units per workgroup is in qp_launch_linear_mfma.
 template <int LSH_>
@@ -1586,16 +1587,19 @@ qp_status qp_launch_linear_mfma(const QpW &w, int scheme, int cb, const void *x,
         split = split_opt != 0;
     }
     // VQ 5 bit at batch 1 - 2: the sixteen-copy table of code pairs (128 KiB, no lookup collisions) where its
-    // longer build is paid back - from 13 units per workgroup on (12 at batch 2), and at 7 - 8 units, where the
-    // table is built behind the loads anyway; never with the rotation inside the kernel, which has no room
-    // beside it.  us per call at batch 1, eight / sixteen copies, by units per workgroup: 4 (4096x4096)
-    // 3.77 / 3.88, 5 4.33 / 4.42, 6 4.48 / 4.48, 7 4.64 / 4.61, 8 (4096x8192, 8192x4096, 2048x8192) 4.87 / 4.78,
-    // 4.87 / 4.79, 4.62 / 4.45, 9 5.55 / 5.84, 10 5.69 / 5.90, 12 (4096x12288, 12288x4096) 6.07 / 6.04,
-    // 5.75 / 5.90, 13 6.58 / 6.50, 14 (4096x14336) 6.66 / 6.50, 16 (4096x16384, 8192x8192) 7.03 / 6.78,
-    // 6.85 / 6.63, 28 (8192x14336) 11.09 / 10.82, 49 (14336x14336) 16.73 / 16.20; at batch 2: 4 3.79 / 3.87,
-    // 8 5.15 / 5.01, 9 5.69 / 5.80, 12 6.25 / 6.02 and 6.05 / 5.92, 14 7.03 / 6.67, 28 11.45 / 10.74.
+    // longer build is paid back on every machine it was measured on - from 20 units per workgroup on, and at
+    // 7 - 8 units, where the table is built behind the loads anyway; never with the rotation inside the kernel,
+    // which has no room beside it.  Two kinds of machine turned up, told apart by the one-launch step of
+    // 4096x14336 (7.3 us on one, 8.1 us on the other: whatever runs on the SIMDs and the LDS in front of the
+    // decode - table build, transform - takes longer there).  us per call at batch 1, eight / sixteen copies, by
+    // units per workgroup, on the first kind: 4 (4096x4096) 3.77 / 3.88, 5 4.33 / 4.42, 6 4.48 / 4.48, 7
+    // 4.64 / 4.61, 8 (4096x8192, 2048x8192) 4.87 / 4.78, 4.62 / 4.45, 9 5.55 / 5.84, 10 5.69 / 5.90, 12
+    // 6.07 / 6.04, 13 6.58 / 6.50, 14 (4096x14336) 6.66 / 6.50, 16 (4096x16384, 8192x8192) 7.03 / 6.78,
+    // 6.85 / 6.63, 20 (10240x8192) 8.34 / 8.01, 28 (8192x14336) 11.09 / 10.82, 49 (14336x14336) 16.73 / 16.20;
+    // on the second kind: 8 4.96 / 4.85, 4.60 / 4.41, 14 6.77 / 6.89, 16 7.25 / 7.66, 7.09 / 7.49, 20 9.11 / 8.78,
+    // 28 11.36 / 10.98, 49 17.63 / 16.92.  Batch 2 follows batch 1 (14 units: 7.03 / 6.67 and 7.27 / 7.45).
     if (scheme == QP_VQ && cb == 5 && B <= 2) {
-        const bool pays = units_wg >= (B == 2 ? 12 : 13) || units_wg == 7 || units_wg == 8;
+        const bool pays = units_wg >= 20 || units_wg == 7 || units_wg == 8;
         split = (split_opt < 0 ? pays : split_opt == 1) && rot_block <= 0;
     }
     if (w.N % 1024 != 0) split = false;   // a last column block cut short: the plain form only

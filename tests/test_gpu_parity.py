@@ -630,7 +630,7 @@ def test_linear_two_wavefronts_per_unit(qp, scheme, cb, M, N, B, split):
 @pytest.mark.parametrize("split", [0, 1])
 def test_vq5_tables_of_code_pairs(qp, M, N, B, split):
     """The 2.5-bit vector quantizer at batch <= 2 decodes two codes per lookup from a table of pairs held
-    eight times (64 KiB) or sixteen times (128 KiB, taken by shape from 13 units per workgroup on, and at 7 - 8); both
+    eight times (64 KiB) or sixteen times (128 KiB, taken by shape from 20 units per workgroup on, and at 7 - 8); both
     forms on layers of one and of several passes, same bits from both (the decoded weights are the same
     and so is the order of the sums)."""
     lay = synth.make_layer(85, M + B, synth.VQ, M, N, 5)

@@ -34,7 +34,7 @@ def cases():
     extra = [(synth.VQ, 5, 40, 20, 1), (synth.VQ, 5, 600, 8, 2), (synth.VQ, 5, 1100, 28, 5), (synth.VQ, 5, 300, 24, 16),
              (synth.SQ, 4, 2000, 8, 1), (synth.VQ, 7, 1300, 32, 1), (synth.TCQH, 6, 2600, 8, 1),
              (synth.TCQ, 3, 3000, 16, 2), (synth.TCQHH, 5, 1000, 14, 1), (synth.SQ, 4, 900, 28, 4),
-             # VQ 5 bit at batch 1 - 2 from 13 units per workgroup on: the sixteen-copy table of code pairs
+             # VQ 5 bit at batch 1 - 2 from 20 units per workgroup on: the sixteen-copy table of code pairs
              (synth.VQ, 5, 1500, 8, 1), (synth.VQ, 5, 700, 28, 2), (synth.VQ, 5, 513, 16, 1)]
     for j, (scheme, cb, rbk, nbc, B) in enumerate(extra):
         out.append((100 + j, scheme, cb, rbk * 16, nbc * 1024, B))
