@@ -224,8 +224,18 @@ struct QpHad1024 {
     }
     // The workgroup works them out once, one dword per thread, into 4 KiB of LDS (1024 dwords, [q][lane][d]);
     // after a barrier every wavefront reads its copy.
+    // (qp_had1024_word with q, lane and d taken from a run-time index compiles to a dozen branches on the
+    // execution mask; the same dword without one: k slot 2 d of the pair, its column c, the parities of k & c and
+    // (k | 1) & c - the second is the first flipped by c's lowest bit.)
     static __device__ __forceinline__ void fill(uint32_t *lds) {
-        for (int idx = threadIdx.x; idx < 1024; idx += blockDim.x) lds[idx] = qp_had1024_word(idx >> 8, (idx >> 2) & 63, idx & 3);
+        for (int idx = threadIdx.x; idx < 1024; idx += blockDim.x) {
+            const uint32_t d = idx & 3, g = (idx >> 6) & 3, j = (idx >> 2) & 15, q = idx >> 8, p2 = q >> 1;
+            const uint32_t k0 = (g << (3 - p2)) + 2 * d + 12 * (p2 & (d >> 1));   // pass 1: 8 g + e; pass 2: pi(g, e); e = 2 d
+            const uint32_t c = 16 * (q & 1) + j;
+            const uint32_t par0 = __builtin_popcount(k0 & c) & 1, par1 = par0 ^ (c & 1);
+            const uint32_t one = 0x2800u + 0x1400u * p2;                          // 2^-5 (pass 1) and 1 (pass 2) in fp16
+            lds[idx] = (one | (par0 << 15)) | ((one | (par1 << 15)) << 16);
+        }
     }
     __device__ __forceinline__ void read(const uint32_t *lds, int lane) {
 #pragma unroll
