@@ -1457,6 +1457,19 @@ __global__ __launch_bounds__(1024) void k_linear_mfma(QpW w, const half_t *x, in
                                                       int x_packed, const int8_t *signs, int rot_block, float rot_norm) {
     using D = typename QpDecSel<S, CB, SPLIT, BP>::type;
     using L = QpLinLds<D, S, CB, BP>;
+    // The 2.5-bit vector quantizer with its table of code pairs and no rotation of its own requests every kernel
+    // argument here, in one go.  Left to itself the compiler fetches each where it is first used, and the three
+    // cache lines of the argument block are then missed one after the other, each with a wait of its own, in
+    // front of the first loads of a wavefront (layer alone: 4096x14336 6.62 -> 6.53 us, batch 2 7.02 -> 6.95,
+    // batch 16 12.43 -> 12.29, 4096x4096 3.75 -> 3.67 us, 8192x8192 6.84 -> 6.76 us).  Not the others: 4-bit scalar
+    // and 3.5-bit pairs measured the same or a per cent slower, and where the first request - the table's source
+    // - only needs the first line, waiting for all three delays it (hybrid trellis 4096x14336 at 2 bits
+    // 7.83 -> 8.02 us, 4096x4096 at 4 bits 5.17 -> 5.29 us; the one-launch step at 2.5 bits 7.46 -> 7.51 us).
+    if constexpr (XL == 0 && S == QP_VQ && CB == 5 && BP != 4) {
+        asm volatile("" ::"s"(w.codes), "s"(w.lut), "s"(w.scales), "s"(w.M), "s"(w.N), "s"(w.row_stride), "s"(w.layout),
+                     "s"(w.nbc), "s"(x), "s"(B), "s"(ldx), "s"(y), "s"(ldy), "s"(G), "s"(rb_q), "s"(rb_r), "s"(nbc_magic),
+                     "s"(x_packed), "s"(blockDim.x));
+    }
     static_assert(XL == 0 || L::ROT, "in-kernel rotation: batch 1");
     static_assert(XL != 2 || L::ROTM, "per-wavefront rotation: tables of at most 64 KiB");
     // One object, the table first: at LDS address 0 a lookup's address register is the whole address;
