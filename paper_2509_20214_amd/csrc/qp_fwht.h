@@ -227,8 +227,8 @@ struct QpHad1024 {
     // (qp_had1024_word with q, lane and d taken from a run-time index compiles to a dozen branches on the
     // execution mask; the same dword without one: k slot 2 d of the pair, its column c, the parities of k & c and
     // (k | 1) & c - the second is the first flipped by c's lowest bit.)
-    static __device__ __forceinline__ void fill(uint32_t *lds) {
-        for (int idx = threadIdx.x; idx < 1024; idx += blockDim.x) {
+    static __device__ __forceinline__ void fill(uint32_t *lds, int wgt) {   // wgt: threads of the workgroup
+        for (int idx = threadIdx.x; idx < 1024; idx += wgt) {
             const uint32_t d = idx & 3, g = (idx >> 6) & 3, j = (idx >> 2) & 15, q = idx >> 8, p2 = q >> 1;
             const uint32_t k0 = (g << (3 - p2)) + 2 * d + 12 * (p2 & (d >> 1));   // pass 1: 8 g + e; pass 2: pi(g, e); e = 2 d
             const uint32_t c = 16 * (q & 1) + j;

@@ -254,12 +254,12 @@ struct QpDecByte {
     struct PreStaged { u32x4_t src[NQ]; };
     struct PreDirect { uint32_t v[4]; };   // the row's entry for idx = thread + k * workgroup size, row idx >> 2
     typedef std::conditional_t<DIRECT, PreDirect, PreStaged> Pre;
-    static __device__ __forceinline__ Pre pre(const uint16_t *g) {
+    static __device__ __forceinline__ Pre pre(const uint16_t *g, int wgt = (int)blockDim.x) {
         Pre p;
         if constexpr (DIRECT) {
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const int idx = threadIdx.x + k * blockDim.x, b = idx >> 2;
+                const int idx = threadIdx.x + k * wgt, b = idx >> 2;
                 p.v[k] = idx < 1024 ? reinterpret_cast<const uint32_t *>(g)[b & ((1 << CB) - 1)] : 0u;
             }
         } else {
@@ -277,7 +277,7 @@ struct QpDecByte {
     }
     static __device__ __forceinline__ void early(uint8_t *tab, uint16_t *small, const uint16_t *g) { build(tab, small, pre(g)); }
     // every thread writes 32 bytes of a row
-    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *small, const Pre &p) {
+    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *small, const Pre &p, int wgt = (int)blockDim.x) {
         if constexpr (!DIRECT) {
             if (threadIdx.x == 0) {
 #pragma unroll
@@ -290,7 +290,7 @@ struct QpDecByte {
         u32x4_t *t4 = reinterpret_cast<u32x4_t *>(tab);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {          // (a workgroup has at least 256 threads)
-            const int idx = threadIdx.x + k * blockDim.x;
+            const int idx = threadIdx.x + k * wgt;
             if (idx < 1024) {
                 const int b = idx >> 2, part = idx & 3;
                 uint32_t v;
@@ -353,25 +353,25 @@ struct QpDecVq5PairT {
     // and an LDS round trip in front of the build (one-launch step of 4096x14336 8.03 -> 7.79 us, 1024x4096
     // 3.71 -> 3.40 us, 4096x4096 3.85 -> 3.80 us, nothing slower).
     struct Pre { uint32_t lo; uint32_t hi[4]; };   // entry idx = thread + k * workgroup size: codes idx & 31 and idx >> 5
-    static __device__ __forceinline__ Pre pre(const uint16_t *g) {
+    static __device__ __forceinline__ Pre pre(const uint16_t *g, int wgt = (int)blockDim.x) {
         const uint32_t *s = reinterpret_cast<const uint32_t *>(g);
         Pre p;
         p.lo = s[threadIdx.x & 31];                // (the workgroup size is a multiple of 32)
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const int idx = threadIdx.x + k * blockDim.x;
+            const int idx = threadIdx.x + k * wgt;
             p.hi[k] = idx < 1024 ? s[idx >> 5] : 0u;
         }
         return p;
     }
     static __device__ __forceinline__ uint32_t lane_const() { return (threadIdx.x & (uint32_t)(COPIES - 1)) << 3; }
     static __device__ __forceinline__ void early(uint8_t *tab, uint16_t *small, const uint16_t *g) { build(tab, small, pre(g)); }
-    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *, const Pre &p) {
+    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *, const Pre &p, int wgt = (int)blockDim.x) {
         u32x4_t *t4 = reinterpret_cast<u32x4_t *>(tab);
         QP_T(12);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {              // (a workgroup has at least 256 threads)
-            const int idx = threadIdx.x + k * blockDim.x;
+            const int idx = threadIdx.x + k * wgt;
             if (idx < 1024) {
                 const u32x4_t v4 = u32x4_t{p.lo, p.hi[k], p.lo, p.hi[k]};   // first code in the low five bits
                 constexpr int NP = COPIES / 2;     // 16-byte pieces per entry
@@ -426,8 +426,8 @@ struct QpDecVq5Private {
     typedef uint32_t Lane;
     struct Pre { const uint16_t *g; };
     static __device__ __forceinline__ void early(uint8_t *, uint16_t *, const uint16_t *) {}
-    static __device__ __forceinline__ Pre pre(const uint16_t *g) { return Pre{g}; }
-    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *, const Pre &p) {
+    static __device__ __forceinline__ Pre pre(const uint16_t *g, int = 0) { return Pre{g}; }
+    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *, const Pre &p, int = 0) {
         qp_scalar_to_lds<8>(qp_scalar_ptr(p.g), reinterpret_cast<u32x4_t *>(tab) + (threadIdx.x >> 6) * 8);
     }
     static __device__ __forceinline__ uint32_t lane_const() { return (threadIdx.x >> 6) << 7; }
@@ -451,7 +451,7 @@ struct QpDecTcq {
     static constexpr int PRE = 8;  // 128 KiB / (1024 threads * 16 bytes)
     struct Pre { u32x4_t raw[PRE]; };
     static __device__ __forceinline__ void early(uint8_t *, uint16_t *, const uint16_t *) {}
-    static __device__ __forceinline__ Pre pre(const uint16_t *g) {  // needs blockDim.x == 1024
+    static __device__ __forceinline__ Pre pre(const uint16_t *g, int = 0) {  // needs blockDim.x == 1024
         Pre p;
         const u32x4_t *g4 = reinterpret_cast<const u32x4_t *>(g);
 #pragma unroll
@@ -463,7 +463,7 @@ struct QpDecTcq {
         __builtin_amdgcn_s_barrier();
         return p;
     }
-    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *, const Pre &p) {
+    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *, const Pre &p, int = 0) {
         u32x4_t *t4 = reinterpret_cast<u32x4_t *>(tab);
 #pragma unroll
         for (int k = 0; k < PRE; ++k) t4[k * 1024 + threadIdx.x] = p.raw[k];
@@ -522,7 +522,7 @@ struct QpDecTcqh {
     typedef QpTcqhLane Lane;
     static __device__ __forceinline__ Lane lane_const() { return Lane{(threadIdx.x & (uint32_t)(COPIES - 1)) << 2, {0u, 0u, 0u, 0u}}; }
     static __device__ __forceinline__ void early(uint8_t *, uint16_t *, const uint16_t *) {}
-    static __device__ __forceinline__ Pre pre(const uint16_t *g) {  // needs blockDim.x == 1024
+    static __device__ __forceinline__ Pre pre(const uint16_t *g, int = 0) {  // needs blockDim.x == 1024
         Pre p;
 #pragma unroll
         // (thread t builds entries t, t + 1024, ... of the table, whose sources are entries (t + 1024 k) mod 2^TB of
@@ -534,7 +534,7 @@ struct QpDecTcqh {
         __builtin_amdgcn_s_barrier();   // every wavefront's table request is queued before any weight load
         return p;
     }
-    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *, const Pre &p) {
+    static __device__ __forceinline__ void build(uint8_t *tab, uint16_t *, const Pre &p, int = 0) {
         // Thread t writes all copies of entries t, t + 1024, ...: COPIES / 4 pieces of 16 bytes
         // each, in an order rotated by the lane so that eight neighbouring lanes always cover
         // all 32 banks (a few dozen instructions per thread instead of one per dword).
@@ -966,11 +966,11 @@ __device__ __forceinline__ float4_t qp_unit_compute(const u32x4_t (&q)[P], half8
 // order (column blocks ascending), scale, round once to fp16 and store.
 template <int BP>
 __device__ __forceinline__ void qp_pass_store(const QpW &w, const float *red, half_t *y, int64_t ldy, int B,
-                                              int rb0, int gcount, int nbc, uint16_t scale_first) {
+                                              int rb0, int gcount, int nbc, uint16_t scale_first, int wgt) {
     constexpr int LB = (BP == 1) ? 0 : (BP == 2) ? 1 : (BP == 4) ? 2 : (BP == 8) ? 3 : 4;
     __syncthreads();
     QP_T(5);
-    for (int o = threadIdx.x; o < (gcount << (4 + LB)); o += blockDim.x) {
+    for (int o = threadIdx.x; o < (gcount << (4 + LB)); o += wgt) {
         const int i = o & 15, b = (o >> 4) & (BP - 1), slot = o >> (4 + LB);
         if (b < B) {
             const int row = (rb0 + slot) * 16 + i;
@@ -1072,9 +1072,13 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
                                (S == QP_TCQ || S == QP_TCQH || S == QP_TCQHH);
     const bool table_late = MOVABLE && (rb_q + (rb_r ? 1 : 0)) * w.nbc <= late_max;
     QP_T(13);
-    const typename D::Pre pre = D::pre(w.lut);
+    // Threads of the workgroup.  XL == 2 always runs 16 wavefronts (the host sets it): a constant there instead of
+    // a kernel argument on a cache line of its own, and the rounds "one entry per thread, as many as it takes" of
+    // the table build and of the transform's constants become straight-line code.
+    const int wgt = (XL == 2) ? 1024 : (int)blockDim.x;
+    const typename D::Pre pre = D::pre(w.lut, wgt);
 
-    const int nw = blockDim.x >> 6;
+    const int nw = wgt >> 6;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int nbc = w.nbc;
     // balanced contiguous partition of the row blocks over the workgroups: the first rb_r
@@ -1203,7 +1207,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
         // per thread, in front of a table build (whose barriers publish them) and behind the first loads:
         // vector work in front of loads delays them, four wavefronts share a SIMD.
         auto rotate_consts = [&]() __attribute__((always_inline)) {
-            if constexpr (XL != 0) QpHad1024::fill(had_lds);
+            if constexpr (XL != 0) QpHad1024::fill(had_lds, wgt);
         };
         u32x4_t q[P];
         bool full;
@@ -1223,7 +1227,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
                     q[0] = qp_stream_load(blk);
                 }
                 rotate_consts();
-                D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
+                D::build(tab, reinterpret_cast<uint16_t *>(red), pre, wgt);
                 if constexpr (!ACT) {
                 } else if constexpr (SPLIT) {
                     if (half1) qp_half_pieces_load<S, CB, P, 1, 2>(blk, ps, q);
@@ -1255,7 +1259,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
                     // (measured with one, two and three pieces ahead of the build: one is best)
                     if constexpr (ACT) q[0] = qp_stream_load(blk);
                     rotate_consts();
-                    if (!table_late) D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
+                    if (!table_late) D::build(tab, reinterpret_cast<uint16_t *>(red), pre, wgt);
                     if constexpr (ACT) {
     #pragma unroll
                         for (int p = 1; p < P; ++p) q[p] = qp_stream_load(blk + p * ps);
@@ -1312,7 +1316,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
         };
         // (Measured slower with the late table build between the two halves: 4096x4096 at 2.5 bits 4.9 -> 5.3 us.)
         if constexpr (!MID_BUILD) {
-            if (!MOVABLE || table_late) D::build(tab, reinterpret_cast<uint16_t *>(red), pre);
+            if (!MOVABLE || table_late) D::build(tab, reinterpret_cast<uint16_t *>(red), pre, wgt);
         }
         rotate_chunks();
         rotate_across();
@@ -1383,7 +1387,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
     // 8.20 -> 7.94, 3.5 bits 8.53 -> 8.27, 4-bit scalar 8.39 -> 8.16 us).
     constexpr bool ONE_PASS = (XL == 2) && !SPLIT;
     const bool one_pass = ONE_PASS || (units <= nw && rb_begin + G >= rb_end);   // the same for every wavefront
-    if (one_pass) qp_pass_store<BP>(w, red, y, ldy, B, rb0, gcount, nbc * SPL, scale_first);
+    if (one_pass) qp_pass_store<BP>(w, red, y, ldy, B, rb0, gcount, nbc * SPL, scale_first, wgt);
     else while (true) {
         // ---- remaining units of this pass ----------------------------------------------
         for (; k < units; k += nw) {
@@ -1432,7 +1436,7 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
             tr_units += 1;
 #endif
         }
-        qp_pass_store<BP>(w, red, y, ldy, B, rb0, gcount, nbc * SPL, scale_first);
+        qp_pass_store<BP>(w, red, y, ldy, B, rb0, gcount, nbc * SPL, scale_first, wgt);
         // ---- next pass ------------------------------------------------------------------
         rb0 += G;
         if (rb0 >= rb_end) break;

@@ -110,7 +110,7 @@ __global__ __launch_bounds__(1024) void k_linear_rowwave_rot(QpW w, const half_t
     const int nch = w.N >> 10;
     QpHad1024In in;
     if (wave < nch) in = qp_fwht1024_fetch(x + 1024 * wave, signs + 1024 * wave, lane);
-    QpHad1024::fill(had);
+    QpHad1024::fill(had, (int)blockDim.x);
     qp_stage_lut<T::LUT_HALVES>(w.lut, lut);
     __syncthreads();
     if (wave < nch) {
