@@ -1072,10 +1072,15 @@ __device__ __forceinline__ void qp_linear_body(const QpW &w, const half_t *x, in
                                (S == QP_TCQ || S == QP_TCQH || S == QP_TCQHH);
     const bool table_late = MOVABLE && (rb_q + (rb_r ? 1 : 0)) * w.nbc <= late_max;
     QP_T(13);
-    // Threads of the workgroup.  XL == 2 always runs 16 wavefronts (the host sets it): a constant there instead of
-    // a kernel argument on a cache line of its own, and the rounds "one entry per thread, as many as it takes" of
-    // the table build and of the transform's constants become straight-line code.
-    const int wgt = (XL == 2) ? 1024 : (int)blockDim.x;
+    // Threads of the workgroup.  XL == 2 always runs 16 wavefronts, and so do the trellis schemes (the host sets
+    // it): a constant there instead of a kernel argument on a cache line of its own, and the rounds "one entry per
+    // thread, as many as it takes" of the table build, the transform's constants and the sums become straight-line
+    // code.  Taken where it measured faster: XL == 2, and the trellis kernels that rotate one block themselves
+    // (hybrid trellis steps 4096x8192 at 2 bits 6.48 -> 6.06 us, 4096x4096 4.79 -> 4.62 us; their other kernels
+    // within 3 % either way; 16 wavefronts and the constant for the scalar and vector quantizers at XL == 1, which
+    // run 8 to 16: 2.5 bits 4096x4096 4.40 -> 4.29 us but 4096x8192 5.96 -> 6.35 us).
+    constexpr bool WG_1024 = XL == 2 || (XL == 1 && (S == QP_TCQH || S == QP_TCQHH));
+    const int wgt = WG_1024 ? 1024 : (int)blockDim.x;
     const typename D::Pre pre = D::pre(w.lut, wgt);
 
     const int nw = wgt >> 6;
